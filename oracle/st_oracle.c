@@ -1,0 +1,224 @@
+/*
+ * CPU oracle for the SilverTorch retrieval hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * This file is the slow, plain definition that the GPU library is checked
+ * against.  It shares no code with the GPU path and must never be called from
+ * it: only the tests, the smoke check and the benchmark's cpu_baseline leg may
+ * load it.
+ *
+ * What it computes (paper sections in brackets):
+ *   - per-item m-bit Bloom signatures VB_i, item-major          [Sec. 4.1, text before Eq. 4]
+ *   - the Bloom match rule (QB & VB_i) == QB                    [Sec. 4.1, Eq. 4]
+ *   - the exact set rule Q subset-of V_i (no hashing)           [Sec. 4.1, Eq. 3]
+ *   - int8 x int8 -> int32 dot products                         [Sec. 4.2, Int8 ANN]
+ *   - scoring only the items whose mask bit is 1, then ArgTopK  [Sec. 4.3, Alg. 1 phases 3-4,
+ *                                                                 every item in scope = all clusters probed]
+ *   - the weighted-sum form of the Value Model over T tasks     [Sec. 5.2]
+ *
+ * Constants the paper leaves open are fixed by the build's problem statement:
+ *   hash  h_j(f) = splitmix64(f XOR j) mod m,  j = 0..k-1
+ *   score = ((float)dot * s_q) * s_i          two separately rounded fp32 multiplies
+ *   agg   = fmaf(w_t, score_t, agg), t ascending, agg starts at +0.0f
+ *   order = score descending, ties (== on floats) by lower item id
+ *   fewer than K passing items: count < K, padding id = -1, score = -inf
+ *
+ * Floating point is fp32 because the problem statement fixes the precision and
+ * the rounding order; the file must be compiled with -ffp-contract=off and
+ * without -ffast-math so that no multiply-add is fused behind our back.
+ *
+ * Pins (tests/test_oracle_pins.py): published splitmix64 outputs, brute force
+ * on raw id sets, no-false-negative and false-positive-rate closed form,
+ * numpy int32 matmul + stable argsort, exact rational arithmetic for the
+ * rescale and the fused multiply-add chain.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* splitmix64 output function applied to x: add the golden-ratio increment, then mix. */
+uint64_t sto_splitmix64(uint64_t x)
+{
+    uint64_t z = x + 0x9E3779B97F4A7C15ULL;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ULL;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBULL;
+    return z ^ (z >> 31);
+}
+
+/* Bit position of hash j of feature f in an m-bit filter.  [Sec. 4.1] */
+int64_t sto_bit_index(uint64_t f, int32_t j, int32_t m)
+{
+    return (int64_t)(sto_splitmix64(f ^ (uint64_t)j) % (uint64_t)m);
+}
+
+static int64_t sig_words(int32_t m) { return ((int64_t)m + 63) / 64; }
+
+/* OR the k hash bits of each of n feature ids into sig (W = ceil(m/64) words,
+ * bit b lives in word b/64 at position b%64, least significant first). */
+void sto_signature(const uint64_t* ids, int64_t n, int32_t m, int32_t k, uint64_t* sig)
+{
+    int64_t W = sig_words(m);
+    memset(sig, 0, (size_t)W * sizeof(uint64_t));
+    for (int64_t a = 0; a < n; ++a)
+        for (int32_t j = 0; j < k; ++j) {
+            int64_t b = sto_bit_index(ids[a], j, m);
+            sig[b / 64] |= 1ULL << (b % 64);
+        }
+}
+
+/* Item-major Bloom index: sigs[i*W .. i*W+W) = VB_i.  Items given as CSR. */
+void sto_bloom_build(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_t n_items,
+                     int32_t m, int32_t k, uint64_t* sigs)
+{
+    int64_t W = sig_words(m);
+    for (int64_t i = 0; i < n_items; ++i)
+        sto_signature(feat_ids + feat_offsets[i], feat_offsets[i + 1] - feat_offsets[i], m, k,
+                      sigs + i * W);
+}
+
+static int bloom_pass(const uint64_t* qb, const uint64_t* vb, int64_t W)
+{
+    for (int64_t w = 0; w < W; ++w)
+        if ((qb[w] & vb[w]) != qb[w]) return 0;
+    return 1;
+}
+
+/* mask[w] bit (i%64) = pass_i for i = 64w + bit; bits at or past n_items are 0.  [Eq. 4] */
+void sto_bloom_mask(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
+                    const uint64_t* filt_ids, int64_t n_filt, uint64_t* mask)
+{
+    int64_t W = sig_words(m);
+    uint64_t* qb = (uint64_t*)malloc((size_t)W * sizeof(uint64_t));
+    sto_signature(filt_ids, n_filt, m, k, qb);
+    memset(mask, 0, (size_t)((n_items + 63) / 64) * sizeof(uint64_t));
+    for (int64_t i = 0; i < n_items; ++i)
+        if (bloom_pass(qb, sigs + i * W, W)) mask[i / 64] |= 1ULL << (i % 64);
+    free(qb);
+}
+
+/* Exact filter on the raw id lists: pass_i iff every filter id occurs in F_i.  [Eq. 3] */
+void sto_exact_mask(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_t n_items,
+                    const uint64_t* filt_ids, int64_t n_filt, uint64_t* mask)
+{
+    memset(mask, 0, (size_t)((n_items + 63) / 64) * sizeof(uint64_t));
+    for (int64_t i = 0; i < n_items; ++i) {
+        int all = 1;
+        for (int64_t a = 0; a < n_filt && all; ++a) {
+            int found = 0;
+            for (int64_t p = feat_offsets[i]; p < feat_offsets[i + 1]; ++p)
+                if (feat_ids[p] == filt_ids[a]) { found = 1; break; }
+            all = found;
+        }
+        if (all) mask[i / 64] |= 1ULL << (i % 64);
+    }
+}
+
+/* int8 dot product with int32 accumulation.  [Sec. 4.2] */
+int32_t sto_dot(const int8_t* q, const int8_t* e, int32_t d)
+{
+    int32_t acc = 0;
+    for (int32_t c = 0; c < d; ++c) acc += (int32_t)q[c] * (int32_t)e[c];
+    return acc;
+}
+
+/* Two separately rounded fp32 multiplies, left to right. */
+float sto_rescale(int32_t dot, float s_q, float s_i)
+{
+    volatile float a = (float)dot * s_q; /* volatile: forces the intermediate rounding */
+    volatile float b = a * s_i;
+    return b;
+}
+
+/* Score of (query b, item i): single task when task_weight is NULL, else the
+ * weighted sum over T tasks as a fused-multiply-add chain, t ascending. */
+float sto_pair_score(const int8_t* queries, const float* query_scale, int32_t n_tasks,
+                     const float* task_weight, int64_t b, const int8_t* item, float s_i, int32_t d)
+{
+    if (task_weight == NULL)
+        return sto_rescale(sto_dot(queries + b * d, item, d), query_scale[b], s_i);
+    float agg = 0.0f;
+    for (int32_t t = 0; t < n_tasks; ++t) {
+        const int8_t* q = queries + (b * n_tasks + t) * (int64_t)d;
+        float st = sto_rescale(sto_dot(q, item, d), query_scale[b * n_tasks + t], s_i);
+        agg = fmaf(task_weight[t], st, agg);
+    }
+    return agg;
+}
+
+typedef struct { float score; int64_t id; } sto_cand;
+
+static int cand_cmp(const void* pa, const void* pb)
+{
+    const sto_cand* a = (const sto_cand*)pa;
+    const sto_cand* b = (const sto_cand*)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    if (a->id < b->id) return -1;
+    if (a->id > b->id) return 1;
+    return 0;
+}
+
+/*
+ * Filtered top-K for a batch.  [Alg. 1 phases 3-4 with every item in scope]
+ *   sigs            item-major signatures from sto_bloom_build
+ *   items           [n_items, d] int8 row-major;  item_scale [n_items]
+ *   queries         [batch, d] (task_weight == NULL) or [batch, n_tasks, d]
+ *   query_scale     [batch] or [batch, n_tasks]
+ *   filt_offsets    [batch+1] into filt_ids; query b's filter is the conjunction
+ *                   of filt_ids[filt_offsets[b] .. filt_offsets[b+1]); empty = all pass
+ *   out_ids/out_scores [batch, K]; out_count [batch]
+ * Every passing item is scored, the full list is sorted, the first K are kept.
+ * Returns 0, or -1 when memory runs out.
+ */
+int sto_search(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
+               const int8_t* items, const float* item_scale, int32_t d,
+               const int8_t* queries, const float* query_scale, int32_t batch,
+               int32_t n_tasks, const float* task_weight,
+               const uint64_t* filt_ids, const int64_t* filt_offsets, int32_t K,
+               int64_t* out_ids, float* out_scores, int32_t* out_count)
+{
+    int64_t W = sig_words(m);
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < batch; ++b) {
+        uint64_t* qb = (uint64_t*)malloc((size_t)W * sizeof(uint64_t));
+        sto_cand* cand = (sto_cand*)malloc((size_t)(n_items > 0 ? n_items : 1) * sizeof(sto_cand));
+        if (!qb || !cand) {
+#pragma omp atomic write
+            failed = 1;
+            free(qb); free(cand);
+            continue;
+        }
+        sto_signature(filt_ids + filt_offsets[b], filt_offsets[b + 1] - filt_offsets[b], m, k, qb);
+        int64_t n = 0;
+        for (int64_t i = 0; i < n_items; ++i) {
+            if (!bloom_pass(qb, sigs + i * W, W)) continue;
+            cand[n].score = sto_pair_score(queries, query_scale, n_tasks, task_weight, b,
+                                           items + i * (int64_t)d, item_scale[i], d);
+            cand[n].id = i;
+            ++n;
+        }
+        qsort(cand, (size_t)n, sizeof(sto_cand), cand_cmp);
+        int64_t keep = n < K ? n : K;
+        for (int64_t r = 0; r < K; ++r) {
+            out_ids[(int64_t)b * K + r] = r < keep ? cand[r].id : -1;
+            out_scores[(int64_t)b * K + r] = r < keep ? cand[r].score : -INFINITY;
+        }
+        out_count[b] = (int32_t)keep;
+        free(qb); free(cand);
+    }
+    return failed ? -1 : 0;
+}
+
+/* Threads sto_search uses (for reporting the CPU baseline honestly). */
+int32_t sto_num_threads(void)
+{
+#ifdef _OPENMP
+    return (int32_t)omp_get_max_threads();
+#else
+    return 1;
+#endif
+}

@@ -1,0 +1,166 @@
+"""ctypes front end of the CPU oracle (``st_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this module; the GPU library never does, and nothing in
+here imports the GPU package.  All arrays are numpy, host memory.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "st_oracle.c")
+_LIB = os.path.join(_HERE, "libst_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  No contraction, no fast-math: the fp32
+    rounding order is part of the definition."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.check_call(cmd)
+    return _LIB
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        p = C.c_void_p
+        L.sto_splitmix64.restype = C.c_uint64
+        L.sto_splitmix64.argtypes = [C.c_uint64]
+        L.sto_bit_index.restype = C.c_int64
+        L.sto_bit_index.argtypes = [C.c_uint64, C.c_int32, C.c_int32]
+        L.sto_signature.restype = None
+        L.sto_signature.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p]
+        L.sto_bloom_build.restype = None
+        L.sto_bloom_build.argtypes = [p, p, C.c_int64, C.c_int32, C.c_int32, p]
+        L.sto_bloom_mask.restype = None
+        L.sto_bloom_mask.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, C.c_int64, p]
+        L.sto_exact_mask.restype = None
+        L.sto_exact_mask.argtypes = [p, p, C.c_int64, p, C.c_int64, p]
+        L.sto_dot.restype = C.c_int32
+        L.sto_dot.argtypes = [p, p, C.c_int32]
+        L.sto_rescale.restype = C.c_float
+        L.sto_rescale.argtypes = [C.c_int32, C.c_float, C.c_float]
+        L.sto_search.restype = C.c_int
+        L.sto_search.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, p, C.c_int32, p, p,
+                                 C.c_int32, C.c_int32, p, p, p, C.c_int32, p, p, p]
+        L.sto_num_threads.restype = C.c_int32
+        L.sto_num_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _ptr(a: np.ndarray | None):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _arr(a, dtype) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(a, dtype=dtype))
+
+
+def splitmix64(x: int) -> int:
+    return int(lib().sto_splitmix64(C.c_uint64(x & 0xFFFFFFFFFFFFFFFF)))
+
+
+def bit_index(f: int, j: int, m: int) -> int:
+    return int(lib().sto_bit_index(C.c_uint64(f & 0xFFFFFFFFFFFFFFFF), j, m))
+
+
+def sig_words(m: int) -> int:
+    return (m + 63) // 64
+
+
+def signature(ids, m: int, k: int) -> np.ndarray:
+    ids = _arr(ids, np.uint64)
+    out = np.zeros(sig_words(m), dtype=np.uint64)
+    lib().sto_signature(_ptr(ids), ids.size, m, k, _ptr(out))
+    return out
+
+
+def bloom_build(feat_offsets, feat_ids, m: int, k: int) -> np.ndarray:
+    """Item-major signatures, shape [n_items, ceil(m/64)] uint64."""
+    off = _arr(feat_offsets, np.int64)
+    ids = _arr(feat_ids, np.uint64)
+    n = off.size - 1
+    sigs = np.zeros((n, sig_words(m)), dtype=np.uint64)
+    lib().sto_bloom_build(_ptr(off), _ptr(ids), n, m, k, _ptr(sigs))
+    return sigs
+
+
+def bloom_mask(sigs: np.ndarray, m: int, k: int, filt_ids) -> np.ndarray:
+    """1 bit per item, ceil(N/64) uint64 words, LSB first."""
+    n = sigs.shape[0]
+    f = _arr(filt_ids, np.uint64)
+    mask = np.zeros((n + 63) // 64, dtype=np.uint64)
+    lib().sto_bloom_mask(_ptr(sigs), n, m, k, _ptr(f), f.size, _ptr(mask))
+    return mask
+
+
+def exact_mask(feat_offsets, feat_ids, filt_ids) -> np.ndarray:
+    off = _arr(feat_offsets, np.int64)
+    ids = _arr(feat_ids, np.uint64)
+    f = _arr(filt_ids, np.uint64)
+    n = off.size - 1
+    mask = np.zeros((n + 63) // 64, dtype=np.uint64)
+    lib().sto_exact_mask(_ptr(off), _ptr(ids), n, _ptr(f), f.size, _ptr(mask))
+    return mask
+
+
+def mask_to_bool(mask: np.ndarray, n: int) -> np.ndarray:
+    bits = np.unpackbits(mask.view(np.uint8), bitorder="little")
+    return bits[:n].astype(bool)
+
+
+def dot(q, e) -> int:
+    q = _arr(q, np.int8)
+    e = _arr(e, np.int8)
+    return int(lib().sto_dot(_ptr(q), _ptr(e), q.size))
+
+
+def rescale(d: int, s_q: float, s_i: float) -> np.float32:
+    return np.float32(lib().sto_rescale(int(d), C.c_float(s_q), C.c_float(s_i)))
+
+
+def search(sigs, m, k, items, item_scale, queries, query_scale, filt_ids, filt_offsets, K,
+           task_weight=None):
+    """Filtered top-K.  queries [B,d] (task_weight None) or [B,T,d].
+    Returns (ids int64 [B,K], scores float32 [B,K], count int32 [B])."""
+    items = _arr(items, np.int8)
+    item_scale = _arr(item_scale, np.float32)
+    queries = _arr(queries, np.int8)
+    query_scale = _arr(query_scale, np.float32)
+    fid = _arr(filt_ids, np.uint64)
+    foff = _arr(filt_offsets, np.int64)
+    n, d = items.shape
+    if task_weight is None:
+        assert queries.ndim == 2 and queries.shape[1] == d
+        B, T, w = queries.shape[0], 1, None
+    else:
+        assert queries.ndim == 3 and queries.shape[2] == d
+        B, T = queries.shape[0], queries.shape[1]
+        w = _arr(task_weight, np.float32)
+        assert w.size == T
+    assert query_scale.size == B * T and foff.size == B + 1 and sigs.shape[0] == n
+    ids = np.empty((B, K), dtype=np.int64)
+    scores = np.empty((B, K), dtype=np.float32)
+    count = np.empty(B, dtype=np.int32)
+    sigs = _arr(sigs, np.uint64)
+    rc = lib().sto_search(_ptr(sigs), n, m, k, _ptr(items), _ptr(item_scale), d, _ptr(queries),
+                          _ptr(query_scale), B, T, _ptr(w), _ptr(fid), _ptr(foff), K,
+                          _ptr(ids), _ptr(scores), _ptr(count))
+    if rc != 0:
+        raise MemoryError("oracle ran out of memory")
+    return ids, scores, count
+
+
+def num_threads() -> int:
+    return int(lib().sto_num_threads())
