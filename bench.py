@@ -1,0 +1,216 @@
+#!/usr/bin/env python3
+"""Benchmark of the filtered int8 top-K hot path on one MI355X.
+
+One "step" is one pass of the whole path -- Bloom test, compaction, int8 scoring, rescale,
+(multi-task aggregation,) per-workgroup candidate admission, selection/merge -- over one batch
+of synthetic queries against the resident corpus.  Inputs are generated on the GPU and are
+resident in HBM before the timed region starts.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mid|tiny|large|multi|mfma]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+INT8_MFMA_PEAK_TOPS = 5000.0  # dense int8 MFMA, published
+
+
+def union_and_rows(st, bloom, w):
+    """Algorithmic-byte ingredients: signature rows each distinct filter touches, fraction of
+    items passing at least one filter of the batch, passing pairs per query."""
+    import torch
+    fo = w.filt_offsets
+    seen, filt = {}, []
+    for b in range(w.cfg.batch):
+        key = tuple(sorted(set(int(x) for x in w.filt_ids[fo[b]:fo[b + 1]])))
+        if key not in seen:
+            seen[key] = len(filt)
+            filt.append(key)
+    fid = np.array([x for f in filt for x in f], dtype=np.uint64)
+    foff = np.concatenate([[0], np.cumsum([len(f) for f in filt])]).astype(np.int64)
+    masks = st.st_bloom_mask(bloom, fid, foff)
+    torch.cuda.synchronize()
+
+    def popcount(t):
+        return int(torch.from_numpy(np.unpackbits(t.cpu().numpy().view(np.uint8))).sum())
+
+    union = masks[0].clone()
+    for j in range(1, masks.shape[0]):
+        union |= masks[j]
+    per_filter = [popcount(masks[j]) for j in range(masks.shape[0])]
+    rows = 0
+    m, k = w.cfg.m_bits, w.cfg.k_hashes
+    # signature rows a filter touches: k per term (an upper bound that is exact unless two of
+    # a filter's k * terms hashes collide, which costs at most one 128-byte line per tile)
+    for f in filt:
+        rows += k * len(f)
+    passing_pairs = 0
+    for b in range(w.cfg.batch):
+        key = tuple(sorted(set(int(x) for x in w.filt_ids[fo[b]:fo[b + 1]])))
+        passing_pairs += per_filter[seen[key]]
+    return {"distinct_filters": len(filt), "rows_touched": rows, "union_items": popcount(union),
+            "passing_pairs": passing_pairs, "per_filter_sel": [p / max(w.cfg.n_items, 1) for p in per_filter]}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=50)
+    ap.add_argument("--config", default="mid")
+    ap.add_argument("--path", type=int, default=0, help="0 auto, 1 wavefront dot, 2 MFMA")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
+              "--gpus above 1 is not supported", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2511_14881_amd import binding as st
+    from paper_2511_14881_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    st.lib()  # fail loudly if the HIP library is missing
+    cfg = synth.CONFIGS[args.config]
+    t0 = time.time()
+    w = synth.make_workload(cfg, device="cuda")
+    torch.cuda.synchronize()
+    gen_s = time.time() - t0
+    T = max(cfg.n_tasks, 1)
+
+    t0 = time.time()
+    bloom = st.st_bloom_build(w.feat_offsets, w.feat_ids, cfg.n_items, cfg.m_bits, cfg.k_hashes)
+    torch.cuda.synchronize()
+    build_s = time.time() - t0
+    buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, T, cfg.top_k)
+    st.st_set_scoring_path(args.path)
+
+    def step():
+        if cfg.n_tasks > 0:
+            st.st_search_multitask(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.task_weight,
+                                   w.filt_ids, w.filt_offsets, cfg.top_k, buffers=buf)
+        else:
+            st.st_search(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.filt_ids,
+                         w.filt_offsets, cfg.top_k, buffers=buf)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = elapsed * 1e3 / args.steps
+
+    # per-kernel durations, HIP events on the launch stream around every kernel of K more steps
+    levels, groups, cap = st.st_search_plan(cfg.n_items, cfg.batch, cfg.top_k)
+    st.st_timing_begin(args.steps * (2 * len(levels) + 1) + 8)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    timing = st.st_timing_end()
+    scan_ms, scan_n = timing["scan"]
+    scan_ms_per_step = scan_ms / args.steps
+
+    stats = union_and_rows(st, bloom, w)
+    n_words = (cfg.n_items + 63) // 64
+    a_bytes = (stats["rows_touched"] * n_words * 8 + stats["union_items"] * (cfg.d + 4)
+               + cfg.batch * T * cfg.d + cfg.batch * cfg.top_k * 12)
+    a_ops = 2.0 * cfg.d * T * stats["passing_pairs"]
+    stream_all = cfg.n_items * (cfg.d + 4) + cfg.n_items * cfg.m_bits // 8
+    achieved_gbs = a_bytes / (scan_ms_per_step * 1e-3) / 1e9 if scan_ms_per_step > 0 else 0.0
+    achieved_tops = a_ops / (scan_ms_per_step * 1e-3) / 1e12 if scan_ms_per_step > 0 else 0.0
+    mfma_bound = args.config == "mfma"
+
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.config)
+        except Exception:
+            traffic = None
+
+    if mfma_bound:
+        roofline = {"bound": "mfma", "achieved": achieved_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
+                    "frac": achieved_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic}
+    else:
+        roofline = {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": traffic}
+    roofline.update({
+        "kernel": "scan", "kernel_ms_per_step": scan_ms_per_step, "kernel_launches_per_step": scan_n / args.steps,
+        "algorithmic_bytes_per_step": a_bytes, "stream_all_bytes_per_step": stream_all,
+        "stream_all_GBs": stream_all / (scan_ms_per_step * 1e-3) / 1e9 if scan_ms_per_step > 0 else 0.0,
+        "algorithmic_ops_per_step": a_ops,
+        "select_ms_per_step": timing["select"][0] / args.steps,
+        "rescue_ms_per_step": timing["rescue"][0] / args.steps,
+    })
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import st_oracle as O
+        # bounded sample of the same workload: a prefix of the corpus and of the batch
+        n_s = min(cfg.n_items, 1_000_000)
+        b_s = min(cfg.batch, 64)
+        items = w.items[:n_s].cpu().numpy()
+        isc = w.item_scale[:n_s].cpu().numpy()
+        off = w.feat_offsets[: n_s + 1].cpu().numpy()
+        ids = w.feat_ids[: int(off[-1])].cpu().numpy().view(np.uint64)
+        q = w.queries[:b_s].cpu().numpy()
+        qs = w.query_scale[:b_s].cpu().numpy()
+        fo = w.filt_offsets[: b_s + 1]
+        fi = w.filt_ids[: int(fo[-1])]
+        sigs = O.bloom_build(off, ids, cfg.m_bits, cfg.k_hashes)
+        reps, spent = 0, 0.0
+        while spent < args.cpu_seconds and reps < 1000:
+            t0 = time.perf_counter()
+            O.search(sigs, cfg.m_bits, cfg.k_hashes, items, isc, q, qs, fi, fo, cfg.top_k,
+                     task_weight=w.task_weight)
+            spent += time.perf_counter() - t0
+            reps += 1
+        per_batch = spent / reps
+        # queries/s on the sample corpus, scaled to the full corpus size (work is linear in N)
+        qps = b_s / per_batch * (n_s / cfg.n_items)
+        cpu = {"value": qps, "unit": "queries/s", "cores": O.num_threads(), "kind": "oracle",
+               "sample": f"{b_s} queries x first {n_s} items, {reps} repetitions, {spent:.1f} s; "
+                         f"scaled by {n_s}/{cfg.n_items} to the full corpus"}
+
+    qps = cfg.batch / (ms_per_step * 1e-3)
+    out = {
+        "metric": "filtered int8 top-K queries/sec", "value": qps, "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
+        "data": "synthetic",
+        "config": {"workload": cfg.name, "n_items": cfg.n_items, "d": cfg.d, "batch": cfg.batch,
+                   "n_tasks": cfg.n_tasks, "m_bits": cfg.m_bits, "k_hashes": cfg.k_hashes,
+                   "filter_terms": cfg.n_terms, "top_k": cfg.top_k, "levels": len(levels),
+                   "scoring_path": args.path, "distinct_filters": stats["distinct_filters"],
+                   "union_selectivity": stats["union_items"] / max(cfg.n_items, 1),
+                   "mean_filter_selectivity": float(np.mean(stats["per_filter_sel"]))},
+        "items_scanned_per_s": cfg.n_items / (ms_per_step * 1e-3),
+        "item_query_pairs_per_s": cfg.n_items * cfg.batch / (ms_per_step * 1e-3),
+        "bloom_build_items_per_s": cfg.n_items / build_s if build_s > 0 else None,
+        "gen_seconds": gen_s,
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,176 @@
+/*
+ * silvertorch.h -- C ABI of the MI355X (gfx950) filtered int8 top-K retrieval library.
+ *
+ * The library implements the retrieval hot path of the SilverTorch paper on one GPU:
+ * a per-item Bloom signature index used as a feature filter (Sec. 4.1), int8 dot-product
+ * scoring with int32 accumulation that streams item rows straight from the embedding
+ * table (Sec. 4.2), scoring only the items whose filter bit is 1 and selecting the global
+ * top-K (Sec. 4.3, Algorithm 1 phases 3-4 with every item in scope, i.e. brute force), and
+ * the weighted-sum Value Model over per-task scores (Sec. 5.2).
+ *
+ * Conventions for every entry point
+ *   - returns ST_OK (0) or a negative st_status; never throws, never aborts.  After a
+ *     failure st_last_error() (thread local) describes it.
+ *   - "dev_" pointers are device memory on the current HIP device, "host_" pointers are
+ *     host memory; the caller owns every buffer it passes and keeps it alive until the
+ *     stream has finished the enqueued work.
+ *   - hip_stream is a hipStream_t passed as void* (NULL = the default stream).  Work is
+ *     enqueued asynchronously; outputs are valid once the stream has synchronised.
+ *   - the search entry points allocate no device memory: the caller passes a workspace of
+ *     at least st_search_workspace_bytes() bytes, 256-byte aligned.
+ *
+ * Numerical contract (checked bit for bit against the CPU oracle)
+ *   hash       h_j(f) = splitmix64(f XOR j) mod m_bits, j = 0 .. k_hashes-1
+ *   pass_i     (QB & VB_i) == QB                                   Eq. 4
+ *   dot        sum_c (int32)q[c] * (int32)e_i[c]                   int32, cannot overflow for d <= 65536/4
+ *   score      ((float)dot * s_q) * s_i                            two rounded fp32 multiplies
+ *   aggregate  agg = fmaf(w[t], score_t, agg), t ascending from +0.0f
+ *   order      score descending, ties by lower item id
+ */
+#ifndef SILVERTORCH_H
+#define SILVERTORCH_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum st_status {
+    ST_OK = 0,
+    ST_EINVAL = -1,     /* bad argument (null pointer, size out of range, misaligned buffer) */
+    ST_ENOMEM = -2,     /* host or device allocation failed */
+    ST_EHIP = -3,       /* a HIP runtime call failed; st_last_error() has hipGetErrorString */
+    ST_EWORKSPACE = -4  /* workspace smaller than st_search_workspace_bytes() */
+} st_status;
+
+/* limits (arguments outside them give ST_EINVAL) */
+#define ST_MAX_M_BITS 65536     /* Bloom bits per item */
+#define ST_MAX_K_HASHES 16
+#define ST_MAX_FILTER_BITS 64   /* distinct signature bits one query's filter may set (<= k * terms) */
+#define ST_MAX_BATCH 4096
+#define ST_MAX_TASKS 8
+#define ST_MAX_TOP_K 16384
+#define ST_MAX_DIM 4096         /* d, a multiple of 16 */
+
+/* Thread-local text of the last failure in the calling thread ("" if none). */
+const char* st_last_error(void);
+
+/* Library version, major*10000 + minor*100 + patch. */
+int32_t st_version(void);
+
+/* ------------------------------------------------------------------ Bloom index
+ * Opaque handle owning the device-resident index: for every item an m_bits-bit Bloom
+ * filter over its feature ids (Sec. 4.1).  Stored bit-sliced ("rotated", Sec. 4.1):
+ * one row per signature bit, 64 items per 64-bit word, blocked in tiles of 1024 items so
+ * that one row segment of a tile is one 128-byte line. */
+typedef struct st_bloom st_bloom;
+
+/* Builds the index.  The items' feature lists arrive as CSR (the forward-index shape of
+ * Sec. 4.1): feat_offsets[n_items+1] (non-decreasing, feat_offsets[0] == 0) and
+ * feat_ids[feat_offsets[n_items]].  Both arrays may be host or device memory (detected).
+ * Duplicate ids in a list are harmless; an empty list gives the zero signature.
+ * 1 <= m_bits <= ST_MAX_M_BITS (any value, not only powers of two), 1 <= k_hashes <=
+ * ST_MAX_K_HASHES, 0 <= n_items < 2^31.  Synchronises hip_stream before returning.
+ * On success *out receives a handle to be released with st_bloom_free. */
+int st_bloom_build(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_t n_items,
+                   int32_t m_bits, int32_t k_hashes, void* hip_stream, st_bloom** out);
+
+/* Frees the handle and its device memory (NULL is allowed). */
+int st_bloom_free(st_bloom* bloom);
+
+/* Device bytes of the index: n_items*m_bits/8 rounded up to whole 1024-item tiles (the
+ * paper's N*M/8 accounting, Sec. 6.2.2).  st_bloom_layout_bytes is the same figure from
+ * the sizes alone and touches no GPU.  Negative st_status on bad arguments. */
+int64_t st_bloom_bytes(const st_bloom* bloom);
+int64_t st_bloom_layout_bytes(int64_t n_items, int32_t m_bits);
+int64_t st_bloom_n_items(const st_bloom* bloom);
+
+/* Parity/debug export, not on the timed path: item-major signatures,
+ * dev_out[n_items][ceil(m_bits/64)], bit b of item i in word b/64 at position b%64. */
+int st_bloom_export_signatures(const st_bloom* bloom, uint64_t* dev_out, void* hip_stream);
+
+/* Parity/debug export of the Bloom test (Eq. 4) as 1 bit per item (Sec. 4.3):
+ * dev_mask[n_filters][ceil(n_items/64)], bit (i%64) of word i/64 is pass_i, bits at or
+ * past n_items are 0.  Filter f is the conjunction of
+ * host_filt_ids[host_filt_offsets[f] .. host_filt_offsets[f+1]); empty = every item passes. */
+int st_bloom_mask(const st_bloom* bloom, const uint64_t* host_filt_ids,
+                  const int64_t* host_filt_offsets, int32_t n_filters, uint64_t* dev_mask,
+                  void* hip_stream);
+
+/* ------------------------------------------------------------------ search
+ * Bytes of device workspace st_search / st_search_multitask need for these sizes
+ * (n_tasks = 1 for st_search).  Pure host arithmetic.  Negative st_status on bad sizes. */
+int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks,
+                                  int32_t K);
+
+/* Filtered top-K for a batch of queries (Algorithm 1, phases 3-4, all items in scope).
+ *   bloom            index built over the same n_items items
+ *   dev_items        [n_items, d] int8 row-major, 16-byte aligned; d % 16 == 0, d <= ST_MAX_DIM
+ *   dev_item_scale   [n_items] fp32, finite and > 0
+ *   dev_queries      [batch, d] int8;  dev_query_scale [batch] fp32, finite and > 0
+ *   host_filt_ids / host_filt_offsets[batch+1]
+ *                    query b keeps item i iff i passes the Bloom test for the conjunction of
+ *                    ids [offsets[b], offsets[b+1]); an empty range keeps every item.  A
+ *                    filter may set at most ST_MAX_FILTER_BITS distinct signature bits.
+ *   K                1 <= K <= ST_MAX_TOP_K
+ *   dev_out_ids      [batch, K] int64, dev_out_scores [batch, K] fp32, dev_out_count [batch]
+ *                    int32: the min(K, #passing) best items by (score desc, id asc); rows past
+ *                    count are id = -1, score = -inf.
+ *   dev_workspace    >= st_search_workspace_bytes(...) bytes, 256-byte aligned; contents are
+ *                    scratch.  Concurrent searches need distinct workspaces.
+ * The host filter arrays are consumed before the call returns. */
+int st_search(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
+              int64_t n_items, int32_t d, const int8_t* dev_queries, const float* dev_query_scale,
+              int32_t batch, const uint64_t* host_filt_ids, const int64_t* host_filt_offsets,
+              int32_t K, int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
+              void* dev_workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* Multi-task variant (Sec. 5.2): one embedding per task and query, item embeddings shared,
+ * one result list per query on the Value Model's weighted sum of the per-task scores.
+ *   dev_queries [batch, n_tasks, d], dev_query_scale [batch, n_tasks],
+ *   host_task_weight [n_tasks] fp32 (finite), 1 <= n_tasks <= ST_MAX_TASKS.
+ * score_t as in st_search; agg = fmaf(w[t], score_t, agg) for t = 0 .. n_tasks-1 from +0.0f;
+ * ranking and outputs are on agg.  Everything else as st_search. */
+int st_search_multitask(const st_bloom* bloom, const int8_t* dev_items,
+                        const float* dev_item_scale, int64_t n_items, int32_t d,
+                        const int8_t* dev_queries, const float* dev_query_scale, int32_t batch,
+                        int32_t n_tasks, const float* host_task_weight,
+                        const uint64_t* host_filt_ids, const int64_t* host_filt_offsets,
+                        int32_t K, int64_t* dev_out_ids, float* dev_out_scores,
+                        int32_t* dev_out_count, void* dev_workspace, int64_t workspace_bytes,
+                        void* hip_stream);
+
+/* Parity/debug export of the scoring arithmetic for chosen (query, item) pairs (Sec. 4.2):
+ * dev_out_dot[p] = int32 dot of query dev_pair_query[p] (a row of dev_queries [*, d]) and item
+ * dev_pair_item[p]; dev_out_score[p] = ((float)dot * s_q) * s_i.  Either output may be NULL. */
+int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t d,
+                   const int8_t* dev_queries, const float* dev_query_scale,
+                   const int64_t* dev_pair_item, const int32_t* dev_pair_query, int64_t n_pairs,
+                   int32_t* dev_out_dot, float* dev_out_score, void* hip_stream);
+
+/* Host-side description of how a search of these sizes is scheduled (pure arithmetic, no
+ * GPU): writes up to max_levels rows of 3 int64 {item_begin, item_end, segment_items} and
+ * returns the number of levels, or a negative st_status.  The corpus is scanned once, in
+ * consecutive chunks ("levels"); after each chunk the running top-K and its K-th key become
+ * the admission threshold of the next.  out_caps receives {workgroups, region_capacity}. */
+int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int64_t* out_levels,
+                       int32_t max_levels, int64_t* out_caps);
+
+/* Search scheduling knobs, mainly for tests: path = 0 auto, 1 force the wavefront
+ * dot-product scorer, 2 force the int8 MFMA scorer where it applies.  Returns the old value. */
+int32_t st_set_scoring_path(int32_t path);
+
+/* Per-kernel timing for benchmarks.  Between st_timing_begin and st_timing_end every kernel the
+ * search entry points launch is bracketed by two HIP events recorded on the caller's stream
+ * (up to max_launches launches; not thread safe, one measuring thread at a time).
+ * st_timing_end waits for the recorded events and returns, per kernel kind (0 = scan,
+ * 1 = select, 2 = slow exact path), the summed elapsed milliseconds in host_out_ms[3] and the
+ * number of launches in host_out_launches[3]. */
+int st_timing_begin(int32_t max_launches);
+int st_timing_end(double* host_out_ms, int64_t* host_out_launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SILVERTORCH_H */

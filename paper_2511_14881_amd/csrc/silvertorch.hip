@@ -1,0 +1,613 @@
+// C ABI of the filtered int8 top-K library (see include/silvertorch.h for the contract).
+// Host logic only: argument checks, filter grouping, scheduling, launches.  Every step of the
+// hot path itself runs in the kernels of st_*_kernels.h.
+#include "../../include/silvertorch.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <map>
+#include <mutex>
+#include <new>
+#include <vector>
+
+#include "st_bloom_kernels.h"
+#include "st_mfma_kernels.h"
+#include "st_plan.h"
+#include "st_search_kernels.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char* fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+#define ST_HIP(call)                                                                       \
+    do {                                                                                   \
+        hipError_t e_ = (call);                                                            \
+        if (e_ != hipSuccess)                                                              \
+            return fail(e_ == hipErrorOutOfMemory ? ST_ENOMEM : ST_EHIP,                   \
+                        "%s failed: %s (%s:%d)", #call, hipGetErrorString(e_), __FILE__,   \
+                        __LINE__);                                                         \
+    } while (0)
+
+int g_scoring_path = 0;  // 0 auto, 1 wavefront dot product, 2 MFMA where it applies
+
+// Optional per-kernel timing with HIP events recorded on the caller's stream around each launch.
+struct Timing {
+    bool on = false;
+    std::vector<hipEvent_t> ev;  // pairs: [2i] before, [2i+1] after launch i
+    std::vector<int> kind;       // 0 scan, 1 select, 2 rescue
+    size_t used = 0;             // launches recorded
+    size_t dropped = 0;
+};
+Timing g_timing;
+
+struct TimedLaunch {
+    hipStream_t stream;
+    bool active;
+    size_t slot;
+    TimedLaunch(int kind, hipStream_t s) : stream(s), active(false), slot(0)
+    {
+        if (!g_timing.on) return;
+        if (2 * (g_timing.used + 1) > g_timing.ev.size()) { ++g_timing.dropped; return; }
+        slot = g_timing.used++;
+        g_timing.kind[slot] = kind;
+        active = hipEventRecord(g_timing.ev[2 * slot], stream) == hipSuccess;
+    }
+    ~TimedLaunch()
+    {
+        if (active) (void)hipEventRecord(g_timing.ev[2 * slot + 1], stream);
+    }
+};
+
+// Pinned staging slots for the per-call group tables: the copy to the device is asynchronous,
+// so a slot is reused only after the event recorded behind its copy has completed.
+struct Stage {
+    void* host = nullptr;
+    size_t bytes = 0;
+    hipEvent_t ev = nullptr;
+    bool in_flight = false;
+};
+constexpr int kStages = 16;
+Stage g_stage[kStages];
+int g_stage_next = 0;
+std::mutex g_stage_mu;
+
+int stage_acquire(size_t bytes, Stage** out)
+{
+    std::lock_guard<std::mutex> lock(g_stage_mu);
+    Stage& s = g_stage[g_stage_next];
+    g_stage_next = (g_stage_next + 1) % kStages;
+    if (!s.ev) ST_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
+    if (s.in_flight) {
+        ST_HIP(hipEventSynchronize(s.ev));
+        s.in_flight = false;
+    }
+    if (s.bytes < bytes) {
+        if (s.host) ST_HIP(hipHostFree(s.host));
+        s.host = nullptr;
+        s.bytes = 0;
+        const size_t want = std::max<size_t>(bytes, 64 * 1024);
+        ST_HIP(hipHostMalloc(&s.host, want, hipHostMallocDefault));
+        s.bytes = want;
+    }
+    *out = &s;
+    return ST_OK;
+}
+
+bool is_device_pointer(const void* p)
+{
+    hipPointerAttribute_t attr;
+    hipError_t e = hipPointerGetAttributes(&attr, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();  // plain host memory reports an error: clear it
+        return false;
+    }
+    return attr.type == hipMemoryTypeDevice || attr.type == hipMemoryTypeManaged;
+}
+
+// Distinct filters of a batch, as sorted lists of signature rows (Eq. 4: the bits QB sets).
+struct Groups {
+    std::vector<int32_t> row_off, rows, q_off, q_list, q2grp;
+    int32_t n_groups = 0;
+};
+
+int build_groups(const uint64_t* filt_ids, const int64_t* filt_off, int32_t n, int32_t m_bits,
+                 int32_t k_hashes, Groups* out)
+{
+    std::map<std::vector<int32_t>, int32_t> index;
+    std::vector<std::vector<int32_t>> keys;
+    std::vector<std::vector<int32_t>> members;
+    out->q2grp.assign(n, 0);
+    for (int32_t b = 0; b < n; ++b) {
+        if (filt_off[b + 1] < filt_off[b]) return fail(ST_EINVAL, "filter offsets decrease at query %d", b);
+        std::vector<int32_t> rows;
+        for (int64_t a = filt_off[b]; a < filt_off[b + 1]; ++a)
+            for (int j = 0; j < k_hashes; ++j)
+                rows.push_back((int32_t)st::bloom_bit(filt_ids[a], j, (uint32_t)m_bits));
+        std::sort(rows.begin(), rows.end());
+        rows.erase(std::unique(rows.begin(), rows.end()), rows.end());
+        if (rows.size() > ST_MAX_FILTER_BITS)
+            return fail(ST_EINVAL, "filter of query %d sets %zu signature bits (limit %d)", b, rows.size(),
+                        ST_MAX_FILTER_BITS);
+        auto it = index.find(rows);
+        int32_t g;
+        if (it == index.end()) {
+            g = (int32_t)keys.size();
+            index.emplace(rows, g);
+            keys.push_back(rows);
+            members.emplace_back();
+        } else {
+            g = it->second;
+        }
+        members[g].push_back(b);
+        out->q2grp[b] = g;
+    }
+    out->n_groups = (int32_t)keys.size();
+    out->row_off.assign(1, 0);
+    out->q_off.assign(1, 0);
+    out->rows.clear();
+    out->q_list.clear();
+    for (int32_t g = 0; g < out->n_groups; ++g) {
+        out->rows.insert(out->rows.end(), keys[g].begin(), keys[g].end());
+        out->row_off.push_back((int32_t)out->rows.size());
+        out->q_list.insert(out->q_list.end(), members[g].begin(), members[g].end());
+        out->q_off.push_back((int32_t)out->q_list.size());
+    }
+    return ST_OK;
+}
+
+// Packs the group tables into one blob; offsets (in bytes) of each table go to `at`.
+struct MetaAt { size_t row_off, rows, q_off, q_list, q2grp, total; };
+
+MetaAt meta_offsets(const Groups& g)
+{
+    MetaAt at;
+    size_t off = 0;
+    auto take = [&](size_t n_int) { size_t o = off; off += (n_int * 4 + 15) / 16 * 16; return o; };
+    at.row_off = take(g.row_off.size());
+    at.rows = take(g.rows.size() + 1);
+    at.q_off = take(g.q_off.size());
+    at.q_list = take(g.q_list.size() + 1);
+    at.q2grp = take(g.q2grp.size() + 1);
+    at.total = off;
+    return at;
+}
+
+void meta_pack(const Groups& g, const MetaAt& at, char* dst)
+{
+    memcpy(dst + at.row_off, g.row_off.data(), g.row_off.size() * 4);
+    if (!g.rows.empty()) memcpy(dst + at.rows, g.rows.data(), g.rows.size() * 4);
+    memcpy(dst + at.q_off, g.q_off.data(), g.q_off.size() * 4);
+    if (!g.q_list.empty()) memcpy(dst + at.q_list, g.q_list.data(), g.q_list.size() * 4);
+    if (!g.q2grp.empty()) memcpy(dst + at.q2grp, g.q2grp.data(), g.q2grp.size() * 4);
+}
+
+}  // namespace
+
+struct st_bloom {
+    uint64_t* dev = nullptr;
+    int64_t n_items = 0;
+    int64_t n_tiles = 0;
+    int32_t m_bits = 0;
+    int32_t k_hashes = 0;
+    int64_t bytes = 0;
+    int device = 0;
+};
+
+extern "C" {
+
+const char* st_last_error(void) { return g_err; }
+
+int32_t st_version(void) { return 100; }
+
+int32_t st_set_scoring_path(int32_t path)
+{
+    int32_t old = g_scoring_path;
+    if (path >= 0 && path <= 2) g_scoring_path = path;
+    return old;
+}
+
+int st_timing_begin(int32_t max_launches)
+{
+    if (max_launches < 1 || max_launches > (1 << 20)) return fail(ST_EINVAL, "max_launches out of range");
+    while (g_timing.ev.size() < 2 * (size_t)max_launches) {
+        hipEvent_t e;
+        ST_HIP(hipEventCreate(&e));
+        g_timing.ev.push_back(e);
+    }
+    g_timing.kind.assign(g_timing.ev.size() / 2, 0);
+    g_timing.used = 0;
+    g_timing.dropped = 0;
+    g_timing.on = true;
+    return ST_OK;
+}
+
+int st_timing_end(double* out_ms, int64_t* out_launches)
+{
+    if (!out_ms || !out_launches) return fail(ST_EINVAL, "null argument");
+    g_timing.on = false;
+    for (int k = 0; k < 3; ++k) { out_ms[k] = 0.0; out_launches[k] = 0; }
+    for (size_t i = 0; i < g_timing.used; ++i) {
+        ST_HIP(hipEventSynchronize(g_timing.ev[2 * i + 1]));
+        float ms = 0.f;
+        ST_HIP(hipEventElapsedTime(&ms, g_timing.ev[2 * i], g_timing.ev[2 * i + 1]));
+        out_ms[g_timing.kind[i]] += ms;
+        out_launches[g_timing.kind[i]] += 1;
+    }
+    if (g_timing.dropped) return fail(ST_EINVAL, "%zu launches were not timed (raise max_launches)", g_timing.dropped);
+    return ST_OK;
+}
+
+int64_t st_bloom_layout_bytes(int64_t n_items, int32_t m_bits)
+{
+    if (n_items < 0 || n_items >= (1LL << 31) || m_bits < 1 || m_bits > ST_MAX_M_BITS)
+        return fail(ST_EINVAL, "bad sizes: n_items=%lld m_bits=%d", (long long)n_items, m_bits);
+    const int64_t tiles = (n_items + st::kTileItems - 1) / st::kTileItems;
+    return tiles * (int64_t)m_bits * st::kTileWords * 8;
+}
+
+int st_bloom_build(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_t n_items,
+                   int32_t m_bits, int32_t k_hashes, void* hip_stream, st_bloom** out)
+{
+    if (!out) return fail(ST_EINVAL, "out is null");
+    *out = nullptr;
+    if (!feat_offsets) return fail(ST_EINVAL, "feat_offsets is null");
+    if (n_items < 0 || n_items >= (1LL << 31)) return fail(ST_EINVAL, "n_items=%lld out of range", (long long)n_items);
+    if (m_bits < 1 || m_bits > ST_MAX_M_BITS) return fail(ST_EINVAL, "m_bits=%d out of range", m_bits);
+    if (k_hashes < 1 || k_hashes > ST_MAX_K_HASHES) return fail(ST_EINVAL, "k_hashes=%d out of range", k_hashes);
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    st_bloom* b = new (std::nothrow) st_bloom;
+    if (!b) return fail(ST_ENOMEM, "out of host memory");
+    b->n_items = n_items;
+    b->m_bits = m_bits;
+    b->k_hashes = k_hashes;
+    b->n_tiles = (n_items + st::kTileItems - 1) / st::kTileItems;
+    b->bytes = st_bloom_layout_bytes(n_items, m_bits);
+    int rc = ST_OK;
+    int64_t* d_off = nullptr;
+    uint64_t* d_ids = nullptr;
+    auto body = [&]() -> int {
+        ST_HIP(hipGetDevice(&b->device));
+        if (b->bytes > 0) ST_HIP(hipMalloc((void**)&b->dev, (size_t)b->bytes));
+        if (n_items == 0) return ST_OK;
+        const int64_t* off = feat_offsets;
+        const uint64_t* ids = feat_ids;
+        int64_t nnz = 0;
+        if (is_device_pointer(feat_offsets)) {
+            ST_HIP(hipMemcpyAsync(&nnz, feat_offsets + n_items, 8, hipMemcpyDeviceToHost, stream));
+            ST_HIP(hipStreamSynchronize(stream));
+        } else {
+            if (feat_offsets[0] != 0) return fail(ST_EINVAL, "feat_offsets[0] must be 0");
+            for (int64_t i = 0; i < n_items; ++i)
+                if (feat_offsets[i + 1] < feat_offsets[i]) return fail(ST_EINVAL, "feat_offsets decrease at item %lld", (long long)i);
+            nnz = feat_offsets[n_items];
+            ST_HIP(hipMalloc((void**)&d_off, (size_t)(n_items + 1) * 8));
+            ST_HIP(hipMemcpyAsync(d_off, feat_offsets, (size_t)(n_items + 1) * 8, hipMemcpyHostToDevice, stream));
+            off = d_off;
+        }
+        if (nnz < 0) return fail(ST_EINVAL, "negative feature count");
+        if (nnz > 0 && !feat_ids) return fail(ST_EINVAL, "feat_ids is null");
+        if (nnz > 0 && !is_device_pointer(feat_ids)) {
+            ST_HIP(hipMalloc((void**)&d_ids, (size_t)nnz * 8));
+            ST_HIP(hipMemcpyAsync(d_ids, feat_ids, (size_t)nnz * 8, hipMemcpyHostToDevice, stream));
+            ids = d_ids;
+        }
+        const int64_t n_words = b->n_tiles * st::kTileWords;
+        const unsigned grid = (unsigned)((n_words + 3) / 4);
+        hipLaunchKernelGGL(st::bloom_build_kernel, dim3(grid), dim3(256), 0, stream, off, ids, n_items,
+                           m_bits, k_hashes, n_words, b->dev);
+        ST_HIP(hipGetLastError());
+        ST_HIP(hipStreamSynchronize(stream));
+        return ST_OK;
+    };
+    rc = body();
+    if (d_off) (void)hipFree(d_off);
+    if (d_ids) (void)hipFree(d_ids);
+    if (rc != ST_OK) {
+        if (b->dev) (void)hipFree(b->dev);
+        delete b;
+        return rc;
+    }
+    *out = b;
+    return ST_OK;
+}
+
+int st_bloom_free(st_bloom* bloom)
+{
+    if (!bloom) return ST_OK;
+    if (bloom->dev) ST_HIP(hipFree(bloom->dev));
+    delete bloom;
+    return ST_OK;
+}
+
+int64_t st_bloom_bytes(const st_bloom* bloom)
+{
+    if (!bloom) return fail(ST_EINVAL, "bloom is null");
+    return bloom->bytes;
+}
+
+int64_t st_bloom_n_items(const st_bloom* bloom)
+{
+    if (!bloom) return fail(ST_EINVAL, "bloom is null");
+    return bloom->n_items;
+}
+
+int st_bloom_export_signatures(const st_bloom* bloom, uint64_t* dev_out, void* hip_stream)
+{
+    if (!bloom || !dev_out) return fail(ST_EINVAL, "null argument");
+    if (bloom->n_items == 0) return ST_OK;
+    const unsigned grid = (unsigned)((bloom->n_items + 255) / 256);
+    hipLaunchKernelGGL(st::bloom_export_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream,
+                       bloom->dev, bloom->n_items, bloom->m_bits, dev_out);
+    ST_HIP(hipGetLastError());
+    return ST_OK;
+}
+
+int st_bloom_mask(const st_bloom* bloom, const uint64_t* host_filt_ids, const int64_t* host_filt_offsets,
+                  int32_t n_filters, uint64_t* dev_mask, void* hip_stream)
+{
+    if (!bloom || !host_filt_offsets || !dev_mask) return fail(ST_EINVAL, "null argument");
+    if (n_filters < 0 || n_filters > 65535) return fail(ST_EINVAL, "n_filters=%d out of range", n_filters);
+    if (host_filt_offsets[n_filters] > 0 && !host_filt_ids) return fail(ST_EINVAL, "host_filt_ids is null");
+    if (n_filters == 0 || bloom->n_items == 0) return ST_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    // one row list per filter, in order (no grouping: the export is per filter)
+    std::vector<int32_t> row_off(1, 0), rows;
+    for (int32_t f = 0; f < n_filters; ++f) {
+        if (host_filt_offsets[f + 1] < host_filt_offsets[f]) return fail(ST_EINVAL, "filter offsets decrease at %d", f);
+        std::vector<int32_t> r;
+        for (int64_t a = host_filt_offsets[f]; a < host_filt_offsets[f + 1]; ++a)
+            for (int j = 0; j < bloom->k_hashes; ++j)
+                r.push_back((int32_t)st::bloom_bit(host_filt_ids[a], j, (uint32_t)bloom->m_bits));
+        std::sort(r.begin(), r.end());
+        r.erase(std::unique(r.begin(), r.end()), r.end());
+        rows.insert(rows.end(), r.begin(), r.end());
+        row_off.push_back((int32_t)rows.size());
+    }
+    rows.push_back(0);
+    int32_t* d_tab = nullptr;
+    const size_t n_int = row_off.size() + rows.size();
+    ST_HIP(hipMalloc((void**)&d_tab, n_int * 4));
+    int rc = ST_OK;
+    auto body = [&]() -> int {
+        ST_HIP(hipMemcpyAsync(d_tab, row_off.data(), row_off.size() * 4, hipMemcpyHostToDevice, stream));
+        ST_HIP(hipMemcpyAsync(d_tab + row_off.size(), rows.data(), rows.size() * 4, hipMemcpyHostToDevice, stream));
+        const int64_t n_words = (bloom->n_items + 63) / 64;
+        dim3 grid((unsigned)((n_words + 255) / 256), (unsigned)n_filters);
+        hipLaunchKernelGGL(st::bloom_mask_kernel, grid, dim3(256), 0, stream, bloom->dev, bloom->m_bits,
+                           bloom->n_items, n_words, d_tab, d_tab + row_off.size(), n_filters, dev_mask);
+        ST_HIP(hipGetLastError());
+        ST_HIP(hipStreamSynchronize(stream));
+        return ST_OK;
+    };
+    rc = body();
+    (void)hipFree(d_tab);
+    return rc;
+}
+
+int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int64_t* out_levels, int32_t max_levels,
+                       int64_t* out_caps)
+{
+    if (n_items < 0 || n_items >= (1LL << 31) || batch < 1 || batch > ST_MAX_BATCH || K < 1 || K > ST_MAX_TOP_K)
+        return fail(ST_EINVAL, "bad sizes");
+    st::Plan p;
+    if (st::make_plan(n_items, K, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (out_levels)
+        for (int i = 0; i < p.n_levels && i < max_levels; ++i) {
+            out_levels[3 * i + 0] = p.level[i].begin;
+            out_levels[3 * i + 1] = p.level[i].end;
+            out_levels[3 * i + 2] = p.level[i].seg_items;
+        }
+    if (out_caps) {
+        out_caps[0] = p.groups;
+        out_caps[1] = p.cap;
+    }
+    return p.n_levels;
+}
+
+int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K)
+{
+    if (n_items < 0 || n_items >= (1LL << 31)) return fail(ST_EINVAL, "n_items=%lld out of range", (long long)n_items);
+    if (d < 16 || d > ST_MAX_DIM || d % 16) return fail(ST_EINVAL, "d=%d must be a multiple of 16 in [16, %d]", d, ST_MAX_DIM);
+    if (batch < 1 || batch > ST_MAX_BATCH) return fail(ST_EINVAL, "batch=%d out of range", batch);
+    if (n_tasks < 1 || n_tasks > ST_MAX_TASKS) return fail(ST_EINVAL, "n_tasks=%d out of range", n_tasks);
+    if (K < 1 || K > ST_MAX_TOP_K) return fail(ST_EINVAL, "K=%d out of range", K);
+    st::Plan p;
+    if (st::make_plan(n_items, K, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    return (int64_t)st::make_layout(p, batch, K).total;
+}
+
+static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
+                       int64_t n_items, int32_t d, const int8_t* dev_queries, const float* dev_query_scale,
+                       int32_t batch, int32_t n_tasks, const float* host_task_weight,
+                       const uint64_t* host_filt_ids, const int64_t* host_filt_offsets, int32_t K,
+                       int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
+                       void* dev_workspace, int64_t workspace_bytes, void* hip_stream)
+{
+    if (!bloom) return fail(ST_EINVAL, "bloom is null");
+    if (!dev_queries || !dev_query_scale || !host_filt_offsets || !dev_out_ids || !dev_out_scores ||
+        !dev_out_count || !dev_workspace)
+        return fail(ST_EINVAL, "null argument");
+    if (n_items != bloom->n_items)
+        return fail(ST_EINVAL, "n_items=%lld but the index holds %lld", (long long)n_items, (long long)bloom->n_items);
+    if (n_items > 0 && (!dev_items || !dev_item_scale)) return fail(ST_EINVAL, "null corpus");
+    const int64_t need = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
+    if (need < 0) return (int)need;
+    if (workspace_bytes < need)
+        return fail(ST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
+    if (((uintptr_t)dev_workspace & 255) || ((uintptr_t)dev_items & 15) || ((uintptr_t)dev_queries & 15))
+        return fail(ST_EINVAL, "misaligned buffer (workspace 256 B, items and queries 16 B)");
+    if (host_filt_offsets[0] != 0) return fail(ST_EINVAL, "host_filt_offsets[0] must be 0");
+    if (host_filt_offsets[batch] > 0 && !host_filt_ids) return fail(ST_EINVAL, "host_filt_ids is null");
+    const bool weighted = host_task_weight != nullptr;
+    if (weighted)
+        for (int t = 0; t < n_tasks; ++t)
+            if (!std::isfinite(host_task_weight[t])) return fail(ST_EINVAL, "task weight %d is not finite", t);
+    hipStream_t stream = (hipStream_t)hip_stream;
+
+    Groups groups;
+    int rc = build_groups(host_filt_ids, host_filt_offsets, batch, bloom->m_bits, bloom->k_hashes, &groups);
+    if (rc != ST_OK) return rc;
+
+    st::Plan plan;
+    if (st::make_plan(n_items, K, &plan) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    const st::Layout L = st::make_layout(plan, batch, K);
+    const MetaAt at = meta_offsets(groups);
+    if (at.total > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
+
+    char* ws = (char*)dev_workspace;
+    Stage* stage = nullptr;
+    rc = stage_acquire(at.total, &stage);
+    if (rc != ST_OK) return rc;
+    meta_pack(groups, at, (char*)stage->host);
+    ST_HIP(hipMemcpyAsync(ws + L.meta, stage->host, at.total, hipMemcpyHostToDevice, stream));
+    ST_HIP(hipEventRecord(stage->ev, stream));
+    stage->in_flight = true;
+
+    st::ScanParams sp;
+    memset(&sp, 0, sizeof(sp));
+    sp.bloom = bloom->dev;
+    sp.m_bits = bloom->m_bits;
+    sp.items = dev_items;
+    sp.iscale = dev_item_scale;
+    sp.n_items = n_items;
+    sp.d = d;
+    sp.queries = dev_queries;
+    sp.qscale = dev_query_scale;
+    sp.batch = batch;
+    sp.n_tasks = n_tasks;
+    sp.weighted = weighted ? 1 : 0;
+    for (int t = 0; t < n_tasks && weighted; ++t) sp.w[t] = host_task_weight[t];
+    sp.n_groups = groups.n_groups;
+    sp.grp_row_off = (const int32_t*)(ws + L.meta + at.row_off);
+    sp.grp_rows = (const int32_t*)(ws + L.meta + at.rows);
+    sp.grp_q_off = (const int32_t*)(ws + L.meta + at.q_off);
+    sp.grp_q = (const int32_t*)(ws + L.meta + at.q_list);
+    sp.tau = (const uint64_t*)(ws + L.tau);
+    sp.cand = (uint64_t*)(ws + L.cand);
+    sp.cnt = (uint32_t*)(ws + L.cnt);
+    sp.ovf = (uint32_t*)(ws + L.ovf);
+    sp.cap = plan.cap;
+    sp.groups = plan.groups;
+
+    st::SelectParams se;
+    memset(&se, 0, sizeof(se));
+    se.cand = sp.cand;
+    se.cnt = sp.cnt;
+    se.cap = plan.cap;
+    se.groups = plan.groups;
+    se.topk_keys = (uint64_t*)(ws + L.topk_keys);
+    se.topk_cnt = (uint32_t*)(ws + L.topk_cnt);
+    se.gath = (uint64_t*)(ws + L.gath);
+    se.gath_cap = L.gath_cap;
+    se.srt = L.k_pad > st::kLdsSortMax ? (uint64_t*)(ws + L.srt) : nullptr;
+    se.K = K;
+    se.k_pad = L.k_pad;
+    se.tau = (uint64_t*)(ws + L.tau);
+    se.ovf = sp.ovf;
+    se.out_ids = dev_out_ids;
+    se.out_scores = dev_out_scores;
+    se.out_count = dev_out_count;
+
+    const st::MfmaChoice mfma = st::choose_mfma(g_scoring_path, d, n_tasks, weighted, batch, groups.n_groups);
+    for (int lv = 0; lv < plan.n_levels; ++lv) {
+        sp.item_begin = plan.level[lv].begin;
+        sp.item_end = plan.level[lv].end;
+        sp.seg_items = plan.level[lv].seg_items;
+        sp.use_tau = lv > 0;
+        {
+            TimedLaunch t(0, stream);
+            if (mfma.use)
+                st::launch_scan_mfma(sp, mfma, stream);
+            else
+                hipLaunchKernelGGL(st::scan_wavedot_kernel, dim3(plan.groups), dim3(st::kScanThreads),
+                                   (size_t)batch * 4, stream, sp);
+        }
+        ST_HIP(hipGetLastError());
+        se.first = lv == 0;
+        se.last = lv == plan.n_levels - 1;
+        {
+            TimedLaunch t(1, stream);
+            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(256), 0, stream, se);
+        }
+        ST_HIP(hipGetLastError());
+    }
+    if (plan.n_levels > 1) {
+        st::RescueParams rp;
+        memset(&rp, 0, sizeof(rp));
+        rp.scan = sp;
+        rp.q2grp = (const int32_t*)(ws + L.meta + at.q2grp);
+        rp.ovf = sp.ovf;
+        rp.gath = se.gath;
+        rp.gath_cap = L.gath_cap;
+        rp.srt = se.srt;
+        rp.K = K;
+        rp.k_pad = L.k_pad;
+        rp.out_ids = dev_out_ids;
+        rp.out_scores = dev_out_scores;
+        rp.out_count = dev_out_count;
+        {
+            TimedLaunch t(2, stream);
+            hipLaunchKernelGGL(st::rescue_kernel, dim3(batch), dim3(256), 0, stream, rp);
+        }
+        ST_HIP(hipGetLastError());
+    }
+    return ST_OK;
+}
+
+int st_search(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale, int64_t n_items,
+              int32_t d, const int8_t* dev_queries, const float* dev_query_scale, int32_t batch,
+              const uint64_t* host_filt_ids, const int64_t* host_filt_offsets, int32_t K,
+              int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count, void* dev_workspace,
+              int64_t workspace_bytes, void* hip_stream)
+{
+    return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, 1,
+                       nullptr, host_filt_ids, host_filt_offsets, K, dev_out_ids, dev_out_scores,
+                       dev_out_count, dev_workspace, workspace_bytes, hip_stream);
+}
+
+int st_search_multitask(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
+                        int64_t n_items, int32_t d, const int8_t* dev_queries, const float* dev_query_scale,
+                        int32_t batch, int32_t n_tasks, const float* host_task_weight,
+                        const uint64_t* host_filt_ids, const int64_t* host_filt_offsets, int32_t K,
+                        int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
+                        void* dev_workspace, int64_t workspace_bytes, void* hip_stream)
+{
+    if (!host_task_weight) return fail(ST_EINVAL, "host_task_weight is null");
+    return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch,
+                       n_tasks, host_task_weight, host_filt_ids, host_filt_offsets, K, dev_out_ids,
+                       dev_out_scores, dev_out_count, dev_workspace, workspace_bytes, hip_stream);
+}
+
+int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t d, const int8_t* dev_queries,
+                   const float* dev_query_scale, const int64_t* dev_pair_item, const int32_t* dev_pair_query,
+                   int64_t n_pairs, int32_t* dev_out_dot, float* dev_out_score, void* hip_stream)
+{
+    if (!dev_items || !dev_item_scale || !dev_queries || !dev_query_scale || !dev_pair_item || !dev_pair_query)
+        return fail(ST_EINVAL, "null argument");
+    if (d < 16 || d > ST_MAX_DIM || d % 16) return fail(ST_EINVAL, "d=%d must be a multiple of 16", d);
+    if (n_pairs < 0) return fail(ST_EINVAL, "n_pairs negative");
+    if (n_pairs == 0) return ST_OK;
+    const unsigned grid = (unsigned)((n_pairs + 255) / 256);
+    hipLaunchKernelGGL(st::score_pairs_kernel, dim3(grid), dim3(256), 0, (hipStream_t)hip_stream, dev_items,
+                       dev_item_scale, d, dev_queries, dev_query_scale, dev_pair_item, dev_pair_query, n_pairs,
+                       dev_out_dot, dev_out_score);
+    ST_HIP(hipGetLastError());
+    return ST_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,106 @@
+// Bloom index kernels: build (Sec. 4.1), item-major export and the stand-alone mask export.
+//
+// Index layout in HBM ("rotated" / bit-sliced, Sec. 4.1, blocked for 128-byte lines):
+//   word(tile, row, w) = bloom[(tile * m_bits + row) * 16 + w],  tile = item / 1024,
+//   w = (item % 1024) / 64, bit (item % 64) of that word = bit `row` of the item's signature.
+// One row segment of a tile is 16 words = 128 bytes; a filter that sets r signature bits
+// touches r such lines per tile.
+#pragma once
+#include "st_device.h"
+
+namespace st {
+
+// One wavefront per 64-item word; lane = item.  For each 64-row slab of the signature the lane
+// recomputes its item's hashes, keeps the bits that fall into the slab, and the wavefront
+// transposes the 64x64 bit block with ballots: lane b ends up holding row (slab*64 + b).
+__global__ __launch_bounds__(256) void bloom_build_kernel(const int64_t* __restrict__ feat_offsets,
+                                                          const uint64_t* __restrict__ feat_ids,
+                                                          int64_t n_items, int32_t m_bits,
+                                                          int32_t k_hashes, int64_t n_words_padded,
+                                                          uint64_t* __restrict__ bloom)
+{
+    const int lane = lane_id();
+    const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // global word index
+    if (gw >= n_words_padded) return;                                 // whole wavefront leaves together
+    const int64_t item = gw * 64 + lane;
+    int64_t f_begin = 0, f_end = 0;
+    if (item < n_items) {
+        f_begin = feat_offsets[item];
+        f_end = feat_offsets[item + 1];
+    }
+    const int64_t tile = gw >> 4;
+    const int w = (int)(gw & 15);
+    uint64_t* base = bloom + (tile * (int64_t)m_bits) * kTileWords + w;
+    const int n_slabs = (m_bits + 63) >> 6;
+    for (int slab = 0; slab < n_slabs; ++slab) {
+        uint64_t sig = 0;
+        for (int64_t p = f_begin; p < f_end; ++p) {
+            const uint64_t f = feat_ids[p];
+            for (int j = 0; j < k_hashes; ++j) {
+                const uint32_t b = bloom_bit(f, j, (uint32_t)m_bits);
+                if ((int)(b >> 6) == slab) sig |= 1ULL << (b & 63);
+            }
+        }
+        uint64_t mine = 0;
+        for (int b = 0; b < 64; ++b) {
+            const uint64_t bal = __ballot((sig >> b) & 1ULL);
+            if (lane == b) mine = bal;
+        }
+        const int row = slab * 64 + lane;
+        if (row < m_bits) base[(int64_t)row * kTileWords] = mine;
+    }
+}
+
+// Item-major signatures for parity checks: out[item][word j] gathers bit `row` from 64 rows.
+__global__ __launch_bounds__(256) void bloom_export_kernel(const uint64_t* __restrict__ bloom,
+                                                           int64_t n_items, int32_t m_bits,
+                                                           uint64_t* __restrict__ out)
+{
+    const int64_t item = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (item >= n_items) return;
+    const int64_t tile = item >> 10;
+    const int w = (int)((item & 1023) >> 6);
+    const int bit = (int)(item & 63);
+    const uint64_t* base = bloom + (tile * (int64_t)m_bits) * kTileWords + w;
+    const int n_slabs = (m_bits + 63) >> 6;
+    for (int slab = 0; slab < n_slabs; ++slab) {
+        uint64_t sig = 0;
+        for (int b = 0; b < 64; ++b) {
+            const int row = slab * 64 + b;
+            if (row < m_bits) sig |= ((base[(int64_t)row * kTileWords] >> bit) & 1ULL) << b;
+        }
+        out[item * n_slabs + slab] = sig;
+    }
+}
+
+// Mask word of one filter: AND of the rows its signature sets, limited to real items.
+__device__ inline uint64_t bloom_mask_word(const uint64_t* __restrict__ bloom, int32_t m_bits,
+                                           int64_t gw, int64_t n_items,
+                                           const int32_t* __restrict__ rows, int n_rows)
+{
+    const int64_t first = gw * 64;
+    if (first >= n_items) return 0;
+    const int64_t left = n_items - first;
+    uint64_t mask = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
+    const uint64_t* base = bloom + ((gw >> 4) * (int64_t)m_bits) * kTileWords + (gw & 15);
+    for (int r = 0; r < n_rows; ++r) mask &= base[(int64_t)rows[r] * kTileWords];
+    return mask;
+}
+
+// dev_mask[f][w] for every filter f and word w (Eq. 4, 64 items per AND).
+__global__ __launch_bounds__(256) void bloom_mask_kernel(const uint64_t* __restrict__ bloom,
+                                                         int32_t m_bits, int64_t n_items,
+                                                         int64_t n_words,
+                                                         const int32_t* __restrict__ row_off,
+                                                         const int32_t* __restrict__ rows,
+                                                         int32_t n_filters,
+                                                         uint64_t* __restrict__ out)
+{
+    const int64_t gw = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int f = blockIdx.y;
+    if (gw >= n_words || f >= n_filters) return;
+    const int r0 = row_off[f], r1 = row_off[f + 1];
+    out[(int64_t)f * n_words + gw] = bloom_mask_word(bloom, m_bits, gw, n_items, rows + r0, r1 - r0);
+}
+
+}  // namespace st

@@ -1,0 +1,134 @@
+// Host-side scheduling of one search: how the corpus is cut into levels, how large the
+// candidate regions are, and where everything sits in the caller's workspace.
+//
+// The corpus is scanned exactly once, in consecutive chunks ("levels").  Level 0 admits every
+// passing (query, item) pair; after each level a selection kernel reduces the candidates to the
+// running top-K and publishes its K-th key as the admission threshold of the next level (any
+// item of the final top-K is at least as good as the K-th best of a prefix of the corpus, so
+// nothing is lost).  Levels grow geometrically so that the expected number of admitted
+// candidates per (workgroup, query) region stays at a quarter of the region's capacity.
+#pragma once
+#include <stdint.h>
+#include <stddef.h>
+
+namespace st {
+
+constexpr int kScanGroups = 512;     // persistent workgroups of the scan kernel (2 per CU on MI355X)
+constexpr int kMaxLevels = 24;
+constexpr int kLdsSortMax = 4096;    // top-K lists up to this (padded) size are sorted in LDS
+
+struct Level {
+    int64_t begin, end;  // item range [begin, end)
+    int32_t seg_items;   // items one workgroup takes per step (multiple of 64, divides 1024)
+};
+
+struct Plan {
+    int32_t groups;  // scan workgroups
+    int32_t cap;     // entries per (workgroup, query) candidate region
+    int32_t n_levels;
+    Level level[kMaxLevels];
+};
+
+inline int64_t round_up(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
+
+inline int32_t pow2_ceil(int32_t v)
+{
+    int32_t p = 1;
+    while (p < v) p <<= 1;
+    return p;
+}
+
+inline int levels_for_cap(int64_t n_items, int32_t K, int32_t cap, Plan* out)
+{
+    const int32_t G = kScanGroups;
+    Plan p;
+    p.groups = G;
+    p.cap = cap;
+    p.n_levels = 0;
+    int64_t n0 = (int64_t)G * cap;
+    if (n0 > n_items) n0 = n_items;
+    p.level[p.n_levels++] = Level{0, n0, cap > 1024 ? 1024 : cap};
+    // level 0 hands each workgroup at most one segment of `cap` items, so no region can overflow
+    if (cap > 1024) return -1;
+    int64_t cur = n0;
+    const double grow = 1.0 + (double)cap * (double)G / (4.0 * (double)K);
+    while (cur < n_items) {
+        if (p.n_levels >= kMaxLevels) return -1;
+        double want = (double)cur * grow;
+        int64_t nxt = want >= (double)n_items ? n_items : (int64_t)want;
+        if (nxt < n_items) nxt = nxt / 1024 * 1024;
+        if (nxt <= cur) nxt = cur + 1024 < n_items ? cur + 1024 : n_items;
+        int32_t seg = 1024;
+        while (seg > 64 && (nxt - cur) / seg < 2 * (int64_t)G) seg >>= 1;
+        p.level[p.n_levels++] = Level{cur, nxt, seg};
+        cur = nxt;
+    }
+    *out = p;
+    return 0;
+}
+
+// Smallest region capacity that keeps the schedule at three levels or fewer (else the largest).
+inline int make_plan(int64_t n_items, int32_t K, Plan* out)
+{
+    static const int32_t caps[] = {64, 128, 256, 512, 1024};
+    Plan best;
+    bool have = false;
+    for (int32_t cap : caps) {
+        // the slow exact path appends into a buffer of K + groups*cap keys, a tile at a time
+        if ((int64_t)kScanGroups * cap < 2 * (int64_t)K + 2048) continue;
+        Plan p;
+        if (levels_for_cap(n_items, K, cap, &p) != 0) continue;
+        best = p;
+        have = true;
+        if (p.n_levels <= 3) break;
+    }
+    if (!have) return -1;
+    *out = best;
+    return 0;
+}
+
+// Byte offsets of the pieces of the device workspace.
+struct Layout {
+    size_t meta, meta_bytes;  // uploaded group tables
+    size_t tau;               // uint64 [B]       admission threshold per query
+    size_t ovf;               // uint32 [B]       1 = a candidate region overflowed
+    size_t topk_keys;         // uint64 [B][K]    running top-K, sorted
+    size_t topk_cnt;          // uint32 [B]
+    size_t cnt;               // uint32 [B][G]    entries used in each region
+    size_t cand;              // uint64 [B][G][cap]
+    size_t gath;              // uint64 [B][K + G*cap]  contiguous copy for selection
+    size_t srt;               // uint64 [B][Kpad]       only when Kpad > kLdsSortMax
+    size_t total;
+    int64_t gath_cap;
+    int32_t k_pad;
+};
+
+inline size_t meta_bound_bytes(int32_t batch)
+{
+    // header + row offsets + rows + query offsets + query list + slack for alignment
+    return (size_t)round_up(64 + (size_t)(batch + 1) * 4 * 2 + (size_t)batch * 64 * 4 +
+                                (size_t)batch * 4 + 64, 256);
+}
+
+inline Layout make_layout(const Plan& p, int32_t batch, int32_t K)
+{
+    Layout L;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = (size_t)round_up((int64_t)(off + bytes), 256); return o; };
+    L.meta_bytes = meta_bound_bytes(batch);
+    L.meta = take(L.meta_bytes);
+    L.tau = take((size_t)batch * 8);
+    L.ovf = take((size_t)batch * 4);
+    L.topk_keys = take((size_t)batch * K * 8);
+    L.topk_cnt = take((size_t)batch * 4);
+    L.cnt = take((size_t)batch * p.groups * 4);
+    L.cand = take((size_t)batch * p.groups * p.cap * 8);
+    L.gath_cap = (int64_t)K + (int64_t)p.groups * p.cap;
+    L.gath = take((size_t)batch * L.gath_cap * 8);
+    L.k_pad = pow2_ceil(K);
+    L.srt = take(L.k_pad > kLdsSortMax ? (size_t)batch * L.k_pad * 8 : 0);
+    L.total = off;
+    return L;
+}
+
+}  // namespace st

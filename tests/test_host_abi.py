@@ -1,0 +1,89 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the header
+declares, and its pure-arithmetic entry points (layout size, schedule, workspace, argument
+checks) behave as documented."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2511_14881_amd import binding as st
+from tests.helpers import read_golden
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    text = open(os.path.join(ROOT, "include", "silvertorch.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(st_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = _declared_symbols()
+    assert len(names) >= 14
+    lib = st.lib()
+    for n in names:
+        assert hasattr(lib, n), f"{n} is declared in the header but not exported"
+    assert sorted(st.EXPORTS) == names
+    assert lib.st_version() >= 100
+
+
+def test_index_size_is_items_times_bits_over_eight():
+    # paper Sec. 6.2.2: 40M items at 512/768/1024/2048 bits -> 2.56/3.84/5/10 GB (+ tile padding)
+    for row in read_golden("paper_arithmetic.txt"):
+        if row[0] != "bytes":
+            continue
+        n, m, nbytes = int(row[1]), int(row[2]), float(row[3])
+        got = st.st_bloom_layout_bytes(n, m)
+        assert got >= nbytes and got - nbytes < 1024 * m / 8 + 1
+    assert st.st_bloom_layout_bytes(1024, 64) == 1024 * 64 // 8
+    assert st.st_bloom_layout_bytes(1, 64) == 1024 * 64 // 8
+    assert st.st_bloom_layout_bytes(0, 64) == 0
+    with pytest.raises(st.StError) as e:
+        st.st_bloom_layout_bytes(10, 0)
+    assert e.value.code == st.ST_EINVAL
+    with pytest.raises(st.StError):
+        st.st_bloom_layout_bytes(1 << 31, 64)
+
+
+@pytest.mark.parametrize("n,B,K", [(0, 1, 1), (1, 1, 10), (10_000, 1, 10), (1_000_000, 64, 100),
+                                   (10_000_000, 256, 500), (5_000_000, 128, 200),
+                                   (20_000_000, 1024, 1000), (123_457, 7, 16384), (2**31 - 1, 4, 5)])
+def test_schedule_covers_the_corpus_once(n, B, K):
+    levels, groups, cap = st.st_search_plan(n, B, K)
+    assert groups == 512 and cap in (64, 128, 256, 512, 1024)
+    assert groups * cap >= 2 * K + 2048
+    assert levels[0, 0] == 0 and levels[-1, 1] == n
+    for i, (b, e, seg) in enumerate(levels):
+        assert e >= b and 1024 % seg == 0 and seg % 64 == 0 and b % seg == 0
+        if i:
+            assert b == levels[i - 1, 1] and e > b and b % 1024 == 0
+    # level 0: one segment of `cap` items per workgroup at most, so its regions cannot overflow
+    b, e, seg = levels[0]
+    assert seg == cap and (e - b + seg - 1) // seg <= groups
+    assert len(levels) <= 24
+
+
+def test_workspace_size_and_argument_checks():
+    a = st.st_search_workspace_bytes(1_000_000, 128, 64, 1, 100)
+    assert a > 0 and a % 256 == 0
+    assert st.st_search_workspace_bytes(1_000_000, 128, 128, 1, 100) > a
+    for bad in [(-1, 128, 1, 1, 1), (10, 100, 1, 1, 1), (10, 0, 1, 1, 1), (10, 128, 0, 1, 1),
+                (10, 128, 5000, 1, 1), (10, 128, 1, 0, 1), (10, 128, 1, 9, 1), (10, 128, 1, 1, 0),
+                (10, 128, 1, 1, 20000), (10, 8192, 1, 1, 1)]:
+        with pytest.raises(st.StError) as e:
+            st.st_search_workspace_bytes(*bad)
+        assert e.value.code == st.ST_EINVAL
+        assert st.last_error()
+
+
+def test_null_arguments_are_rejected_without_touching_a_gpu():
+    lib = st.lib()
+    assert lib.st_bloom_free(None) == 0
+    assert lib.st_bloom_bytes(None) == st.ST_EINVAL
+    assert lib.st_bloom_build(None, None, 0, 64, 2, None, None) == st.ST_EINVAL
+    assert lib.st_search(None, None, None, 0, 16, None, None, 1, None, None, 1, None, None, None, None, 0,
+                         None) == st.ST_EINVAL
+    assert lib.st_score_pairs(None, None, 16, None, None, None, None, 0, None, None, None) == st.ST_EINVAL
+    assert lib.st_set_scoring_path(0) in (0, 1, 2)
