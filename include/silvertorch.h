@@ -153,9 +153,11 @@ int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t
  * GPU): writes up to max_levels rows of 3 int64 {item_begin, item_end, segment_items} and
  * returns the number of levels, or a negative st_status.  The corpus is scanned once, in
  * consecutive chunks ("levels"); after each chunk the running top-K and its K-th key become
- * the admission threshold of the next.  out_caps receives {workgroups, region_capacity}. */
-int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int64_t* out_levels,
-                       int32_t max_levels, int64_t* out_caps);
+ * the admission threshold of the next.  q_split (a power of two, 1 unless the query rows of a large batch are
+ * spread over several rows of workgroups) divides the workgroups that share one query's
+ * candidates.  out_caps receives {workgroups, region_capacity}. */
+int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_split,
+                       int64_t* out_levels, int32_t max_levels, int64_t* out_caps);
 
 /* Search scheduling knobs, mainly for tests: path = 0 auto, 1 force the wavefront
  * dot-product scorer, 2 force the int8 MFMA scorer where it applies.  Returns the old value. */

@@ -65,7 +65,7 @@ def lib() -> C.CDLL:
         L.st_score_pairs.restype = C.c_int
         L.st_score_pairs.argtypes = [p, p, i32, p, p, p, p, i64, p, p, p]
         L.st_search_plan.restype = i32
-        L.st_search_plan.argtypes = [i64, i32, i32, p, i32, p]
+        L.st_search_plan.argtypes = [i64, i32, i32, i32, p, i32, p]
         L.st_set_scoring_path.restype = i32
         L.st_set_scoring_path.argtypes = [i32]
         L.st_timing_begin.restype = C.c_int
@@ -185,10 +185,10 @@ def st_search_workspace_bytes(n_items: int, d: int, batch: int, n_tasks: int, K:
     return _check(lib().st_search_workspace_bytes(n_items, d, batch, n_tasks, K))
 
 
-def st_search_plan(n_items: int, batch: int, K: int):
+def st_search_plan(n_items: int, batch: int, K: int, q_split: int = 1):
     levels = np.zeros((32, 3), dtype=np.int64)
     caps = np.zeros(2, dtype=np.int64)
-    n = _check(lib().st_search_plan(n_items, batch, K, _hptr(levels), 32, _hptr(caps)))
+    n = _check(lib().st_search_plan(n_items, batch, K, q_split, _hptr(levels), 32, _hptr(caps)))
     return levels[:n].copy(), int(caps[0]), int(caps[1])
 
 

@@ -169,30 +169,43 @@ int build_groups(const uint64_t* filt_ids, const int64_t* filt_off, int32_t n, i
     return ST_OK;
 }
 
-// Packs the group tables into one blob; offsets (in bytes) of each table go to `at`.
-struct MetaAt { size_t row_off, rows, q_off, q_list, q2grp, total; };
+// One contiguous blob of int32 tables, each 16-byte aligned; uploaded in one copy.
+struct Blob {
+    std::vector<int32_t> data;
+    size_t add(const std::vector<int32_t>& v)
+    {
+        const size_t at = data.size();
+        data.insert(data.end(), v.begin(), v.end());
+        data.resize((data.size() + 4) / 4 * 4, 0);  // pad (always leaves at least one spare int)
+        return at * 4;
+    }
+    size_t bytes() const { return data.size() * 4; }
+};
 
-MetaAt meta_offsets(const Groups& g)
+// A subset of the groups with its own tables (one per scorer).
+struct GroupSet {
+    std::vector<int32_t> row_off{0}, rows, q_off{0}, q_list;
+    int32_t n = 0;
+    void add(const Groups& all, int32_t g)
+    {
+        rows.insert(rows.end(), all.rows.begin() + all.row_off[g], all.rows.begin() + all.row_off[g + 1]);
+        row_off.push_back((int32_t)rows.size());
+        q_list.insert(q_list.end(), all.q_list.begin() + all.q_off[g], all.q_list.begin() + all.q_off[g + 1]);
+        q_off.push_back((int32_t)q_list.size());
+        ++n;
+    }
+};
+
+struct SetAt { size_t row_off, rows, q_off, q_list; };
+
+SetAt add_set(Blob& blob, const GroupSet& s)
 {
-    MetaAt at;
-    size_t off = 0;
-    auto take = [&](size_t n_int) { size_t o = off; off += (n_int * 4 + 15) / 16 * 16; return o; };
-    at.row_off = take(g.row_off.size());
-    at.rows = take(g.rows.size() + 1);
-    at.q_off = take(g.q_off.size());
-    at.q_list = take(g.q_list.size() + 1);
-    at.q2grp = take(g.q2grp.size() + 1);
-    at.total = off;
+    SetAt at;
+    at.row_off = blob.add(s.row_off);
+    at.rows = blob.add(s.rows);
+    at.q_off = blob.add(s.q_off);
+    at.q_list = blob.add(s.q_list);
     return at;
-}
-
-void meta_pack(const Groups& g, const MetaAt& at, char* dst)
-{
-    memcpy(dst + at.row_off, g.row_off.data(), g.row_off.size() * 4);
-    if (!g.rows.empty()) memcpy(dst + at.rows, g.rows.data(), g.rows.size() * 4);
-    memcpy(dst + at.q_off, g.q_off.data(), g.q_off.size() * 4);
-    if (!g.q_list.empty()) memcpy(dst + at.q_list, g.q_list.data(), g.q_list.size() * 4);
-    if (!g.q2grp.empty()) memcpy(dst + at.q2grp, g.q2grp.data(), g.q2grp.size() * 4);
 }
 
 }  // namespace
@@ -399,13 +412,14 @@ int st_bloom_mask(const st_bloom* bloom, const uint64_t* host_filt_ids, const in
     return rc;
 }
 
-int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int64_t* out_levels, int32_t max_levels,
-                       int64_t* out_caps)
+int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_split, int64_t* out_levels,
+                       int32_t max_levels, int64_t* out_caps)
 {
-    if (n_items < 0 || n_items >= (1LL << 31) || batch < 1 || batch > ST_MAX_BATCH || K < 1 || K > ST_MAX_TOP_K)
+    if (n_items < 0 || n_items >= (1LL << 31) || batch < 1 || batch > ST_MAX_BATCH || K < 1 ||
+        K > ST_MAX_TOP_K || q_split < 1 || q_split > 32 || (q_split & (q_split - 1)))
         return fail(ST_EINVAL, "bad sizes");
     st::Plan p;
-    if (st::make_plan(n_items, K, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (st::make_plan(n_items, K, q_split, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
     if (out_levels)
         for (int i = 0; i < p.n_levels && i < max_levels; ++i) {
             out_levels[3 * i + 0] = p.level[i].begin;
@@ -427,7 +441,7 @@ int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int
     if (n_tasks < 1 || n_tasks > ST_MAX_TASKS) return fail(ST_EINVAL, "n_tasks=%d out of range", n_tasks);
     if (K < 1 || K > ST_MAX_TOP_K) return fail(ST_EINVAL, "K=%d out of range", K);
     st::Plan p;
-    if (st::make_plan(n_items, K, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (st::make_plan(n_items, K, 1, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
     return (int64_t)st::make_layout(p, batch, K).total;
 }
 
@@ -463,20 +477,54 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     int rc = build_groups(host_filt_ids, host_filt_offsets, batch, bloom->m_bits, bloom->k_hashes, &groups);
     if (rc != ST_OK) return rc;
 
+    // split the groups between the two scorers: MFMA where scoring is a real dense contraction
+    // (enough query rows share the filter), the wavefront dot product otherwise
+    const bool shape_ok = st::mfma_shape_ok(d, n_tasks) && g_scoring_path != 1;
+    const int min_rows = g_scoring_path == 2 ? 1 : st::kMfmaMinRows;
+    GroupSet set_mfma, set_dot;
+    std::vector<int32_t> blk_off{0}, blk_row;
+    for (int32_t g = 0; g < groups.n_groups; ++g) {
+        const int32_t n_q = groups.q_off[g + 1] - groups.q_off[g];
+        if (shape_ok && n_q * n_tasks >= min_rows) {
+            set_mfma.add(groups, g);
+            for (int32_t i = 0; i < n_q; ++i)
+                for (int32_t t = 0; t < n_tasks; ++t) blk_row.push_back(groups.q_list[groups.q_off[g] + i] * n_tasks + t);
+            blk_row.resize((blk_row.size() + 15) / 16 * 16, -1);
+            blk_off.push_back((int32_t)(blk_row.size() / 16));
+        } else {
+            set_dot.add(groups, g);
+        }
+    }
+    st::MfmaParams mp;
+    memset(&mp, 0, sizeof(mp));
+    mp.n_blocks = (int32_t)(blk_row.size() / 16);
+    mp.q_split = set_mfma.n ? st::mfma_q_split(mp.n_blocks, d) : 1;
+    if (mp.q_split > 32) return fail(ST_EINVAL, "query batch too large for the resident-query scorer");
+
     st::Plan plan;
-    if (st::make_plan(n_items, K, &plan) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
-    const st::Layout L = st::make_layout(plan, batch, K);
-    const MetaAt at = meta_offsets(groups);
-    if (at.total > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
+    if (st::make_plan(n_items, K, mp.q_split, &plan) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    st::Plan plan1;
+    if (st::make_plan(n_items, K, 1, &plan1) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    const st::Layout L = st::make_layout(plan1, batch, K);  // layout depends on sizes only
+
+    Blob blob;
+    Groups& ga = groups;
+    const size_t at_all_row_off = blob.add(ga.row_off), at_all_rows = blob.add(ga.rows);
+    const size_t at_all_q_off = blob.add(ga.q_off), at_all_q = blob.add(ga.q_list);
+    const size_t at_q2grp = blob.add(ga.q2grp);
+    const SetAt at_m = add_set(blob, set_mfma), at_d = add_set(blob, set_dot);
+    const size_t at_blk_off = blob.add(blk_off), at_blk_row = blob.add(blk_row);
+    if (blob.bytes() > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
 
     char* ws = (char*)dev_workspace;
     Stage* stage = nullptr;
-    rc = stage_acquire(at.total, &stage);
+    rc = stage_acquire(blob.bytes(), &stage);
     if (rc != ST_OK) return rc;
-    meta_pack(groups, at, (char*)stage->host);
-    ST_HIP(hipMemcpyAsync(ws + L.meta, stage->host, at.total, hipMemcpyHostToDevice, stream));
+    memcpy(stage->host, blob.data.data(), blob.bytes());
+    ST_HIP(hipMemcpyAsync(ws + L.meta, stage->host, blob.bytes(), hipMemcpyHostToDevice, stream));
     ST_HIP(hipEventRecord(stage->ev, stream));
     stage->in_flight = true;
+    auto tab = [&](size_t at) { return (const int32_t*)(ws + L.meta + at); };
 
     st::ScanParams sp;
     memset(&sp, 0, sizeof(sp));
@@ -492,17 +540,31 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp.n_tasks = n_tasks;
     sp.weighted = weighted ? 1 : 0;
     for (int t = 0; t < n_tasks && weighted; ++t) sp.w[t] = host_task_weight[t];
-    sp.n_groups = groups.n_groups;
-    sp.grp_row_off = (const int32_t*)(ws + L.meta + at.row_off);
-    sp.grp_rows = (const int32_t*)(ws + L.meta + at.rows);
-    sp.grp_q_off = (const int32_t*)(ws + L.meta + at.q_off);
-    sp.grp_q = (const int32_t*)(ws + L.meta + at.q_list);
     sp.tau = (const uint64_t*)(ws + L.tau);
     sp.cand = (uint64_t*)(ws + L.cand);
     sp.cnt = (uint32_t*)(ws + L.cnt);
     sp.ovf = (uint32_t*)(ws + L.ovf);
     sp.cap = plan.cap;
     sp.groups = plan.groups;
+
+    st::ScanParams sp_m = sp, sp_d = sp, sp_all = sp;
+    sp_m.n_groups = set_mfma.n;
+    sp_m.grp_row_off = tab(at_m.row_off);
+    sp_m.grp_rows = tab(at_m.rows);
+    sp_m.grp_q_off = tab(at_m.q_off);
+    sp_m.grp_q = tab(at_m.q_list);
+    sp_d.n_groups = set_dot.n;
+    sp_d.grp_row_off = tab(at_d.row_off);
+    sp_d.grp_rows = tab(at_d.rows);
+    sp_d.grp_q_off = tab(at_d.q_off);
+    sp_d.grp_q = tab(at_d.q_list);
+    sp_all.n_groups = ga.n_groups;
+    sp_all.grp_row_off = tab(at_all_row_off);
+    sp_all.grp_rows = tab(at_all_rows);
+    sp_all.grp_q_off = tab(at_all_q_off);
+    sp_all.grp_q = tab(at_all_q);
+    mp.grp_blk_off = tab(at_blk_off);
+    mp.blk_row = tab(at_blk_row);
 
     st::SelectParams se;
     memset(&se, 0, sizeof(se));
@@ -523,21 +585,24 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     se.out_scores = dev_out_scores;
     se.out_count = dev_out_count;
 
-    const st::MfmaChoice mfma = st::choose_mfma(g_scoring_path, d, n_tasks, weighted, batch, groups.n_groups);
     for (int lv = 0; lv < plan.n_levels; ++lv) {
-        sp.item_begin = plan.level[lv].begin;
-        sp.item_end = plan.level[lv].end;
-        sp.seg_items = plan.level[lv].seg_items;
-        sp.use_tau = lv > 0;
-        {
-            TimedLaunch t(0, stream);
-            if (mfma.use)
-                st::launch_scan_mfma(sp, mfma, stream);
-            else
-                hipLaunchKernelGGL(st::scan_wavedot_kernel, dim3(plan.groups), dim3(st::kScanThreads),
-                                   (size_t)batch * 4, stream, sp);
+        for (st::ScanParams* q : {&sp_m, &sp_d}) {
+            q->item_begin = plan.level[lv].begin;
+            q->item_end = plan.level[lv].end;
+            q->seg_items = plan.level[lv].seg_items;
+            q->use_tau = lv > 0;
         }
-        ST_HIP(hipGetLastError());
+        if (set_mfma.n) {
+            st::mfma_lds_layout(&mp, d, n_tasks, sp_m.seg_items);
+            TimedLaunch t(0, stream);
+            ST_HIP(st::launch_scan_mfma(sp_m, mp, stream));
+        }
+        if (set_dot.n) {
+            TimedLaunch t(0, stream);
+            hipLaunchKernelGGL(st::scan_wavedot_kernel, dim3(plan.groups), dim3(st::kScanThreads),
+                               (size_t)batch * 4, stream, sp_d);
+            ST_HIP(hipGetLastError());
+        }
         se.first = lv == 0;
         se.last = lv == plan.n_levels - 1;
         {
@@ -549,8 +614,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     if (plan.n_levels > 1) {
         st::RescueParams rp;
         memset(&rp, 0, sizeof(rp));
-        rp.scan = sp;
-        rp.q2grp = (const int32_t*)(ws + L.meta + at.q2grp);
+        rp.scan = sp_all;
+        rp.q2grp = tab(at_q2grp);
         rp.ovf = sp.ovf;
         rp.gath = se.gath;
         rp.gath_cap = L.gath_cap;

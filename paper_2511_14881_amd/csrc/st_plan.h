@@ -14,7 +14,8 @@
 namespace st {
 
 constexpr int kScanGroups = 512;     // persistent workgroups of the scan kernel (2 per CU on MI355X)
-constexpr int kMaxLevels = 24;
+constexpr int kMaxLevels = 32;
+constexpr int kMaxSegItems = 512;    // items one workgroup takes per step, at most
 constexpr int kLdsSortMax = 4096;    // top-K lists up to this (padded) size are sorted in LDS
 
 struct Level {
@@ -38,28 +39,38 @@ inline int32_t pow2_ceil(int32_t v)
     return p;
 }
 
-inline int levels_for_cap(int64_t n_items, int32_t K, int32_t cap, Plan* out)
+inline int scan_groups()
 {
-    const int32_t G = kScanGroups;
+    return kScanGroups;
+}
+
+// Levels for a given region capacity.  g_eff = workgroups that share one query's candidates
+// (all of them, unless the query rows are split over several workgroup rows).
+inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, Plan* out)
+{
     Plan p;
-    p.groups = G;
+    p.groups = scan_groups();
     p.cap = cap;
     p.n_levels = 0;
-    int64_t n0 = (int64_t)G * cap;
-    if (n0 > n_items) n0 = n_items;
-    p.level[p.n_levels++] = Level{0, n0, cap > 1024 ? 1024 : cap};
+    if (cap > kMaxSegItems || g_eff < 1) return -1;
     // level 0 hands each workgroup at most one segment of `cap` items, so no region can overflow
-    if (cap > 1024) return -1;
+    int64_t n0 = (int64_t)g_eff * cap;
+    if (n0 > n_items) n0 = n_items;
+    p.level[p.n_levels++] = Level{0, n0, cap};
     int64_t cur = n0;
-    const double grow = 1.0 + (double)cap * (double)G / (4.0 * (double)K);
+    // expected admissions per region in a level that grows the scanned prefix by `grow` are
+    // K*(grow-1)/g_eff; aim at cap/4.  Never grow by less than 2x (extreme K with few sharing
+    // workgroups): regions may then overflow and the slow exact path takes those queries.
+    double grow = 1.0 + (double)cap * (double)g_eff / (4.0 * (double)K);
+    if (grow < 2.0) grow = 2.0;
     while (cur < n_items) {
         if (p.n_levels >= kMaxLevels) return -1;
         double want = (double)cur * grow;
         int64_t nxt = want >= (double)n_items ? n_items : (int64_t)want;
         if (nxt < n_items) nxt = nxt / 1024 * 1024;
         if (nxt <= cur) nxt = cur + 1024 < n_items ? cur + 1024 : n_items;
-        int32_t seg = 1024;
-        while (seg > 64 && (nxt - cur) / seg < 2 * (int64_t)G) seg >>= 1;
+        int32_t seg = kMaxSegItems;
+        while (seg > 64 && (nxt - cur) / seg < 2 * (int64_t)g_eff) seg >>= 1;
         p.level[p.n_levels++] = Level{cur, nxt, seg};
         cur = nxt;
     }
@@ -67,24 +78,28 @@ inline int levels_for_cap(int64_t n_items, int32_t K, int32_t cap, Plan* out)
     return 0;
 }
 
-// Smallest region capacity that keeps the schedule at three levels or fewer (else the largest).
-inline int make_plan(int64_t n_items, int32_t K, Plan* out)
+// Region capacity from the sizes alone (it fixes the workspace layout): the smallest that keeps
+// the schedule at three levels or fewer when every workgroup shares every query, else the largest.
+inline int choose_cap(int64_t n_items, int32_t K)
 {
-    static const int32_t caps[] = {64, 128, 256, 512, 1024};
-    Plan best;
-    bool have = false;
+    static const int32_t caps[] = {64, 128, 256, 512};
+    int best = -1;
     for (int32_t cap : caps) {
         // the slow exact path appends into a buffer of K + groups*cap keys, a tile at a time
-        if ((int64_t)kScanGroups * cap < 2 * (int64_t)K + 2048) continue;
+        if ((int64_t)scan_groups() * cap < 2 * (int64_t)K + 2048) continue;
         Plan p;
-        if (levels_for_cap(n_items, K, cap, &p) != 0) continue;
-        best = p;
-        have = true;
+        if (make_levels(n_items, K, cap, scan_groups(), &p) != 0) continue;
+        best = cap;
         if (p.n_levels <= 3) break;
     }
-    if (!have) return -1;
-    *out = best;
-    return 0;
+    return best;
+}
+
+inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, Plan* out)
+{
+    const int cap = choose_cap(n_items, K);
+    if (cap < 0 || q_split < 1 || scan_groups() % q_split) return -1;
+    return make_levels(n_items, K, cap, scan_groups() / q_split, out);
 }
 
 // Byte offsets of the pieces of the device workspace.
@@ -105,9 +120,9 @@ struct Layout {
 
 inline size_t meta_bound_bytes(int32_t batch)
 {
-    // header + row offsets + rows + query offsets + query list + slack for alignment
-    return (size_t)round_up(64 + (size_t)(batch + 1) * 4 * 2 + (size_t)batch * 64 * 4 +
-                                (size_t)batch * 4 + 64, 256);
+    // group tables (rows: at most 64 per query, twice: all groups and the per-scorer copies),
+    // query lists, offsets, MFMA block tables (at most 16*(T/16 + 1) rows per query), slack
+    return (size_t)round_up(4096 + (size_t)batch * 720, 256);
 }
 
 inline Layout make_layout(const Plan& p, int32_t batch, int32_t K)

@@ -142,7 +142,10 @@ __global__ __launch_bounds__(kScanThreads) void scan_wavedot_kernel(ScanParams p
         }
     }
     __syncthreads();
-    for (int q = tid; q < p.batch; q += kScanThreads) {
+    // region fill counts of the queries this launch owns
+    const int n_q = p.grp_q_off[p.n_groups];
+    for (int i = tid; i < n_q; i += kScanThreads) {
+        const int q = p.grp_q[i];
         const uint32_t c = cnt_l[q];
         p.cnt[(int64_t)q * p.groups + blockIdx.x] = c < (uint32_t)p.cap ? c : (uint32_t)p.cap;
         if (c > (uint32_t)p.cap) p.ovf[q] = 1u;

@@ -158,25 +158,47 @@ def test_tiny_config():
     check_search(S.make_workload(S.CONFIGS["tiny"]), S.CONFIGS["tiny"].top_k)
 
 
+# scoring path: 0 = the library's own choice, 1 = wavefront dot product only, 2 = MFMA for every
+# group whose shape allows it (also groups of a single query)
+PATHS = [0, 1, 2]
+
+
+@pytest.mark.parametrize("path", PATHS)
 @pytest.mark.parametrize("n", [3_000, 100_003])
-def test_mid_recipe_small(n):
+def test_mid_recipe_small(n, path):
     cfg = S.scaled(S.CONFIGS["mid"], n)
-    check_search(S.make_workload(cfg), cfg.top_k)
+    check_search(S.make_workload(cfg), cfg.top_k, path=path)
 
 
-def test_multitask_recipe_small():
+@pytest.mark.parametrize("path", PATHS)
+def test_multitask_recipe_small(path):
     cfg = S.scaled(S.CONFIGS["multi"], 60_000, batch=16)
-    check_search(S.make_workload(cfg), cfg.top_k)
+    check_search(S.make_workload(cfg), cfg.top_k, path=path)
 
 
-def test_large_recipe_small():
+@pytest.mark.parametrize("path", PATHS)
+def test_large_recipe_small(path):
     cfg = S.scaled(S.CONFIGS["large"], 50_000, batch=32)
-    check_search(S.make_workload(cfg), cfg.top_k)
+    check_search(S.make_workload(cfg), cfg.top_k, path=path)
 
 
-def test_mfma_recipe_small():
+@pytest.mark.parametrize("path", PATHS)
+def test_mfma_recipe_small(path):
     cfg = S.scaled(S.CONFIGS["mfma"], 40_000, batch=64, top_k=300)
-    check_search(S.make_workload(cfg), cfg.top_k)
+    check_search(S.make_workload(cfg), cfg.top_k, path=path)
+
+
+def test_large_batch_splits_query_rows_over_workgroup_rows():
+    # 1024 query rows of 128 bytes exceed one workgroup's resident-query budget: the rows are
+    # split over two rows of workgroups, each scanning the corpus for its own queries
+    cfg = S.scaled(S.CONFIGS["mfma"], 70_000, batch=1024, top_k=100)
+    check_search(S.make_workload(cfg), cfg.top_k, queries=range(0, 1024, 37))
+
+
+@pytest.mark.parametrize("T,d", [(1, 64), (2, 64), (4, 256), (2, 512), (3, 128)])
+def test_multitask_shapes(T, d):
+    w = ragged_workload(900 + T + d, 20_000, d, 24, 6, 3, 128, 2, T=T)
+    check_search(w, 64, path=2, label=f"multitask T={T} d={d}")
 
 
 def test_mid_config_full_size_every_query():
@@ -191,11 +213,12 @@ def test_mid_config_full_size_every_query():
                                        (65, 48, 2, 100, 0), (1023, 64, 5, 7, 0), (1025, 64, 5, 2000, 0),
                                        (40_000, 32, 20, 50, 0), (33_000, 16, 40, 10, 0),
                                        (5000, 32, 6, 20, 3), (5000, 64, 3, 6000, 0), (2000, 16, 4, 9, 8)])
-def test_ragged_sizes_and_filters(n, d, B, K, T):
+@pytest.mark.parametrize("path", [0, 2])
+def test_ragged_sizes_and_filters(n, d, B, K, T, path):
     # ragged and empty feature lists, empty filters, filters nothing passes, K above the
     # number of passing items and above the corpus size, more distinct filters than one pass holds
     w = ragged_workload(n + d, n, d, B, 12, 4, 100, 3, T=T)
-    ids, scores, count = check_search(w, K, label=f"ragged n={n} d={d} B={B} K={K} T={T}")
+    ids, scores, count = check_search(w, K, path=path, label=f"ragged n={n} d={d} B={B} K={K} T={T}")
     for b in range(B):
         assert (ids[b, count[b]:] == -1).all() and np.isneginf(scores[b, count[b]:]).all()
 
@@ -235,8 +258,9 @@ def test_rising_scores_overflow_the_regions_and_take_the_exact_slow_path():
     w.queries[1] = -1            # for this query scores fall with the id: no overflow
     w.item_scale = (0.5 + torch.arange(n, dtype=torch.float32) / n).contiguous()
     w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
-    ids, _, _ = check_search(w, 50, label="rising scores")
-    assert ids[0, 0] == n - 1 and ids[1, 0] == 0
+    for path in (1, 2):
+        ids, _, _ = check_search(w, 50, path=path, label="rising scores")
+        assert ids[0, 0] == n - 1 and ids[1, 0] == 0
 
 
 def test_results_are_deterministic():

@@ -50,19 +50,20 @@ def test_index_size_is_items_times_bits_over_eight():
 @pytest.mark.parametrize("n,B,K", [(0, 1, 1), (1, 1, 10), (10_000, 1, 10), (1_000_000, 64, 100),
                                    (10_000_000, 256, 500), (5_000_000, 128, 200),
                                    (20_000_000, 1024, 1000), (123_457, 7, 16384), (2**31 - 1, 4, 5)])
-def test_schedule_covers_the_corpus_once(n, B, K):
-    levels, groups, cap = st.st_search_plan(n, B, K)
-    assert groups == 512 and cap in (64, 128, 256, 512, 1024)
+@pytest.mark.parametrize("q_split", [1, 2, 8])
+def test_schedule_covers_the_corpus_once(n, B, K, q_split):
+    levels, groups, cap = st.st_search_plan(n, B, K, q_split)
+    assert groups == 512 and cap in (64, 128, 256, 512)
     assert groups * cap >= 2 * K + 2048
     assert levels[0, 0] == 0 and levels[-1, 1] == n
     for i, (b, e, seg) in enumerate(levels):
-        assert e >= b and 1024 % seg == 0 and seg % 64 == 0 and b % seg == 0
+        assert e >= b and 1024 % seg == 0 and seg % 64 == 0 and b % seg == 0 and seg <= 512
         if i:
             assert b == levels[i - 1, 1] and e > b and b % 1024 == 0
     # level 0: one segment of `cap` items per workgroup at most, so its regions cannot overflow
     b, e, seg = levels[0]
-    assert seg == cap and (e - b + seg - 1) // seg <= groups
-    assert len(levels) <= 24
+    assert seg == cap and (e - b + seg - 1) // seg <= groups // q_split
+    assert len(levels) <= 32
 
 
 def test_workspace_size_and_argument_checks():
