@@ -120,7 +120,7 @@ def main():
 
     # per-kernel durations, HIP events on the launch stream around every kernel of K more steps
     levels, groups, cap = st.st_search_plan(cfg.n_items, cfg.batch, cfg.top_k)
-    st.st_timing_begin(args.steps * (2 * len(levels) + 1) + 8)
+    st.st_timing_begin(args.steps * (3 * len(levels) + 1) + 8)
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()

@@ -419,12 +419,13 @@ int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_spli
         K > ST_MAX_TOP_K || q_split < 1 || q_split > 32 || (q_split & (q_split - 1)))
         return fail(ST_EINVAL, "bad sizes");
     st::Plan p;
-    if (st::make_plan(n_items, K, q_split, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (st::make_plan(n_items, K, q_split, st::kMaxSegItems, &p) != 0)
+        return fail(ST_EINVAL, "no schedule for these sizes");
     if (out_levels)
         for (int i = 0; i < p.n_levels && i < max_levels; ++i) {
             out_levels[3 * i + 0] = p.level[i].begin;
             out_levels[3 * i + 1] = p.level[i].end;
-            out_levels[3 * i + 2] = p.level[i].seg_items;
+            out_levels[3 * i + 2] = (int64_t)p.level[i].seg_items * p.level[i].seg_per_visit;
         }
     if (out_caps) {
         out_caps[0] = p.groups;
@@ -441,7 +442,7 @@ int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int
     if (n_tasks < 1 || n_tasks > ST_MAX_TASKS) return fail(ST_EINVAL, "n_tasks=%d out of range", n_tasks);
     if (K < 1 || K > ST_MAX_TOP_K) return fail(ST_EINVAL, "K=%d out of range", K);
     st::Plan p;
-    if (st::make_plan(n_items, K, 1, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
     return (int64_t)st::make_layout(p, batch, K).total;
 }
 
@@ -480,12 +481,24 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     // split the groups between the two scorers: MFMA where scoring is a real dense contraction
     // (enough query rows share the filter), the wavefront dot product otherwise
     const bool shape_ok = st::mfma_shape_ok(d, n_tasks) && g_scoring_path != 1;
-    const int min_rows = g_scoring_path == 2 ? 1 : st::kMfmaMinRows;
+    int min_rows = g_scoring_path == 2 ? 1 : st::kMfmaMinRows;
+    if (shape_ok && min_rows > 1) {
+        // a second scorer means a second pass over the corpus: when some group is dense enough
+        // for MFMA, the small groups ride along unless their padding would more than double
+        // the resident query blocks
+        int64_t blocks_big = 0, blocks_all = 0;
+        for (int32_t g = 0; g < groups.n_groups; ++g) {
+            const int64_t rows = (int64_t)(groups.q_off[g + 1] - groups.q_off[g]) * n_tasks;
+            blocks_all += (rows + 15) / 16;
+            if (rows >= min_rows) blocks_big += (rows + 15) / 16;
+        }
+        if (blocks_big > 0 && blocks_all <= std::max<int64_t>(2 * blocks_big, blocks_big + 8)) min_rows = 1;
+    }
     GroupSet set_mfma, set_dot;
     std::vector<int32_t> blk_off{0}, blk_row;
     for (int32_t g = 0; g < groups.n_groups; ++g) {
         const int32_t n_q = groups.q_off[g + 1] - groups.q_off[g];
-        if (shape_ok && n_q * n_tasks >= min_rows) {
+        if (shape_ok && n_q * n_tasks >= min_rows && set_mfma.n < st::kMfmaMaxGroups) {
             set_mfma.add(groups, g);
             for (int32_t i = 0; i < n_q; ++i)
                 for (int32_t t = 0; t < n_tasks; ++t) blk_row.push_back(groups.q_list[groups.q_off[g] + i] * n_tasks + t);
@@ -501,10 +514,13 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     mp.q_split = set_mfma.n ? st::mfma_q_split(mp.n_blocks, d) : 1;
     if (mp.q_split > 32) return fail(ST_EINVAL, "query batch too large for the resident-query scorer");
 
+    const int32_t seg_cap = set_mfma.n ? st::mfma_max_seg_items(d) : st::kMaxSegItems;
     st::Plan plan;
-    if (st::make_plan(n_items, K, mp.q_split, &plan) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (st::make_plan(n_items, K, mp.q_split, seg_cap, &plan) != 0)
+        return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
-    if (st::make_plan(n_items, K, 1, &plan1) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, &plan1) != 0)
+        return fail(ST_EINVAL, "no schedule for these sizes");
     const st::Layout L = st::make_layout(plan1, batch, K);  // layout depends on sizes only
 
     Blob blob;
@@ -585,17 +601,29 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     se.out_scores = dev_out_scores;
     se.out_count = dev_out_count;
 
+    se.scan = sp_all;
+    se.q2grp = tab(at_q2grp);
     for (int lv = 0; lv < plan.n_levels; ++lv) {
+        const st::Level& L_ = plan.level[lv];
         for (st::ScanParams* q : {&sp_m, &sp_d}) {
-            q->item_begin = plan.level[lv].begin;
-            q->item_end = plan.level[lv].end;
-            q->seg_items = plan.level[lv].seg_items;
+            q->item_begin = L_.begin;
+            q->item_end = L_.end;
+            q->seg_items = L_.seg_items;
+            q->seg_per_visit = L_.seg_per_visit;
             q->use_tau = lv > 0;
         }
+        // workgroups with work: one visit (seg_per_visit segments) per step; launching no more
+        // keeps idle workgroups from staging queries, and the selection reads only their regions
+        const int64_t n_seg = (L_.end - L_.begin + L_.seg_items - 1) / L_.seg_items;
+        const int64_t n_visit = (n_seg + L_.seg_per_visit - 1) / L_.seg_per_visit;
+        int32_t regions = plan.groups;
         if (set_mfma.n) {
-            st::mfma_lds_layout(&mp, d, n_tasks, sp_m.seg_items);
+            int32_t gx = plan.groups / mp.q_split;
+            if (!set_dot.n && n_visit < gx) gx = (int32_t)std::max<int64_t>(n_visit, 1);
+            regions = set_dot.n ? plan.groups : gx * mp.q_split;
+            st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n);
             TimedLaunch t(0, stream);
-            ST_HIP(st::launch_scan_mfma(sp_m, mp, stream));
+            ST_HIP(st::launch_scan_mfma(sp_m, mp, gx, stream));
         }
         if (set_dot.n) {
             TimedLaunch t(0, stream);
@@ -605,29 +633,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         }
         se.first = lv == 0;
         se.last = lv == plan.n_levels - 1;
+        se.regions = regions;
         {
             TimedLaunch t(1, stream);
-            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(256), 0, stream, se);
-        }
-        ST_HIP(hipGetLastError());
-    }
-    if (plan.n_levels > 1) {
-        st::RescueParams rp;
-        memset(&rp, 0, sizeof(rp));
-        rp.scan = sp_all;
-        rp.q2grp = tab(at_q2grp);
-        rp.ovf = sp.ovf;
-        rp.gath = se.gath;
-        rp.gath_cap = L.gath_cap;
-        rp.srt = se.srt;
-        rp.K = K;
-        rp.k_pad = L.k_pad;
-        rp.out_ids = dev_out_ids;
-        rp.out_scores = dev_out_scores;
-        rp.out_count = dev_out_count;
-        {
-            TimedLaunch t(2, stream);
-            hipLaunchKernelGGL(st::rescue_kernel, dim3(batch), dim3(256), 0, stream, rp);
+            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), 0, stream, se);
         }
         ST_HIP(hipGetLastError());
     }

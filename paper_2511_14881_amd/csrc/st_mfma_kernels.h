@@ -1,8 +1,17 @@
 // Scan with the int8 MFMA scorer (v_mfma_i32_16x16x64_i8), for filter groups that carry enough
 // query rows to make scoring a dense contraction (Sec. 4.2: item rows are streamed from the
 // embedding table and multiplied with the batched queries on the fly, nothing is gathered into
-// a temporary).  Queries stay resident in LDS for the whole launch; the passing items of a
-// segment, compacted per filter group, are loaded straight from HBM into the B operand.
+// a temporary in HBM).  Queries stay resident in LDS for the whole launch and are the only thing
+// the four wavefronts of a workgroup share; in the main loop every wavefront works alone, on
+// its own segments of the corpus, without barriers:
+//   1. lane (filter, word) ANDs the Bloom rows of its filter for its 64-item word (the words of
+//      the next segment are fetched while the current one is scored),
+//   2. the set bits of each filter's words become a dense list of passing items (wave-private
+//      LDS),
+//   3. 32 passing items of one filter at a time go straight from HBM into the B operand (the
+//      loads of the next 32 are in flight while the current ones are multiplied) and are
+//      contracted with the filter group's query blocks; scores that reach the query's
+//      threshold are admitted to the workgroup's candidate region.
 //
 // Contraction layout per MFMA (M = 16 query rows, N = 16 items, K = 64 bytes of the embedding):
 //   A (queries): lane l supplies row (l % 16), bytes [16*(l/16), +16) of the 64-byte k-step
@@ -20,6 +29,12 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 constexpr int kMfmaFilterBatch = 8;        // distinct filters handled per pass over a segment
 constexpr int kMfmaQueryLds = 64 * 1024;   // LDS bytes for resident query rows per workgroup
 constexpr int kMfmaMinRows = 4;            // a group needs this many query rows to go to MFMA
+constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
+constexpr int kPrefetchRows = 8;           // signature rows per filter whose next-segment words are prefetched
+constexpr int kMfmaSegItems = 256;         // items per wavefront segment, at most (4 mask words x 8 filters = 32 lanes)
+constexpr int kMfmaWaves = kScanThreads / 64;
+
+inline constexpr int mfma_max_seg_items(int) { return kMfmaSegItems; }
 
 struct MfmaParams {
     const int32_t* grp_blk_off;  // [F+1] first 16-row block of each group
@@ -28,11 +43,11 @@ struct MfmaParams {
     int32_t q_split;             // S: gridDim.y; block b belongs to y = b % S, local index b / S
     int32_t rows_local;          // 16 * blocks per y (max over y)
     // dynamic LDS layout (byte offsets)
-    int32_t lds_sq, lds_tauf, lds_qrow, lds_cnt, lds_mask, lds_list, lds_listcnt, lds_total;
+    int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_prow, lds_blkoff, lds_total;
 };
 
-// chunk swizzle for the resident query rows: keeps the 16 rows of a block on distinct banks
-// when the 16 lanes of a quarter-wave read the same 16-byte chunk of 16 consecutive rows
+// chunk swizzle: keeps 16 consecutive rows of d bytes on distinct LDS banks when the 16 lanes
+// of a quarter-wave read the same 16-byte chunk of each
 template <int KS>
 __device__ inline int swz(int row)
 {
@@ -41,42 +56,64 @@ __device__ inline int swz(int row)
     return (row >> sh) & ((nch < 16 ? nch : 16) - 1);
 }
 
+// Item rows of one work item (up to 32 passing items of one filter group) in MFMA B layout.
+template <int KS>
+struct WorkRegs {
+    v4i b[2][KS];
+    float si[2];
+    int item[2];    // item index relative to the segment start, of lane's item (l % 16) in each half
+    bool valid[2];
+};
+
 template <int KS, int TT>
-__global__ __launch_bounds__(kScanThreads) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
+__global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 4 : 2)) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int D = KS * 64;
+    constexpr int CH = D / 16;  // 16-byte chunks per row
+    constexpr int FB = kMfmaFilterBatch;
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
+    uint64_t* s_tau64 = reinterpret_cast<uint64_t*>(lds + mp.lds_tau64);    // [rows_local / TT]
     int* s_qrow = reinterpret_cast<int*>(lds + mp.lds_qrow);
     uint32_t* s_cnt = reinterpret_cast<uint32_t*>(lds + mp.lds_cnt);
-    uint64_t* s_mask = reinterpret_cast<uint64_t*>(lds + mp.lds_mask);      // [FB][16]
-    uint16_t* s_list = reinterpret_cast<uint16_t*>(lds + mp.lds_list);      // [FB][seg_items]
-    int* s_listcnt = reinterpret_cast<int*>(lds + mp.lds_listcnt);
+    int* s_prow = reinterpret_cast<int*>(lds + mp.lds_prow);                // [groups][kPrefetchRows]
+    int* s_blkoff = reinterpret_cast<int*>(lds + mp.lds_blkoff);            // [groups + 1]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
     const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
     const int l16 = lane & 15, kg = lane >> 4;
+    uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
 
-    // ---- resident state: this y's query rows (swizzled), their scales, thresholds, owners
+    // ---- workgroup-wide set-up: tables and resident queries into LDS
+    for (int i = tid; i < p.n_groups * kPrefetchRows; i += kScanThreads) {
+        const int g = i / kPrefetchRows, r = i - g * kPrefetchRows;
+        const int r0 = p.grp_row_off[g], nr = p.grp_row_off[g + 1] - r0;
+        s_prow[i] = r < nr ? p.grp_rows[r0 + r] : -1;
+    }
+    for (int i = tid; i <= p.n_groups; i += kScanThreads) s_blkoff[i] = mp.grp_blk_off[i];
     for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
         const int b = (lr >> 4) * S + y;
         const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
         s_qrow[lr] = grow;
         float sq = 0.0f, tf = __builtin_inff();
+        uint64_t t64 = 0ULL;
         if (grow >= 0) {
             sq = p.qscale[grow];
-            const uint64_t t64 = p.use_tau ? p.tau[grow / TT] : 0ULL;
+            t64 = p.use_tau ? p.tau[grow / TT] : 0ULL;
             tf = t64 ? key_score(t64) : -__builtin_inff();
         }
         s_sq[lr] = sq;
         s_tauf[lr] = tf;
-        if ((lr % TT) == 0) s_cnt[lr / TT] = 0;
+        if ((lr % TT) == 0) {
+            s_cnt[lr / TT] = 0;
+            s_tau64[lr / TT] = t64;
+        }
     }
-    for (int i = tid; i < mp.rows_local * (D / 16); i += kScanThreads) {
-        const int lr = i / (D / 16), c = i - lr * (D / 16);
+    for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) {
+        const int lr = i / CH, c = i - lr * CH;
         const int b = (lr >> 4) * S + y;
         const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
         int4 v = make_int4(0, 0, 0, 0);
@@ -85,133 +122,201 @@ __global__ __launch_bounds__(kScanThreads) void scan_mfma_kernel(ScanParams p, M
     }
     __syncthreads();
 
-    const int seg_words = p.seg_items >> 6;
-    const int64_t n_seg = (p.item_end - p.item_begin + p.seg_items - 1) / p.seg_items;
+    // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
+    // workgroup; inside a visit wavefront w takes segments w, w + 4, ...  Stages of a wavefront
+    // are numbered (visit, segment slot, filter batch).
+    const int seg_items = p.seg_items;
+    const int SW = seg_items >> 6;  // mask words per segment (1, 2 or 4)
+    const int spv = p.seg_per_visit;
     const int64_t item_lim = p.item_end < p.n_items ? p.item_end : p.n_items;
-    for (int64_t seg = blockIdx.x; seg < n_seg; seg += gridDim.x) {
-        const int64_t item0 = p.item_begin + seg * p.seg_items;
-        const int64_t word0 = item0 >> 6;
-        for (int g0 = 0; g0 < p.n_groups; g0 += kMfmaFilterBatch) {
-            const int nf = min(kMfmaFilterBatch, p.n_groups - g0);
-            // (1) Bloom test
-            for (int idx = tid; idx < nf * seg_words; idx += kScanThreads) {
-                const int gi = idx / seg_words, w = idx - gi * seg_words;
-                const int g = g0 + gi;
-                const int r0 = p.grp_row_off[g], r1 = p.grp_row_off[g + 1];
-                s_mask[gi * kTileWords + w] =
-                    bloom_mask_word(p.bloom, p.m_bits, word0 + w, item_lim, p.grp_rows + r0, r1 - r0);
-            }
-            __syncthreads();
-            // (2) compaction
-            for (int gi = wave; gi < nf; gi += kScanThreads / 64) {
-                uint64_t mask = lane < seg_words ? s_mask[gi * kTileWords + lane] : 0ULL;
-                const int c = __popcll(mask);
-                int incl = c;
-                for (int o = 1; o < kTileWords; o <<= 1) {
-                    const int v = __shfl_up(incl, o);
-                    if (lane >= o) incl += v;
-                }
-                int pos = incl - c;
-                uint16_t* list = s_list + gi * p.seg_items;
-                while (mask) {
-                    const int b = __ffsll((long long)mask) - 1;
-                    mask &= mask - 1;
-                    list[pos++] = (uint16_t)(lane * 64 + b);
-                }
-                const int total = __shfl(incl, kTileWords - 1);
-                if (lane == 0) s_listcnt[gi] = total;
-            }
-            __syncthreads();
-            // (3) contraction + epilogue: a wavefront takes 64 passing items (4 x 16) at a time
-            for (int gi = 0; gi < nf; ++gi) {
-                const int n = s_listcnt[gi];
-                const int g = g0 + gi;
-                const int blk_end = mp.grp_blk_off[g + 1];
-                int blk_first = mp.grp_blk_off[g];
-                blk_first += ((y - blk_first) % S + S) % S;  // first block of the group owned by this y
-                if (blk_first >= blk_end) continue;
-                const uint16_t* list = s_list + gi * p.seg_items;
-                for (int b0 = ((wave + gi) & 3) * 64; b0 < n; b0 += kScanThreads) {
-                    const int left = n - b0;
-                    const int nsb = left >= 64 ? 4 : (left + 15) >> 4;
-                    v4i breg[4][KS];
-                    float si[4];
-                    int64_t item[4];
-                    bool valid[4];
+    const int n_seg = (int)((p.item_end - p.item_begin + seg_items - 1) / seg_items);
+    const int n_visit = (n_seg + spv - 1) / spv;
+    const int n_batches = (p.n_groups + FB - 1) / FB;
+    const int slots = wave < spv ? (spv - wave + kMfmaWaves - 1) / kMfmaWaves : 0;  // my segments per visit
+    const int my_visits = (int)blockIdx.x < n_visit ? (n_visit - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
+    const int per_visit = slots * n_batches;
+    const int n_stages = my_visits * per_visit;
+    auto stage_seg = [&](int t) {  // segment index of stage t (may lie past the level's end: no items there)
+        const int v = t / per_visit, r = t - v * per_visit;
+        return ((int)blockIdx.x + v * (int)gridDim.x) * spv + wave + (r / n_batches) * kMfmaWaves;
+    };
+    auto stage_batch = [&](int t) { return (t % per_visit) % n_batches; };
+
+    // Bloom words: lane (gi * SW + w) owns word w of filter gi of the stage's batch.
+    const bool pair_lane = lane < FB * SW;
+    const int pr_gi = lane / SW, pr_w = lane - pr_gi * SW;
+    uint64_t pre[kPrefetchRows];
 #pragma unroll
-                    for (int sb = 0; sb < 4; ++sb) {
-                        if (sb < nsb) {
-                            const int li = b0 + sb * 16 + l16;
-                            valid[sb] = li < n;
-                            item[sb] = item0 + (int)list[valid[sb] ? li : b0];
-                            const int4* rp = reinterpret_cast<const int4*>(p.items + item[sb] * D) + kg;
+    for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
+    auto prefetch_issue = [&](int t) {
+        if (!pair_lane || t >= n_stages) return;
+        const int g = stage_batch(t) * FB + pr_gi;
+        if (g >= p.n_groups) return;
+        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(t) * seg_items) >> 6) + pr_w;
+        if (gw * 64 >= item_lim) return;
+        const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
-                            for (int s = 0; s < KS; ++s) {
-                                const int4 v = rp[4 * s];
-                                breg[sb][s] = v4i{v.x, v.y, v.z, v.w};
-                            }
-                            si[sb] = p.iscale[item[sb]];
-                        }
+        for (int r = 0; r < kPrefetchRows; ++r) {
+            const int row = s_prow[g * kPrefetchRows + r];
+            pre[r] = row >= 0 ? base[(int64_t)row * kTileWords] : ~0ULL;
+        }
+    };
+    auto prefetch_mask = [&](int t) -> uint64_t {  // mask word of my (filter, word) pair for stage t
+        if (!pair_lane) return 0ULL;
+        const int g = stage_batch(t) * FB + pr_gi;
+        if (g >= p.n_groups) return 0ULL;
+        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(t) * seg_items) >> 6) + pr_w;
+        const int64_t first = gw * 64;
+        if (first >= item_lim) return 0ULL;
+        const int64_t left = item_lim - first;
+        uint64_t mask = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
+#pragma unroll
+        for (int r = 0; r < kPrefetchRows; ++r) mask &= pre[r];
+        const int r0 = p.grp_row_off[g], nr = p.grp_row_off[g + 1] - r0;
+        if (nr > kPrefetchRows) {  // long filters: the remaining rows, not prefetched
+            const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
+            for (int r = kPrefetchRows; r < nr; ++r) mask &= base[(int64_t)p.grp_rows[r0 + r] * kTileWords];
+        }
+        return mask;
+    };
+    if (n_stages > 0) prefetch_issue(0);
+
+    for (int t = 0; t < n_stages; ++t) {
+        const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
+        const int g0 = stage_batch(t) * FB;
+        const int nf = min(FB, p.n_groups - g0);
+
+        // (1) + (2): mask word of my pair, then the set bits of each filter's words, in item
+        // order, into the filter's list
+        uint64_t mask = prefetch_mask(t);
+#pragma unroll
+        for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
+        prefetch_issue(t + 1);
+        const int c = __popcll(mask);
+        int incl = c;  // running count over the words of my filter
+        for (int o = 1; o < SW; o <<= 1) {
+            const int v = __shfl_up(incl, o);
+            if (pr_w >= o) incl += v;
+        }
+        {
+            int pos = incl - c;
+            uint8_t* list = s_list + pr_gi * kMfmaSegItems;
+            while (mask) {
+                const int b = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+                list[pos++] = (uint8_t)(pr_w * 64 + b);
+            }
+        }
+        // list sizes: the last word's lane of each filter holds the total
+        auto n_of = [&](int gi) { return __builtin_amdgcn_readlane(incl, gi * SW + SW - 1); };
+
+        // (3) work items = (filter gi, 32 passing items from b0), in order; the item rows of the
+        // next work item are loaded while the current one is contracted
+        // uniform bases + 32-bit lane offsets: the segment's rows span at most 256 * D bytes
+        const char* seg_rows = reinterpret_cast<const char*>(p.items + item0 * D);
+        const float* seg_scale = p.iscale + item0;
+        auto wi_load = [&](WorkRegs<KS>& w, int gi, int b0, int n) {
+            const uint8_t* list = s_list + gi * kMfmaSegItems;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                if (b0 + h * 16 < n) {
+                    const int li = b0 + h * 16 + l16;
+                    w.valid[h] = li < n;
+                    w.item[h] = (int)list[w.valid[h] ? li : b0];
+                    const uint32_t off = (uint32_t)(w.item[h] * D + kg * 16);
+#pragma unroll
+                    for (int s = 0; s < KS; ++s) {
+                        const int4 v = *reinterpret_cast<const int4*>(seg_rows + (off + 64u * s));
+                        w.b[h][s] = v4i{v.x, v.y, v.z, v.w};
                     }
-                    for (int blk = blk_first; blk < blk_end; blk += S) {
-                        const int lrow = (blk / S) * 16;
-                        v4i areg[KS];
-                        {
-                            const int r = lrow + l16;
-                            const int8_t* qp = s_q + r * D;
-                            const int sw = swz<KS>(r);
+                    w.si[h] = seg_scale[(uint32_t)w.item[h]];
+                }
+            }
+        };
+        auto wi_compute = [&](const WorkRegs<KS>& w, int gi, int b0, int n) {
+            const int g = g0 + gi;
+            const int blk_end = s_blkoff[g + 1];
+            int blk_first = s_blkoff[g];
+            blk_first += ((y - blk_first) % S + S) % S;  // first block of the group owned by this y
+            for (int blk = blk_first; blk < blk_end; blk += S) {
+                const int lrow = (blk / S) * 16;
+                v4i areg[KS];
+                {
+                    const int r = lrow + l16;
+                    const int8_t* qp = s_q + r * D;
+                    const int sw = swz<KS>(r);
 #pragma unroll
-                            for (int s = 0; s < KS; ++s) {
-                                const int4 v = *reinterpret_cast<const int4*>(qp + (((kg + 4 * s) ^ sw) << 4));
-                                areg[s] = v4i{v.x, v.y, v.z, v.w};
+                    for (int s = 0; s < KS; ++s) {
+                        const int4 v = *reinterpret_cast<const int4*>(qp + (((kg + 4 * s) ^ sw) << 4));
+                        areg[s] = v4i{v.x, v.y, v.z, v.w};
+                    }
+                }
+                const int row4 = lrow + 4 * kg;
+                const float4 sq4 = *reinterpret_cast<const float4*>(s_sq + row4);
+                const float4 tf4 = *reinterpret_cast<const float4*>(s_tauf + row4);
+                const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
+                const float tfv[4] = {tf4.x, tf4.y, tf4.z, tf4.w};
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    if (b0 + h * 16 < n) {
+                        v4i acc = {0, 0, 0, 0};
+#pragma unroll
+                        for (int s = 0; s < KS; ++s)
+                            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(areg[s], w.b[h][s], acc, 0, 0, 0);
+                        float sc[4];
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si[h]);
+                        if (p.weighted) {
+                            // Value-Model sum over the TT tasks of each query this lane holds
+#pragma unroll
+                            for (int q0 = 0; q0 < 4; q0 += TT) {
+                                float agg = 0.0f;
+#pragma unroll
+                                for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
+                                sc[q0] = agg;
                             }
                         }
-                        const int row4 = lrow + 4 * kg;
-                        const float4 sq4 = *reinterpret_cast<const float4*>(s_sq + row4);
-                        const float4 tf4 = *reinterpret_cast<const float4*>(s_tauf + row4);
-                        const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
-                        const float tfv[4] = {tf4.x, tf4.y, tf4.z, tf4.w};
+                        bool any = false;
 #pragma unroll
-                        for (int sb = 0; sb < 4; ++sb) {
-                            if (sb < nsb) {
-                                v4i acc = {0, 0, 0, 0};
+                        for (int r = 0; r < 4; r += TT) any = any || (sc[r] >= tfv[r]);
+                        if (any && w.valid[h]) {
+                            const int64_t it = item0 + w.item[h];
 #pragma unroll
-                                for (int s = 0; s < KS; ++s)
-                                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(areg[s], breg[sb][s], acc, 0, 0, 0);
-                                float sc[4];
-#pragma unroll
-                                for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], si[sb]);
-                                if (p.weighted) {
-                                    // Value-Model sum over the TT tasks of each query this lane holds
-#pragma unroll
-                                    for (int q0 = 0; q0 < 4; q0 += TT) {
-                                        float agg = 0.0f;
-#pragma unroll
-                                        for (int t = 0; t < TT; ++t) agg = __fmaf_rn(p.w[t], sc[q0 + t], agg);
-                                        sc[q0] = agg;
+                            for (int r = 0; r < 4; r += TT) {
+                                const int grow = s_qrow[row4 + r];
+                                if (sc[r] >= tfv[r] && grow >= 0) {
+                                    const uint64_t key = make_key(sc[r], (uint32_t)it);
+                                    if (key >= s_tau64[(row4 + r) / TT]) {
+                                        const uint32_t at = atomicAdd(&s_cnt[(row4 + r) / TT], 1u);
+                                        if (at < (uint32_t)p.cap)
+                                            p.cand[((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at] = key;
                                     }
                                 }
-#pragma unroll
-                                for (int r = 0; r < 4; r += TT) {
-                                    if (sc[r] >= tfv[r]) {
-                                        const int grow = s_qrow[row4 + r];
-                                        if (valid[sb] && grow >= 0) {
-                                            const int q = grow / TT;
-                                            const uint64_t key = make_key(sc[r], (uint32_t)item[sb]);
-                                            if (!p.use_tau || key >= p.tau[q]) {
-                                                const uint32_t slot = atomicAdd(&s_cnt[(row4 + r) / TT], 1u);
-                                                if (slot < (uint32_t)p.cap)
-                                                    p.cand[((int64_t)q * p.groups + wg_lin) * p.cap + slot] = key;
-                                            }
-                                        }
-                                    }
-                                }
                             }
                         }
                     }
                 }
             }
-            __syncthreads();
+        };
+        // iterate the work items with two register sets, A holding even ones, B odd ones
+        int gi_a = 0, b0_a = 0;
+        auto skip_empty = [&](int& gi, int& b0) {
+            while (gi < nf && b0 >= n_of(gi)) { ++gi; b0 = 0; }
+        };
+        auto advance = [&](int& gi, int& b0) { b0 += 32; skip_empty(gi, b0); };
+        skip_empty(gi_a, b0_a);
+        WorkRegs<KS> ra, rb;
+        if (gi_a < nf) wi_load(ra, gi_a, b0_a, n_of(gi_a));
+        while (gi_a < nf) {
+            int gi_b = gi_a, b0_b = b0_a;
+            advance(gi_b, b0_b);
+            if (gi_b < nf) wi_load(rb, gi_b, b0_b, n_of(gi_b));
+            wi_compute(ra, gi_a, b0_a, n_of(gi_a));
+            if (gi_b >= nf) break;
+            gi_a = gi_b; b0_a = b0_b;
+            advance(gi_a, b0_a);
+            if (gi_a < nf) wi_load(ra, gi_a, b0_a, n_of(gi_a));
+            wi_compute(rb, gi_b, b0_b, n_of(gi_b));
         }
     }
     __syncthreads();
@@ -241,25 +346,26 @@ inline int mfma_q_split(int n_blocks, int d)
     return S;
 }
 
-inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int seg_items)
+inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups)
 {
     const int blocks_local = (mp->n_blocks + mp->q_split - 1) / mp->q_split;
     mp->rows_local = blocks_local * 16;
-    int off = mp->rows_local * d;
+    int off = 0;
     auto take = [&](int bytes) { int o = off; off = (off + bytes + 15) / 16 * 16; return o; };
-    take(0);
+    take(mp->rows_local * d);  // resident queries at offset 0
     mp->lds_sq = take(mp->rows_local * 4);
     mp->lds_tauf = take(mp->rows_local * 4);
+    mp->lds_tau64 = take((mp->rows_local / n_tasks + 1) * 8);
     mp->lds_qrow = take(mp->rows_local * 4);
     mp->lds_cnt = take((mp->rows_local / n_tasks + 1) * 4);
-    mp->lds_mask = take(kMfmaFilterBatch * kTileWords * 8);
-    mp->lds_list = take(kMfmaFilterBatch * seg_items * 2);
-    mp->lds_listcnt = take(kMfmaFilterBatch * 4);
+    mp->lds_list = take(kMfmaWaves * kMfmaFilterBatch * kMfmaSegItems);
+    mp->lds_prow = take(n_groups * kPrefetchRows * 4);
+    mp->lds_blkoff = take((n_groups + 1) * 4);
     mp->lds_total = off;
 }
 
 template <int KS, int TT>
-inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp, hipStream_t stream)
+inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
     static int max_set = 0;  // largest dynamic LDS size this instantiation has been allowed
     if (mp.lds_total > max_set) {
@@ -268,16 +374,18 @@ inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp,
         if (e != hipSuccess) return e;
         max_set = mp.lds_total;
     }
-    const dim3 grid((unsigned)(sp.groups / mp.q_split), (unsigned)mp.q_split);
+    const dim3 grid((unsigned)gx, (unsigned)mp.q_split);
     hipLaunchKernelGGL((scan_mfma_kernel<KS, TT>), grid, dim3(kScanThreads), (size_t)mp.lds_total, stream, sp, mp);
     return hipGetLastError();
 }
 
-inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, hipStream_t stream)
+// gx = workgroups per row of the grid (at most groups / q_split); region index = x + y * gx
+inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
+    if (sp.seg_items > mfma_max_seg_items(sp.d) || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
     const int ks = sp.d / 64, tt = sp.n_tasks;
 #define ST_CASE(K_, T_) \
-    if (ks == K_ && tt == T_) return launch_scan_mfma_t<K_, T_>(sp, mp, stream);
+    if (ks == K_ && tt == T_) return launch_scan_mfma_t<K_, T_>(sp, mp, gx, stream);
     ST_CASE(1, 1) ST_CASE(1, 2) ST_CASE(1, 4)
     ST_CASE(2, 1) ST_CASE(2, 2) ST_CASE(2, 4)
     ST_CASE(4, 1) ST_CASE(4, 2) ST_CASE(4, 4)

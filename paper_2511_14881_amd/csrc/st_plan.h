@@ -10,17 +10,20 @@
 #pragma once
 #include <stdint.h>
 #include <stddef.h>
+#include <stdlib.h>
 
 namespace st {
 
-constexpr int kScanGroups = 512;     // persistent workgroups of the scan kernel (2 per CU on MI355X)
+constexpr int kScanGroups = 1024;    // persistent workgroups of the scan kernel (4 per CU on MI355X)
+constexpr int kMaxScanGroups = 2048;
 constexpr int kMaxLevels = 32;
 constexpr int kMaxSegItems = 512;    // items one workgroup takes per step, at most
-constexpr int kLdsSortMax = 4096;    // top-K lists up to this (padded) size are sorted in LDS
+constexpr int kLdsSortMax = 2048;    // top-K lists up to this (padded) size are sorted in LDS
 
 struct Level {
-    int64_t begin, end;  // item range [begin, end)
-    int32_t seg_items;   // items one workgroup takes per step (multiple of 64, divides 1024)
+    int64_t begin, end;      // item range [begin, end)
+    int32_t seg_items;       // items one workgroup stages per step (multiple of 64, divides 1024)
+    int32_t seg_per_visit;   // consecutive segments a workgroup takes before striding on
 };
 
 struct Plan {
@@ -39,24 +42,39 @@ inline int32_t pow2_ceil(int32_t v)
     return p;
 }
 
+// Workgroups the scan kernels are launched with (fixes the candidate-region layout).  The
+// environment variable ST_SCAN_GROUPS overrides the default for tuning runs: a power of two
+// between 64 and 2048, read once per process.
 inline int scan_groups()
 {
-    return kScanGroups;
+    static int g = 0;
+    if (g == 0) {
+        g = kScanGroups;
+        const char* e = getenv("ST_SCAN_GROUPS");
+        if (e) {
+            const int v = atoi(e);
+            if (v >= 64 && v <= kMaxScanGroups && (v & (v - 1)) == 0) g = v;
+        }
+    }
+    return g;
 }
 
 // Levels for a given region capacity.  g_eff = workgroups that share one query's candidates
 // (all of them, unless the query rows are split over several workgroup rows).
-inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, Plan* out)
+inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, int32_t seg_cap, Plan* out)
 {
     Plan p;
     p.groups = scan_groups();
     p.cap = cap;
     p.n_levels = 0;
-    if (cap > kMaxSegItems || g_eff < 1) return -1;
-    // level 0 hands each workgroup at most one segment of `cap` items, so no region can overflow
+    if (cap > kMaxSegItems || g_eff < 1 || seg_cap < 64 || seg_cap > kMaxSegItems || (seg_cap & (seg_cap - 1)))
+        return -1;
+    // level 0 hands each workgroup at most `cap` consecutive items (one visit), so no region can
+    // overflow
     int64_t n0 = (int64_t)g_eff * cap;
     if (n0 > n_items) n0 = n_items;
-    p.level[p.n_levels++] = Level{0, n0, cap};
+    const int32_t seg0 = cap < seg_cap ? cap : seg_cap;
+    p.level[p.n_levels++] = Level{0, n0, seg0, cap / seg0};
     int64_t cur = n0;
     // expected admissions per region in a level that grows the scanned prefix by `grow` are
     // K*(grow-1)/g_eff; aim at cap/4.  Never grow by less than 2x (extreme K with few sharing
@@ -69,9 +87,11 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, P
         int64_t nxt = want >= (double)n_items ? n_items : (int64_t)want;
         if (nxt < n_items) nxt = nxt / 1024 * 1024;
         if (nxt <= cur) nxt = cur + 1024 < n_items ? cur + 1024 : n_items;
-        int32_t seg = kMaxSegItems;
-        while (seg > 64 && (nxt - cur) / seg < 2 * (int64_t)g_eff) seg >>= 1;
-        p.level[p.n_levels++] = Level{cur, nxt, seg};
+        // large segments fill the 16-item MFMA tiles best; shrink them only when the level would
+        // otherwise occupy fewer than about eight wavefronts per compute unit
+        int32_t seg = seg_cap;
+        while (seg > 64 && (nxt - cur) / seg < 2048) seg >>= 1;
+        p.level[p.n_levels++] = Level{cur, nxt, seg, 4};  // one segment per wavefront of the workgroup
         cur = nxt;
     }
     *out = p;
@@ -88,18 +108,33 @@ inline int choose_cap(int64_t n_items, int32_t K)
         // the slow exact path appends into a buffer of K + groups*cap keys, a tile at a time
         if ((int64_t)scan_groups() * cap < 2 * (int64_t)K + 2048) continue;
         Plan p;
-        if (make_levels(n_items, K, cap, scan_groups(), &p) != 0) continue;
+        if (make_levels(n_items, K, cap, scan_groups(), kMaxSegItems, &p) != 0) continue;
         best = cap;
         if (p.n_levels <= 3) break;
     }
     return best;
 }
 
-inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, Plan* out)
+// Largest segment the planner may use; ST_SEG_ITEMS overrides it for tuning runs.
+inline int seg_limit(int32_t seg_cap)
+{
+    static int e = -1;
+    if (e < 0) {
+        e = 0;
+        const char* s = getenv("ST_SEG_ITEMS");
+        if (s) {
+            const int v = atoi(s);
+            if (v >= 64 && v <= kMaxSegItems && (v & (v - 1)) == 0) e = v;
+        }
+    }
+    return e > 0 && e < seg_cap ? e : seg_cap;
+}
+
+inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, Plan* out)
 {
     const int cap = choose_cap(n_items, K);
     if (cap < 0 || q_split < 1 || scan_groups() % q_split) return -1;
-    return make_levels(n_items, K, cap, scan_groups() / q_split, out);
+    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_limit(seg_cap), out);
 }
 
 // Byte offsets of the pieces of the device workspace.

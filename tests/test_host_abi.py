@@ -53,11 +53,11 @@ def test_index_size_is_items_times_bits_over_eight():
 @pytest.mark.parametrize("q_split", [1, 2, 8])
 def test_schedule_covers_the_corpus_once(n, B, K, q_split):
     levels, groups, cap = st.st_search_plan(n, B, K, q_split)
-    assert groups == 512 and cap in (64, 128, 256, 512)
+    assert groups == 1024 and cap in (64, 128, 256, 512)
     assert groups * cap >= 2 * K + 2048
     assert levels[0, 0] == 0 and levels[-1, 1] == n
     for i, (b, e, seg) in enumerate(levels):
-        assert e >= b and 1024 % seg == 0 and seg % 64 == 0 and b % seg == 0 and seg <= 512
+        assert e >= b and seg % 64 == 0 and seg <= 2048  # seg = items a workgroup takes per visit
         if i:
             assert b == levels[i - 1, 1] and e > b and b % 1024 == 0
     # level 0: one segment of `cap` items per workgroup at most, so its regions cannot overflow
