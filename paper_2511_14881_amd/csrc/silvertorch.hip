@@ -443,7 +443,7 @@ int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int
     if (K < 1 || K > ST_MAX_TOP_K) return fail(ST_EINVAL, "K=%d out of range", K);
     st::Plan p;
     if (st::make_plan(n_items, K, 1, st::kMaxSegItems, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
-    return (int64_t)st::make_layout(p, batch, K).total;
+    return (int64_t)st::make_layout(p, batch, K, d, n_tasks).total;
 }
 
 static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
@@ -521,7 +521,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     st::Plan plan1;
     if (st::make_plan(n_items, K, 1, st::kMaxSegItems, &plan1) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
-    const st::Layout L = st::make_layout(plan1, batch, K);  // layout depends on sizes only
+    const st::Layout L = st::make_layout(plan1, batch, K, d, n_tasks);  // layout depends on sizes only
 
     Blob blob;
     Groups& ga = groups;
@@ -530,6 +530,28 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     const size_t at_q2grp = blob.add(ga.q2grp);
     const SetAt at_m = add_set(blob, set_mfma), at_d = add_set(blob, set_dot);
     const size_t at_blk_off = blob.add(blk_off), at_blk_row = blob.add(blk_row);
+    // MFMA scorer: first signature rows of each of its filters (padded with -1), and where the
+    // selection kernel stores each query's threshold in the resident-query image
+    mp.q_split = std::max(mp.q_split, 1);
+    const int32_t rows_local = ((mp.n_blocks + mp.q_split - 1) / mp.q_split) * 16;
+    std::vector<int32_t> prow((size_t)set_mfma.n * st::kPrefetchRows + 1, -1), q_taupos(batch, -1);
+    for (int32_t g = 0; g < set_mfma.n; ++g) {
+        const int32_t nr = set_mfma.row_off[g + 1] - set_mfma.row_off[g];
+        for (int32_t r = 0; r < nr && r < st::kPrefetchRows; ++r)
+            prow[(size_t)g * st::kPrefetchRows + r] = set_mfma.rows[set_mfma.row_off[g] + r];
+        if (g < st::kMfmaFilterBatch) {
+            for (int32_t r = 0; r < nr && r < st::kPrefetchRows; ++r)
+                mp.prow_pack[g][r / 4] |= (uint64_t)(uint16_t)set_mfma.rows[set_mfma.row_off[g] + r] << (16 * (r % 4));
+            mp.prow_n |= (uint64_t)std::min<int32_t>(nr, st::kPrefetchRows) << (8 * g);
+        }
+    }
+    for (size_t i = 0; i < blk_row.size(); ++i)
+        if (blk_row[i] >= 0 && blk_row[i] % n_tasks == 0) {
+            const int32_t b = (int32_t)(i / 16), yy = b % mp.q_split, lr = (b / mp.q_split) * 16 + (int32_t)(i % 16);
+            q_taupos[blk_row[i] / n_tasks] = yy * (rows_local / n_tasks) + lr / n_tasks;
+        }
+    if ((size_t)rows_local * mp.q_split > L.img_rows) return fail(ST_EINVAL, "resident-query image too small");
+    const size_t at_prow = blob.add(prow), at_taupos = blob.add(q_taupos);
     if (blob.bytes() > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
 
     char* ws = (char*)dev_workspace;
@@ -562,6 +584,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp.ovf = (uint32_t*)(ws + L.ovf);
     sp.cap = plan.cap;
     sp.groups = plan.groups;
+    { const char* e = getenv("ST_DEBUG_STOP"); sp.debug_stop = e ? atoi(e) : 0; }
 
     st::ScanParams sp_m = sp, sp_d = sp, sp_all = sp;
     sp_m.n_groups = set_mfma.n;
@@ -581,6 +604,11 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp_all.grp_q = tab(at_all_q);
     mp.grp_blk_off = tab(at_blk_off);
     mp.blk_row = tab(at_blk_row);
+    mp.prow = tab(at_prow);
+    mp.img_q = (int8_t*)(ws + L.img_q);
+    mp.img_sq = (float*)(ws + L.img_sq);
+    mp.img_qrow = (int32_t*)(ws + L.img_qrow);
+    mp.img_tau = (uint64_t*)(ws + L.img_tau);
 
     st::SelectParams se;
     memset(&se, 0, sizeof(se));
@@ -603,6 +631,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
 
     se.scan = sp_all;
     se.q2grp = tab(at_q2grp);
+    se.tau_img = set_mfma.n ? mp.img_tau : nullptr;
+    se.q_taupos = tab(at_taupos);
     for (int lv = 0; lv < plan.n_levels; ++lv) {
         const st::Level& L_ = plan.level[lv];
         for (st::ScanParams* q : {&sp_m, &sp_d}) {
@@ -622,6 +652,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             if (!set_dot.n && n_visit < gx) gx = (int32_t)std::max<int64_t>(n_visit, 1);
             regions = set_dot.n ? plan.groups : gx * mp.q_split;
             st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n);
+            mp.first_level = lv == 0;
             TimedLaunch t(0, stream);
             ST_HIP(st::launch_scan_mfma(sp_m, mp, gx, stream));
         }

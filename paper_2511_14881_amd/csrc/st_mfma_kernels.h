@@ -8,10 +8,10 @@
 //      the next segment are fetched while the current one is scored),
 //   2. the set bits of each filter's words become a dense list of passing items (wave-private
 //      LDS),
-//   3. 32 passing items of one filter at a time go straight from HBM into the B operand (the
-//      loads of the next 32 are in flight while the current ones are multiplied) and are
-//      contracted with the filter group's query blocks; scores that reach the query's
-//      threshold are admitted to the workgroup's candidate region.
+//   3. 16 passing items of one filter at a time go straight from HBM into the B operand (a ring
+//      of register slots keeps the loads of the next units in flight while the current one is
+//      multiplied) and are contracted with the filter group's query blocks; scores that reach
+//      the query's threshold are admitted to the workgroup's candidate region.
 //
 // Contraction layout per MFMA (M = 16 query rows, N = 16 items, K = 64 bytes of the embedding):
 //   A (queries): lane l supplies row (l % 16), bytes [16*(l/16), +16) of the 64-byte k-step
@@ -27,10 +27,10 @@ namespace st {
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaFilterBatch = 8;        // distinct filters handled per pass over a segment
+constexpr int kPrefetchRows = 8;           // signature rows per filter whose next-segment words are prefetched
 constexpr int kMfmaQueryLds = 64 * 1024;   // LDS bytes for resident query rows per workgroup
 constexpr int kMfmaMinRows = 4;            // a group needs this many query rows to go to MFMA
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
-constexpr int kPrefetchRows = 8;           // signature rows per filter whose next-segment words are prefetched
 constexpr int kMfmaSegItems = 256;         // items per wavefront segment, at most (4 mask words x 8 filters = 32 lanes)
 constexpr int kMfmaWaves = kScanThreads / 64;
 
@@ -42,8 +42,21 @@ struct MfmaParams {
     int32_t n_blocks;            // all groups
     int32_t q_split;             // S: gridDim.y; block b belongs to y = b % S, local index b / S
     int32_t rows_local;          // 16 * blocks per y (max over y)
+    const int32_t* prow;         // [groups][kPrefetchRows] first signature rows of each filter, -1 padded
+    // The same rows for the first batch of filters, resident in the kernel arguments so that the
+    // very first Bloom words can be requested before anything has been read from memory:
+    // row r of filter g is bits [16*(r%4), +16) of prow_pack[g][r/4]; prow_n holds the row counts.
+    uint64_t prow_pack[kMfmaFilterBatch][2];
+    uint64_t prow_n;             // byte g = min(rows of filter g, kPrefetchRows)
+    // Resident-query image in the workspace: written by workgroup x = 0 of each row of the grid
+    // on the first level, read by every workgroup afterwards (one round trip instead of two).
+    int8_t* img_q;               // [S][rows_local][d]   swizzled as in LDS
+    float* img_sq;               // [S][rows_local]
+    int32_t* img_qrow;           // [S][rows_local]
+    uint64_t* img_tau;           // [S][rows_local / T]  written by the selection kernel
+    int32_t first_level;         // 1: build the resident state from the tables and write the image
     // dynamic LDS layout (byte offsets)
-    int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_prow, lds_blkoff, lds_total;
+    int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_prow, lds_blkoff, lds_rowoff, lds_total;
 };
 
 // chunk swizzle: keeps 16 consecutive rows of d bytes on distinct LDS banks when the 16 lanes
@@ -56,17 +69,18 @@ __device__ inline int swz(int row)
     return (row >> sh) & ((nch < 16 ? nch : 16) - 1);
 }
 
-// Item rows of one work item (up to 32 passing items of one filter group) in MFMA B layout.
+// Item rows of one unit (up to 16 passing items of one filter group) in MFMA B layout.
 template <int KS>
-struct WorkRegs {
-    v4i b[2][KS];
-    float si[2];
-    int item[2];    // item index relative to the segment start, of lane's item (l % 16) in each half
-    bool valid[2];
+struct UnitRegs {
+    v4i b[KS];
+    float si;
+    int item;    // lane's item (l % 16), relative to the segment start
+    int gi;      // filter within the batch (uniform)
+    bool valid;
 };
 
 template <int KS, int TT>
-__global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 4 : 2)) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
+__global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int D = KS * 64;
@@ -80,47 +94,13 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 4 : 2)) void scan_mfma_ker
     uint32_t* s_cnt = reinterpret_cast<uint32_t*>(lds + mp.lds_cnt);
     int* s_prow = reinterpret_cast<int*>(lds + mp.lds_prow);                // [groups][kPrefetchRows]
     int* s_blkoff = reinterpret_cast<int*>(lds + mp.lds_blkoff);            // [groups + 1]
+    int* s_rowoff = reinterpret_cast<int*>(lds + mp.lds_rowoff);            // [groups + 1]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
     const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
     const int l16 = lane & 15, kg = lane >> 4;
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
-
-    // ---- workgroup-wide set-up: tables and resident queries into LDS
-    for (int i = tid; i < p.n_groups * kPrefetchRows; i += kScanThreads) {
-        const int g = i / kPrefetchRows, r = i - g * kPrefetchRows;
-        const int r0 = p.grp_row_off[g], nr = p.grp_row_off[g + 1] - r0;
-        s_prow[i] = r < nr ? p.grp_rows[r0 + r] : -1;
-    }
-    for (int i = tid; i <= p.n_groups; i += kScanThreads) s_blkoff[i] = mp.grp_blk_off[i];
-    for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
-        const int b = (lr >> 4) * S + y;
-        const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
-        s_qrow[lr] = grow;
-        float sq = 0.0f, tf = __builtin_inff();
-        uint64_t t64 = 0ULL;
-        if (grow >= 0) {
-            sq = p.qscale[grow];
-            t64 = p.use_tau ? p.tau[grow / TT] : 0ULL;
-            tf = t64 ? key_score(t64) : -__builtin_inff();
-        }
-        s_sq[lr] = sq;
-        s_tauf[lr] = tf;
-        if ((lr % TT) == 0) {
-            s_cnt[lr / TT] = 0;
-            s_tau64[lr / TT] = t64;
-        }
-    }
-    for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) {
-        const int lr = i / CH, c = i - lr * CH;
-        const int b = (lr >> 4) * S + y;
-        const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
-        int4 v = make_int4(0, 0, 0, 0);
-        if (grow >= 0) v = reinterpret_cast<const int4*>(p.queries + (int64_t)grow * D)[c];
-        *reinterpret_cast<int4*>(s_q + lr * D + ((c ^ swz<KS>(lr)) << 4)) = v;
-    }
-    __syncthreads();
 
     // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
     // workgroup; inside a visit wavefront w takes segments w, w + 4, ...  Stages of a wavefront
@@ -172,16 +152,98 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 4 : 2)) void scan_mfma_ker
         uint64_t mask = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
 #pragma unroll
         for (int r = 0; r < kPrefetchRows; ++r) mask &= pre[r];
-        const int r0 = p.grp_row_off[g], nr = p.grp_row_off[g + 1] - r0;
+        const int r0 = s_rowoff[g], nr = s_rowoff[g + 1] - r0;
         if (nr > kPrefetchRows) {  // long filters: the remaining rows, not prefetched
             const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
             for (int r = kPrefetchRows; r < nr; ++r) mask &= base[(int64_t)p.grp_rows[r0 + r] * kTileWords];
         }
         return mask;
     };
-    if (n_stages > 0) prefetch_issue(0);
+    // ---- first Bloom words: rows from the kernel arguments, requested before any table is read
+    if (pair_lane && n_stages > 0) {
+        uint64_t lo = 0, hi = 0;
+        int nr = 0;
+#pragma unroll
+        for (int g = 0; g < FB; ++g)
+            if (pr_gi == g) {
+                lo = mp.prow_pack[g][0];
+                hi = mp.prow_pack[g][1];
+                nr = (int)((mp.prow_n >> (8 * g)) & 255);
+            }
+        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(0) * seg_items) >> 6) + pr_w;
+        if (pr_gi < p.n_groups && gw * 64 < item_lim) {
+            const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
+#pragma unroll
+            for (int r = 0; r < kPrefetchRows; ++r) {
+                const int row = (int)(((r < 4 ? lo : hi) >> (16 * (r & 3))) & 0xFFFF);
+                if (r < nr) pre[r] = base[(int64_t)row * kTileWords];
+            }
+        }
+    }
 
-    for (int t = 0; t < n_stages; ++t) {
+    if (p.debug_stop == 1) {  // TEMP: launch + epilogue only
+        for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) s_cnt[lr / TT] = 0;
+        __syncthreads();
+        for (int i = tid * TT; i < mp.n_blocks * 16; i += kScanThreads * TT) {
+            const int grow = mp.blk_row[i];
+            if (grow >= 0) p.cnt[(int64_t)(grow / TT) * p.groups + wg_lin] = 0;
+        }
+        return;
+    }
+    // ---- workgroup-wide set-up: tables and resident queries into LDS
+    for (int i = tid; i < p.n_groups * kPrefetchRows; i += kScanThreads) s_prow[i] = mp.prow[i];
+    for (int i = tid; i <= p.n_groups; i += kScanThreads) {
+        s_blkoff[i] = mp.grp_blk_off[i];
+        s_rowoff[i] = p.grp_row_off[i];
+    }
+    if (mp.first_level) {
+        for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
+            const int b = (lr >> 4) * S + y;
+            const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
+            s_qrow[lr] = grow;
+            s_sq[lr] = grow >= 0 ? p.qscale[grow] : 0.0f;
+            s_tauf[lr] = grow >= 0 ? -__builtin_inff() : __builtin_inff();
+            if ((lr % TT) == 0) {
+                s_cnt[lr / TT] = 0;
+                s_tau64[lr / TT] = 0ULL;
+            }
+        }
+        for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) {
+            const int lr = i / CH, c = i - lr * CH;
+            const int b = (lr >> 4) * S + y;
+            const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
+            int4 v = make_int4(0, 0, 0, 0);
+            if (grow >= 0) v = reinterpret_cast<const int4*>(p.queries + (int64_t)grow * D)[c];
+            *reinterpret_cast<int4*>(s_q + lr * D + ((c ^ swz<KS>(lr)) << 4)) = v;
+        }
+        __syncthreads();
+        if (blockIdx.x == 0) {  // publish the image for the later levels
+            int4* gq = reinterpret_cast<int4*>(mp.img_q + (int64_t)y * mp.rows_local * D);
+            for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) gq[i] = reinterpret_cast<const int4*>(s_q)[i];
+            for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
+                mp.img_sq[y * mp.rows_local + lr] = s_sq[lr];
+                mp.img_qrow[y * mp.rows_local + lr] = s_qrow[lr];
+            }
+        }
+    } else {
+        const int4* gq = reinterpret_cast<const int4*>(mp.img_q + (int64_t)y * mp.rows_local * D);
+        for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) reinterpret_cast<int4*>(s_q)[i] = gq[i];
+        for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
+            const int grow = mp.img_qrow[y * mp.rows_local + lr];
+            s_qrow[lr] = grow;
+            s_sq[lr] = mp.img_sq[y * mp.rows_local + lr];
+            const uint64_t t64 = mp.img_tau[y * (mp.rows_local / TT) + lr / TT];
+            s_tauf[lr] = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
+            if ((lr % TT) == 0) {
+                s_cnt[lr / TT] = 0;
+                s_tau64[lr / TT] = t64;
+            }
+        }
+        __syncthreads();
+    }
+
+
+    for (int t = 0; t < (p.debug_stop == 2 ? 0 : n_stages); ++t) {
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
         const int nf = min(FB, p.n_groups - g0);
@@ -207,48 +269,56 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 4 : 2)) void scan_mfma_ker
                 list[pos++] = (uint8_t)(pr_w * 64 + b);
             }
         }
-        // list sizes: the last word's lane of each filter holds the total
-        auto n_of = [&](int gi) { return __builtin_amdgcn_readlane(incl, gi * SW + SW - 1); };
+        // list size of filter gi -> lane gi; 16-item units per filter and their running sum
+        // (the shuffle runs in every lane: a lane switched off would read as 0 for the others)
+        const int last_word = __shfl(incl, (lane * SW + SW - 1) & 63);
+        const int gcount = lane < nf ? last_word : 0;
+        const int gunits = (gcount + 15) >> 4;
+        int ucum = gunits;  // inclusive over filters
+        for (int o = 1; o < FB; o <<= 1) {
+            const int v = __shfl_up(ucum, o);
+            if (lane >= o) ucum += v;
+        }
+        const int n_units = __builtin_amdgcn_readlane(ucum, FB - 1);
 
-        // (3) work items = (filter gi, 32 passing items from b0), in order; the item rows of the
-        // next work item are loaded while the current one is contracted
-        // uniform bases + 32-bit lane offsets: the segment's rows span at most 256 * D bytes
+        if (p.debug_stop == 3) continue;
+        // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
+        // register slots keeps the item rows of the next NB units in flight while one is
+        // contracted: uniform bases + 32-bit lane offsets (the segment spans at most 256 * D bytes)
         const char* seg_rows = reinterpret_cast<const char*>(p.items + item0 * D);
         const float* seg_scale = p.iscale + item0;
-        auto wi_load = [&](WorkRegs<KS>& w, int gi, int b0, int n) {
-            const uint8_t* list = s_list + gi * kMfmaSegItems;
+        auto unit_load = [&](UnitRegs<KS>& w, int u) {
+            const int gi = __popcll(__ballot(lane < nf && ucum <= u));  // filters wholly before unit u
+            const int b0 = (u - (__builtin_amdgcn_readlane(ucum, gi) - __builtin_amdgcn_readlane(gunits, gi))) << 4;
+            const int n = __builtin_amdgcn_readlane(gcount, gi);
+            w.gi = gi;
+            const int li = b0 + l16;
+            w.valid = li < n;
+            w.item = (int)s_list[gi * kMfmaSegItems + (w.valid ? li : b0)];
+            const uint32_t off = (uint32_t)(w.item * D + kg * 16);
 #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                if (b0 + h * 16 < n) {
-                    const int li = b0 + h * 16 + l16;
-                    w.valid[h] = li < n;
-                    w.item[h] = (int)list[w.valid[h] ? li : b0];
-                    const uint32_t off = (uint32_t)(w.item[h] * D + kg * 16);
-#pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-                        const int4 v = *reinterpret_cast<const int4*>(seg_rows + (off + 64u * s));
-                        w.b[h][s] = v4i{v.x, v.y, v.z, v.w};
-                    }
-                    w.si[h] = seg_scale[(uint32_t)w.item[h]];
-                }
+            for (int k = 0; k < KS; ++k) {
+                const int4 v = *reinterpret_cast<const int4*>(seg_rows + (off + 64u * k));
+                w.b[k] = v4i{v.x, v.y, v.z, v.w};
             }
+            w.si = seg_scale[(uint32_t)w.item];
         };
-        auto wi_compute = [&](const WorkRegs<KS>& w, int gi, int b0, int n) {
-            const int g = g0 + gi;
+        auto unit_compute = [&](const UnitRegs<KS>& w) {
+            const int g = g0 + w.gi;
             const int blk_end = s_blkoff[g + 1];
             int blk_first = s_blkoff[g];
             blk_first += ((y - blk_first) % S + S) % S;  // first block of the group owned by this y
             for (int blk = blk_first; blk < blk_end; blk += S) {
                 const int lrow = (blk / S) * 16;
-                v4i areg[KS];
+                v4i acc = {0, 0, 0, 0};
                 {
                     const int r = lrow + l16;
                     const int8_t* qp = s_q + r * D;
                     const int sw = swz<KS>(r);
 #pragma unroll
-                    for (int s = 0; s < KS; ++s) {
-                        const int4 v = *reinterpret_cast<const int4*>(qp + (((kg + 4 * s) ^ sw) << 4));
-                        areg[s] = v4i{v.x, v.y, v.z, v.w};
+                    for (int k = 0; k < KS; ++k) {
+                        const int4 v = *reinterpret_cast<const int4*>(qp + (((kg + 4 * k) ^ sw) << 4));
+                        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(v4i{v.x, v.y, v.z, v.w}, w.b[k], acc, 0, 0, 0);
                     }
                 }
                 const int row4 = lrow + 4 * kg;
@@ -256,67 +326,53 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 4 : 2)) void scan_mfma_ker
                 const float4 tf4 = *reinterpret_cast<const float4*>(s_tauf + row4);
                 const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
                 const float tfv[4] = {tf4.x, tf4.y, tf4.z, tf4.w};
+                float sc[4];
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    if (b0 + h * 16 < n) {
-                        v4i acc = {0, 0, 0, 0};
+                for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si);
+                if (p.weighted) {
+                    // Value-Model sum over the TT tasks of each query this lane holds
 #pragma unroll
-                        for (int s = 0; s < KS; ++s)
-                            acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(areg[s], w.b[h][s], acc, 0, 0, 0);
-                        float sc[4];
+                    for (int q0 = 0; q0 < 4; q0 += TT) {
+                        float agg = 0.0f;
 #pragma unroll
-                        for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si[h]);
-                        if (p.weighted) {
-                            // Value-Model sum over the TT tasks of each query this lane holds
+                        for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
+                        sc[q0] = agg;
+                    }
+                }
+                bool any = false;
 #pragma unroll
-                            for (int q0 = 0; q0 < 4; q0 += TT) {
-                                float agg = 0.0f;
+                for (int r = 0; r < 4; r += TT) any = any || (sc[r] >= tfv[r]);
+                if (any && w.valid && p.debug_stop != 4) {
+                    const int64_t it = item0 + w.item;
 #pragma unroll
-                                for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
-                                sc[q0] = agg;
-                            }
-                        }
-                        bool any = false;
-#pragma unroll
-                        for (int r = 0; r < 4; r += TT) any = any || (sc[r] >= tfv[r]);
-                        if (any && w.valid[h]) {
-                            const int64_t it = item0 + w.item[h];
-#pragma unroll
-                            for (int r = 0; r < 4; r += TT) {
-                                const int grow = s_qrow[row4 + r];
-                                if (sc[r] >= tfv[r] && grow >= 0) {
-                                    const uint64_t key = make_key(sc[r], (uint32_t)it);
-                                    if (key >= s_tau64[(row4 + r) / TT]) {
-                                        const uint32_t at = atomicAdd(&s_cnt[(row4 + r) / TT], 1u);
-                                        if (at < (uint32_t)p.cap)
-                                            p.cand[((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at] = key;
-                                    }
-                                }
+                    for (int r = 0; r < 4; r += TT) {
+                        const int grow = s_qrow[row4 + r];
+                        if (sc[r] >= tfv[r] && grow >= 0) {
+                            const uint64_t key = make_key(sc[r], (uint32_t)it);
+                            if (key >= s_tau64[(row4 + r) / TT]) {
+                                const uint32_t at = atomicAdd(&s_cnt[(row4 + r) / TT], 1u);
+                                if (at < (uint32_t)p.cap)
+                                    p.cand[((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at] = key;
                             }
                         }
                     }
                 }
             }
         };
-        // iterate the work items with two register sets, A holding even ones, B odd ones
-        int gi_a = 0, b0_a = 0;
-        auto skip_empty = [&](int& gi, int& b0) {
-            while (gi < nf && b0 >= n_of(gi)) { ++gi; b0 = 0; }
-        };
-        auto advance = [&](int& gi, int& b0) { b0 += 32; skip_empty(gi, b0); };
-        skip_empty(gi_a, b0_a);
-        WorkRegs<KS> ra, rb;
-        if (gi_a < nf) wi_load(ra, gi_a, b0_a, n_of(gi_a));
-        while (gi_a < nf) {
-            int gi_b = gi_a, b0_b = b0_a;
-            advance(gi_b, b0_b);
-            if (gi_b < nf) wi_load(rb, gi_b, b0_b, n_of(gi_b));
-            wi_compute(ra, gi_a, b0_a, n_of(gi_a));
-            if (gi_b >= nf) break;
-            gi_a = gi_b; b0_a = b0_b;
-            advance(gi_a, b0_a);
-            if (gi_a < nf) wi_load(ra, gi_a, b0_a, n_of(gi_a));
-            wi_compute(rb, gi_b, b0_b, n_of(gi_b));
+        constexpr int NB = KS <= 2 ? 8 : (KS == 4 ? 4 : 2);
+        UnitRegs<KS> ring[NB];
+#pragma unroll
+        for (int k = 0; k < NB; ++k)
+            if (k < n_units) unit_load(ring[k], k);
+        for (int base = 0; base < n_units; base += NB) {
+#pragma unroll
+            for (int k = 0; k < NB; ++k) {
+                const int u = base + k;
+                if (u < n_units) {
+                    unit_compute(ring[k]);
+                    if (u + NB < n_units) unit_load(ring[k], u + NB);
+                }
+            }
         }
     }
     __syncthreads();
@@ -361,6 +417,7 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups)
     mp->lds_list = take(kMfmaWaves * kMfmaFilterBatch * kMfmaSegItems);
     mp->lds_prow = take(n_groups * kPrefetchRows * 4);
     mp->lds_blkoff = take((n_groups + 1) * 4);
+    mp->lds_rowoff = take((n_groups + 1) * 4);
     mp->lds_total = off;
 }
 

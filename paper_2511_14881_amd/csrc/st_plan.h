@@ -148,6 +148,8 @@ struct Layout {
     size_t cand;              // uint64 [B][G][cap]
     size_t gath;              // uint64 [B][K + G*cap]  contiguous copy for selection
     size_t srt;               // uint64 [B][Kpad]       only when Kpad > kLdsSortMax
+    size_t img_q, img_sq, img_qrow, img_tau;  // resident-query image of the MFMA scorer
+    size_t img_rows;          // rows the image has room for
     size_t total;
     int64_t gath_cap;
     int32_t k_pad;
@@ -160,7 +162,7 @@ inline size_t meta_bound_bytes(int32_t batch)
     return (size_t)round_up(4096 + (size_t)batch * 720, 256);
 }
 
-inline Layout make_layout(const Plan& p, int32_t batch, int32_t K)
+inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 16, int32_t n_tasks = 1)
 {
     Layout L;
     size_t off = 0;
@@ -177,6 +179,13 @@ inline Layout make_layout(const Plan& p, int32_t batch, int32_t K)
     L.gath = take((size_t)batch * L.gath_cap * 8);
     L.k_pad = pow2_ceil(K);
     L.srt = take(L.k_pad > kLdsSortMax ? (size_t)batch * L.k_pad * 8 : 0);
+    // query rows padded to 16-row blocks per filter group (at most 128 groups use the image),
+    // and again to whole blocks per row of workgroups (at most 32 rows)
+    L.img_rows = (size_t)batch * n_tasks + 16 * 128 + 16 * 32;
+    L.img_q = take(L.img_rows * d);
+    L.img_sq = take(L.img_rows * 4);
+    L.img_qrow = take(L.img_rows * 4);
+    L.img_tau = take(L.img_rows * 8);
     L.total = off;
     return L;
 }

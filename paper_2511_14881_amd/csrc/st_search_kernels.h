@@ -46,6 +46,7 @@ struct ScanParams {
     uint32_t* ovf;               // [B]
     int32_t cap;
     int32_t groups;              // G (== gridDim.x)
+    int32_t debug_stop;          // TEMP profiling aid
 };
 
 // Score of one (query, item) pair from the item row held by this lane.
@@ -387,7 +388,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     __shared__ uint32_t s_off[kMaxScanGroups + 1];
     const int q = blockIdx.x, tid = threadIdx.x;
     constexpr int NT = kSelectThreads;
-    const uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
+    // counts are clamped to what the buffers can hold, whatever the memory says
+    uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
+    n_prev = n_prev < (uint32_t)p.K ? n_prev : (uint32_t)p.K;
     const bool overflowed = !p.first && p.ovf[q] != 0u;
     if (p.first && tid == 0) p.ovf[q] = 0u;
     if (p.last && overflowed) {  // uniform over the workgroup
@@ -402,7 +405,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     uint32_t mine = 0;
     for (int j = 0; j < per; ++j) {
         const int w = tid * per + j;
-        if (w < R) mine += cq[w];
+        if (w < R) mine += min(cq[w], (uint32_t)p.cap);
     }
     s_scan[tid] = mine;
     __syncthreads();
@@ -421,7 +424,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         for (int j = 0; j < per; ++j) {
             const int w = tid * per + j;
             if (w < R) {
-                const uint32_t c = cq[w];
+                const uint32_t c = min(cq[w], (uint32_t)p.cap);
                 const uint64_t* src = p.cand + ((int64_t)q * p.groups + w) * p.cap;
                 for (uint32_t i0 = 0; i0 < c; i0 += 4) {
                     uint64_t v[4];
