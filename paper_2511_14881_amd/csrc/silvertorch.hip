@@ -551,6 +551,9 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             q_taupos[blk_row[i] / n_tasks] = yy * (rows_local / n_tasks) + lr / n_tasks;
         }
     if ((size_t)rows_local * mp.q_split > L.img_rows) return fail(ST_EINVAL, "resident-query image too small");
+    int32_t max_local_blocks = 0;  // most query blocks one workgroup row holds of a single filter group
+    for (int32_t g = 0; g < set_mfma.n; ++g)
+        max_local_blocks = std::max(max_local_blocks, (blk_off[g + 1] - blk_off[g] + mp.q_split - 1) / mp.q_split);
     const size_t at_prow = blob.add(prow), at_taupos = blob.add(q_taupos);
     if (blob.bytes() > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
 
@@ -585,6 +588,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp.cap = plan.cap;
     sp.groups = plan.groups;
     { const char* e = getenv("ST_DEBUG_STOP"); sp.debug_stop = e ? atoi(e) : 0; }
+    { const char* e = getenv("ST_DEBUG_TS"); sp.debug_ts = e ? (uint64_t*)strtoull(e, nullptr, 0) : nullptr; }
 
     st::ScanParams sp_m = sp, sp_d = sp, sp_all = sp;
     sp_m.n_groups = set_mfma.n;
@@ -653,6 +657,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             regions = set_dot.n ? plan.groups : gx * mp.q_split;
             st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n);
             mp.first_level = lv == 0;
+            mp.ring_ok = (lv > 0 && max_local_blocks <= st::kRingMaxBlocks) ? 1 : 0;
             TimedLaunch t(0, stream);
             ST_HIP(st::launch_scan_mfma(sp_m, mp, gx, stream));
         }

@@ -20,6 +20,8 @@
 // so with T in {1, 2, 4} tasks the rows one lane holds are whole queries and the Value-Model
 // sum needs no cross-lane traffic.
 #pragma once
+#include <type_traits>
+
 #include "st_search_kernels.h"
 
 namespace st {
@@ -33,6 +35,8 @@ constexpr int kMfmaMinRows = 4;            // a group needs this many query rows
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
 constexpr int kMfmaSegItems = 256;         // items per wavefront segment, at most (4 mask words x 8 filters = 32 lanes)
 constexpr int kMfmaWaves = kScanThreads / 64;
+constexpr int kQueueSlots = 256;           // queued admissions per wavefront
+constexpr int kRingMaxBlocks = 3;          // query blocks per filter group up to which admissions are only queued in the row pipeline
 
 inline constexpr int mfma_max_seg_items(int) { return kMfmaSegItems; }
 
@@ -55,8 +59,9 @@ struct MfmaParams {
     int32_t* img_qrow;           // [S][rows_local]
     uint64_t* img_tau;           // [S][rows_local / T]  written by the selection kernel
     int32_t first_level;         // 1: build the resident state from the tables and write the image
+    int32_t ring_ok;             // 1: thresholds are set and no group has more than kRingMaxBlocks local blocks
     // dynamic LDS layout (byte offsets)
-    int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_prow, lds_blkoff, lds_rowoff, lds_total;
+    int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_total;
 };
 
 // chunk swizzle: keeps 16 consecutive rows of d bytes on distinct LDS banks when the 16 lanes
@@ -74,18 +79,24 @@ template <int KS>
 struct UnitRegs {
     v4i b[KS];
     float si;
-    int item;    // lane's item (l % 16), relative to the segment start
+    int item;    // lane's item (l % 16), relative to the segment start; -1 = padding lane
     int gi;      // filter within the batch (uniform)
-    bool valid;
 };
 
-template <int KS, int TT>
-__global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
+#ifndef ST_MINW
+#define ST_MINW 4
+#endif
+#ifndef ST_NB2
+#define ST_NB2 3
+#endif
+template <int KS, int TT, bool WEIGHTED>
+__global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int D = KS * 64;
     constexpr int CH = D / 16;  // 16-byte chunks per row
     constexpr int FB = kMfmaFilterBatch;
+    constexpr int NB = KS == 1 ? 4 : (KS == 2 ? ST_NB2 : 2);  // ring slots (units with rows in flight)
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
@@ -93,14 +104,20 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_ker
     int* s_qrow = reinterpret_cast<int*>(lds + mp.lds_qrow);
     uint32_t* s_cnt = reinterpret_cast<uint32_t*>(lds + mp.lds_cnt);
     int* s_prow = reinterpret_cast<int*>(lds + mp.lds_prow);                // [groups][kPrefetchRows]
-    int* s_blkoff = reinterpret_cast<int*>(lds + mp.lds_blkoff);            // [groups + 1]
+    int* s_glrow = reinterpret_cast<int*>(lds + mp.lds_blkoff);             // [groups] first local query row of the group
+    int* s_gnblk = s_glrow + p.n_groups;                                    // [groups] local 16-row blocks of the group
     int* s_rowoff = reinterpret_cast<int*>(lds + mp.lds_rowoff);            // [groups + 1]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
     const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
+    uint64_t* ts = p.debug_ts ? p.debug_ts + ((int64_t)(p.use_tau ? 1 : 0) * 4096 + wg_lin) * 40 : nullptr;
+#define ST_TS(k) do { if (ts && tid == 0) ts[k] = wall_clock64(); } while (0)
+    ST_TS(0);
     const int l16 = lane & 15, kg = lane >> 4;
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
+    uint64_t* s_queue_key = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
+    int* s_queue_row = reinterpret_cast<int*>(lds + mp.lds_queue + kMfmaWaves * kQueueSlots * 8) + wave * kQueueSlots;
 
     // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
     // workgroup; inside a visit wavefront w takes segments w, w + 4, ...  Stages of a wavefront
@@ -181,20 +198,16 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_ker
         }
     }
 
-    if (p.debug_stop == 1) {  // TEMP: launch + epilogue only
-        for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) s_cnt[lr / TT] = 0;
-        __syncthreads();
-        for (int i = tid * TT; i < mp.n_blocks * 16; i += kScanThreads * TT) {
-            const int grow = mp.blk_row[i];
-            if (grow >= 0) p.cnt[(int64_t)(grow / TT) * p.groups + wg_lin] = 0;
-        }
-        return;
-    }
     // ---- workgroup-wide set-up: tables and resident queries into LDS
     for (int i = tid; i < p.n_groups * kPrefetchRows; i += kScanThreads) s_prow[i] = mp.prow[i];
-    for (int i = tid; i <= p.n_groups; i += kScanThreads) {
-        s_blkoff[i] = mp.grp_blk_off[i];
-        s_rowoff[i] = p.grp_row_off[i];
+    for (int g = tid; g <= p.n_groups; g += kScanThreads) {
+        s_rowoff[g] = p.grp_row_off[g];
+        if (g < p.n_groups) {  // the group's 16-row blocks that live in this row of workgroups
+            const int b0 = mp.grp_blk_off[g], b1 = mp.grp_blk_off[g + 1];
+            const int bf = b0 + ((y - b0) % S + S) % S;
+            s_gnblk[g] = bf < b1 ? (b1 - bf + S - 1) / S : 0;
+            s_glrow[g] = (bf / S) * 16;
+        }
     }
     if (mp.first_level) {
         for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
@@ -242,8 +255,15 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_ker
         __syncthreads();
     }
 
+    // lane constants of the MFMA operand reads: byte offset of this lane's chunk k inside a
+    // 16-row query block (the swizzle of row lrow + l16 depends on l16 only: lrow is a multiple
+    // of 16), and of its four rows in the per-row tables
+    int a_off[KS];
+#pragma unroll
+    for (int k = 0; k < KS; ++k) a_off[k] = l16 * D + (((kg + 4 * k) ^ swz<KS>(l16)) << 4);
 
-    for (int t = 0; t < (p.debug_stop == 2 ? 0 : n_stages); ++t) {
+    ST_TS(1);
+    for (int t = 0; t < n_stages; ++t) {
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
         const int nf = min(FB, p.n_groups - g0);
@@ -254,6 +274,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_ker
 #pragma unroll
         for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
         prefetch_issue(t + 1);
+        if (t == 0) ST_TS(2);
         const int c = __popcll(mask);
         int incl = c;  // running count over the words of my filter
         for (int o = 1; o < SW; o <<= 1) {
@@ -280,56 +301,102 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_ker
             if (lane >= o) ucum += v;
         }
         const int n_units = __builtin_amdgcn_readlane(ucum, FB - 1);
+        // first local query row and local block count of filter gi -> lane gi
+        const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
+        const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;
+        if (t == 0) ST_TS(3);
 
-        if (p.debug_stop == 3) continue;
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
         // contracted: uniform bases + 32-bit lane offsets (the segment spans at most 256 * D bytes)
-        const char* seg_rows = reinterpret_cast<const char*>(p.items + item0 * D);
+        const char* seg_rows = reinterpret_cast<const char*>(p.items + item0 * D) + kg * 16;
         const float* seg_scale = p.iscale + item0;
-        auto unit_load = [&](UnitRegs<KS>& w, int u) {
-            const int gi = __popcll(__ballot(lane < nf && ucum <= u));  // filters wholly before unit u
-            const int b0 = (u - (__builtin_amdgcn_readlane(ucum, gi) - __builtin_amdgcn_readlane(gunits, gi))) << 4;
-            const int n = __builtin_amdgcn_readlane(gcount, gi);
-            w.gi = gi;
-            const int li = b0 + l16;
-            w.valid = li < n;
-            w.item = (int)s_list[gi * kMfmaSegItems + (w.valid ? li : b0)];
-            const uint32_t off = (uint32_t)(w.item * D + kg * 16);
+        int qn = 0;          // queued admissions (uniform)
+        int cur_lrow = -1;   // query block held in areg / cur_sq / cur_tf
+        v4i areg[KS];
+        float4 cur_sq = make_float4(0.f, 0.f, 0.f, 0.f), cur_tf = cur_sq;
+
+        // unit generator: (gen_gi, gen_b0) is the next unit to request; it stays on the last unit
+        // once all have been produced, so that requests past the end are harmless repeats
+        int gen_gi = 0, gen_b0 = 0, gen_n = 0, gen_left = 0;
+        auto gen_seek = [&](int u) {  // position on unit u (cold)
+            gen_gi = __popcll(__ballot(lane < nf && ucum <= u));
+            gen_b0 = (u - (__builtin_amdgcn_readlane(ucum, gen_gi) - __builtin_amdgcn_readlane(gunits, gen_gi))) << 4;
+            gen_n = __builtin_amdgcn_readlane(gcount, gen_gi);
+            gen_left = n_units - 1 - u;
+        };
+        auto unit_load = [&](UnitRegs<KS>& w) {
+            const int li = gen_b0 + l16;
+            const int idx = (int)s_list[gen_gi * kMfmaSegItems + min(li, gen_n - 1)];
+            w.item = li < gen_n ? idx : -1;
+            w.gi = gen_gi;
+            const uint32_t off = (uint32_t)(idx * D);
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
                 const int4 v = *reinterpret_cast<const int4*>(seg_rows + (off + 64u * k));
                 w.b[k] = v4i{v.x, v.y, v.z, v.w};
             }
-            w.si = seg_scale[(uint32_t)w.item];
+            w.si = seg_scale[(uint32_t)idx];
+            if (gen_left > 0) {  // advance (scalar)
+                --gen_left;
+                gen_b0 += 16;
+                while (gen_b0 >= gen_n) {
+                    ++gen_gi;
+                    gen_b0 = 0;
+                    gen_n = __builtin_amdgcn_readlane(gcount, gen_gi);
+                }
+            }
         };
-        auto unit_compute = [&](const UnitRegs<KS>& w) {
-            const int g = g0 + w.gi;
-            const int blk_end = s_blkoff[g + 1];
-            int blk_first = s_blkoff[g];
-            blk_first += ((y - blk_first) % S + S) % S;  // first block of the group owned by this y
-            for (int blk = blk_first; blk < blk_end; blk += S) {
-                const int lrow = (blk / S) * 16;
-                v4i acc = {0, 0, 0, 0};
-                {
-                    const int r = lrow + l16;
-                    const int8_t* qp = s_q + r * D;
-                    const int sw = swz<KS>(r);
+        // Admissions are queued (wave-private LDS, positions from a ballot: no waiting) and
+        // drained 64 at a time, one candidate per lane, so that the LDS round trips of the
+        // counter update are paid once per 64 candidates instead of once per unit.
+        auto drain = [&]() {
+            if (lane < qn) {
+                const uint64_t key = s_queue_key[lane];
+                const int srow = s_queue_row[lane];  // local row of the query's first task
+                const int grow = s_qrow[srow];
+                if (grow >= 0 && key >= s_tau64[srow / TT]) {
+                    const uint32_t at = atomicAdd(&s_cnt[srow / TT], 1u);
+                    if (at < (uint32_t)p.cap)
+                        p.cand[((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at] = key;
+                }
+            }
+            if (qn > 64) {  // entries past the first 64 move to the front
+                uint64_t k2 = 0;
+                int r2 = 0;
+                if (lane + 64 < qn) { k2 = s_queue_key[lane + 64]; r2 = s_queue_row[lane + 64]; }
+                if (lane + 64 < qn) { s_queue_key[lane] = k2; s_queue_row[lane] = r2; }
+                qn -= 64;
+            } else {
+                qn = 0;
+            }
+        };
+        auto unit_compute = [&](const UnitRegs<KS>& w, auto drain_inside) {
+            const int lrow0 = __builtin_amdgcn_readlane(glrow, w.gi);
+            const int nblk = __builtin_amdgcn_readlane(gnblk, w.gi);
+            for (int j = 0; j < nblk; ++j) {
+                const int lrow = lrow0 + 16 * j;
+                if (lrow != cur_lrow) {  // query block operands stay in registers across units
+                    cur_lrow = lrow;
+                    const int8_t* qp = s_q + lrow * D;
 #pragma unroll
                     for (int k = 0; k < KS; ++k) {
-                        const int4 v = *reinterpret_cast<const int4*>(qp + (((kg + 4 * k) ^ sw) << 4));
-                        acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(v4i{v.x, v.y, v.z, v.w}, w.b[k], acc, 0, 0, 0);
+                        const int4 v = *reinterpret_cast<const int4*>(qp + a_off[k]);
+                        areg[k] = v4i{v.x, v.y, v.z, v.w};
                     }
+                    cur_sq = *reinterpret_cast<const float4*>(s_sq + lrow + 4 * kg);
+                    cur_tf = *reinterpret_cast<const float4*>(s_tauf + lrow + 4 * kg);
                 }
-                const int row4 = lrow + 4 * kg;
-                const float4 sq4 = *reinterpret_cast<const float4*>(s_sq + row4);
-                const float4 tf4 = *reinterpret_cast<const float4*>(s_tauf + row4);
-                const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
-                const float tfv[4] = {tf4.x, tf4.y, tf4.z, tf4.w};
+                v4i acc = {0, 0, 0, 0};
+#pragma unroll
+                for (int k = 0; k < KS; ++k)
+                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(areg[k], w.b[k], acc, 0, 0, 0);
+                const float sqv[4] = {cur_sq.x, cur_sq.y, cur_sq.z, cur_sq.w};
+                const float tfv[4] = {cur_tf.x, cur_tf.y, cur_tf.z, cur_tf.w};
                 float sc[4];
 #pragma unroll
                 for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si);
-                if (p.weighted) {
+                if (WEIGHTED) {
                     // Value-Model sum over the TT tasks of each query this lane holds
 #pragma unroll
                     for (int q0 = 0; q0 < 4; q0 += TT) {
@@ -339,43 +406,70 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_ker
                         sc[q0] = agg;
                     }
                 }
-                bool any = false;
 #pragma unroll
-                for (int r = 0; r < 4; r += TT) any = any || (sc[r] >= tfv[r]);
-                if (any && w.valid && p.debug_stop != 4) {
-                    const int64_t it = item0 + w.item;
-#pragma unroll
-                    for (int r = 0; r < 4; r += TT) {
-                        const int grow = s_qrow[row4 + r];
-                        if (sc[r] >= tfv[r] && grow >= 0) {
-                            const uint64_t key = make_key(sc[r], (uint32_t)it);
-                            if (key >= s_tau64[(row4 + r) / TT]) {
-                                const uint32_t at = atomicAdd(&s_cnt[(row4 + r) / TT], 1u);
-                                if (at < (uint32_t)p.cap)
-                                    p.cand[((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at] = key;
-                            }
+                for (int r = 0; r < 4; r += TT) {
+                    const bool hit = sc[r] >= tfv[r] && w.item >= 0;
+                    const uint64_t m = __ballot(hit);
+                    if (m) {  // uniform
+                        if (hit) {
+                            const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                            s_queue_key[pos] = make_key(sc[r], (uint32_t)(item0 + w.item));
+                            s_queue_row[pos] = lrow + 4 * kg + r;
+                        }
+                        qn += __popcll(m);
+                        if constexpr (decltype(drain_inside)::value) {
+                            if (qn >= 64) drain();
                         }
                     }
                 }
             }
         };
-        constexpr int NB = KS <= 2 ? 8 : (KS == 4 ? 4 : 2);
         UnitRegs<KS> ring[NB];
+        if (mp.ring_ok) {
+            // No store may sit inside the pipelined loop: on this target loads and stores share one
+            // outstanding-operation counter, and a store that may be pending makes every wait for a
+            // unit's rows wait for all younger loads as well.  Admissions are only queued here; when
+            // the queue could not take another unit the loop is left, the queue drained, and the
+            // ring restarted behind the last finished unit.  Every load in the loop is
+            // unconditional (requests past the end repeat the last unit): only then is the number
+            // of loads between a unit's request and its use a constant the compiler can wait on.
+            int u_next = 0;
+            while (u_next < n_units) {
+                gen_seek(u_next);
 #pragma unroll
-        for (int k = 0; k < NB; ++k)
-            if (k < n_units) unit_load(ring[k], k);
-        for (int base = 0; base < n_units; base += NB) {
+                for (int k = 0; k < NB; ++k) unit_load(ring[k]);
+                bool full = false;
+                for (int base = u_next; base < n_units && !full; base += NB) {
 #pragma unroll
-            for (int k = 0; k < NB; ++k) {
-                const int u = base + k;
-                if (u < n_units) {
-                    unit_compute(ring[k]);
-                    if (u + NB < n_units) unit_load(ring[k], u + NB);
+                    for (int k = 0; k < NB; ++k) {
+                        if (!full && base + k < n_units) {
+                            unit_compute(ring[k], std::false_type{});
+                            u_next = base + k + 1;
+                            full = qn > kQueueSlots - 64 * kRingMaxBlocks;
+                        }
+                        unit_load(ring[k]);
+                    }
+                }
+                while (qn > 0) drain();
+            }
+        } else if (n_units > 0) {
+            gen_seek(0);
+#pragma unroll
+            for (int k = 0; k < NB; ++k) unit_load(ring[k]);
+            for (int base = 0; base < n_units; base += NB) {
+#pragma unroll
+                for (int k = 0; k < NB; ++k) {
+                    if (base + k < n_units) unit_compute(ring[k], std::true_type{});
+                    unit_load(ring[k]);
                 }
             }
+            while (qn > 0) drain();
         }
     }
+    ST_TS(4);
     __syncthreads();
+    ST_TS(5);
     // region fill counts: real ones for the queries this workgroup row owns, zero for the others
     for (int i = tid * TT; i < mp.n_blocks * 16; i += kScanThreads * TT) {
         const int grow = mp.blk_row[i];
@@ -387,6 +481,8 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? 3 : 2)) void scan_mfma_ker
         p.cnt[(int64_t)q * p.groups + wg_lin] = c < (uint32_t)p.cap ? c : (uint32_t)p.cap;
         if (c > (uint32_t)p.cap) p.ovf[q] = 1u;
     }
+    ST_TS(6);
+#undef ST_TS
 }
 
 inline bool mfma_shape_ok(int d, int n_tasks)
@@ -415,24 +511,25 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups)
     mp->lds_qrow = take(mp->rows_local * 4);
     mp->lds_cnt = take((mp->rows_local / n_tasks + 1) * 4);
     mp->lds_list = take(kMfmaWaves * kMfmaFilterBatch * kMfmaSegItems);
+    mp->lds_queue = take(kMfmaWaves * kQueueSlots * 12);
     mp->lds_prow = take(n_groups * kPrefetchRows * 4);
-    mp->lds_blkoff = take((n_groups + 1) * 4);
+    mp->lds_blkoff = take((2 * n_groups + 2) * 4);
     mp->lds_rowoff = take((n_groups + 1) * 4);
     mp->lds_total = off;
 }
 
-template <int KS, int TT>
+template <int KS, int TT, bool WEIGHTED>
 inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
     static int max_set = 0;  // largest dynamic LDS size this instantiation has been allowed
     if (mp.lds_total > max_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, mp.lds_total);
         if (e != hipSuccess) return e;
         max_set = mp.lds_total;
     }
     const dim3 grid((unsigned)gx, (unsigned)mp.q_split);
-    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT>), grid, dim3(kScanThreads), (size_t)mp.lds_total, stream, sp, mp);
+    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED>), grid, dim3(kScanThreads), (size_t)mp.lds_total, stream, sp, mp);
     return hipGetLastError();
 }
 
@@ -441,8 +538,10 @@ inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, i
 {
     if (sp.seg_items > mfma_max_seg_items(sp.d) || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
     const int ks = sp.d / 64, tt = sp.n_tasks;
-#define ST_CASE(K_, T_) \
-    if (ks == K_ && tt == T_) return launch_scan_mfma_t<K_, T_>(sp, mp, gx, stream);
+#define ST_CASE(K_, T_)                                                                   \
+    if (ks == K_ && tt == T_)                                                             \
+        return sp.weighted ? launch_scan_mfma_t<K_, T_, true>(sp, mp, gx, stream)         \
+                           : launch_scan_mfma_t<K_, T_, false>(sp, mp, gx, stream);
     ST_CASE(1, 1) ST_CASE(1, 2) ST_CASE(1, 4)
     ST_CASE(2, 1) ST_CASE(2, 2) ST_CASE(2, 4)
     ST_CASE(4, 1) ST_CASE(4, 2) ST_CASE(4, 4)

@@ -47,6 +47,7 @@ struct ScanParams {
     int32_t cap;
     int32_t groups;              // G (== gridDim.x)
     int32_t debug_stop;          // TEMP profiling aid
+    uint64_t* debug_ts;          // TEMP profiling aid: [level][workgroup][8] timestamps
 };
 
 // Score of one (query, item) pair from the item row held by this lane.
