@@ -419,7 +419,7 @@ int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_spli
         K > ST_MAX_TOP_K || q_split < 1 || q_split > 32 || (q_split & (q_split - 1)))
         return fail(ST_EINVAL, "bad sizes");
     st::Plan p;
-    if (st::make_plan(n_items, K, q_split, st::kMaxSegItems, &p) != 0)
+    if (st::make_plan(n_items, K, q_split, st::kMaxSegItems, batch, &p) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     if (out_levels)
         for (int i = 0; i < p.n_levels && i < max_levels; ++i) {
@@ -442,7 +442,8 @@ int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int
     if (n_tasks < 1 || n_tasks > ST_MAX_TASKS) return fail(ST_EINVAL, "n_tasks=%d out of range", n_tasks);
     if (K < 1 || K > ST_MAX_TOP_K) return fail(ST_EINVAL, "K=%d out of range", K);
     st::Plan p;
-    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, &p) != 0) return fail(ST_EINVAL, "no schedule for these sizes");
+    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p) != 0)
+        return fail(ST_EINVAL, "no schedule for these sizes");
     return (int64_t)st::make_layout(p, batch, K, d, n_tasks).total;
 }
 
@@ -516,10 +517,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
 
     const int32_t seg_cap = set_mfma.n ? st::mfma_max_seg_items(d) : st::kMaxSegItems;
     st::Plan plan;
-    if (st::make_plan(n_items, K, mp.q_split, seg_cap, &plan) != 0)
+    if (st::make_plan(n_items, K, mp.q_split, seg_cap, batch * n_tasks, &plan) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
-    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, &plan1) != 0)
+    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     const st::Layout L = st::make_layout(plan1, batch, K, d, n_tasks);  // layout depends on sizes only
 
@@ -555,6 +556,15 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     for (int32_t g = 0; g < set_mfma.n; ++g)
         max_local_blocks = std::max(max_local_blocks, (blk_off[g + 1] - blk_off[g] + mp.q_split - 1) / mp.q_split);
     const size_t at_prow = blob.add(prow), at_taupos = blob.add(q_taupos);
+    // seed kernel: the first signature rows of every query's filter and their number
+    std::vector<int32_t> q_prow((size_t)batch * (st::kSeedRows + 1), -1);
+    for (int32_t b = 0; b < batch; ++b) {
+        const int32_t g = groups.q2grp[b], nr = groups.row_off[g + 1] - groups.row_off[g];
+        for (int32_t r = 0; r < nr && r < st::kSeedRows; ++r)
+            q_prow[(size_t)b * (st::kSeedRows + 1) + r] = groups.rows[groups.row_off[g] + r];
+        q_prow[(size_t)b * (st::kSeedRows + 1) + st::kSeedRows] = nr;
+    }
+    const size_t at_qprow = blob.add(q_prow);
     if (blob.bytes() > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
 
     char* ws = (char*)dev_workspace;
@@ -637,8 +647,17 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     se.q2grp = tab(at_q2grp);
     se.tau_img = set_mfma.n ? mp.img_tau : nullptr;
     se.q_taupos = tab(at_taupos);
+    se.q_prow = tab(at_qprow);
+    bool mfma_started = false;  // the first MFMA launch builds the resident-query image
     for (int lv = 0; lv < plan.n_levels; ++lv) {
         const st::Level& L_ = plan.level[lv];
+        se.first = lv == 0;
+        se.last = lv == plan.n_levels - 1;
+        if (L_.seed) {  // per-query scan + selection of the prefix in one launch
+            TimedLaunch t(1, stream);
+            ST_HIP(st::launch_seed(se, L_.end, batch, stream));
+            continue;
+        }
         for (st::ScanParams* q : {&sp_m, &sp_d}) {
             q->item_begin = L_.begin;
             q->item_end = L_.end;
@@ -656,7 +675,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             if (!set_dot.n && n_visit < gx) gx = (int32_t)std::max<int64_t>(n_visit, 1);
             regions = set_dot.n ? plan.groups : gx * mp.q_split;
             st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n);
-            mp.first_level = lv == 0;
+            mp.first_level = mfma_started ? 0 : 1;
+            mfma_started = true;
             mp.ring_ok = (lv > 0 && max_local_blocks <= st::kRingMaxBlocks) ? 1 : 0;
             TimedLaunch t(0, stream);
             ST_HIP(st::launch_scan_mfma(sp_m, mp, gx, stream));
@@ -667,12 +687,16 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                                (size_t)batch * 4, stream, sp_d);
             ST_HIP(hipGetLastError());
         }
-        se.first = lv == 0;
-        se.last = lv == plan.n_levels - 1;
         se.regions = regions;
         {
             TimedLaunch t(1, stream);
-            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), 0, stream, se);
+            static bool lds_set = false;
+            if (!lds_set) {
+                ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&st::select_kernel),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, st::kSelectLdsBytes));
+                lds_set = true;
+            }
+            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), st::kSelectLdsBytes, stream, se);
         }
         ST_HIP(hipGetLastError());
     }

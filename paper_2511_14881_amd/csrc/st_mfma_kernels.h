@@ -215,10 +215,11 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
             const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
             s_qrow[lr] = grow;
             s_sq[lr] = grow >= 0 ? p.qscale[grow] : 0.0f;
-            s_tauf[lr] = grow >= 0 ? -__builtin_inff() : __builtin_inff();
+            const uint64_t t64 = (grow >= 0 && p.use_tau) ? p.tau[grow / TT] : 0ULL;
+            s_tauf[lr] = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
             if ((lr % TT) == 0) {
                 s_cnt[lr / TT] = 0;
-                s_tau64[lr / TT] = 0ULL;
+                s_tau64[lr / TT] = t64;
             }
         }
         for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) {

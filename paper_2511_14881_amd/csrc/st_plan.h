@@ -24,6 +24,7 @@ struct Level {
     int64_t begin, end;      // item range [begin, end)
     int32_t seg_items;       // items one workgroup stages per step (multiple of 64, divides 1024)
     int32_t seg_per_visit;   // consecutive segments a workgroup takes before striding on
+    int32_t seed;            // 1: this prefix is handled by the per-query seed kernel
 };
 
 struct Plan {
@@ -61,7 +62,18 @@ inline int scan_groups()
 
 // Levels for a given region capacity.  g_eff = workgroups that share one query's candidates
 // (all of them, unless the query rows are split over several workgroup rows).
-inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, int32_t seg_cap, Plan* out)
+constexpr int kSeedItems = 32768;      // prefix the seed kernel scans (one workgroup per query)
+constexpr int kSeedMaxRows = 128;      // query rows (batch x tasks) up to which the seed kernel is used
+
+// Small batches start with a seed pass: one workgroup per query scans a short prefix on its own
+// and selects its top-K there, which replaces the first cooperative level and its selection.
+inline int64_t seed_items_for(int64_t n_items, int32_t batch_rows)
+{
+    return (batch_rows <= kSeedMaxRows && n_items >= 8 * (int64_t)kSeedItems) ? kSeedItems : 0;
+}
+
+inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, int32_t seg_cap, int64_t seed_items,
+                       Plan* out)
 {
     Plan p;
     p.groups = scan_groups();
@@ -74,7 +86,12 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
     int64_t n0 = (int64_t)g_eff * cap;
     if (n0 > n_items) n0 = n_items;
     const int32_t seg0 = cap < seg_cap ? cap : seg_cap;
-    p.level[p.n_levels++] = Level{0, n0, seg0, cap / seg0};
+    if (seed_items > 0) {
+        n0 = seed_items < n_items ? seed_items : n_items;
+        p.level[p.n_levels++] = Level{0, n0, 0, 0, 1};
+    } else {
+        p.level[p.n_levels++] = Level{0, n0, seg0, cap / seg0, 0};
+    }
     int64_t cur = n0;
     // expected admissions per region in a level that grows the scanned prefix by `grow` are
     // K*(grow-1)/g_eff; aim at cap/4.  Never grow by less than 2x (extreme K with few sharing
@@ -91,7 +108,7 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
         // otherwise occupy fewer than about eight wavefronts per compute unit
         int32_t seg = seg_cap;
         while (seg > 64 && (nxt - cur) / seg < 2048) seg >>= 1;
-        p.level[p.n_levels++] = Level{cur, nxt, seg, 4};  // one segment per wavefront of the workgroup
+        p.level[p.n_levels++] = Level{cur, nxt, seg, 4, 0};  // one segment per wavefront of the workgroup
         cur = nxt;
     }
     *out = p;
@@ -108,7 +125,7 @@ inline int choose_cap(int64_t n_items, int32_t K)
         // the slow exact path appends into a buffer of K + groups*cap keys, a tile at a time
         if ((int64_t)scan_groups() * cap < 2 * (int64_t)K + 2048) continue;
         Plan p;
-        if (make_levels(n_items, K, cap, scan_groups(), kMaxSegItems, &p) != 0) continue;
+        if (make_levels(n_items, K, cap, scan_groups(), kMaxSegItems, 0, &p) != 0) continue;
         best = cap;
         if (p.n_levels <= 3) break;
     }
@@ -130,11 +147,12 @@ inline int seg_limit(int32_t seg_cap)
     return e > 0 && e < seg_cap ? e : seg_cap;
 }
 
-inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, Plan* out)
+inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, Plan* out)
 {
     const int cap = choose_cap(n_items, K);
     if (cap < 0 || q_split < 1 || scan_groups() % q_split) return -1;
-    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_limit(seg_cap), out);
+    const int64_t seed = K <= kLdsSortMax ? seed_items_for(n_items, batch_rows) : 0;
+    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_limit(seg_cap), seed, out);
 }
 
 // Byte offsets of the pieces of the device workspace.
@@ -159,7 +177,7 @@ inline size_t meta_bound_bytes(int32_t batch)
 {
     // group tables (rows: at most 64 per query, twice: all groups and the per-scorer copies),
     // query lists, offsets, MFMA block tables (at most 16*(T/16 + 1) rows per query), slack
-    return (size_t)round_up(4096 + (size_t)batch * 720, 256);
+    return (size_t)round_up(4096 + (size_t)batch * 768, 256);
 }
 
 inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 16, int32_t n_tasks = 1)

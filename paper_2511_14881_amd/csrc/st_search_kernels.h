@@ -302,6 +302,146 @@ __device__ inline void write_result(const uint64_t* sorted, int n_out, int K, in
     if (threadIdx.x == 0) *out_count = n_out;
 }
 
+// Faster variant for keys that sit in LDS and fit in registers: every thread keeps up to
+// kTopkRegs keys in registers for all passes; a pass costs one barrier (three histograms rotate,
+// every wavefront scans the histogram for itself).  Requires n <= kTopkRegs * blockDim.x,
+// blockDim.x a multiple of 256 and at most 1024, k_pad <= room in sorted (LDS).
+constexpr int kTopkRegs = 16;
+
+__device__ inline int lds_topk(const uint64_t* keys, int n, int K, uint64_t* sorted, int k_pad,
+                               uint32_t* s_hist3 /*[3][256]*/, uint32_t* s_misc /*[8]*/, uint64_t* s_red /*[2*16]*/)
+{
+    const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wv = tid >> 6, nw = nt >> 6;
+    const int n_out = n < K ? n : K;
+    int P = 1;
+    while (P < n_out) P <<= 1;
+    if (P > k_pad) P = k_pad;
+    if (n <= K) {
+        for (int i = tid; i < P; i += nt) sorted[i] = i < n_out ? keys[i] : 0ULL;
+        __syncthreads();
+    } else {
+        uint64_t kr[kTopkRegs];
+        uint64_t lo = ~0ULL, hi = 0ULL;
+        const int ne = (n + nt - 1) / nt;  // register slots in use (uniform)
+#pragma unroll
+        for (int j = 0; j < kTopkRegs; ++j) {
+            const int i = tid + j * nt;
+            kr[j] = i < n ? keys[i] : 0ULL;  // 0 is below every real key
+            if (i < n) {
+                lo = kr[j] < lo ? kr[j] : lo;
+                hi = kr[j] > hi ? kr[j] : hi;
+            }
+        }
+        for (int o = 32; o > 0; o >>= 1) {
+            const uint64_t l2 = __shfl_xor((unsigned long long)lo, o), h2 = __shfl_xor((unsigned long long)hi, o);
+            lo = l2 < lo ? l2 : lo;
+            hi = h2 > hi ? h2 : hi;
+        }
+        if (lane == 0) { s_red[2 * wv] = lo; s_red[2 * wv + 1] = hi; }
+        for (int i = tid; i < 3 * 256; i += nt) s_hist3[i] = 0;
+        if (tid == 0) s_misc[2] = 0;
+        __syncthreads();
+        for (int w = 0; w < nw; ++w) {
+            const uint64_t l2 = s_red[2 * w], h2 = s_red[2 * w + 1];
+            lo = l2 < lo ? l2 : lo;
+            hi = h2 > hi ? h2 : hi;
+        }
+        const int top_shift = 56 - (__clzll((long long)(lo ^ hi)) >> 3) * 8;  // n > K >= 1: lo != hi
+        uint64_t prefix_mask = top_shift == 56 ? 0ULL : ~((1ULL << (top_shift + 8)) - 1ULL);
+        uint64_t prefix = hi & prefix_mask;
+        uint32_t want = (uint32_t)K;
+        int pass = 0;
+        for (int shift = top_shift; shift >= 0; shift -= 8, ++pass) {
+            uint32_t* hist = s_hist3 + (pass % 3) * 256;
+#pragma unroll
+            for (int j = 0; j < kTopkRegs; ++j)
+                if (j < ne && kr[j] && (kr[j] & prefix_mask) == prefix) atomicAdd(&hist[(kr[j] >> shift) & 255], 1u);
+            uint32_t* stale = s_hist3 + ((pass + 2) % 3) * 256;  // used two passes from now
+            if (tid < 256) stale[tid] = 0;
+            __syncthreads();
+            // every wavefront: lane l owns digits 255-4l .. 252-4l (descending)
+            uint32_t h[4], sum = 0;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { h[j] = hist[255 - 4 * lane - j]; sum += h[j]; }
+            uint32_t incl = sum;
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t v = __shfl_up(incl, o);
+                if (lane >= o) incl += v;
+            }
+            uint32_t before = incl - sum;
+            const bool mine = before < want && want <= incl;
+            uint32_t digit = 0, rest = 0, whole = 0;
+            if (mine) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    if (want > before && want <= before + h[j]) {
+                        digit = (uint32_t)(255 - 4 * lane - j);
+                        rest = want - before;
+                        whole = rest == h[j] ? 1u : 0u;
+                    }
+                    before += h[j];
+                }
+            }
+            const int src = __ffsll((long long)__ballot(mine)) - 1;  // exactly one lane
+            digit = __shfl(digit, src);
+            rest = __shfl(rest, src);
+            whole = __shfl(whole, src);
+            prefix |= (uint64_t)digit << shift;
+            prefix_mask |= 0xFFULL << shift;
+            want = rest;
+            if (whole) break;  // uniform: every wavefront computed the same
+        }
+        const uint64_t kth = prefix;  // keys are distinct: exactly K of them are >= kth
+#pragma unroll
+        for (int j = 0; j < kTopkRegs; ++j)
+            if (j < ne && kr[j] >= kth && kr[j]) {
+                const uint32_t slot = atomicAdd(&s_misc[2], 1u);
+                if (slot < (uint32_t)P) sorted[slot] = kr[j];
+            }
+        for (int i = K + tid; i < P; i += nt) sorted[i] = 0ULL;
+        __syncthreads();
+    }
+    if (P <= nt) {
+        uint64_t key = 0;
+        int rank = 0;
+        if (tid < P) {
+            key = sorted[tid];
+            if (P >= 8) {
+                for (int j = 0; j < P; j += 8) {  // eight reads in flight at a time
+                    uint64_t o[8];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) o[u] = sorted[j + u];
+#pragma unroll
+                    for (int u = 0; u < 8; ++u) rank += (o[u] > key || (o[u] == key && j + u < tid)) ? 1 : 0;
+                }
+            } else {
+                for (int j = 0; j < P; ++j) {
+                    const uint64_t o = sorted[j];
+                    rank += (o > key || (o == key && j < tid)) ? 1 : 0;
+                }
+            }
+        }
+        __syncthreads();
+        if (tid < P) sorted[rank] = key;
+        __syncthreads();
+        return n_out;
+    }
+    for (int k2 = 2; k2 <= P; k2 <<= 1) {
+        for (int j = k2 >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < P; i += nt) {
+                const int x = i ^ j;
+                if (x > i) {
+                    const uint64_t a = sorted[i], b = sorted[x];
+                    const bool desc = (i & k2) == 0;
+                    if (desc ? (a < b) : (a > b)) { sorted[i] = b; sorted[x] = a; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    return n_out;
+}
+
 struct SelectParams {
     const uint64_t* cand;   // [B][G][cap]
     const uint32_t* cnt;    // [B][G]
@@ -316,6 +456,7 @@ struct SelectParams {
     uint64_t* tau;          // [B] out
     uint64_t* tau_img;      // thresholds in the order of the scorer's resident query image, or null
     const int32_t* q_taupos;  // [B] position of each query in tau_img (-1: none)
+    const int32_t* q_prow;    // [B][kSeedRows + 1] first signature rows of each query's filter (-1 padded), then their count
     uint32_t* ovf;          // [B]
     int32_t first, last;
     int64_t* out_ids;       // [B][K]
@@ -327,7 +468,7 @@ struct SelectParams {
 };
 
 constexpr int kSelectThreads = 512;
-constexpr int kLdsKeys = 4096;  // candidates per query gathered in LDS; more go through global memory
+constexpr int kLdsKeys = 8192;  // candidates per query gathered in LDS; more go through global memory
 
 // Slow exact path for a query whose candidate region overflowed in some level: rescans the whole
 // corpus for that query alone, keeping at most gath_cap keys and pruning to the best K whenever
@@ -377,18 +518,24 @@ __device__ inline void rescue_query(const SelectParams& r, int q, uint64_t* s_so
 // (LDS when it fits), select and sort the best K, publish the K-th key as the next admission
 // threshold.  On the last level it writes the result rows, through the slow exact path if one
 // of the query's regions overflowed.
+static_assert(kLdsSortMax * 8 >= kLdsKeys * 2, "the sort buffer doubles as the seed kernel's 16-bit item list");
+constexpr int kSelectLdsBytes = kLdsKeys * 8 + kLdsSortMax * 8 + 3 * 256 * 4 + 64 * 8 + 64 * 4;
+
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
 {
-    __shared__ uint64_t s_keys[kLdsKeys];
-    __shared__ uint64_t s_sorted[kLdsSortMax];
-    __shared__ uint64_t s_red[2 * kSelectThreads / 64];
-    __shared__ uint64_t s_mask[kTileWords];
-    __shared__ uint32_t s_hist[256];
-    __shared__ uint32_t s_misc[8];
-    __shared__ uint32_t s_scan[kSelectThreads];
-    __shared__ uint32_t s_off[kMaxScanGroups + 1];
-    const int q = blockIdx.x, tid = threadIdx.x;
+    extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
+    uint64_t* s_keys = reinterpret_cast<uint64_t*>(sel_lds);                       // [kLdsKeys]
+    uint64_t* s_sorted = s_keys + kLdsKeys;                                        // [kLdsSortMax]
+    uint64_t* s_red = s_sorted + kLdsSortMax;                                      // [32]
+    uint64_t* s_mask = s_red + 32;                                                 // [16]
+    uint32_t* s_hist = reinterpret_cast<uint32_t*>(s_mask + 16);                   // [3][256]
+    uint32_t* s_misc = s_hist + 3 * 256;                                           // [8]
+    uint32_t* s_wsum = s_misc + 8;                                                 // [16]
+    const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     constexpr int NT = kSelectThreads;
+    uint64_t* ts = p.scan.debug_ts ? p.scan.debug_ts + (2 * 4096 * 40) + ((int64_t)(p.last ? 1 : 0) * 4096 + q) * 8 : nullptr;
+#define ST_TS(k) do { if (ts && tid == 0) ts[k] = wall_clock64(); } while (0)
+    ST_TS(0);
     // counts are clamped to what the buffers can hold, whatever the memory says
     uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
     n_prev = n_prev < (uint32_t)p.K ? n_prev : (uint32_t)p.K;
@@ -399,7 +546,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         return;
     }
 
-    // exclusive prefix sum of the region counts, NT threads x ceil(regions/NT) regions each
+    // exclusive prefix sum of the region counts: NT threads x ceil(regions/NT) regions each,
+    // shuffles inside a wavefront, one LDS exchange between the wavefronts
     const int R = p.regions;
     const int per = (R + NT - 1) / NT;
     const uint32_t* cq = p.cnt + (int64_t)q * p.groups;
@@ -408,20 +556,26 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         const int w = tid * per + j;
         if (w < R) mine += min(cq[w], (uint32_t)p.cap);
     }
-    s_scan[tid] = mine;
-    __syncthreads();
-    for (int o = 1; o < NT; o <<= 1) {
-        const uint32_t v = tid >= o ? s_scan[tid - o] : 0u;
-        __syncthreads();
-        s_scan[tid] += v;
-        __syncthreads();
+    uint32_t incl = mine;
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
     }
-    const uint32_t total = n_prev + s_scan[NT - 1];
+    if (lane == 63) s_wsum[wv] = incl;
+    __syncthreads();
+    uint32_t wbase = 0, all = 0;
+    for (int w = 0; w < NT / 64; ++w) {
+        const uint32_t v = s_wsum[w];
+        if (w < wv) wbase += v;
+        all += v;
+    }
+    const uint32_t total = n_prev + all;
+    ST_TS(1);
     const bool in_lds = total <= (uint32_t)kLdsKeys;
     uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
     {
         // each thread copies the entries of its own regions (loads independent of each other)
-        uint32_t off = n_prev + s_scan[tid] - mine;
+        uint32_t off = n_prev + wbase + incl - mine;
         for (int j = 0; j < per; ++j) {
             const int w = tid * per + j;
             if (w < R) {
@@ -449,10 +603,15 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         else gkeys[i] = v;
     }
     __syncthreads();
+    ST_TS(2);
 
-    const uint64_t* keys = in_lds ? s_keys : gkeys;
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
-    const int n_out = wg_topk(keys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
+    int n_out;
+    if (in_lds && !p.srt)
+        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red);
+    else
+        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
+    ST_TS(3);
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
         if (tid == 0) {
@@ -467,6 +626,209 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     } else {
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
+    }
+    ST_TS(4);
+    if (ts && tid == 0) ts[5] = total;
+#undef ST_TS
+}
+
+// Seed pass for small batches: one workgroup per query scans the prefix [0, seed_items) of the
+// corpus on its own -- Bloom test of every word at once, compaction, one lane per passing item
+// for the int8 dot products (Sec. 4.2) -- and selects its top-K there (Algorithm 1 phase 4 on the
+// prefix).  It leaves the running top-K and the admission threshold exactly as the first
+// cooperative level and its selection would, in one launch.
+constexpr int kSeedThreads = 512;
+constexpr int kSeedRows = 8;  // signature rows per query in the seed kernel's row table
+static_assert(kSeedItems / 64 <= kSeedThreads, "one Bloom word per thread");
+
+// D16 = d / 16 for d in {64, 128, 256} (item rows staged in registers, two items per thread in
+// flight), 0 = any other d (plain loop).
+template <int D16>
+__global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int64_t seed_items)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
+    uint64_t* s_keys = reinterpret_cast<uint64_t*>(sel_lds);                       // [kLdsKeys]
+    uint64_t* s_sorted = s_keys + kLdsKeys;                                        // [kLdsSortMax]
+    uint64_t* s_red = s_sorted + kLdsSortMax;                                      // [32]
+    uint64_t* s_mask = s_red + 32;                                                 // [16]
+    uint32_t* s_hist = reinterpret_cast<uint32_t*>(s_mask + 16);                   // [3][256]
+    uint32_t* s_misc = s_hist + 3 * 256;                                           // [8]
+    uint32_t* s_wsum = s_misc + 8;                                                 // [16]
+    const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    constexpr int NT = kSeedThreads;
+    const ScanParams& sp = p.scan;
+    uint64_t* ts = sp.debug_ts ? sp.debug_ts + (2 * 4096 * 40) + (int64_t)q * 8 : nullptr;
+#define ST_TS(k) do { if (ts && tid == 0) ts[k] = wall_clock64(); } while (0)
+    ST_TS(0);
+    const int64_t n = seed_items < sp.n_items ? seed_items : sp.n_items;
+    const int n_words = (int)((n + 63) >> 6);  // <= NT: one word per thread (kSeedItems / 64 <= kSeedThreads)
+    uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
+    // the query's candidate regions are free at this point: scratch for the list of passing items
+    uint32_t* glist = reinterpret_cast<uint32_t*>(const_cast<uint64_t*>(p.cand) + (int64_t)q * p.groups * p.cap);
+
+    // Bloom test: thread w owns word w.  The first signature rows of the query's filter come from
+    // a per-query table (one round trip), longer filters fetch the rest through the group tables.
+    uint64_t mword = 0;
+    if (tid < n_words) {
+        const int64_t first = (int64_t)tid * 64;
+        const int64_t left = n - first;
+        mword = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
+        const uint64_t* base = sp.bloom + (((int64_t)tid >> 4) * (int64_t)sp.m_bits) * kTileWords + (tid & 15);
+        const int* qr = p.q_prow + q * (kSeedRows + 1);
+        const int nr = qr[kSeedRows];
+#pragma unroll
+        for (int r = 0; r < kSeedRows; ++r) {
+            const int row = qr[r];
+            if (row >= 0) mword &= base[(int64_t)row * kTileWords];
+        }
+        if (nr > kSeedRows) {
+            const int g = p.q2grp[q];
+            const int r0 = sp.grp_row_off[g];
+            for (int r = kSeedRows; r < nr; ++r) mword &= base[(int64_t)sp.grp_rows[r0 + r] * kTileWords];
+        }
+    }
+    const uint32_t mine = (uint32_t)__popcll(mword);
+    uint32_t incl = mine;
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t v = __shfl_up(incl, o);
+        if (lane >= o) incl += v;
+    }
+    if (lane == 63) s_wsum[wv] = incl;
+    __syncthreads();
+    ST_TS(1);
+    uint32_t wbase = 0, total = 0;
+    for (int w = 0; w < NT / 64; ++w) {
+        const uint32_t v = s_wsum[w];
+        if (w < wv) wbase += v;
+        total += v;
+    }
+    const bool in_lds = total <= (uint32_t)kLdsKeys;
+    // list of passing items: 16-bit entries in the (still unused) sort buffer when the keys fit
+    // LDS, else 32-bit entries in the query's candidate regions
+    uint16_t* slist = reinterpret_cast<uint16_t*>(s_sorted);  // kLdsSortMax * 8 bytes = kLdsKeys * 2
+    {
+        uint32_t off = wbase + incl - mine;
+        uint64_t m = mword;
+        while (m) {
+            const int b = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            if (in_lds) slist[off] = (uint16_t)(tid * 64 + b);
+            else glist[off] = (uint32_t)(tid * 64 + b);
+            ++off;
+        }
+    }
+    __syncthreads();
+    ST_TS(2);
+    // scores: one lane per passing item
+    auto score_of = [&](int dot_or_unused, int64_t item, const int8_t* row, float s_i) -> float {
+        (void)dot_or_unused;
+        if (!sp.weighted) return rescale(dot_rows(row, sp.queries + (int64_t)q * sp.d, sp.d), sp.qscale[q], s_i);
+        float sc = 0.0f;
+        for (int t = 0; t < sp.n_tasks; ++t) {
+            const int64_t qr = (int64_t)q * sp.n_tasks + t;
+            sc = __fmaf_rn(sp.w[t], rescale(dot_rows(row, sp.queries + qr * sp.d, sp.d), sp.qscale[qr], s_i), sc);
+        }
+        (void)item;
+        return sc;
+    };
+    if (D16 == 0) {
+        for (uint32_t e = tid; e < total; e += NT) {
+            const int64_t item = in_lds ? (int64_t)slist[e] : (int64_t)glist[e];
+            const float sc = score_of(0, item, sp.items + item * sp.d, sp.iscale[item]);
+            const uint64_t key = make_key(sc, (uint32_t)item);
+            if (in_lds) s_keys[e] = key;
+            else gkeys[e] = key;
+        }
+    } else {
+        constexpr int DD = D16 > 0 ? D16 : 1;
+        // two items per thread and round: all of their row loads are in flight together
+        for (uint32_t e0 = tid; e0 < total; e0 += 2 * NT) {
+            int4 ra[2][DD];
+            float si[2];
+            int64_t item[2];
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint32_t e = e0 + u * NT;
+                const uint32_t ec = e < total ? e : e0;
+                item[u] = in_lds ? (int64_t)slist[ec] : (int64_t)glist[ec];
+                const int4* rp = reinterpret_cast<const int4*>(sp.items + item[u] * (DD * 16));
+#pragma unroll
+                for (int c = 0; c < DD; ++c) ra[u][c] = rp[c];
+                si[u] = sp.iscale[item[u]];
+            }
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                const uint32_t e = e0 + u * NT;
+                float sc = 0.0f;
+                const int nt_ = sp.weighted ? sp.n_tasks : 1;
+                for (int t = 0; t < nt_; ++t) {
+                    const int64_t qr = (int64_t)q * nt_ + t;
+                    const int4* qp = reinterpret_cast<const int4*>(sp.queries + qr * (DD * 16));
+                    int acc = 0;
+#pragma unroll
+                    for (int c = 0; c < DD; ++c) acc = dot16(ra[u][c], qp[c], acc);
+                    const float st = rescale(acc, sp.qscale[qr], si[u]);
+                    sc = sp.weighted ? __fmaf_rn(sp.w[t], st, sc) : st;
+                }
+                if (e < total) {
+                    const uint64_t key = make_key(sc, (uint32_t)item[u]);
+                    if (in_lds) s_keys[e] = key;
+                    else gkeys[e] = key;
+                }
+            }
+        }
+    }
+    __syncthreads();
+    ST_TS(3);
+
+    uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
+    int n_out;
+    if (in_lds && !p.srt)
+        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red);
+    else
+        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
+    ST_TS(4);
+    if (ts && tid == 0) ts[5] = total;
+    if (tid == 0) p.ovf[q] = 0u;
+    if (!p.last) {
+        for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
+        if (tid == 0) {
+            const uint64_t t64 = n_out == p.K ? sorted[p.K - 1] : 0ULL;
+            p.topk_cnt[q] = (uint32_t)n_out;
+            p.tau[q] = t64;
+            if (p.tau_img) {
+                const int pos = p.q_taupos[q];
+                if (pos >= 0) p.tau_img[pos] = t64;
+            }
+        }
+    } else {
+        write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
+                     p.out_count + q);
+    }
+#undef ST_TS
+}
+
+template <int D16>
+inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int batch, hipStream_t stream)
+{
+    static bool lds_set = false;
+    if (!lds_set) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&seed_kernel<D16>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLdsBytes);
+        if (e != hipSuccess) return e;
+        lds_set = true;
+    }
+    hipLaunchKernelGGL(seed_kernel<D16>, dim3(batch), dim3(kSeedThreads), kSelectLdsBytes, stream, se, seed_items);
+    return hipGetLastError();
+}
+
+inline hipError_t launch_seed(const SelectParams& se, int64_t seed_items, int batch, hipStream_t stream)
+{
+    switch (se.scan.d) {
+        case 64: return launch_seed_t<4>(se, seed_items, batch, stream);
+        case 128: return launch_seed_t<8>(se, seed_items, batch, stream);
+        case 256: return launch_seed_t<16>(se, seed_items, batch, stream);
+        default: return launch_seed_t<0>(se, seed_items, batch, stream);
     }
 }
 

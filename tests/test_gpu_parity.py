@@ -208,6 +208,17 @@ def test_mid_config_full_size_every_query():
     check_search(w, cfg.top_k)
 
 
+@pytest.mark.parametrize("d,T,all_pass", [(128, 0, False), (128, 0, True), (64, 2, False), (48, 0, False), (256, 4, False)])
+def test_seed_pass_small_batch_large_corpus(d, T, all_pass):
+    # few query rows over a corpus of at least 8 x 32768 items: the prefix is scanned by one
+    # workgroup per query.  With every item passing, the prefix holds more candidates than fit
+    # in LDS and the selection runs through global memory.
+    w = ragged_workload(4000 + d + T, 270_001, d, 6, 9, 4, 128, 2, T=T)
+    if all_pass:
+        w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(7, np.int64)
+    check_search(w, 150, label=f"seed pass d={d} T={T} all_pass={all_pass}")
+
+
 # ------------------------------------------------------------------ search: edges
 @pytest.mark.parametrize("n,d,B,K,T", [(1, 16, 1, 1, 0), (63, 16, 3, 5, 0), (64, 32, 2, 64, 0),
                                        (65, 48, 2, 100, 0), (1023, 64, 5, 7, 0), (1025, 64, 5, 2000, 0),

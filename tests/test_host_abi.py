@@ -60,9 +60,13 @@ def test_schedule_covers_the_corpus_once(n, B, K, q_split):
         assert e >= b and seg % 64 == 0 and seg <= 2048  # seg = items a workgroup takes per visit
         if i:
             assert b == levels[i - 1, 1] and e > b and b % 1024 == 0
-    # level 0: one segment of `cap` items per workgroup at most, so its regions cannot overflow
     b, e, seg = levels[0]
-    assert seg == cap and (e - b + seg - 1) // seg <= groups // q_split
+    if seg == 0:
+        # small batch, large corpus: the prefix is scanned by the per-query seed kernel
+        assert B <= 128 and n >= 8 * 32768 and e == 32768
+    else:
+        # level 0: `cap` items per workgroup at most, so its regions cannot overflow
+        assert seg == cap and (e - b + seg - 1) // seg <= groups // q_split
     assert len(levels) <= 32
 
 
