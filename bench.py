@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 wavefront dot, 2 MFMA")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run one plain 256 MiB device copy, as the known-size reference for "
+                         "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (no sharding, no collectives); "
@@ -107,6 +110,14 @@ def main():
         else:
             st.st_search(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.filt_ids,
                          w.filt_offsets, cfg.top_k, buffers=buf)
+
+    if args.copy_probe:
+        src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        torch.cuda.synchronize()
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()
