@@ -597,8 +597,6 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp.ovf = (uint32_t*)(ws + L.ovf);
     sp.cap = plan.cap;
     sp.groups = plan.groups;
-    { const char* e = getenv("ST_DEBUG_STOP"); sp.debug_stop = e ? atoi(e) : 0; }
-    { const char* e = getenv("ST_DEBUG_TS"); sp.debug_ts = e ? (uint64_t*)strtoull(e, nullptr, 0) : nullptr; }
 
     st::ScanParams sp_m = sp, sp_d = sp, sp_all = sp;
     sp_m.n_groups = set_mfma.n;

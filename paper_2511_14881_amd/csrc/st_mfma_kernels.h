@@ -111,9 +111,6 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
     const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
-    uint64_t* ts = p.debug_ts ? p.debug_ts + ((int64_t)(p.use_tau ? 1 : 0) * 4096 + wg_lin) * 40 : nullptr;
-#define ST_TS(k) do { if (ts && tid == 0) ts[k] = wall_clock64(); } while (0)
-    ST_TS(0);
     const int l16 = lane & 15, kg = lane >> 4;
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
     uint64_t* s_queue_key = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
@@ -263,7 +260,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
 #pragma unroll
     for (int k = 0; k < KS; ++k) a_off[k] = l16 * D + (((kg + 4 * k) ^ swz<KS>(l16)) << 4);
 
-    ST_TS(1);
+    bool use_ring = mp.ring_ok != 0;  // per wavefront: pipelined row loop with queued admissions
     for (int t = 0; t < n_stages; ++t) {
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
@@ -275,7 +272,6 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
 #pragma unroll
         for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
         prefetch_issue(t + 1);
-        if (t == 0) ST_TS(2);
         const int c = __popcll(mask);
         int incl = c;  // running count over the words of my filter
         for (int o = 1; o < SW; o <<= 1) {
@@ -305,7 +301,6 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         // first local query row and local block count of filter gi -> lane gi
         const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
         const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;
-        if (t == 0) ST_TS(3);
 
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
@@ -351,10 +346,11 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         // Admissions are queued (wave-private LDS, positions from a ballot: no waiting) and
         // drained 64 at a time, one candidate per lane, so that the LDS round trips of the
         // counter update are paid once per 64 candidates instead of once per unit.
-        auto drain = [&]() {
-            if (lane < qn) {
-                const uint64_t key = s_queue_key[lane];
-                const int srow = s_queue_row[lane];  // local row of the query's first task
+        auto drain = [&]() {  // takes the last (up to) 64 queued entries; the order inside a region is free
+            const int base = qn > 64 ? qn - 64 : 0;
+            if (base + lane < qn) {
+                const uint64_t key = s_queue_key[base + lane];
+                const int srow = s_queue_row[base + lane];  // local row of the query's first task
                 const int grow = s_qrow[srow];
                 if (grow >= 0 && key >= s_tau64[srow / TT]) {
                     const uint32_t at = atomicAdd(&s_cnt[srow / TT], 1u);
@@ -362,17 +358,12 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                         p.cand[((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at] = key;
                 }
             }
-            if (qn > 64) {  // entries past the first 64 move to the front
-                uint64_t k2 = 0;
-                int r2 = 0;
-                if (lane + 64 < qn) { k2 = s_queue_key[lane + 64]; r2 = s_queue_row[lane + 64]; }
-                if (lane + 64 < qn) { s_queue_key[lane] = k2; s_queue_row[lane] = r2; }
-                qn -= 64;
-            } else {
-                qn = 0;
-            }
+            qn = base;
         };
-        auto unit_compute = [&](const UnitRegs<KS>& w, auto drain_inside) {
+        // Contracts one unit with the query blocks of its filter group and queues the admissions.
+        // Without draining inside (pipelined loop) it returns false, with a possibly partial set
+        // of this unit's admissions queued, as soon as the queue cannot take a whole ballot.
+        auto unit_compute = [&](const UnitRegs<KS>& w, auto drain_inside) -> bool {
             const int lrow0 = __builtin_amdgcn_readlane(glrow, w.gi);
             const int nblk = __builtin_amdgcn_readlane(gnblk, w.gi);
             for (int j = 0; j < nblk; ++j) {
@@ -412,6 +403,9 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                     const bool hit = sc[r] >= tfv[r] && w.item >= 0;
                     const uint64_t m = __ballot(hit);
                     if (m) {  // uniform
+                        if constexpr (!decltype(drain_inside)::value) {
+                            if (qn + __popcll(m) > kQueueSlots) return false;
+                        }
                         if (hit) {
                             const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
                                                                         __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
@@ -425,40 +419,51 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                     }
                 }
             }
+            return true;
         };
         UnitRegs<KS> ring[NB];
-        if (mp.ring_ok) {
+        int u_next = 0;
+        if (use_ring) {
             // No store may sit inside the pipelined loop: on this target loads and stores share one
             // outstanding-operation counter, and a store that may be pending makes every wait for a
             // unit's rows wait for all younger loads as well.  Admissions are only queued here; when
-            // the queue could not take another unit the loop is left, the queue drained, and the
-            // ring restarted behind the last finished unit.  Every load in the loop is
-            // unconditional (requests past the end repeat the last unit): only then is the number
-            // of loads between a unit's request and its use a constant the compiler can wait on.
-            int u_next = 0;
-            while (u_next < n_units) {
+            // the queue is nearly full the loop is left, the queue drained, and the ring restarted
+            // behind the last finished unit.  A unit whose admissions do not fit the queue is rolled
+            // back and the wavefront falls back to the draining loop below for the rest of the
+            // launch (thresholds this loose admit a large share of all pairs).  Every load in the
+            // loop is unconditional (requests past the end repeat the last unit): only then is the
+            // number of loads between a unit's request and its use a constant the compiler can
+            // wait on.
+            while (u_next < n_units && use_ring) {
                 gen_seek(u_next);
 #pragma unroll
                 for (int k = 0; k < NB; ++k) unit_load(ring[k]);
-                bool full = false;
-                for (int base = u_next; base < n_units && !full; base += NB) {
+                bool stop = false;
+                for (int base = u_next; base < n_units && !stop; base += NB) {
 #pragma unroll
                     for (int k = 0; k < NB; ++k) {
-                        if (!full && base + k < n_units) {
-                            unit_compute(ring[k], std::false_type{});
-                            u_next = base + k + 1;
-                            full = qn > kQueueSlots - 64 * kRingMaxBlocks;
+                        if (!stop && base + k < n_units) {
+                            const int qn_before = qn;
+                            if (unit_compute(ring[k], std::false_type{})) {
+                                u_next = base + k + 1;
+                                stop = qn > kQueueSlots - 64 * kRingMaxBlocks;
+                            } else {
+                                qn = qn_before;
+                                stop = true;
+                                use_ring = false;
+                            }
                         }
                         unit_load(ring[k]);
                     }
                 }
                 while (qn > 0) drain();
             }
-        } else if (n_units > 0) {
-            gen_seek(0);
+        }
+        if (u_next < n_units) {
+            gen_seek(u_next);
 #pragma unroll
             for (int k = 0; k < NB; ++k) unit_load(ring[k]);
-            for (int base = 0; base < n_units; base += NB) {
+            for (int base = u_next; base < n_units; base += NB) {
 #pragma unroll
                 for (int k = 0; k < NB; ++k) {
                     if (base + k < n_units) unit_compute(ring[k], std::true_type{});
@@ -468,9 +473,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
             while (qn > 0) drain();
         }
     }
-    ST_TS(4);
     __syncthreads();
-    ST_TS(5);
     // region fill counts: real ones for the queries this workgroup row owns, zero for the others
     for (int i = tid * TT; i < mp.n_blocks * 16; i += kScanThreads * TT) {
         const int grow = mp.blk_row[i];
@@ -482,8 +485,6 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         p.cnt[(int64_t)q * p.groups + wg_lin] = c < (uint32_t)p.cap ? c : (uint32_t)p.cap;
         if (c > (uint32_t)p.cap) p.ovf[q] = 1u;
     }
-    ST_TS(6);
-#undef ST_TS
 }
 
 inline bool mfma_shape_ok(int d, int n_tasks)

@@ -46,8 +46,6 @@ struct ScanParams {
     uint32_t* ovf;               // [B]
     int32_t cap;
     int32_t groups;              // G (== gridDim.x)
-    int32_t debug_stop;          // TEMP profiling aid
-    uint64_t* debug_ts;          // TEMP profiling aid: [level][workgroup][8] timestamps
 };
 
 // Score of one (query, item) pair from the item row held by this lane.
@@ -533,9 +531,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     uint32_t* s_wsum = s_misc + 8;                                                 // [16]
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     constexpr int NT = kSelectThreads;
-    uint64_t* ts = p.scan.debug_ts ? p.scan.debug_ts + (2 * 4096 * 40) + ((int64_t)(p.last ? 1 : 0) * 4096 + q) * 8 : nullptr;
-#define ST_TS(k) do { if (ts && tid == 0) ts[k] = wall_clock64(); } while (0)
-    ST_TS(0);
     // counts are clamped to what the buffers can hold, whatever the memory says
     uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
     n_prev = n_prev < (uint32_t)p.K ? n_prev : (uint32_t)p.K;
@@ -570,7 +565,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         all += v;
     }
     const uint32_t total = n_prev + all;
-    ST_TS(1);
     const bool in_lds = total <= (uint32_t)kLdsKeys;
     uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
     {
@@ -603,7 +597,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         else gkeys[i] = v;
     }
     __syncthreads();
-    ST_TS(2);
 
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
@@ -611,7 +604,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red);
     else
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
-    ST_TS(3);
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
         if (tid == 0) {
@@ -627,9 +619,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
     }
-    ST_TS(4);
-    if (ts && tid == 0) ts[5] = total;
-#undef ST_TS
 }
 
 // Seed pass for small batches: one workgroup per query scans the prefix [0, seed_items) of the
@@ -657,9 +646,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     constexpr int NT = kSeedThreads;
     const ScanParams& sp = p.scan;
-    uint64_t* ts = sp.debug_ts ? sp.debug_ts + (2 * 4096 * 40) + (int64_t)q * 8 : nullptr;
-#define ST_TS(k) do { if (ts && tid == 0) ts[k] = wall_clock64(); } while (0)
-    ST_TS(0);
     const int64_t n = seed_items < sp.n_items ? seed_items : sp.n_items;
     const int n_words = (int)((n + 63) >> 6);  // <= NT: one word per thread (kSeedItems / 64 <= kSeedThreads)
     uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
@@ -695,7 +681,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     }
     if (lane == 63) s_wsum[wv] = incl;
     __syncthreads();
-    ST_TS(1);
     uint32_t wbase = 0, total = 0;
     for (int w = 0; w < NT / 64; ++w) {
         const uint32_t v = s_wsum[w];
@@ -718,7 +703,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
-    ST_TS(2);
     // scores: one lane per passing item
     auto score_of = [&](int dot_or_unused, int64_t item, const int8_t* row, float s_i) -> float {
         (void)dot_or_unused;
@@ -779,7 +763,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
-    ST_TS(3);
 
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
@@ -787,8 +770,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red);
     else
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
-    ST_TS(4);
-    if (ts && tid == 0) ts[5] = total;
     if (tid == 0) p.ovf[q] = 0u;
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
@@ -805,7 +786,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
     }
-#undef ST_TS
 }
 
 template <int D16>

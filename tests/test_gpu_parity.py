@@ -208,6 +208,16 @@ def test_mid_config_full_size_every_query():
     check_search(w, cfg.top_k)
 
 
+@pytest.mark.parametrize("name", ["large", "multi", "mfma"])
+def test_big_configs_full_size_sampled_queries(name):
+    # full-size corpus and batch through the library; the oracle recomputes 64 queries spread
+    # over the batch (every distinct filter of the batch is among them)
+    cfg = S.CONFIGS[name]
+    w = S.make_workload(cfg, device="cuda")
+    step = max(cfg.batch // 64, 1)
+    check_search(w, cfg.top_k, queries=range(0, cfg.batch, step))
+
+
 @pytest.mark.parametrize("d,T,all_pass", [(128, 0, False), (128, 0, True), (64, 2, False), (48, 0, False), (256, 4, False)])
 def test_seed_pass_small_batch_large_corpus(d, T, all_pass):
     # few query rows over a corpus of at least 8 x 32768 items: the prefix is scanned by one
@@ -272,6 +282,20 @@ def test_rising_scores_overflow_the_regions_and_take_the_exact_slow_path():
     for path in (1, 2):
         ids, _, _ = check_search(w, 50, path=path, label="rising scores")
         assert ids[0, 0] == n - 1 and ids[1, 0] == 0
+
+
+@pytest.mark.parametrize("B", [16, 48])
+def test_loose_threshold_admits_most_pairs_of_a_later_level(B):
+    # K is close to the number of items of the first level that pass the filter, so the threshold
+    # the second level starts with admits most of its (query, item) pairs: with three query blocks
+    # in one filter group a single 16-item unit yields more admissions than a wavefront's queue
+    # holds, and the scan has to fall back from its pipelined loop without losing or doubling any
+    n = 150_000
+    w = ragged_workload(77, n, 64, B, 40, 3, 256, 2)
+    w.filt_ids, w.filt_offsets = np.full(B, 7, np.uint64), np.arange(B + 1, dtype=np.int64)
+    levels, _, _ = st.st_search_plan(n, B, 2000)
+    assert len(levels) >= 2
+    check_search(w, 2000, label=f"loose threshold B={B}")
 
 
 def test_results_are_deterministic():
