@@ -552,9 +552,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             q_taupos[blk_row[i] / n_tasks] = yy * (rows_local / n_tasks) + lr / n_tasks;
         }
     if ((size_t)rows_local * mp.q_split > L.img_rows) return fail(ST_EINVAL, "resident-query image too small");
-    int32_t max_local_blocks = 0;  // most query blocks one workgroup row holds of a single filter group
     for (int32_t g = 0; g < set_mfma.n; ++g)
-        max_local_blocks = std::max(max_local_blocks, (blk_off[g + 1] - blk_off[g] + mp.q_split - 1) / mp.q_split);
+        if ((blk_off[g + 1] - blk_off[g] + mp.q_split - 1) / mp.q_split > 1) mp.multi_block = 1;
     const size_t at_prow = blob.add(prow), at_taupos = blob.add(q_taupos);
     // seed kernel: the first signature rows of every query's filter and their number
     std::vector<int32_t> q_prow((size_t)batch * (st::kSeedRows + 1), -1);
@@ -675,7 +674,6 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n);
             mp.first_level = mfma_started ? 0 : 1;
             mfma_started = true;
-            mp.ring_ok = (lv > 0 && max_local_blocks <= st::kRingMaxBlocks) ? 1 : 0;
             TimedLaunch t(0, stream);
             ST_HIP(st::launch_scan_mfma(sp_m, mp, gx, stream));
         }

@@ -43,7 +43,7 @@ __global__ __launch_bounds__(256) void bloom_build_kernel(const int64_t* __restr
         }
         uint64_t mine = 0;
         for (int b = 0; b < 64; ++b) {
-            const uint64_t bal = __ballot((sig >> b) & 1ULL);
+            const uint64_t bal = ballot((sig >> b) & 1ULL);
             if (lane == b) mine = bal;
         }
         const int row = slab * 64 + lane;

@@ -72,6 +72,10 @@ __device__ inline int dot_rows(const int8_t* a, const int8_t* b, int d)
     return acc;
 }
 
+// Lanes of the wavefront for which the predicate holds (the compiler folds the comparison that
+// produced the predicate into this, which it does not do for the int-taking __ballot).
+__device__ inline uint64_t ballot(bool pred) { return __builtin_amdgcn_ballot_w64(pred); }
+
 __device__ inline int lane_id() { return (int)(threadIdx.x & 63); }
 
 }  // namespace st

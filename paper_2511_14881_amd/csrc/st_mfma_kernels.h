@@ -35,8 +35,7 @@ constexpr int kMfmaMinRows = 4;            // a group needs this many query rows
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
 constexpr int kMfmaSegItems = 256;         // items per wavefront segment, at most (4 mask words x 8 filters = 32 lanes)
 constexpr int kMfmaWaves = kScanThreads / 64;
-constexpr int kQueueSlots = 256;           // queued admissions per wavefront
-constexpr int kRingMaxBlocks = 3;          // query blocks per filter group up to which admissions are only queued in the row pipeline
+constexpr int kQueueSlots = 128;           // queued admissions per wavefront (drained whenever 64 are waiting)
 
 inline constexpr int mfma_max_seg_items(int) { return kMfmaSegItems; }
 
@@ -59,7 +58,7 @@ struct MfmaParams {
     int32_t* img_qrow;           // [S][rows_local]
     uint64_t* img_tau;           // [S][rows_local / T]  written by the selection kernel
     int32_t first_level;         // 1: build the resident state from the tables and write the image
-    int32_t ring_ok;             // 1: thresholds are set and no group has more than kRingMaxBlocks local blocks
+    int32_t multi_block;         // 1: some filter group holds more than one query block in a row of workgroups
     // dynamic LDS layout (byte offsets)
     int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_total;
 };
@@ -89,7 +88,8 @@ struct UnitRegs {
 #ifndef ST_NB2
 #define ST_NB2 3
 #endif
-template <int KS, int TT, bool WEIGHTED>
+// MULTI = some filter group holds more than one 16-row query block in a row of workgroups.
+template <int KS, int TT, bool WEIGHTED, bool MULTI>
 __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
@@ -260,7 +260,6 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
 #pragma unroll
     for (int k = 0; k < KS; ++k) a_off[k] = l16 * D + (((kg + 4 * k) ^ swz<KS>(l16)) << 4);
 
-    bool use_ring = mp.ring_ok != 0;  // per wavefront: pipelined row loop with queued admissions
     for (int t = 0; t < n_stages; ++t) {
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
@@ -308,15 +307,15 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         const char* seg_rows = reinterpret_cast<const char*>(p.items + item0 * D) + kg * 16;
         const float* seg_scale = p.iscale + item0;
         int qn = 0;          // queued admissions (uniform)
-        int cur_lrow = -1;   // query block held in areg / cur_sq / cur_tf
-        v4i areg[KS];
+        int cur_lrow = -1;   // query block whose A operand, scales and thresholds sit in areg / cur_sq / cur_tf
         float4 cur_sq = make_float4(0.f, 0.f, 0.f, 0.f), cur_tf = cur_sq;
+        v4i areg[KS];
 
         // unit generator: (gen_gi, gen_b0) is the next unit to request; it stays on the last unit
         // once all have been produced, so that requests past the end are harmless repeats
         int gen_gi = 0, gen_b0 = 0, gen_n = 0, gen_left = 0;
         auto gen_seek = [&](int u) {  // position on unit u (cold)
-            gen_gi = __popcll(__ballot(lane < nf && ucum <= u));
+            gen_gi = __popcll(ballot(lane < nf && ucum <= u));
             gen_b0 = (u - (__builtin_amdgcn_readlane(ucum, gen_gi) - __builtin_amdgcn_readlane(gunits, gen_gi))) << 4;
             gen_n = __builtin_amdgcn_readlane(gcount, gen_gi);
             gen_left = n_units - 1 - u;
@@ -346,6 +345,13 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         // Admissions are queued (wave-private LDS, positions from a ballot: no waiting) and
         // drained 64 at a time, one candidate per lane, so that the LDS round trips of the
         // counter update are paid once per 64 candidates instead of once per unit.
+        //
+        // The store of a drained candidate is written in assembly and waited for on the spot.
+        // On this target loads and stores share one outstanding-operation counter; a store the
+        // compiler knows of, possibly pending, turns every later wait for a unit's rows into a
+        // wait for all younger loads as well, which would flatten the row pipeline.  This way the
+        // compiler keeps counting loads only (its waits stay exact: everything older has
+        // completed once the store has), and the full wait is paid only when a drain happens.
         auto drain = [&]() {  // takes the last (up to) 64 queued entries; the order inside a region is free
             const int base = qn > 64 ? qn - 64 : 0;
             if (base + lane < qn) {
@@ -354,119 +360,126 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                 const int grow = s_qrow[srow];
                 if (grow >= 0 && key >= s_tau64[srow / TT]) {
                     const uint32_t at = atomicAdd(&s_cnt[srow / TT], 1u);
-                    if (at < (uint32_t)p.cap)
-                        p.cand[((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at] = key;
+                    if (at < (uint32_t)p.cap) {
+                        uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at;
+                        asm volatile("global_store_dwordx2 %0, %1, off\n\ts_waitcnt vmcnt(0)" : : "v"(dst), "v"(key) : "memory");
+                    }
                 }
             }
             qn = base;
         };
-        // Contracts one unit with the query blocks of its filter group and queues the admissions.
-        // Without draining inside (pipelined loop) it returns false, with a possibly partial set
-        // of this unit's admissions queued, as soon as the queue cannot take a whole ballot.
-        auto unit_compute = [&](const UnitRegs<KS>& w, auto drain_inside) -> bool {
+        // Scores of one block's accumulators (this lane: one item, four query rows; with TT tasks
+        // per query the aggregate of query q0 is left in sc[q0]) and the lanes with an admission.
+        auto block_scores = [&](const float4& sq4, const float4& tf4, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid,
+                                float (&sc)[4], uint64_t (&hits)[4]) -> bool {
+            const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
+            const float tfv[4] = {tf4.x, tf4.y, tf4.z, tf4.w};
+#pragma unroll
+            for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si);
+            if (WEIGHTED) {
+                // Value-Model sum over the TT tasks of each query this lane holds
+#pragma unroll
+                for (int q0 = 0; q0 < 4; q0 += TT) {
+                    float agg = 0.0f;
+#pragma unroll
+                    for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
+                    sc[q0] = agg;
+                }
+            }
+            uint64_t any = 0;
+#pragma unroll
+            for (int r = 0; r < 4; r += TT) {
+                hits[r] = ballot(sc[r] >= tfv[r]) & valid;
+                any |= hits[r];
+            }
+            return any != 0;
+        };
+        // Queues the admissions of a block (rare path).
+        auto block_push = [&](int lrow, const UnitRegs<KS>& w, const float (&sc)[4], const uint64_t (&hits)[4]) {
+#pragma unroll
+            for (int r = 0; r < 4; r += TT) {
+                const uint64_t m = hits[r];
+                if (m) {  // uniform
+                    if ((m >> lane) & 1ULL) {
+                        const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
+                                                                    __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                        s_queue_key[pos] = make_key(sc[r], (uint32_t)(item0 + w.item));
+                        s_queue_row[pos] = lrow + 4 * kg + r;
+                    }
+                    qn += __popcll(m);
+                    if (qn >= 64) drain();
+                }
+            }
+        };
+        auto block_a = [&](int lrow, v4i (&a)[KS]) {
+            const int8_t* qp = s_q + lrow * D;
+#pragma unroll
+            for (int k = 0; k < KS; ++k) {
+                const int4 v = *reinterpret_cast<const int4*>(qp + a_off[k]);
+                a[k] = v4i{v.x, v.y, v.z, v.w};
+            }
+        };
+        auto block_mfma = [&](const v4i (&a)[KS], const UnitRegs<KS>& w) -> v4i {
+            v4i acc = {0, 0, 0, 0};
+#pragma unroll
+            for (int k = 0; k < KS; ++k) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[k], w.b[k], acc, 0, 0, 0);
+            return acc;
+        };
+        // Contracts one unit with the query blocks of its filter group, two blocks per round (the
+        // operands of both are read before either is used).  A group of a single block keeps its
+        // A operand in registers from one unit to the next.
+        auto unit_compute = [&](const UnitRegs<KS>& w) {
             const int lrow0 = __builtin_amdgcn_readlane(glrow, w.gi);
             const int nblk = __builtin_amdgcn_readlane(gnblk, w.gi);
-            for (int j = 0; j < nblk; ++j) {
-                const int lrow = lrow0 + 16 * j;
-                if (lrow != cur_lrow) {  // query block operands stay in registers across units
-                    cur_lrow = lrow;
-                    const int8_t* qp = s_q + lrow * D;
-#pragma unroll
-                    for (int k = 0; k < KS; ++k) {
-                        const int4 v = *reinterpret_cast<const int4*>(qp + a_off[k]);
-                        areg[k] = v4i{v.x, v.y, v.z, v.w};
-                    }
-                    cur_sq = *reinterpret_cast<const float4*>(s_sq + lrow + 4 * kg);
-                    cur_tf = *reinterpret_cast<const float4*>(s_tauf + lrow + 4 * kg);
+            float sc[4], sc2[4];
+            uint64_t hits[4], hits2[4];
+            const uint64_t valid = ballot(w.item >= 0);  // lanes that hold a real item
+            auto row_sq = [&](int lrow) { return *reinterpret_cast<const float4*>(s_sq + lrow + 4 * kg); };
+            auto row_tf = [&](int lrow) { return *reinterpret_cast<const float4*>(s_tauf + lrow + 4 * kg); };
+            if (!MULTI || nblk == 1) {
+                if (cur_lrow != lrow0) {
+                    block_a(lrow0, areg);
+                    cur_sq = row_sq(lrow0);
+                    cur_tf = row_tf(lrow0);
+                    cur_lrow = lrow0;
                 }
-                v4i acc = {0, 0, 0, 0};
-#pragma unroll
-                for (int k = 0; k < KS; ++k)
-                    acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(areg[k], w.b[k], acc, 0, 0, 0);
-                const float sqv[4] = {cur_sq.x, cur_sq.y, cur_sq.z, cur_sq.w};
-                const float tfv[4] = {cur_tf.x, cur_tf.y, cur_tf.z, cur_tf.w};
-                float sc[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si);
-                if (WEIGHTED) {
-                    // Value-Model sum over the TT tasks of each query this lane holds
-#pragma unroll
-                    for (int q0 = 0; q0 < 4; q0 += TT) {
-                        float agg = 0.0f;
-#pragma unroll
-                        for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
-                        sc[q0] = agg;
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < 4; r += TT) {
-                    const bool hit = sc[r] >= tfv[r] && w.item >= 0;
-                    const uint64_t m = __ballot(hit);
-                    if (m) {  // uniform
-                        if constexpr (!decltype(drain_inside)::value) {
-                            if (qn + __popcll(m) > kQueueSlots) return false;
-                        }
-                        if (hit) {
-                            const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
-                                                                        __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                            s_queue_key[pos] = make_key(sc[r], (uint32_t)(item0 + w.item));
-                            s_queue_row[pos] = lrow + 4 * kg + r;
-                        }
-                        qn += __popcll(m);
-                        if constexpr (decltype(drain_inside)::value) {
-                            if (qn >= 64) drain();
-                        }
-                    }
-                }
+                const v4i acc = block_mfma(areg, w);
+                if (block_scores(cur_sq, cur_tf, acc, w, valid, sc, hits)) block_push(lrow0, w, sc, hits);
+                return;
             }
-            return true;
+            if (!MULTI) return;
+            int j = 0;
+            for (; j + 1 < nblk; j += 2) {
+                v4i a[KS], b[KS];
+                block_a(lrow0 + 16 * j, a);
+                block_a(lrow0 + 16 * j + 16, b);
+                const v4i acc = block_mfma(a, w);
+                const v4i acc2 = block_mfma(b, w);
+                const bool any = block_scores(row_sq(lrow0 + 16 * j), row_tf(lrow0 + 16 * j), acc, w, valid, sc, hits);
+                const bool any2 = block_scores(row_sq(lrow0 + 16 * j + 16), row_tf(lrow0 + 16 * j + 16), acc2, w, valid, sc2, hits2);
+                if (any) block_push(lrow0 + 16 * j, w, sc, hits);
+                if (any2) block_push(lrow0 + 16 * j + 16, w, sc2, hits2);
+            }
+            if (j < nblk) {
+                v4i a[KS];
+                block_a(lrow0 + 16 * j, a);
+                const v4i acc = block_mfma(a, w);
+                if (block_scores(row_sq(lrow0 + 16 * j), row_tf(lrow0 + 16 * j), acc, w, valid, sc, hits))
+                    block_push(lrow0 + 16 * j, w, sc, hits);
+            }
         };
+        // Every load in the loop is unconditional (requests past the end repeat the last unit):
+        // only then is the number of loads between a unit's request and its use a constant the
+        // compiler can wait on.
         UnitRegs<KS> ring[NB];
-        int u_next = 0;
-        if (use_ring) {
-            // No store may sit inside the pipelined loop: on this target loads and stores share one
-            // outstanding-operation counter, and a store that may be pending makes every wait for a
-            // unit's rows wait for all younger loads as well.  Admissions are only queued here; when
-            // the queue is nearly full the loop is left, the queue drained, and the ring restarted
-            // behind the last finished unit.  A unit whose admissions do not fit the queue is rolled
-            // back and the wavefront falls back to the draining loop below for the rest of the
-            // launch (thresholds this loose admit a large share of all pairs).  Every load in the
-            // loop is unconditional (requests past the end repeat the last unit): only then is the
-            // number of loads between a unit's request and its use a constant the compiler can
-            // wait on.
-            while (u_next < n_units && use_ring) {
-                gen_seek(u_next);
-#pragma unroll
-                for (int k = 0; k < NB; ++k) unit_load(ring[k]);
-                bool stop = false;
-                for (int base = u_next; base < n_units && !stop; base += NB) {
-#pragma unroll
-                    for (int k = 0; k < NB; ++k) {
-                        if (!stop && base + k < n_units) {
-                            const int qn_before = qn;
-                            if (unit_compute(ring[k], std::false_type{})) {
-                                u_next = base + k + 1;
-                                stop = qn > kQueueSlots - 64 * kRingMaxBlocks;
-                            } else {
-                                qn = qn_before;
-                                stop = true;
-                                use_ring = false;
-                            }
-                        }
-                        unit_load(ring[k]);
-                    }
-                }
-                while (qn > 0) drain();
-            }
-        }
-        if (u_next < n_units) {
-            gen_seek(u_next);
+        if (n_units > 0) {
+            gen_seek(0);
 #pragma unroll
             for (int k = 0; k < NB; ++k) unit_load(ring[k]);
-            for (int base = u_next; base < n_units; base += NB) {
+            for (int base = 0; base < n_units; base += NB) {
 #pragma unroll
                 for (int k = 0; k < NB; ++k) {
-                    if (base + k < n_units) unit_compute(ring[k], std::true_type{});
+                    if (base + k < n_units) unit_compute(ring[k]);
                     unit_load(ring[k]);
                 }
             }
@@ -520,18 +533,18 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups)
     mp->lds_total = off;
 }
 
-template <int KS, int TT, bool WEIGHTED>
+template <int KS, int TT, bool WEIGHTED, bool MULTI>
 inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
     static int max_set = 0;  // largest dynamic LDS size this instantiation has been allowed
     if (mp.lds_total > max_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED, MULTI>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, mp.lds_total);
         if (e != hipSuccess) return e;
         max_set = mp.lds_total;
     }
     const dim3 grid((unsigned)gx, (unsigned)mp.q_split);
-    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED>), grid, dim3(kScanThreads), (size_t)mp.lds_total, stream, sp, mp);
+    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED, MULTI>), grid, dim3(kScanThreads), (size_t)mp.lds_total, stream, sp, mp);
     return hipGetLastError();
 }
 
@@ -540,10 +553,14 @@ inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, i
 {
     if (sp.seg_items > mfma_max_seg_items(sp.d) || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
     const int ks = sp.d / 64, tt = sp.n_tasks;
-#define ST_CASE(K_, T_)                                                                   \
-    if (ks == K_ && tt == T_)                                                             \
-        return sp.weighted ? launch_scan_mfma_t<K_, T_, true>(sp, mp, gx, stream)         \
-                           : launch_scan_mfma_t<K_, T_, false>(sp, mp, gx, stream);
+#define ST_CASE(K_, T_)                                                                                          \
+    if (ks == K_ && tt == T_) {                                                                                  \
+        if (mp.multi_block)                                                                                      \
+            return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true>(sp, mp, gx, stream)                      \
+                               : launch_scan_mfma_t<K_, T_, false, true>(sp, mp, gx, stream);                    \
+        return sp.weighted ? launch_scan_mfma_t<K_, T_, true, false>(sp, mp, gx, stream)                         \
+                           : launch_scan_mfma_t<K_, T_, false, false>(sp, mp, gx, stream);                       \
+    }
     ST_CASE(1, 1) ST_CASE(1, 2) ST_CASE(1, 4)
     ST_CASE(2, 1) ST_CASE(2, 2) ST_CASE(2, 4)
     ST_CASE(4, 1) ST_CASE(4, 2) ST_CASE(4, 4)

@@ -380,7 +380,7 @@ __device__ inline int lds_topk(const uint64_t* keys, int n, int K, uint64_t* sor
                     before += h[j];
                 }
             }
-            const int src = __ffsll((long long)__ballot(mine)) - 1;  // exactly one lane
+            const int src = __ffsll((long long)ballot(mine)) - 1;  // exactly one lane
             digit = __shfl(digit, src);
             rest = __shfl(rest, src);
             whole = __shfl(whole, src);
