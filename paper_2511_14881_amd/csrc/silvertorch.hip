@@ -564,6 +564,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         q_prow[(size_t)b * (st::kSeedRows + 1) + st::kSeedRows] = nr;
     }
     const size_t at_qprow = blob.add(q_prow);
+    const size_t at_done = blob.add(std::vector<int32_t>((size_t)batch, 0));  // seed pass: slices finished per query
     if (blob.bytes() > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
 
     char* ws = (char*)dev_workspace;
@@ -596,6 +597,12 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp.ovf = (uint32_t*)(ws + L.ovf);
     sp.cap = plan.cap;
     sp.groups = plan.groups;
+#ifdef ST_STAMPS
+    {  // tuning builds: ST_STAMPS_PTR = device address of a zeroed uint64 [3][4096][16] buffer
+        const char* e = getenv("ST_STAMPS_PTR");
+        sp.stamps = e ? (uint64_t*)strtoull(e, nullptr, 0) : nullptr;
+    }
+#endif
 
     st::ScanParams sp_m = sp, sp_d = sp, sp_all = sp;
     sp_m.n_groups = set_mfma.n;
@@ -652,7 +659,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         se.last = lv == plan.n_levels - 1;
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
-            ST_HIP(st::launch_seed(se, L_.end, batch, stream));
+            ST_HIP(st::launch_seed(se, L_.end, batch, st::seed_parts(batch, L.k_pad), (uint32_t*)(ws + L.meta + at_done), stream));
             continue;
         }
         for (st::ScanParams* q : {&sp_m, &sp_d}) {

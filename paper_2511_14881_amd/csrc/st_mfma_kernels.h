@@ -111,10 +111,10 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
     const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
+    ST_STAMP(p.stamps, 0, wg_lin, 0);
     const int l16 = lane & 15, kg = lane >> 4;
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
-    uint64_t* s_queue_key = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
-    int* s_queue_row = reinterpret_cast<int*>(lds + mp.lds_queue + kMfmaWaves * kQueueSlots * 8) + wave * kQueueSlots;
+    uint64_t* s_queue = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
 
     // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
     // workgroup; inside a visit wavefront w takes segments w, w + 4, ...  Stages of a wavefront
@@ -260,6 +260,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
 #pragma unroll
     for (int k = 0; k < KS; ++k) a_off[k] = l16 * D + (((kg + 4 * k) ^ swz<KS>(l16)) << 4);
 
+    ST_STAMP(p.stamps, 0, wg_lin, 1);
     for (int t = 0; t < n_stages; ++t) {
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
@@ -271,6 +272,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
 #pragma unroll
         for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
         prefetch_issue(t + 1);
+        if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 2);
         const int c = __popcll(mask);
         int incl = c;  // running count over the words of my filter
         for (int o = 1; o < SW; o <<= 1) {
@@ -300,6 +302,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         // first local query row and local block count of filter gi -> lane gi
         const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
         const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;
+        if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 3);
 
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
@@ -355,8 +358,9 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         auto drain = [&]() {  // takes the last (up to) 64 queued entries; the order inside a region is free
             const int base = qn > 64 ? qn - 64 : 0;
             if (base + lane < qn) {
-                const uint64_t key = s_queue_key[base + lane];
-                const int srow = s_queue_row[base + lane];  // local row of the query's first task
+                const uint64_t e = s_queue[base + lane];
+                const int srow = (int)((uint32_t)e >> 8);  // local row of the query's first task
+                const uint64_t key = make_key(__uint_as_float((uint32_t)(e >> 32)), (uint32_t)(item0 + (int)(e & 255u)));
                 const int grow = s_qrow[srow];
                 if (grow >= 0 && key >= s_tau64[srow / TT]) {
                     const uint32_t at = atomicAdd(&s_cnt[srow / TT], 1u);
@@ -403,8 +407,8 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                     if ((m >> lane) & 1ULL) {
                         const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                        s_queue_key[pos] = make_key(sc[r], (uint32_t)(item0 + w.item));
-                        s_queue_row[pos] = lrow + 4 * kg + r;
+                        // raw score, local row and item: the sort key is built when the entry is drained
+                        s_queue[pos] = ((uint64_t)__float_as_uint(sc[r]) << 32) | (uint32_t)(((lrow + 4 * kg + r) << 8) | w.item);
                     }
                     qn += __popcll(m);
                     if (qn >= 64) drain();
@@ -481,12 +485,17 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                 for (int k = 0; k < NB; ++k) {
                     if (base + k < n_units) unit_compute(ring[k]);
                     unit_load(ring[k]);
+                    if (t == 0 && base == 0 && k == 0) ST_STAMP(p.stamps, 0, wg_lin, 4);
                 }
             }
+            if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 5);
             while (qn > 0) drain();
         }
+        if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 6);
     }
+    ST_STAMP(p.stamps, 0, wg_lin, 7);
     __syncthreads();
+    ST_STAMP(p.stamps, 0, wg_lin, 8);
     // region fill counts: real ones for the queries this workgroup row owns, zero for the others
     for (int i = tid * TT; i < mp.n_blocks * 16; i += kScanThreads * TT) {
         const int grow = mp.blk_row[i];
@@ -498,6 +507,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         p.cnt[(int64_t)q * p.groups + wg_lin] = c < (uint32_t)p.cap ? c : (uint32_t)p.cap;
         if (c > (uint32_t)p.cap) p.ovf[q] = 1u;
     }
+    ST_STAMP(p.stamps, 0, wg_lin, 9);
 }
 
 inline bool mfma_shape_ok(int d, int n_tasks)
@@ -526,7 +536,7 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups)
     mp->lds_qrow = take(mp->rows_local * 4);
     mp->lds_cnt = take((mp->rows_local / n_tasks + 1) * 4);
     mp->lds_list = take(kMfmaWaves * kMfmaFilterBatch * kMfmaSegItems);
-    mp->lds_queue = take(kMfmaWaves * kQueueSlots * 12);
+    mp->lds_queue = take(kMfmaWaves * kQueueSlots * 8);
     mp->lds_prow = take(n_groups * kPrefetchRows * 4);
     mp->lds_blkoff = take((2 * n_groups + 2) * 4);
     mp->lds_rowoff = take((n_groups + 1) * 4);

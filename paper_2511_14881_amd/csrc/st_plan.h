@@ -151,7 +151,9 @@ inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_ca
 {
     const int cap = choose_cap(n_items, K);
     if (cap < 0 || q_split < 1 || scan_groups() % q_split) return -1;
-    const int64_t seed = K <= kLdsSortMax ? seed_items_for(n_items, batch_rows) : 0;
+    // the seed pass borrows the candidate regions and the gather buffer of a query as scratch
+    const bool seed_fits = K <= kLdsSortMax && (int64_t)scan_groups() * cap >= 2 * (int64_t)kSeedItems;
+    const int64_t seed = seed_fits ? seed_items_for(n_items, batch_rows) : 0;
     return make_levels(n_items, K, cap, scan_groups() / q_split, seg_limit(seg_cap), seed, out);
 }
 
@@ -176,8 +178,9 @@ struct Layout {
 inline size_t meta_bound_bytes(int32_t batch)
 {
     // group tables (rows: at most 64 per query, twice: all groups and the per-scorer copies),
-    // query lists, offsets, MFMA block tables (at most 16*(T/16 + 1) rows per query), slack
-    return (size_t)round_up(4096 + (size_t)batch * 768, 256);
+    // query lists, offsets, MFMA block tables (at most 16*(T/16 + 1) rows per query), the seed pass's
+    // completion counters, slack
+    return (size_t)round_up(4096 + (size_t)batch * 776, 256);
 }
 
 inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 16, int32_t n_tasks = 1)

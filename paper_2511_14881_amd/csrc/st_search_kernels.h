@@ -46,7 +46,21 @@ struct ScanParams {
     uint32_t* ovf;               // [B]
     int32_t cap;
     int32_t groups;              // G (== gridDim.x)
+    uint64_t* stamps;            // null unless the library is built with ST_STAMPS (timeline probe)
 };
+
+// Timeline probe for tuning builds (-DST_STAMPS): thread 0 of a workgroup records the 10-ns wall
+// clock at point k into stamps[((kind * 4096) + slot) * 16 + k].  Compiles to nothing otherwise.
+#ifdef ST_STAMPS
+#define ST_STAMP(buf, kind, slot, k)                                                                   \
+    do {                                                                                               \
+        if ((buf) && threadIdx.x == 0 && (slot) < 4096) (buf)[(((kind) * 4096) + (slot)) * 16 + (k)] = wall_clock64(); \
+    } while (0)
+#else
+#define ST_STAMP(buf, kind, slot, k) \
+    do {                             \
+    } while (0)
+#endif
 
 // Score of one (query, item) pair from the item row held by this lane.
 __device__ inline float pair_score(const ScanParams& p, int q, const int8_t* item_row, float s_i)
@@ -303,52 +317,59 @@ __device__ inline void write_result(const uint64_t* sorted, int n_out, int K, in
 // Faster variant for keys that sit in LDS and fit in registers: every thread keeps up to
 // kTopkRegs keys in registers for all passes; a pass costs one barrier (three histograms rotate,
 // every wavefront scans the histogram for itself).  Requires n <= kTopkRegs * blockDim.x,
-// blockDim.x a multiple of 256 and at most 1024, k_pad <= room in sorted (LDS).
+// blockDim.x a multiple of 256 and at most 1024, k_pad <= room in sorted (LDS).  The key buffer
+// is overwritten (it serves as scratch once the keys sit in registers).
+//
+// kth receives the K-th best key (0 if n < K).  With want_sorted the best min(n, K) keys end up
+// in sorted[] in descending order; without, they are there in no particular order (callers that
+// only carry the set forward and need the threshold skip the sort).
 constexpr int kTopkRegs = 16;
 
-__device__ inline int lds_topk(const uint64_t* keys, int n, int K, uint64_t* sorted, int k_pad,
-                               uint32_t* s_hist3 /*[3][256]*/, uint32_t* s_misc /*[8]*/, uint64_t* s_red /*[2*16]*/)
+__device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, int k_pad,
+                               uint32_t* s_hist3 /*[3][256]*/, uint32_t* s_misc /*[8]*/, uint64_t* s_red /*[2*16]*/,
+                               bool want_sorted, uint64_t& kth, uint64_t* stamps = nullptr, int st_kind = 0,
+                               int st_slot = 0, int st_k = 0)
 {
+    (void)stamps; (void)st_kind; (void)st_slot; (void)st_k;
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wv = tid >> 6, nw = nt >> 6;
     const int n_out = n < K ? n : K;
     int P = 1;
     while (P < n_out) P <<= 1;
     if (P > k_pad) P = k_pad;
+    kth = 0;
     if (n <= K) {
         for (int i = tid; i < P; i += nt) sorted[i] = i < n_out ? keys[i] : 0ULL;
         __syncthreads();
+        if (n < K && !want_sorted) return n_out;
+        want_sorted = true;  // n == K: the threshold is the smallest key, read off the sorted list
     } else {
         uint64_t kr[kTopkRegs];
-        uint64_t lo = ~0ULL, hi = 0ULL;
+        const uint64_t k0 = keys[0];
+        uint64_t diff = 0;  // bits in which some key differs from the first
         const int ne = (n + nt - 1) / nt;  // register slots in use (uniform)
 #pragma unroll
         for (int j = 0; j < kTopkRegs; ++j) {
             const int i = tid + j * nt;
             kr[j] = i < n ? keys[i] : 0ULL;  // 0 is below every real key
-            if (i < n) {
-                lo = kr[j] < lo ? kr[j] : lo;
-                hi = kr[j] > hi ? kr[j] : hi;
-            }
+            if (i < n) diff |= kr[j] ^ k0;
         }
+        uint32_t dl = (uint32_t)diff, dh = (uint32_t)(diff >> 32);
         for (int o = 32; o > 0; o >>= 1) {
-            const uint64_t l2 = __shfl_xor((unsigned long long)lo, o), h2 = __shfl_xor((unsigned long long)hi, o);
-            lo = l2 < lo ? l2 : lo;
-            hi = h2 > hi ? h2 : hi;
+            dl |= __shfl_xor(dl, o);
+            dh |= __shfl_xor(dh, o);
         }
-        if (lane == 0) { s_red[2 * wv] = lo; s_red[2 * wv + 1] = hi; }
+        if (lane == 0) s_red[wv] = ((uint64_t)dh << 32) | dl;
         for (int i = tid; i < 3 * 256; i += nt) s_hist3[i] = 0;
         if (tid == 0) s_misc[2] = 0;
         __syncthreads();
-        for (int w = 0; w < nw; ++w) {
-            const uint64_t l2 = s_red[2 * w], h2 = s_red[2 * w + 1];
-            lo = l2 < lo ? l2 : lo;
-            hi = h2 > hi ? h2 : hi;
-        }
-        const int top_shift = 56 - (__clzll((long long)(lo ^ hi)) >> 3) * 8;  // n > K >= 1: lo != hi
+        diff = 0;
+        for (int w = 0; w < nw; ++w) diff |= s_red[w];
+        const int top_shift = 56 - (__clzll((long long)diff) >> 3) * 8;  // n > K >= 1 distinct keys: diff != 0
         uint64_t prefix_mask = top_shift == 56 ? 0ULL : ~((1ULL << (top_shift + 8)) - 1ULL);
-        uint64_t prefix = hi & prefix_mask;
+        uint64_t prefix = k0 & prefix_mask;
         uint32_t want = (uint32_t)K;
         int pass = 0;
+        ST_STAMP(stamps, st_kind, st_slot, st_k);
         for (int shift = top_shift; shift >= 0; shift -= 8, ++pass) {
             uint32_t* hist = s_hist3 + (pass % 3) * 256;
 #pragma unroll
@@ -389,39 +410,75 @@ __device__ inline int lds_topk(const uint64_t* keys, int n, int K, uint64_t* sor
             want = rest;
             if (whole) break;  // uniform: every wavefront computed the same
         }
-        const uint64_t kth = prefix;  // keys are distinct: exactly K of them are >= kth
+        // keys are distinct: exactly K of them are >= prefix; when the search stopped on a whole
+        // bucket the K-th key is the smallest of them
+        const uint64_t bound = prefix;
+        ST_STAMP(stamps, st_kind, st_slot, st_k + 1);
+        uint64_t low = ~0ULL;
 #pragma unroll
         for (int j = 0; j < kTopkRegs; ++j)
-            if (j < ne && kr[j] >= kth && kr[j]) {
+            if (j < ne && kr[j] >= bound && kr[j]) {
                 const uint32_t slot = atomicAdd(&s_misc[2], 1u);
                 if (slot < (uint32_t)P) sorted[slot] = kr[j];
+                low = kr[j] < low ? kr[j] : low;
             }
         for (int i = K + tid; i < P; i += nt) sorted[i] = 0ULL;
+        if (!want_sorted) {
+            // threshold = smallest collected key: wavefront minimum, then across wavefronts
+            uint32_t ll = (uint32_t)low, lh = (uint32_t)(low >> 32);
+            for (int o = 32; o > 0; o >>= 1) {
+                const uint32_t ol = __shfl_xor(ll, o), oh = __shfl_xor(lh, o);
+                const bool less = oh < lh || (oh == lh && ol < ll);
+                ll = less ? ol : ll;
+                lh = less ? oh : lh;
+            }
+            if (lane == 0) s_red[16 + wv] = ((uint64_t)lh << 32) | ll;
+        }
         __syncthreads();
+        if (!want_sorted) {
+            uint64_t m = ~0ULL;
+            for (int w = 0; w < nw; ++w) m = s_red[16 + w] < m ? s_red[16 + w] : m;
+            kth = m;
+            return n_out;
+        }
     }
+    ST_STAMP(stamps, st_kind, st_slot, st_k + 2);
     if (P <= nt) {
+        // rank sort with every thread at work: thread (c, i) counts, among one share of the list,
+        // the keys that precede key i; shares are summed in LDS (padding zeros tie among
+        // themselves and are ordered by position)
+        uint32_t* s_rank = reinterpret_cast<uint32_t*>(keys);
+        int chunks = nt / P;
+        if (chunks > P) chunks = P;
+        const int seg = P / chunks;
+        const int i = tid % P, c = tid / P;
+        if (tid < P) s_rank[tid] = 0;
+        __syncthreads();
         uint64_t key = 0;
-        int rank = 0;
-        if (tid < P) {
-            key = sorted[tid];
-            if (P >= 8) {
-                for (int j = 0; j < P; j += 8) {  // eight reads in flight at a time
+        if (c < chunks) {
+            key = sorted[i];
+            int rank = 0;
+            const int j0 = c * seg;
+            if (seg >= 8) {
+                for (int j = j0; j < j0 + seg; j += 8) {  // eight reads in flight at a time
                     uint64_t o[8];
 #pragma unroll
                     for (int u = 0; u < 8; ++u) o[u] = sorted[j + u];
 #pragma unroll
-                    for (int u = 0; u < 8; ++u) rank += (o[u] > key || (o[u] == key && j + u < tid)) ? 1 : 0;
+                    for (int u = 0; u < 8; ++u) rank += (o[u] > key || (o[u] == key && j + u < i)) ? 1 : 0;
                 }
             } else {
-                for (int j = 0; j < P; ++j) {
+                for (int j = j0; j < j0 + seg; ++j) {
                     const uint64_t o = sorted[j];
-                    rank += (o > key || (o == key && j < tid)) ? 1 : 0;
+                    rank += (o > key || (o == key && j < i)) ? 1 : 0;
                 }
             }
+            if (rank) atomicAdd(&s_rank[i], (uint32_t)rank);
         }
         __syncthreads();
-        if (tid < P) sorted[rank] = key;
+        if (tid < P) sorted[s_rank[tid]] = key;  // tid < P implies c == 0: key is sorted[tid]
         __syncthreads();
+        if (n_out == K) kth = sorted[K - 1];
         return n_out;
     }
     for (int k2 = 2; k2 <= P; k2 <<= 1) {
@@ -437,6 +494,7 @@ __device__ inline int lds_topk(const uint64_t* keys, int n, int K, uint64_t* sor
             __syncthreads();
         }
     }
+    if (n_out == K) kth = sorted[K - 1];
     return n_out;
 }
 
@@ -531,6 +589,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     uint32_t* s_wsum = s_misc + 8;                                                 // [16]
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     constexpr int NT = kSelectThreads;
+    ST_STAMP(p.scan.stamps, 1, q, 0);
     // counts are clamped to what the buffers can hold, whatever the memory says
     uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
     n_prev = n_prev < (uint32_t)p.K ? n_prev : (uint32_t)p.K;
@@ -565,6 +624,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         all += v;
     }
     const uint32_t total = n_prev + all;
+    ST_STAMP(p.scan.stamps, 1, q, 1);
     const bool in_lds = total <= (uint32_t)kLdsKeys;
     uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
     {
@@ -597,17 +657,23 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         else gkeys[i] = v;
     }
     __syncthreads();
+    ST_STAMP(p.scan.stamps, 1, q, 2);
 
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
-    if (in_lds && !p.srt)
-        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red);
-    else
+    uint64_t kth = 0;  // K-th best key so far (0: fewer than K candidates yet)
+    if (in_lds && !p.srt) {
+        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
+                         1, q, 9);
+    } else {
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
+        kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
+    }
+    ST_STAMP(p.scan.stamps, 1, q, 3);
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
         if (tid == 0) {
-            const uint64_t t64 = n_out == p.K ? sorted[p.K - 1] : 0ULL;
+            const uint64_t t64 = kth;
             p.topk_cnt[q] = (uint32_t)n_out;
             p.tau[q] = t64;
             if (p.tau_img) {
@@ -619,21 +685,35 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
     }
+    ST_STAMP(p.scan.stamps, 1, q, 4);
 }
 
-// Seed pass for small batches: one workgroup per query scans the prefix [0, seed_items) of the
-// corpus on its own -- Bloom test of every word at once, compaction, one lane per passing item
-// for the int8 dot products (Sec. 4.2) -- and selects its top-K there (Algorithm 1 phase 4 on the
-// prefix).  It leaves the running top-K and the admission threshold exactly as the first
-// cooperative level and its selection would, in one launch.
+// Seed pass for small batches: the prefix [0, seed_items) of the corpus is scanned per query by
+// `parts` workgroups, each on its own slice -- Bloom test of every word at once, compaction, one
+// lane per passing item for the int8 dot products (Sec. 4.2), top-K of the slice (Algorithm 1
+// phase 4).  The workgroup that finishes a query's last slice merges the slices' lists.  The pass
+// leaves the running top-K and the admission threshold exactly as the first cooperative level
+// and its selection would, in one launch.
 constexpr int kSeedThreads = 512;
-constexpr int kSeedRows = 8;  // signature rows per query in the seed kernel's row table
+constexpr int kSeedRows = 8;       // signature rows per query in the seed kernel's row table
+constexpr int kSeedMaxParts = 8;
 static_assert(kSeedItems / 64 <= kSeedThreads, "one Bloom word per thread");
 
+// Slices per query: enough workgroups to occupy the chip, whole 1024-item tiles per slice, and all
+// slice results (parts * k_pad keys) together within the LDS key buffer of the merge.
+inline int seed_parts(int batch, int k_pad)
+{
+    int parts = 1;
+    while (parts < kSeedMaxParts && batch * parts < 256 && 2 * parts * k_pad <= kLdsKeys &&
+           kSeedItems / (2 * parts) >= kTileItems)
+        parts *= 2;
+    return parts;
+}
+
 // D16 = d / 16 for d in {64, 128, 256} (item rows staged in registers, two items per thread in
-// flight), 0 = any other d (plain loop).
+// flight), 0 = any other d (plain loop).  Grid (batch, parts).  done[batch] must be zero at launch.
 template <int D16>
-__global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int64_t seed_items)
+__global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int64_t seed_items, uint32_t* done)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
     uint64_t* s_keys = reinterpret_cast<uint64_t*>(sel_lds);                       // [kLdsKeys]
@@ -644,22 +724,33 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     uint32_t* s_misc = s_hist + 3 * 256;                                           // [8]
     uint32_t* s_wsum = s_misc + 8;                                                 // [16]
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int parts = (int)gridDim.y, part = (int)blockIdx.y;
     constexpr int NT = kSeedThreads;
     const ScanParams& sp = p.scan;
-    const int64_t n = seed_items < sp.n_items ? seed_items : sp.n_items;
-    const int n_words = (int)((n + 63) >> 6);  // <= NT: one word per thread (kSeedItems / 64 <= kSeedThreads)
-    uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
+    const int slot = q * parts + part;
+    ST_STAMP(sp.stamps, 2, slot, 0);
+    const int64_t n_all = seed_items < sp.n_items ? seed_items : sp.n_items;
+    const int64_t part_items = seed_items / parts;  // whole tiles
+    const int64_t begin = part * part_items;
+    const int64_t n = n_all - begin < part_items ? (n_all - begin > 0 ? n_all - begin : 0) : part_items;  // items of this slice
+    const int n_words = (int)((n + 63) >> 6);  // <= NT: one word per thread
+    // per query: [parts][pstride] slice results, then room for the keys of slices too large for LDS.
+    // A slice with few passing items publishes all of their keys, a larger one its own top-K.
+    const int pshare = kLdsKeys / parts;
+    const int pstride = p.K > pshare ? p.K : pshare;
+    uint64_t* gpart = p.gath + (int64_t)q * p.gath_cap;
+    uint64_t* gkeys = gpart + (int64_t)parts * pstride + begin;
     // the query's candidate regions are free at this point: scratch for the list of passing items
-    uint32_t* glist = reinterpret_cast<uint32_t*>(const_cast<uint64_t*>(p.cand) + (int64_t)q * p.groups * p.cap);
+    uint32_t* glist = reinterpret_cast<uint32_t*>(const_cast<uint64_t*>(p.cand) + (int64_t)q * p.groups * p.cap) + begin;
 
-    // Bloom test: thread w owns word w.  The first signature rows of the query's filter come from
-    // a per-query table (one round trip), longer filters fetch the rest through the group tables.
+    // Bloom test: thread w owns word w of the slice.  The first signature rows of the query's filter
+    // come from a per-query table (one round trip), longer filters fetch the rest through the group tables.
     uint64_t mword = 0;
     if (tid < n_words) {
-        const int64_t first = (int64_t)tid * 64;
-        const int64_t left = n - first;
+        const int64_t left = n - (int64_t)tid * 64;
         mword = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
-        const uint64_t* base = sp.bloom + (((int64_t)tid >> 4) * (int64_t)sp.m_bits) * kTileWords + (tid & 15);
+        const int64_t gw = (begin >> 6) + tid;
+        const uint64_t* base = sp.bloom + ((gw >> 4) * (int64_t)sp.m_bits) * kTileWords + (gw & 15);
         const int* qr = p.q_prow + q * (kSeedRows + 1);
         const int nr = qr[kSeedRows];
 #pragma unroll
@@ -681,6 +772,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     }
     if (lane == 63) s_wsum[wv] = incl;
     __syncthreads();
+    ST_STAMP(sp.stamps, 2, slot, 1);
     uint32_t wbase = 0, total = 0;
     for (int w = 0; w < NT / 64; ++w) {
         const uint32_t v = s_wsum[w];
@@ -688,8 +780,8 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         total += v;
     }
     const bool in_lds = total <= (uint32_t)kLdsKeys;
-    // list of passing items: 16-bit entries in the (still unused) sort buffer when the keys fit
-    // LDS, else 32-bit entries in the query's candidate regions
+    // list of passing items (relative to the slice): 16-bit entries in the (still unused) sort
+    // buffer when the keys fit LDS, else 32-bit entries in the query's candidate regions
     uint16_t* slist = reinterpret_cast<uint16_t*>(s_sorted);  // kLdsSortMax * 8 bytes = kLdsKeys * 2
     {
         uint32_t off = wbase + incl - mine;
@@ -703,22 +795,12 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
+    ST_STAMP(sp.stamps, 2, slot, 2);
     // scores: one lane per passing item
-    auto score_of = [&](int dot_or_unused, int64_t item, const int8_t* row, float s_i) -> float {
-        (void)dot_or_unused;
-        if (!sp.weighted) return rescale(dot_rows(row, sp.queries + (int64_t)q * sp.d, sp.d), sp.qscale[q], s_i);
-        float sc = 0.0f;
-        for (int t = 0; t < sp.n_tasks; ++t) {
-            const int64_t qr = (int64_t)q * sp.n_tasks + t;
-            sc = __fmaf_rn(sp.w[t], rescale(dot_rows(row, sp.queries + qr * sp.d, sp.d), sp.qscale[qr], s_i), sc);
-        }
-        (void)item;
-        return sc;
-    };
     if (D16 == 0) {
         for (uint32_t e = tid; e < total; e += NT) {
-            const int64_t item = in_lds ? (int64_t)slist[e] : (int64_t)glist[e];
-            const float sc = score_of(0, item, sp.items + item * sp.d, sp.iscale[item]);
+            const int64_t item = begin + (in_lds ? (int64_t)slist[e] : (int64_t)glist[e]);
+            const float sc = pair_score(sp, q, sp.items + item * sp.d, sp.iscale[item]);
             const uint64_t key = make_key(sc, (uint32_t)item);
             if (in_lds) s_keys[e] = key;
             else gkeys[e] = key;
@@ -734,7 +816,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
             for (int u = 0; u < 2; ++u) {
                 const uint32_t e = e0 + u * NT;
                 const uint32_t ec = e < total ? e : e0;
-                item[u] = in_lds ? (int64_t)slist[ec] : (int64_t)glist[ec];
+                item[u] = begin + (in_lds ? (int64_t)slist[ec] : (int64_t)glist[ec]);
                 const int4* rp = reinterpret_cast<const int4*>(sp.items + item[u] * (DD * 16));
 #pragma unroll
                 for (int c = 0; c < DD; ++c) ra[u][c] = rp[c];
@@ -763,18 +845,58 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
+    ST_STAMP(sp.stamps, 2, slot, 3);
 
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
-    if (in_lds && !p.srt)
-        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red);
-    else
+    uint64_t kth = 0;
+    const bool publish_all = parts > 1 && total <= (uint32_t)pshare;
+    if (publish_all) {
+        n_out = (int)total;
+        sorted = s_keys;
+    } else if (in_lds && !p.srt) {
+        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, parts == 1 && p.last, kth,
+                         sp.stamps, 2, slot, 9);
+    } else {
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
+        kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
+    }
+    ST_STAMP(sp.stamps, 2, slot, 4);
+
+    if (parts > 1) {
+        // Publish this slice's list; the workgroup that completes the query merges all of them.
+        // Every store and load of the exchange is an agent-scope atomic (written through to, and
+        // read from, the level all compute dies share), and each thread waits for its stores
+        // before the completion counter is raised: no cache-wide write-back or invalidate is needed.
+        for (int i = tid; i < n_out; i += NT)
+            __hip_atomic_store(&gpart[(int64_t)part * pstride + i], sorted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid == 0)
+            __hip_atomic_store(&sp.cnt[(int64_t)q * p.groups + part], (uint32_t)n_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (tid == 0) s_misc[5] = __hip_atomic_fetch_add(&done[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __syncthreads();
+        ST_STAMP(sp.stamps, 2, slot, 5);
+        if (s_misc[5] != (uint32_t)(parts - 1)) return;  // uniform
+        uint32_t off = 0;
+        for (int pp = 0; pp < parts; ++pp) {
+            const uint32_t c = min(__hip_atomic_load(&sp.cnt[(int64_t)q * p.groups + pp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
+                                   (uint32_t)pstride);
+            for (uint32_t i = tid; i < c; i += NT)
+                s_keys[off + i] = __hip_atomic_load(&gpart[(int64_t)pp * pstride + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            off += c;
+        }
+        __syncthreads();
+        ST_STAMP(sp.stamps, 2, slot, 6);
+        n_out = lds_topk(s_keys, (int)off, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
+        sorted = s_sorted;
+        ST_STAMP(sp.stamps, 2, slot, 7);
+    }
     if (tid == 0) p.ovf[q] = 0u;
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
         if (tid == 0) {
-            const uint64_t t64 = n_out == p.K ? sorted[p.K - 1] : 0ULL;
+            const uint64_t t64 = kth;
             p.topk_cnt[q] = (uint32_t)n_out;
             p.tau[q] = t64;
             if (p.tau_img) {
@@ -786,10 +908,12 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
     }
+    ST_STAMP(sp.stamps, 2, slot, 8);
 }
 
 template <int D16>
-inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int batch, hipStream_t stream)
+inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int batch, int parts, uint32_t* done,
+                                hipStream_t stream)
 {
     static bool lds_set = false;
     if (!lds_set) {
@@ -798,17 +922,20 @@ inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int 
         if (e != hipSuccess) return e;
         lds_set = true;
     }
-    hipLaunchKernelGGL(seed_kernel<D16>, dim3(batch), dim3(kSeedThreads), kSelectLdsBytes, stream, se, seed_items);
+    hipLaunchKernelGGL(seed_kernel<D16>, dim3(batch, parts), dim3(kSeedThreads), kSelectLdsBytes, stream, se, seed_items,
+                       done);
     return hipGetLastError();
 }
 
-inline hipError_t launch_seed(const SelectParams& se, int64_t seed_items, int batch, hipStream_t stream)
+// done: batch zeroed counters in device memory (one per query)
+inline hipError_t launch_seed(const SelectParams& se, int64_t seed_items, int batch, int parts, uint32_t* done,
+                              hipStream_t stream)
 {
     switch (se.scan.d) {
-        case 64: return launch_seed_t<4>(se, seed_items, batch, stream);
-        case 128: return launch_seed_t<8>(se, seed_items, batch, stream);
-        case 256: return launch_seed_t<16>(se, seed_items, batch, stream);
-        default: return launch_seed_t<0>(se, seed_items, batch, stream);
+        case 64: return launch_seed_t<4>(se, seed_items, batch, parts, done, stream);
+        case 128: return launch_seed_t<8>(se, seed_items, batch, parts, done, stream);
+        case 256: return launch_seed_t<16>(se, seed_items, batch, parts, done, stream);
+        default: return launch_seed_t<0>(se, seed_items, batch, parts, done, stream);
     }
 }
 
