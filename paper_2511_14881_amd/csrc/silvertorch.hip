@@ -512,8 +512,12 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     st::MfmaParams mp;
     memset(&mp, 0, sizeof(mp));
     mp.n_blocks = (int32_t)(blk_row.size() / 16);
-    mp.q_split = set_mfma.n ? st::mfma_q_split(mp.n_blocks, d) : 1;
-    if (mp.q_split > 32) return fail(ST_EINVAL, "query batch too large for the resident-query scorer");
+    mp.q_split = 1;
+    mp.waves = 4;
+    if (set_mfma.n) {
+        st::mfma_choose_config(mp.n_blocks, d, n_tasks, set_mfma.n, 32, &mp.q_split, &mp.waves);
+        if (mp.q_split < 1) return fail(ST_EINVAL, "query batch too large for the resident-query scorer");
+    }
 
     const int32_t seg_cap = set_mfma.n ? st::mfma_max_seg_items(d) : st::kMaxSegItems;
     st::Plan plan;
@@ -598,7 +602,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp.cap = plan.cap;
     sp.groups = plan.groups;
 #ifdef ST_STAMPS
-    {  // tuning builds: ST_STAMPS_PTR = device address of a zeroed uint64 [3][4096][16] buffer
+    {  // tuning builds: ST_STAMPS_PTR = device address of a zeroed uint64 [17][4096][16] buffer (scan levels 0-7, select levels 8-15, seed 16)
         const char* e = getenv("ST_STAMPS_PTR");
         sp.stamps = e ? (uint64_t*)strtoull(e, nullptr, 0) : nullptr;
     }
@@ -657,6 +661,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         const st::Level& L_ = plan.level[lv];
         se.first = lv == 0;
         se.last = lv == plan.n_levels - 1;
+        se.scan.stamp_level = sp_m.stamp_level = sp_d.stamp_level = lv < 8 ? lv : 7;
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
             ST_HIP(st::launch_seed(se, L_.end, batch, st::seed_parts(batch, L.k_pad), (uint32_t*)(ws + L.meta + at_done), stream));
@@ -669,16 +674,18 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             q->seg_per_visit = L_.seg_per_visit;
             q->use_tau = lv > 0;
         }
+        // past the first level a visit is one segment per wavefront of the workgroup
+        if (lv > 0 && mp.waves > L_.seg_per_visit) sp_m.seg_per_visit = mp.waves;
         // workgroups with work: one visit (seg_per_visit segments) per step; launching no more
         // keeps idle workgroups from staging queries, and the selection reads only their regions
         const int64_t n_seg = (L_.end - L_.begin + L_.seg_items - 1) / L_.seg_items;
-        const int64_t n_visit = (n_seg + L_.seg_per_visit - 1) / L_.seg_per_visit;
+        const int64_t n_visit = (n_seg + sp_m.seg_per_visit - 1) / sp_m.seg_per_visit;
         int32_t regions = plan.groups;
         if (set_mfma.n) {
             int32_t gx = plan.groups / mp.q_split;
             if (!set_dot.n && n_visit < gx) gx = (int32_t)std::max<int64_t>(n_visit, 1);
             regions = set_dot.n ? plan.groups : gx * mp.q_split;
-            st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n);
+            st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n, mp.waves);
             mp.first_level = mfma_started ? 0 : 1;
             mfma_started = true;
             TimedLaunch t(0, stream);

@@ -34,7 +34,6 @@ constexpr int kMfmaQueryLds = 64 * 1024;   // LDS bytes for resident query rows 
 constexpr int kMfmaMinRows = 4;            // a group needs this many query rows to go to MFMA
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
 constexpr int kMfmaSegItems = 256;         // items per wavefront segment, at most (4 mask words x 8 filters = 32 lanes)
-constexpr int kMfmaWaves = kScanThreads / 64;
 constexpr int kQueueSlots = 128;           // queued admissions per wavefront (drained whenever 64 are waiting)
 
 inline constexpr int mfma_max_seg_items(int) { return kMfmaSegItems; }
@@ -59,6 +58,7 @@ struct MfmaParams {
     uint64_t* img_tau;           // [S][rows_local / T]  written by the selection kernel
     int32_t first_level;         // 1: build the resident state from the tables and write the image
     int32_t multi_block;         // 1: some filter group holds more than one query block in a row of workgroups
+    int32_t waves;               // wavefronts per workgroup: 4 or 8
     // dynamic LDS layout (byte offsets)
     int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_total;
 };
@@ -89,9 +89,12 @@ struct UnitRegs {
 #define ST_NB2 3
 #endif
 // MULTI = some filter group holds more than one 16-row query block in a row of workgroups.
-template <int KS, int TT, bool WEIGHTED, bool MULTI>
-__global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
+// NW = wavefronts per workgroup: 4, or 8 when the resident queries leave room for one workgroup
+// per compute unit only (twice the wavefronts then share one query image).
+template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW>
+__global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
+    constexpr int kThreads = NW * 64;
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int D = KS * 64;
     constexpr int CH = D / 16;  // 16-byte chunks per row
@@ -111,7 +114,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
     const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
-    ST_STAMP(p.stamps, 0, wg_lin, 0);
+    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 0);
     const int l16 = lane & 15, kg = lane >> 4;
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
     uint64_t* s_queue = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
@@ -126,13 +129,13 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
     const int n_seg = (int)((p.item_end - p.item_begin + seg_items - 1) / seg_items);
     const int n_visit = (n_seg + spv - 1) / spv;
     const int n_batches = (p.n_groups + FB - 1) / FB;
-    const int slots = wave < spv ? (spv - wave + kMfmaWaves - 1) / kMfmaWaves : 0;  // my segments per visit
+    const int slots = wave < spv ? (spv - wave + NW - 1) / NW : 0;  // my segments per visit
     const int my_visits = (int)blockIdx.x < n_visit ? (n_visit - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
     const int per_visit = slots * n_batches;
     const int n_stages = my_visits * per_visit;
     auto stage_seg = [&](int t) {  // segment index of stage t (may lie past the level's end: no items there)
         const int v = t / per_visit, r = t - v * per_visit;
-        return ((int)blockIdx.x + v * (int)gridDim.x) * spv + wave + (r / n_batches) * kMfmaWaves;
+        return ((int)blockIdx.x + v * (int)gridDim.x) * spv + wave + (r / n_batches) * NW;
     };
     auto stage_batch = [&](int t) { return (t % per_visit) % n_batches; };
 
@@ -195,11 +198,63 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         }
     }
 
-    // ---- workgroup-wide set-up: tables and resident queries into LDS
-    for (int i = tid; i < p.n_groups * kPrefetchRows; i += kScanThreads) s_prow[i] = mp.prow[i];
-    for (int g = tid; g <= p.n_groups; g += kScanThreads) {
+    // ---- workgroup-wide set-up: tables and resident queries into LDS.  The compiler keeps a
+    // global load behind the LDS stores that precede it, so a copy loop per table would pay one
+    // memory round trip each.  The first share of every table (all of it for ordinary sizes) is
+    // therefore requested up front, into registers, and stored afterwards; loops take what is left.
+    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 10);
+    const int n_prow = p.n_groups * kPrefetchRows;
+    const int n_piece = mp.first_level ? 0 : mp.rows_local * CH;   // 16-byte pieces of the query image
+    const int n_imgrow = mp.first_level ? 0 : mp.rows_local;
+    const int4* gq = reinterpret_cast<const int4*>(mp.img_q + (int64_t)y * mp.rows_local * D);
+    {
+        const int v_prow = mp.prow[tid < n_prow ? tid : 0];
+        const int gc = tid <= p.n_groups ? tid : 0;
+        const int v_rowoff = p.grp_row_off[gc];
+        const int v_b0 = mp.grp_blk_off[gc < p.n_groups ? gc : 0], v_b1 = mp.grp_blk_off[gc < p.n_groups ? gc + 1 : 0];
+        int4 v_img[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = tid + u * kThreads;
+            v_img[u] = i < n_piece ? gq[i] : make_int4(0, 0, 0, 0);
+        }
+        int v_qrow = -1;
+        float v_sq = 0.0f;
+        uint64_t v_tau = 0;
+        if (tid < n_imgrow) {
+            v_qrow = mp.img_qrow[y * mp.rows_local + tid];
+            v_sq = mp.img_sq[y * mp.rows_local + tid];
+            v_tau = mp.img_tau[y * (mp.rows_local / TT) + tid / TT];
+        }
+        if (tid < n_prow) s_prow[tid] = v_prow;
+        if (tid <= p.n_groups) {
+            s_rowoff[tid] = v_rowoff;
+            if (tid < p.n_groups) {  // the group's 16-row blocks that live in this row of workgroups
+                const int bf = v_b0 + ((y - v_b0) % S + S) % S;
+                s_gnblk[tid] = bf < v_b1 ? (v_b1 - bf + S - 1) / S : 0;
+                s_glrow[tid] = (bf / S) * 16;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = tid + u * kThreads;
+            if (i < n_piece) reinterpret_cast<int4*>(s_q)[i] = v_img[u];
+        }
+        if (tid < n_imgrow) {
+            s_qrow[tid] = v_qrow;
+            s_sq[tid] = v_sq;
+            s_tauf[tid] = v_qrow >= 0 ? (v_tau ? key_score(v_tau) : -__builtin_inff()) : __builtin_inff();
+            if ((tid % TT) == 0) {
+                s_cnt[tid / TT] = 0;
+                s_tau64[tid / TT] = v_tau;
+            }
+        }
+    }
+    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 11);
+    for (int i = tid + kThreads; i < n_prow; i += kThreads) s_prow[i] = mp.prow[i];
+    for (int g = tid + kThreads; g <= p.n_groups; g += kThreads) {
         s_rowoff[g] = p.grp_row_off[g];
-        if (g < p.n_groups) {  // the group's 16-row blocks that live in this row of workgroups
+        if (g < p.n_groups) {
             const int b0 = mp.grp_blk_off[g], b1 = mp.grp_blk_off[g + 1];
             const int bf = b0 + ((y - b0) % S + S) % S;
             s_gnblk[g] = bf < b1 ? (b1 - bf + S - 1) / S : 0;
@@ -207,7 +262,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         }
     }
     if (mp.first_level) {
-        for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
+        for (int lr = tid; lr < mp.rows_local; lr += kThreads) {
             const int b = (lr >> 4) * S + y;
             const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
             s_qrow[lr] = grow;
@@ -219,7 +274,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                 s_tau64[lr / TT] = t64;
             }
         }
-        for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) {
+        for (int i = tid; i < mp.rows_local * CH; i += kThreads) {
             const int lr = i / CH, c = i - lr * CH;
             const int b = (lr >> 4) * S + y;
             const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
@@ -230,16 +285,28 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         __syncthreads();
         if (blockIdx.x == 0) {  // publish the image for the later levels
             int4* gq = reinterpret_cast<int4*>(mp.img_q + (int64_t)y * mp.rows_local * D);
-            for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) gq[i] = reinterpret_cast<const int4*>(s_q)[i];
-            for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
+            for (int i = tid; i < mp.rows_local * CH; i += kThreads) gq[i] = reinterpret_cast<const int4*>(s_q)[i];
+            for (int lr = tid; lr < mp.rows_local; lr += kThreads) {
                 mp.img_sq[y * mp.rows_local + lr] = s_sq[lr];
                 mp.img_qrow[y * mp.rows_local + lr] = s_qrow[lr];
             }
         }
     } else {
-        const int4* gq = reinterpret_cast<const int4*>(mp.img_q + (int64_t)y * mp.rows_local * D);
-        for (int i = tid; i < mp.rows_local * CH; i += kScanThreads) reinterpret_cast<int4*>(s_q)[i] = gq[i];
-        for (int lr = tid; lr < mp.rows_local; lr += kScanThreads) {
+        // what the first share above did not cover
+        for (int i0 = tid + 8 * kThreads; i0 < n_piece; i0 += 8 * kThreads) {
+            int4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                v[u] = gq[i < n_piece ? i : i0];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + u * kThreads;
+                if (i < n_piece) reinterpret_cast<int4*>(s_q)[i] = v[u];
+            }
+        }
+        for (int lr = tid + kThreads; lr < mp.rows_local; lr += kThreads) {
             const int grow = mp.img_qrow[y * mp.rows_local + lr];
             s_qrow[lr] = grow;
             s_sq[lr] = mp.img_sq[y * mp.rows_local + lr];
@@ -260,7 +327,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
 #pragma unroll
     for (int k = 0; k < KS; ++k) a_off[k] = l16 * D + (((kg + 4 * k) ^ swz<KS>(l16)) << 4);
 
-    ST_STAMP(p.stamps, 0, wg_lin, 1);
+    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 1);
     for (int t = 0; t < n_stages; ++t) {
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
@@ -272,7 +339,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
 #pragma unroll
         for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
         prefetch_issue(t + 1);
-        if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 2);
+        if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 2);
         const int c = __popcll(mask);
         int incl = c;  // running count over the words of my filter
         for (int o = 1; o < SW; o <<= 1) {
@@ -302,7 +369,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         // first local query row and local block count of filter gi -> lane gi
         const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
         const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;
-        if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 3);
+        if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 3);
 
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
@@ -485,19 +552,19 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
                 for (int k = 0; k < NB; ++k) {
                     if (base + k < n_units) unit_compute(ring[k]);
                     unit_load(ring[k]);
-                    if (t == 0 && base == 0 && k == 0) ST_STAMP(p.stamps, 0, wg_lin, 4);
+                    if (t == 0 && base == 0 && k == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
                 }
             }
-            if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 5);
+            if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 5);
             while (qn > 0) drain();
         }
-        if (t == 0) ST_STAMP(p.stamps, 0, wg_lin, 6);
+        if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 6);
     }
-    ST_STAMP(p.stamps, 0, wg_lin, 7);
+    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 7);
     __syncthreads();
-    ST_STAMP(p.stamps, 0, wg_lin, 8);
+    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 8);
     // region fill counts: real ones for the queries this workgroup row owns, zero for the others
-    for (int i = tid * TT; i < mp.n_blocks * 16; i += kScanThreads * TT) {
+    for (int i = tid * TT; i < mp.n_blocks * 16; i += kThreads * TT) {
         const int grow = mp.blk_row[i];
         if (grow < 0) continue;
         const int q = grow / TT;
@@ -507,7 +574,7 @@ __global__ __launch_bounds__(kScanThreads, (KS <= 2 ? ST_MINW : 2)) void scan_mf
         p.cnt[(int64_t)q * p.groups + wg_lin] = c < (uint32_t)p.cap ? c : (uint32_t)p.cap;
         if (c > (uint32_t)p.cap) p.ovf[q] = 1u;
     }
-    ST_STAMP(p.stamps, 0, wg_lin, 9);
+    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 9);
 }
 
 inline bool mfma_shape_ok(int d, int n_tasks)
@@ -515,15 +582,38 @@ inline bool mfma_shape_ok(int d, int n_tasks)
     return (d == 64 || d == 128 || d == 256 || d == 512) && (n_tasks == 1 || n_tasks == 2 || n_tasks == 4);
 }
 
-// Smallest power of two S such that ceil(n_blocks / S) blocks of 16 rows of d bytes fit the LDS budget.
-inline int mfma_q_split(int n_blocks, int d)
+// LDS one workgroup needs with the resident queries split S ways and `waves` wavefronts.
+inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves);
+
+// Chooses the split S of the resident queries over rows of workgroups (every row scans the
+// corpus for its share of the queries) and the wavefronts per workgroup.  Cost model: passes
+// over the corpus divided by the wavefronts a compute unit holds at once (160 KB of LDS; at most
+// 16 wavefronts for d <= 128 and 8 above, from the register budget).  Ties go to fewer passes.
+inline void mfma_choose_config(int n_blocks, int d, int n_tasks, int n_groups, int max_split, int* out_S, int* out_waves)
 {
-    int S = 1;
-    while (((n_blocks + S - 1) / S) * 16 * d > kMfmaQueryLds) S <<= 1;
-    return S;
+    const int wave_cap = d <= 128 ? 16 : 8;
+    double best = 1e30;
+    int best_S = 0, best_w = 4;
+    for (int S = 1; S <= max_split; S <<= 1) {
+        for (int waves = 4; waves <= 8; waves += 4) {
+            const int lds = mfma_lds_bytes(n_blocks, S, d, n_tasks, n_groups, waves);
+            if (lds > 160 * 1024) continue;
+            int wgs = (160 * 1024) / lds;
+            if (wgs * waves > wave_cap) wgs = wave_cap / waves;
+            if (wgs < 1) continue;
+            const double cost = (double)S / (double)(wgs * waves);
+            if (cost < best * 0.999) {
+                best = cost;
+                best_S = S;
+                best_w = waves;
+            }
+        }
+    }
+    *out_S = best_S;  // 0: not even the largest split fits
+    *out_waves = best_w;
 }
 
-inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups)
+inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, int waves)
 {
     const int blocks_local = (mp->n_blocks + mp->q_split - 1) / mp->q_split;
     mp->rows_local = blocks_local * 16;
@@ -535,26 +625,35 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups)
     mp->lds_tau64 = take((mp->rows_local / n_tasks + 1) * 8);
     mp->lds_qrow = take(mp->rows_local * 4);
     mp->lds_cnt = take((mp->rows_local / n_tasks + 1) * 4);
-    mp->lds_list = take(kMfmaWaves * kMfmaFilterBatch * kMfmaSegItems);
-    mp->lds_queue = take(kMfmaWaves * kQueueSlots * 8);
+    mp->lds_list = take(waves * kMfmaFilterBatch * kMfmaSegItems);
+    mp->lds_queue = take(waves * kQueueSlots * 8);
     mp->lds_prow = take(n_groups * kPrefetchRows * 4);
     mp->lds_blkoff = take((2 * n_groups + 2) * 4);
     mp->lds_rowoff = take((n_groups + 1) * 4);
     mp->lds_total = off;
 }
 
-template <int KS, int TT, bool WEIGHTED, bool MULTI>
+inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves)
+{
+    MfmaParams t;
+    t.n_blocks = n_blocks;
+    t.q_split = S;
+    mfma_lds_layout(&t, d, n_tasks, n_groups, waves);
+    return t.lds_total;
+}
+
+template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW>
 inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
     static int max_set = 0;  // largest dynamic LDS size this instantiation has been allowed
     if (mp.lds_total > max_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED, MULTI>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, mp.lds_total);
         if (e != hipSuccess) return e;
         max_set = mp.lds_total;
     }
     const dim3 grid((unsigned)gx, (unsigned)mp.q_split);
-    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED, MULTI>), grid, dim3(kScanThreads), (size_t)mp.lds_total, stream, sp, mp);
+    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW>), grid, dim3(NW * 64), (size_t)mp.lds_total, stream, sp, mp);
     return hipGetLastError();
 }
 
@@ -565,11 +664,14 @@ inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, i
     const int ks = sp.d / 64, tt = sp.n_tasks;
 #define ST_CASE(K_, T_)                                                                                          \
     if (ks == K_ && tt == T_) {                                                                                  \
+        if (mp.waves == 8)                                                                                       \
+            return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true, 8>(sp, mp, gx, stream)                   \
+                               : launch_scan_mfma_t<K_, T_, false, true, 8>(sp, mp, gx, stream);                 \
         if (mp.multi_block)                                                                                      \
-            return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true>(sp, mp, gx, stream)                      \
-                               : launch_scan_mfma_t<K_, T_, false, true>(sp, mp, gx, stream);                    \
-        return sp.weighted ? launch_scan_mfma_t<K_, T_, true, false>(sp, mp, gx, stream)                         \
-                           : launch_scan_mfma_t<K_, T_, false, false>(sp, mp, gx, stream);                       \
+            return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true, 4>(sp, mp, gx, stream)                   \
+                               : launch_scan_mfma_t<K_, T_, false, true, 4>(sp, mp, gx, stream);                 \
+        return sp.weighted ? launch_scan_mfma_t<K_, T_, true, false, 4>(sp, mp, gx, stream)                      \
+                           : launch_scan_mfma_t<K_, T_, false, false, 4>(sp, mp, gx, stream);                    \
     }
     ST_CASE(1, 1) ST_CASE(1, 2) ST_CASE(1, 4)
     ST_CASE(2, 1) ST_CASE(2, 2) ST_CASE(2, 4)

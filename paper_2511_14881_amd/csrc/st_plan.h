@@ -19,6 +19,7 @@ constexpr int kMaxScanGroups = 2048;
 constexpr int kMaxLevels = 32;
 constexpr int kMaxSegItems = 512;    // items one workgroup takes per step, at most
 constexpr int kLdsSortMax = 2048;    // top-K lists up to this (padded) size are sorted in LDS
+constexpr int kSelectLdsKeys = 8192; // candidates per query the selection kernel handles in LDS
 
 struct Level {
     int64_t begin, end;      // item range [begin, end)
@@ -97,6 +98,12 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
     // K*(grow-1)/g_eff; aim at cap/4.  Never grow by less than 2x (extreme K with few sharing
     // workgroups): regions may then overflow and the slow exact path takes those queries.
     double grow = 1.0 + (double)cap * (double)g_eff / (4.0 * (double)K);
+    // a level should not admit more candidates per query (about K * (grow - 1)) than the selection
+    // kernel handles in LDS together with the running top-K
+    if (K <= kLdsSortMax) {
+        const double fit = 1.0 + 0.8 * (double)(kSelectLdsKeys - K) / (double)K;
+        if (grow > fit) grow = fit;
+    }
     if (grow < 2.0) grow = 2.0;
     while (cur < n_items) {
         if (p.n_levels >= kMaxLevels) return -1;
@@ -115,8 +122,10 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
     return 0;
 }
 
-// Region capacity from the sizes alone (it fixes the workspace layout): the smallest that keeps
-// the schedule at three levels or fewer when every workgroup shares every query, else the largest.
+// Region capacity from the sizes alone (it fixes the workspace layout).  The first level admits
+// every passing pair of groups * cap items, so its cost grows with the capacity; later levels
+// grow by at most cap * groups / (4K).  The smallest capacity that keeps the schedule at six
+// levels or fewer (every workgroup sharing every query) is taken, else the largest.
 inline int choose_cap(int64_t n_items, int32_t K)
 {
     static const int32_t caps[] = {64, 128, 256, 512};
@@ -127,7 +136,7 @@ inline int choose_cap(int64_t n_items, int32_t K)
         Plan p;
         if (make_levels(n_items, K, cap, scan_groups(), kMaxSegItems, 0, &p) != 0) continue;
         best = cap;
-        if (p.n_levels <= 3) break;
+        if (p.n_levels <= 6) break;
     }
     return best;
 }

@@ -47,6 +47,7 @@ struct ScanParams {
     int32_t cap;
     int32_t groups;              // G (== gridDim.x)
     uint64_t* stamps;            // null unless the library is built with ST_STAMPS (timeline probe)
+    int32_t stamp_level;         // level index the probe files this launch under
 };
 
 // Timeline probe for tuning builds (-DST_STAMPS): thread 0 of a workgroup records the 10-ns wall
@@ -524,7 +525,7 @@ struct SelectParams {
 };
 
 constexpr int kSelectThreads = 512;
-constexpr int kLdsKeys = 8192;  // candidates per query gathered in LDS; more go through global memory
+constexpr int kLdsKeys = kSelectLdsKeys;  // candidates per query gathered in LDS; more go through global memory
 
 // Slow exact path for a query whose candidate region overflowed in some level: rescans the whole
 // corpus for that query alone, keeping at most gath_cap keys and pruning to the best K whenever
@@ -589,7 +590,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     uint32_t* s_wsum = s_misc + 8;                                                 // [16]
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     constexpr int NT = kSelectThreads;
-    ST_STAMP(p.scan.stamps, 1, q, 0);
+    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 0);
     // counts are clamped to what the buffers can hold, whatever the memory says
     uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
     n_prev = n_prev < (uint32_t)p.K ? n_prev : (uint32_t)p.K;
@@ -624,7 +625,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         all += v;
     }
     const uint32_t total = n_prev + all;
-    ST_STAMP(p.scan.stamps, 1, q, 1);
+    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 1);
     const bool in_lds = total <= (uint32_t)kLdsKeys;
     uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
     {
@@ -657,7 +658,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         else gkeys[i] = v;
     }
     __syncthreads();
-    ST_STAMP(p.scan.stamps, 1, q, 2);
+    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 2);
 
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
@@ -669,7 +670,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
         kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
     }
-    ST_STAMP(p.scan.stamps, 1, q, 3);
+    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 3);
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
         if (tid == 0) {
@@ -685,7 +686,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
     }
-    ST_STAMP(p.scan.stamps, 1, q, 4);
+    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 4);
+#ifdef ST_STAMPS
+    if (p.scan.stamps && q < 4096)  // end of the slowest thread
+        atomicMax((unsigned long long*)&p.scan.stamps[(((8 + p.scan.stamp_level) * 4096) + q) * 16 + 5], (unsigned long long)wall_clock64());
+#endif
 }
 
 // Seed pass for small batches: the prefix [0, seed_items) of the corpus is scanned per query by
@@ -728,7 +733,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     constexpr int NT = kSeedThreads;
     const ScanParams& sp = p.scan;
     const int slot = q * parts + part;
-    ST_STAMP(sp.stamps, 2, slot, 0);
+    ST_STAMP(sp.stamps, 16, slot, 0);
     const int64_t n_all = seed_items < sp.n_items ? seed_items : sp.n_items;
     const int64_t part_items = seed_items / parts;  // whole tiles
     const int64_t begin = part * part_items;
@@ -772,7 +777,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     }
     if (lane == 63) s_wsum[wv] = incl;
     __syncthreads();
-    ST_STAMP(sp.stamps, 2, slot, 1);
+    ST_STAMP(sp.stamps, 16, slot, 1);
     uint32_t wbase = 0, total = 0;
     for (int w = 0; w < NT / 64; ++w) {
         const uint32_t v = s_wsum[w];
@@ -795,7 +800,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
-    ST_STAMP(sp.stamps, 2, slot, 2);
+    ST_STAMP(sp.stamps, 16, slot, 2);
     // scores: one lane per passing item
     if (D16 == 0) {
         for (uint32_t e = tid; e < total; e += NT) {
@@ -845,7 +850,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
-    ST_STAMP(sp.stamps, 2, slot, 3);
+    ST_STAMP(sp.stamps, 16, slot, 3);
 
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
@@ -856,12 +861,12 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         sorted = s_keys;
     } else if (in_lds && !p.srt) {
         n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, parts == 1 && p.last, kth,
-                         sp.stamps, 2, slot, 9);
+                         sp.stamps, 16, slot, 9);
     } else {
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
         kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
     }
-    ST_STAMP(sp.stamps, 2, slot, 4);
+    ST_STAMP(sp.stamps, 16, slot, 4);
 
     if (parts > 1) {
         // Publish this slice's list; the workgroup that completes the query merges all of them.
@@ -876,7 +881,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         __syncthreads();
         if (tid == 0) s_misc[5] = __hip_atomic_fetch_add(&done[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         __syncthreads();
-        ST_STAMP(sp.stamps, 2, slot, 5);
+        ST_STAMP(sp.stamps, 16, slot, 5);
         if (s_misc[5] != (uint32_t)(parts - 1)) return;  // uniform
         uint32_t off = 0;
         for (int pp = 0; pp < parts; ++pp) {
@@ -887,10 +892,10 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
             off += c;
         }
         __syncthreads();
-        ST_STAMP(sp.stamps, 2, slot, 6);
+        ST_STAMP(sp.stamps, 16, slot, 6);
         n_out = lds_topk(s_keys, (int)off, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
         sorted = s_sorted;
-        ST_STAMP(sp.stamps, 2, slot, 7);
+        ST_STAMP(sp.stamps, 16, slot, 7);
     }
     if (tid == 0) p.ovf[q] = 0u;
     if (!p.last) {
@@ -908,7 +913,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
     }
-    ST_STAMP(sp.stamps, 2, slot, 8);
+    ST_STAMP(sp.stamps, 16, slot, 8);
 }
 
 template <int D16>
