@@ -107,8 +107,8 @@ int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int
 /* Filtered top-K for a batch of queries (Algorithm 1, phases 3-4, all items in scope).
  *   bloom            index built over the same n_items items
  *   dev_items        [n_items, d] int8 row-major, 16-byte aligned; d % 16 == 0, d <= ST_MAX_DIM
- *   dev_item_scale   [n_items] fp32, finite and > 0
- *   dev_queries      [batch, d] int8;  dev_query_scale [batch] fp32, finite and > 0
+ *   dev_item_scale   [n_items] fp32, finite and > 0, 16-byte aligned
+ *   dev_queries      [batch, d] int8, 16-byte aligned;  dev_query_scale [batch] fp32, finite and > 0
  *   host_filt_ids / host_filt_offsets[batch+1]
  *                    query b keeps item i iff i passes the Bloom test for the conjunction of
  *                    ids [offsets[b], offsets[b+1]); an empty range keeps every item.  A

@@ -465,8 +465,9 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     if (need < 0) return (int)need;
     if (workspace_bytes < need)
         return fail(ST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
-    if (((uintptr_t)dev_workspace & 255) || ((uintptr_t)dev_items & 15) || ((uintptr_t)dev_queries & 15))
-        return fail(ST_EINVAL, "misaligned buffer (workspace 256 B, items and queries 16 B)");
+    if (((uintptr_t)dev_workspace & 255) || ((uintptr_t)dev_items & 15) || ((uintptr_t)dev_queries & 15) ||
+        ((uintptr_t)dev_item_scale & 15))
+        return fail(ST_EINVAL, "misaligned buffer (workspace 256 B; items, item scales and queries 16 B)");
     if (host_filt_offsets[0] != 0) return fail(ST_EINVAL, "host_filt_offsets[0] must be 0");
     if (host_filt_offsets[batch] > 0 && !host_filt_ids) return fail(ST_EINVAL, "host_filt_ids is null");
     const bool weighted = host_task_weight != nullptr;

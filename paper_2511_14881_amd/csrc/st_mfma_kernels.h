@@ -60,7 +60,7 @@ struct MfmaParams {
     int32_t multi_block;         // 1: some filter group holds more than one query block in a row of workgroups
     int32_t waves;               // wavefronts per workgroup: 4 or 8
     // dynamic LDS layout (byte offsets)
-    int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_total;
+    int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_tq, lds_thr, lds_scl, lds_total;
 };
 
 // chunk swizzle: keeps 16 consecutive rows of d bytes on distinct LDS banks when the 16 lanes
@@ -77,7 +77,8 @@ __device__ inline int swz(int row)
 template <int KS>
 struct UnitRegs {
     v4i b[KS];
-    float si;
+    float si;    // scale of the lane's item
+    int si_fix;  // the same as a fixed-point factor for the integer cull (plain search)
     int item;    // lane's item (l % 16), relative to the segment start; -1 = padding lane
     int gi;      // filter within the batch (uniform)
 };
@@ -118,6 +119,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     const int l16 = lane & 15, kg = lane >> 4;
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
     uint64_t* s_queue = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
+    float* s_tq = reinterpret_cast<float*>(lds + mp.lds_tq);                                    // [rows_local] tau / s_q per row
+    int* s_thr = reinterpret_cast<int*>(lds + mp.lds_thr) + wave * mp.rows_local;               // wave-private [rows_local]
+    float* s_scl = reinterpret_cast<float*>(lds + mp.lds_scl) + wave * kMfmaSegItems;           // wave-private [seg] item scales
 
     // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
     // workgroup; inside a visit wavefront w takes segments w, w + 4, ...  Stages of a wavefront
@@ -156,6 +160,20 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         for (int r = 0; r < kPrefetchRows; ++r) {
             const int row = s_prow[g * kPrefetchRows + r];
             pre[r] = row >= 0 ? base[(int64_t)row * kTileWords] : ~0ULL;
+        }
+    };
+    // item scales of a stage's segment: lane l fetches items 4l .. 4l+3 (zero past the end)
+    float4 pre_sc = make_float4(0.f, 0.f, 0.f, 0.f);
+    auto scale_issue = [&](int t) {
+        pre_sc = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (t >= n_stages || 4 * lane >= seg_items) return;
+        const int64_t i0 = p.item_begin + (int64_t)stage_seg(t) * seg_items + 4 * lane;
+        if (i0 + 3 < item_lim) {
+            pre_sc = *reinterpret_cast<const float4*>(p.iscale + i0);
+        } else {
+            if (i0 < item_lim) pre_sc.x = p.iscale[i0];
+            if (i0 + 1 < item_lim) pre_sc.y = p.iscale[i0 + 1];
+            if (i0 + 2 < item_lim) pre_sc.z = p.iscale[i0 + 2];
         }
     };
     auto prefetch_mask = [&](int t) -> uint64_t {  // mask word of my (filter, word) pair for stage t
@@ -197,6 +215,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             }
         }
     }
+    scale_issue(0);
 
     // ---- workgroup-wide set-up: tables and resident queries into LDS.  The compiler keeps a
     // global load behind the LDS stores that precede it, so a copy loop per table would pay one
@@ -320,6 +339,25 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         __syncthreads();
     }
 
+    // Plain search: tau / s_q per row, so that a pair can only be admitted if dot * s_i reaches it.
+    // +inf marks padding rows (never admitted), -inf rows that cannot be culled (no threshold yet,
+    // tau <= 0, or a quotient outside the range the bound is valid for).
+    if (!WEIGHTED) {
+        for (int lr = tid; lr < mp.rows_local; lr += kThreads) {
+            const float tf = s_tauf[lr];
+            const float inf = __builtin_inff();
+            float tq = -inf;
+            if (tf == inf) {
+                tq = inf;
+            } else if (tf > 0.0f) {
+                tq = tf / s_sq[lr];
+                if (!(tq > 0.0f && tq < inf)) tq = -inf;
+            }
+            s_tq[lr] = tq;
+        }
+        __syncthreads();
+    }
+
     // lane constants of the MFMA operand reads: byte offset of this lane's chunk k inside a
     // 16-row query block (the swizzle of row lrow + l16 depends on l16 only: lrow is a multiple
     // of 16), and of its four rows in the per-row tables
@@ -371,14 +409,48 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;
         if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 3);
 
+        // Item scales of the segment into LDS.  Plain search: their maximum fixes a power of two
+        // 2^E above every scale of the segment; the lane's scale becomes the fixed-point factor
+        // ceil(s_i * 2^(31-E)) and every row gets the integer bound floor(tau / s_q * 2^-(E+1)),
+        // shaved by more than all roundings involved.  A pair can only be admitted if
+        // mulhi(dot, factor) reaches the bound of its row, which costs two integer instructions per
+        // pair; the exact fp32 arithmetic runs when an entry is drained from the queue.
+        float fix_scale = 0.0f;  // 2^(31-E); 0: no cull in this segment
+        {
+            const float4 sc4 = pre_sc;
+            scale_issue(t + 1);
+            if (4 * lane < seg_items) *reinterpret_cast<float4*>(s_scl + 4 * lane) = sc4;
+            if (!WEIGHTED && n_units > 0) {
+                float smax = fmaxf(fmaxf(sc4.x, sc4.y), fmaxf(sc4.z, sc4.w));
+                for (int o = 32; o > 0; o >>= 1) smax = fmaxf(smax, __shfl_xor(smax, o));
+                int E = 0;
+                bool cull = smax > 0.0f && smax < __builtin_inff();
+                if (cull) {
+                    E = ilogbf(smax) + 1;  // 2^E > smax
+                    cull = E > -90 && E < 90;
+                }
+                fix_scale = cull ? ldexpf(1.0f, 31 - E) : 0.0f;
+                const float thr_scale = ldexpf(0.99999618530273f, -(E + 1));  // (1 - 2^-18) * 2^-(E+1)
+                for (int row = lane; row < mp.rows_local; row += 64) {
+                    const float tq = s_tq[row];
+                    int thr = (int)0x80000000;  // no bound
+                    if (tq == __builtin_inff())
+                        thr = 0x7FFFFFFF;       // padding row
+                    else if (cull && tq > 0.0f)
+                        thr = __float2int_rd(fminf(tq * thr_scale, 2.0e9f));
+                    s_thr[row] = thr;
+                }
+            }
+        }
+
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
         // contracted: uniform bases + 32-bit lane offsets (the segment spans at most 256 * D bytes)
         const char* seg_rows = reinterpret_cast<const char*>(p.items + item0 * D) + kg * 16;
-        const float* seg_scale = p.iscale + item0;
         int qn = 0;          // queued admissions (uniform)
-        int cur_lrow = -1;   // query block whose A operand, scales and thresholds sit in areg / cur_sq / cur_tf
-        float4 cur_sq = make_float4(0.f, 0.f, 0.f, 0.f), cur_tf = cur_sq;
+        int cur_lrow = -1;   // query block whose A operand (and per-row constants) sit in registers
+        float4 cur_sq = make_float4(0.f, 0.f, 0.f, 0.f), cur_tf = cur_sq;  // weighted search
+        int4 cur_thr = make_int4(0, 0, 0, 0);                              // plain search
         v4i areg[KS];
 
         // unit generator: (gen_gi, gen_b0) is the next unit to request; it stays on the last unit
@@ -401,7 +473,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 const int4 v = *reinterpret_cast<const int4*>(seg_rows + (off + 64u * k));
                 w.b[k] = v4i{v.x, v.y, v.z, v.w};
             }
-            w.si = seg_scale[(uint32_t)idx];
+            w.si = s_scl[idx];
+            w.si_fix = 0;
+            if (!WEIGHTED) w.si_fix = __float2int_ru(w.si * fix_scale);  // < 2^31: s_i < 2^E
             if (gen_left > 0) {  // advance (scalar)
                 --gen_left;
                 gen_b0 += 16;
@@ -414,7 +488,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         };
         // Admissions are queued (wave-private LDS, positions from a ballot: no waiting) and
         // drained 64 at a time, one candidate per lane, so that the LDS round trips of the
-        // counter update are paid once per 64 candidates instead of once per unit.
+        // counter update are paid once per 64 candidates instead of once per unit.  An entry holds
+        // the local row, the item's place in the segment and the aggregated score (weighted
+        // search) or the int32 dot product (plain search, rescaled here).
         //
         // The store of a drained candidate is written in assembly and waited for on the spot.
         // On this target loads and stores share one outstanding-operation counter; a store the
@@ -427,7 +503,13 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             if (base + lane < qn) {
                 const uint64_t e = s_queue[base + lane];
                 const int srow = (int)((uint32_t)e >> 8);  // local row of the query's first task
-                const uint64_t key = make_key(__uint_as_float((uint32_t)(e >> 32)), (uint32_t)(item0 + (int)(e & 255u)));
+                const int it = (int)(e & 255u);
+                float score;
+                if (WEIGHTED)
+                    score = __uint_as_float((uint32_t)(e >> 32));
+                else
+                    score = rescale((int)(uint32_t)(e >> 32), s_sq[srow], s_scl[it]);
+                const uint64_t key = make_key(score, (uint32_t)(item0 + it));
                 const int grow = s_qrow[srow];
                 if (grow >= 0 && key >= s_tau64[srow / TT]) {
                     const uint32_t at = atomicAdd(&s_cnt[srow / TT], 1u);
@@ -439,34 +521,47 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             }
             qn = base;
         };
-        // Scores of one block's accumulators (this lane: one item, four query rows; with TT tasks
-        // per query the aggregate of query q0 is left in sc[q0]) and the lanes with an admission.
+        // Weighted search: scores of one block's accumulators (this lane: one item, four query
+        // rows; the aggregate of query q0 is left in sc[q0]) and the lanes with an admission.
         auto block_scores = [&](const float4& sq4, const float4& tf4, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid,
-                                float (&sc)[4], uint64_t (&hits)[4]) -> bool {
+                                uint32_t (&val)[4], uint64_t (&hits)[4]) -> bool {
             const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
             const float tfv[4] = {tf4.x, tf4.y, tf4.z, tf4.w};
+            float sc[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si);
-            if (WEIGHTED) {
-                // Value-Model sum over the TT tasks of each query this lane holds
+            // Value-Model sum over the TT tasks of each query this lane holds
 #pragma unroll
-                for (int q0 = 0; q0 < 4; q0 += TT) {
-                    float agg = 0.0f;
+            for (int q0 = 0; q0 < 4; q0 += TT) {
+                float agg = 0.0f;
 #pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
-                    sc[q0] = agg;
-                }
+                for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
+                sc[q0] = agg;
             }
             uint64_t any = 0;
 #pragma unroll
             for (int r = 0; r < 4; r += TT) {
                 hits[r] = ballot(sc[r] >= tfv[r]) & valid;
+                val[r] = __float_as_uint(sc[r]);
                 any |= hits[r];
             }
             return any != 0;
         };
-        // Queues the admissions of a block (rare path).
-        auto block_push = [&](int lrow, const UnitRegs<KS>& w, const float (&sc)[4], const uint64_t (&hits)[4]) {
+        // Plain search: the integer cull; candidates carry their int32 dot product.
+        auto block_cull = [&](const int4& thr, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid, uint32_t (&val)[4],
+                              uint64_t (&hits)[4]) -> bool {
+            const int thv[4] = {thr.x, thr.y, thr.z, thr.w};
+            uint64_t any = 0;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                hits[r] = ballot(__mulhi(acc[r], w.si_fix) >= thv[r]) & valid;
+                val[r] = (uint32_t)acc[r];
+                any |= hits[r];
+            }
+            return any != 0;
+        };
+        // Queues the candidates of a block (rare path).
+        auto block_push = [&](int lrow, const UnitRegs<KS>& w, const uint32_t (&val)[4], const uint64_t (&hits)[4]) {
 #pragma unroll
             for (int r = 0; r < 4; r += TT) {
                 const uint64_t m = hits[r];
@@ -474,8 +569,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                     if ((m >> lane) & 1ULL) {
                         const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                        // raw score, local row and item: the sort key is built when the entry is drained
-                        s_queue[pos] = ((uint64_t)__float_as_uint(sc[r]) << 32) | (uint32_t)(((lrow + 4 * kg + r) << 8) | w.item);
+                        s_queue[pos] = ((uint64_t)val[r] << 32) | (uint32_t)(((lrow + 4 * kg + r) << 8) | w.item);
                     }
                     qn += __popcll(m);
                     if (qn >= 64) drain();
@@ -496,26 +590,39 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             for (int k = 0; k < KS; ++k) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[k], w.b[k], acc, 0, 0, 0);
             return acc;
         };
+        auto row_sq = [&](int lrow) { return *reinterpret_cast<const float4*>(s_sq + lrow + 4 * kg); };
+        auto row_tf = [&](int lrow) { return *reinterpret_cast<const float4*>(s_tauf + lrow + 4 * kg); };
+        auto row_thr = [&](int lrow) { return *reinterpret_cast<const int4*>(s_thr + lrow + 4 * kg); };
+        // the test of one block, from the per-row constants in LDS
+        auto block_test = [&](int lrow, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid, uint32_t (&val)[4],
+                              uint64_t (&hits)[4]) -> bool {
+            if (WEIGHTED) return block_scores(row_sq(lrow), row_tf(lrow), acc, w, valid, val, hits);
+            return block_cull(row_thr(lrow), acc, w, valid, val, hits);
+        };
         // Contracts one unit with the query blocks of its filter group, two blocks per round (the
         // operands of both are read before either is used).  A group of a single block keeps its
-        // A operand in registers from one unit to the next.
+        // A operand and per-row constants in registers from one unit to the next.
         auto unit_compute = [&](const UnitRegs<KS>& w) {
             const int lrow0 = __builtin_amdgcn_readlane(glrow, w.gi);
             const int nblk = __builtin_amdgcn_readlane(gnblk, w.gi);
-            float sc[4], sc2[4];
+            uint32_t val[4], val2[4];
             uint64_t hits[4], hits2[4];
             const uint64_t valid = ballot(w.item >= 0);  // lanes that hold a real item
-            auto row_sq = [&](int lrow) { return *reinterpret_cast<const float4*>(s_sq + lrow + 4 * kg); };
-            auto row_tf = [&](int lrow) { return *reinterpret_cast<const float4*>(s_tauf + lrow + 4 * kg); };
             if (!MULTI || nblk == 1) {
                 if (cur_lrow != lrow0) {
                     block_a(lrow0, areg);
-                    cur_sq = row_sq(lrow0);
-                    cur_tf = row_tf(lrow0);
+                    if (WEIGHTED) {
+                        cur_sq = row_sq(lrow0);
+                        cur_tf = row_tf(lrow0);
+                    } else {
+                        cur_thr = row_thr(lrow0);
+                    }
                     cur_lrow = lrow0;
                 }
                 const v4i acc = block_mfma(areg, w);
-                if (block_scores(cur_sq, cur_tf, acc, w, valid, sc, hits)) block_push(lrow0, w, sc, hits);
+                const bool any = WEIGHTED ? block_scores(cur_sq, cur_tf, acc, w, valid, val, hits)
+                                          : block_cull(cur_thr, acc, w, valid, val, hits);
+                if (any) block_push(lrow0, w, val, hits);
                 return;
             }
             if (!MULTI) return;
@@ -526,17 +633,16 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 block_a(lrow0 + 16 * j + 16, b);
                 const v4i acc = block_mfma(a, w);
                 const v4i acc2 = block_mfma(b, w);
-                const bool any = block_scores(row_sq(lrow0 + 16 * j), row_tf(lrow0 + 16 * j), acc, w, valid, sc, hits);
-                const bool any2 = block_scores(row_sq(lrow0 + 16 * j + 16), row_tf(lrow0 + 16 * j + 16), acc2, w, valid, sc2, hits2);
-                if (any) block_push(lrow0 + 16 * j, w, sc, hits);
-                if (any2) block_push(lrow0 + 16 * j + 16, w, sc2, hits2);
+                const bool any = block_test(lrow0 + 16 * j, acc, w, valid, val, hits);
+                const bool any2 = block_test(lrow0 + 16 * j + 16, acc2, w, valid, val2, hits2);
+                if (any) block_push(lrow0 + 16 * j, w, val, hits);
+                if (any2) block_push(lrow0 + 16 * j + 16, w, val2, hits2);
             }
             if (j < nblk) {
                 v4i a[KS];
                 block_a(lrow0 + 16 * j, a);
                 const v4i acc = block_mfma(a, w);
-                if (block_scores(row_sq(lrow0 + 16 * j), row_tf(lrow0 + 16 * j), acc, w, valid, sc, hits))
-                    block_push(lrow0 + 16 * j, w, sc, hits);
+                if (block_test(lrow0 + 16 * j, acc, w, valid, val, hits)) block_push(lrow0 + 16 * j, w, val, hits);
             }
         };
         // Every load in the loop is unconditional (requests past the end repeat the last unit):
@@ -630,6 +736,9 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, in
     mp->lds_prow = take(n_groups * kPrefetchRows * 4);
     mp->lds_blkoff = take((2 * n_groups + 2) * 4);
     mp->lds_rowoff = take((n_groups + 1) * 4);
+    mp->lds_tq = take(mp->rows_local * 4);
+    mp->lds_thr = take(waves * mp->rows_local * 4);
+    mp->lds_scl = take(waves * kMfmaSegItems * 4);
     mp->lds_total = off;
 }
 
