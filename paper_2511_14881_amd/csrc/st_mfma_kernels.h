@@ -312,19 +312,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         }
     } else {
         // what the first share above did not cover
-        for (int i0 = tid + 8 * kThreads; i0 < n_piece; i0 += 8 * kThreads) {
-            int4 v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = i0 + u * kThreads;
-                v[u] = gq[i < n_piece ? i : i0];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int i = i0 + u * kThreads;
-                if (i < n_piece) reinterpret_cast<int4*>(s_q)[i] = v[u];
-            }
-        }
+        for (int i = tid + 8 * kThreads; i < n_piece; i += kThreads) reinterpret_cast<int4*>(s_q)[i] = gq[i];
         for (int lr = tid + kThreads; lr < mp.rows_local; lr += kThreads) {
             const int grow = mp.img_qrow[y * mp.rows_local + lr];
             s_qrow[lr] = grow;
@@ -541,11 +529,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             uint64_t any = 0;
 #pragma unroll
             for (int r = 0; r < 4; r += TT) {
-                hits[r] = ballot(sc[r] >= tfv[r]) & valid;
+                hits[r] = ballot(sc[r] >= tfv[r]);
                 val[r] = __float_as_uint(sc[r]);
                 any |= hits[r];
             }
-            return any != 0;
+            return (any & valid) != 0;
         };
         // Plain search: the integer cull; candidates carry their int32 dot product.
         auto block_cull = [&](const int4& thr, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid, uint32_t (&val)[4],
@@ -554,17 +542,18 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             uint64_t any = 0;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                hits[r] = ballot(__mulhi(acc[r], w.si_fix) >= thv[r]) & valid;
+                hits[r] = ballot(__mulhi(acc[r], w.si_fix) >= thv[r]);
                 val[r] = (uint32_t)acc[r];
                 any |= hits[r];
             }
-            return any != 0;
+            return (any & valid) != 0;
         };
         // Queues the candidates of a block (rare path).
-        auto block_push = [&](int lrow, const UnitRegs<KS>& w, const uint32_t (&val)[4], const uint64_t (&hits)[4]) {
+        auto block_push = [&](int lrow, const UnitRegs<KS>& w, uint64_t valid, const uint32_t (&val)[4],
+                              const uint64_t (&hits)[4]) {
 #pragma unroll
             for (int r = 0; r < 4; r += TT) {
-                const uint64_t m = hits[r];
+                const uint64_t m = hits[r] & valid;
                 if (m) {  // uniform
                     if ((m >> lane) & 1ULL) {
                         const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
@@ -605,8 +594,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         auto unit_compute = [&](const UnitRegs<KS>& w) {
             const int lrow0 = __builtin_amdgcn_readlane(glrow, w.gi);
             const int nblk = __builtin_amdgcn_readlane(gnblk, w.gi);
-            uint32_t val[4], val2[4];
-            uint64_t hits[4], hits2[4];
+            uint32_t val[4];
+            uint64_t hits[4];
             const uint64_t valid = ballot(w.item >= 0);  // lanes that hold a real item
             if (!MULTI || nblk == 1) {
                 if (cur_lrow != lrow0) {
@@ -622,27 +611,52 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 const v4i acc = block_mfma(areg, w);
                 const bool any = WEIGHTED ? block_scores(cur_sq, cur_tf, acc, w, valid, val, hits)
                                           : block_cull(cur_thr, acc, w, valid, val, hits);
-                if (any) block_push(lrow0, w, val, hits);
+                if (any) block_push(lrow0, w, valid, val, hits);
                 return;
             }
             if (!MULTI) return;
             int j = 0;
-            for (; j + 1 < nblk; j += 2) {
-                v4i a[KS], b[KS];
-                block_a(lrow0 + 16 * j, a);
-                block_a(lrow0 + 16 * j + 16, b);
-                const v4i acc = block_mfma(a, w);
-                const v4i acc2 = block_mfma(b, w);
-                const bool any = block_test(lrow0 + 16 * j, acc, w, valid, val, hits);
-                const bool any2 = block_test(lrow0 + 16 * j + 16, acc2, w, valid, val2, hits2);
-                if (any) block_push(lrow0 + 16 * j, w, val, hits);
-                if (any2) block_push(lrow0 + 16 * j + 16, w, val2, hits2);
+            if (NW == 8) {  // four blocks per round: independent chains, the registers allow it at 8 wavefronts
+                for (; j + 4 <= nblk; j += 4) {
+                    const int l0 = lrow0 + 16 * j;
+                    v4i a0[KS], a1[KS], a2[KS], a3[KS];
+                    uint32_t v0[4], v1[4], v2[4], v3[4];
+                    uint64_t h0[4], h1[4], h2[4], h3[4];
+                    block_a(l0, a0);
+                    block_a(l0 + 16, a1);
+                    block_a(l0 + 32, a2);
+                    block_a(l0 + 48, a3);
+                    const v4i c0 = block_mfma(a0, w), c1 = block_mfma(a1, w), c2 = block_mfma(a2, w), c3 = block_mfma(a3, w);
+                    const bool y0 = block_test(l0, c0, w, valid, v0, h0);
+                    const bool y1 = block_test(l0 + 16, c1, w, valid, v1, h1);
+                    const bool y2 = block_test(l0 + 32, c2, w, valid, v2, h2);
+                    const bool y3 = block_test(l0 + 48, c3, w, valid, v3, h3);
+                    if (y0) block_push(l0, w, valid, v0, h0);
+                    if (y1) block_push(l0 + 16, w, valid, v1, h1);
+                    if (y2) block_push(l0 + 32, w, valid, v2, h2);
+                    if (y3) block_push(l0 + 48, w, valid, v3, h3);
+                }
             }
-            if (j < nblk) {
+            for (; j + 2 <= nblk; j += 2) {
+                const int l0 = lrow0 + 16 * j;
+                v4i a0[KS], a1[KS];
+                uint32_t v0[4], v1[4];
+                uint64_t h0[4], h1[4];
+                block_a(l0, a0);
+                block_a(l0 + 16, a1);
+                const v4i c0 = block_mfma(a0, w), c1 = block_mfma(a1, w);
+                const bool y0 = block_test(l0, c0, w, valid, v0, h0);
+                const bool y1 = block_test(l0 + 16, c1, w, valid, v1, h1);
+                if (y0) block_push(l0, w, valid, v0, h0);
+                if (y1) block_push(l0 + 16, w, valid, v1, h1);
+            }
+            for (; j < nblk; ++j) {
                 v4i a[KS];
+                uint32_t val[4];
+                uint64_t hits[4];
                 block_a(lrow0 + 16 * j, a);
                 const v4i acc = block_mfma(a, w);
-                if (block_test(lrow0 + 16 * j, acc, w, valid, val, hits)) block_push(lrow0 + 16 * j, w, val, hits);
+                if (block_test(lrow0 + 16 * j, acc, w, valid, val, hits)) block_push(lrow0 + 16 * j, w, valid, val, hits);
             }
         };
         // Every load in the loop is unconditional (requests past the end repeat the last unit):
