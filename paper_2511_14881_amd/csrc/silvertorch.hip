@@ -11,7 +11,9 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
+#include <atomic>
 #include <mutex>
+#include <random>
 #include <new>
 #include <vector>
 
@@ -76,6 +78,7 @@ struct TimedLaunch {
 // so a slot is reused only after the event recorded behind its copy has completed.
 struct Stage {
     void* host = nullptr;
+    void* dev_view = nullptr;  // the same memory as the device addresses it
     size_t bytes = 0;
     hipEvent_t ev = nullptr;
     bool in_flight = false;
@@ -84,6 +87,17 @@ constexpr int kStages = 16;
 Stage g_stage[kStages];
 int g_stage_next = 0;
 std::mutex g_stage_mu;
+
+// Per-call mark of the seed pass: starts from a random value and never repeats in a process.
+uint64_t next_epoch()
+{
+    static std::atomic<uint64_t> e{[] {
+        std::random_device rd;
+        return ((uint64_t)rd() << 32) ^ (uint64_t)rd() ^ 0x9E3779B97F4A7C15ULL;
+    }()};
+    uint64_t v = e.fetch_add(1, std::memory_order_relaxed);
+    return v ? v : e.fetch_add(1, std::memory_order_relaxed);
+}
 
 int stage_acquire(size_t bytes, Stage** out)
 {
@@ -102,6 +116,7 @@ int stage_acquire(size_t bytes, Stage** out)
         const size_t want = std::max<size_t>(bytes, 64 * 1024);
         ST_HIP(hipHostMalloc(&s.host, want, hipHostMallocDefault));
         s.bytes = want;
+        ST_HIP(hipHostGetDevicePointer(&s.dev_view, s.host, 0));
     }
     *out = &s;
     return ST_OK;
@@ -569,7 +584,6 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         q_prow[(size_t)b * (st::kSeedRows + 1) + st::kSeedRows] = nr;
     }
     const size_t at_qprow = blob.add(q_prow);
-    const size_t at_done = blob.add(std::vector<int32_t>((size_t)batch, 0));  // seed pass: slices finished per query
     if (blob.bytes() > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
 
     char* ws = (char*)dev_workspace;
@@ -577,8 +591,13 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     rc = stage_acquire(blob.bytes(), &stage);
     if (rc != ST_OK) return rc;
     memcpy(stage->host, blob.data.data(), blob.bytes());
-    ST_HIP(hipMemcpyAsync(ws + L.meta, stage->host, blob.bytes(), hipMemcpyHostToDevice, stream));
-    ST_HIP(hipEventRecord(stage->ev, stream));
+    // A search that starts with the seed pass lets that kernel bring the tables over (it reads its
+    // own from the pinned copy); otherwise they are copied ahead of the first kernel.
+    const bool seed_uploads = plan.n_levels > 0 && plan.level[0].seed;
+    if (!seed_uploads) {
+        ST_HIP(hipMemcpyAsync(ws + L.meta, stage->host, blob.bytes(), hipMemcpyHostToDevice, stream));
+        ST_HIP(hipEventRecord(stage->ev, stream));
+    }
     stage->in_flight = true;
     auto tab = [&](size_t at) { return (const int32_t*)(ws + L.meta + at); };
 
@@ -665,7 +684,21 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         se.scan.stamp_level = sp_m.stamp_level = sp_d.stamp_level = lv < 8 ? lv : 7;
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
-            ST_HIP(st::launch_seed(se, L_.end, batch, st::seed_parts(batch, L.k_pad), (uint32_t*)(ws + L.meta + at_done), stream));
+            st::SeedUpload up;
+            up.src = (const int32_t*)stage->dev_view;
+            up.dst = (int32_t*)(ws + L.meta);
+            up.words = (int32_t)(blob.bytes() / 4);
+            up.epoch = next_epoch();
+            up.flags = (uint64_t*)(ws + L.seed_flags);
+            st::SelectParams se_seed = se;  // the seed pass reads its tables from the pinned copy
+            auto host_tab = [&](size_t at) { return (const int32_t*)((const char*)stage->dev_view + at); };
+            se_seed.q_prow = host_tab(at_qprow);
+            se_seed.q2grp = host_tab(at_q2grp);
+            se_seed.q_taupos = host_tab(at_taupos);
+            se_seed.scan.grp_row_off = host_tab(at_all_row_off);
+            se_seed.scan.grp_rows = host_tab(at_all_rows);
+            ST_HIP(st::launch_seed(se_seed, L_.end, batch, st::seed_parts(batch, L.k_pad), up, stream));
+            ST_HIP(hipEventRecord(stage->ev, stream));
             continue;
         }
         for (st::ScanParams* q : {&sp_m, &sp_d}) {

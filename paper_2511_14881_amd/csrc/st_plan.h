@@ -178,6 +178,7 @@ struct Layout {
     size_t gath;              // uint64 [B][K + G*cap]  contiguous copy for selection
     size_t srt;               // uint64 [B][Kpad]       only when Kpad > kLdsSortMax
     size_t img_q, img_sq, img_qrow, img_tau;  // resident-query image of the MFMA scorer
+    size_t seed_flags;        // uint64 [B][9]    seed pass: slice completion marks and the merge claim
     size_t img_rows;          // rows the image has room for
     size_t total;
     int64_t gath_cap;
@@ -187,8 +188,7 @@ struct Layout {
 inline size_t meta_bound_bytes(int32_t batch)
 {
     // group tables (rows: at most 64 per query, twice: all groups and the per-scorer copies),
-    // query lists, offsets, MFMA block tables (at most 16*(T/16 + 1) rows per query), the seed pass's
-    // completion counters, slack
+    // query lists, offsets, MFMA block tables (at most 16*(T/16 + 1) rows per query), slack
     return (size_t)round_up(4096 + (size_t)batch * 776, 256);
 }
 
@@ -216,6 +216,7 @@ inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 1
     L.img_sq = take(L.img_rows * 4);
     L.img_qrow = take(L.img_rows * 4);
     L.img_tau = take(L.img_rows * 8);
+    L.seed_flags = take((size_t)batch * 9 * 8);
     L.total = off;
     return L;
 }

@@ -715,10 +715,23 @@ inline int seed_parts(int batch, int k_pad)
     return parts;
 }
 
+// The seed pass is the first kernel of a search, so it also brings the call's table blob to the
+// device: its own tables are read from the caller-side pinned copy (the table pointers in p that it
+// uses point there), and the workgroups copy the blob, a share each, to where the later kernels
+// expect it.  flags[batch][kSeedMaxParts + 1] need no initialisation: a slice marks its result with
+// the call's epoch, a value no earlier content of the workspace equals.
+struct SeedUpload {
+    const int32_t* src;  // pinned host memory, device-visible
+    int32_t* dst;        // table area of the workspace
+    int32_t words;
+    uint64_t epoch;
+    uint64_t* flags;
+};
+
 // D16 = d / 16 for d in {64, 128, 256} (item rows staged in registers, two items per thread in
-// flight), 0 = any other d (plain loop).  Grid (batch, parts).  done[batch] must be zero at launch.
+// flight), 0 = any other d (plain loop).  Grid (batch, parts).
 template <int D16>
-__global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int64_t seed_items, uint32_t* done)
+__global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int64_t seed_items, SeedUpload up)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
     uint64_t* s_keys = reinterpret_cast<uint64_t*>(sel_lds);                       // [kLdsKeys]
@@ -734,6 +747,12 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     const ScanParams& sp = p.scan;
     const int slot = q * parts + part;
     ST_STAMP(sp.stamps, 16, slot, 0);
+    {  // this workgroup's share of the table blob
+        const int n_wg = (int)(gridDim.x * gridDim.y);
+        const int share = (up.words + n_wg - 1) / n_wg;
+        const int w0 = slot * share;
+        for (int i = tid; i < share && w0 + i < up.words; i += NT) up.dst[w0 + i] = up.src[w0 + i];
+    }
     const int64_t n_all = seed_items < sp.n_items ? seed_items : sp.n_items;
     const int64_t part_items = seed_items / parts;  // whole tiles
     const int64_t begin = part * part_items;
@@ -872,17 +891,30 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         // Publish this slice's list; the workgroup that completes the query merges all of them.
         // Every store and load of the exchange is an agent-scope atomic (written through to, and
         // read from, the level all compute dies share), and each thread waits for its stores
-        // before the completion counter is raised: no cache-wide write-back or invalidate is needed.
+        // before the slice is marked done: no cache-wide write-back or invalidate is needed.
         for (int i = tid; i < n_out; i += NT)
             __hip_atomic_store(&gpart[(int64_t)part * pstride + i], sorted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (tid == 0)
             __hip_atomic_store(&sp.cnt[(int64_t)q * p.groups + part], (uint32_t)n_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();
-        if (tid == 0) s_misc[5] = __hip_atomic_fetch_add(&done[q], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // mark this slice done, then look at all marks: the workgroup whose mark lands last sees
+        // every other mark.  Two that finish together may both see all, so the merge is claimed
+        // with an exchange on one more word: only the first to put the epoch there goes on.
+        if (tid == 0) {
+            uint64_t* fq = up.flags + (int64_t)q * (kSeedMaxParts + 1);
+            __hip_atomic_store(&fq[part], up.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            uint32_t all = 1;
+            for (int pp = 0; pp < parts; ++pp)
+                all &= __hip_atomic_load(&fq[pp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == up.epoch ? 1u : 0u;
+            if (all)
+                all = __hip_atomic_exchange(&fq[kSeedMaxParts], up.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != up.epoch ? 1u : 0u;
+            s_misc[5] = all;
+        }
         __syncthreads();
         ST_STAMP(sp.stamps, 16, slot, 5);
-        if (s_misc[5] != (uint32_t)(parts - 1)) return;  // uniform
+        if (s_misc[5] == 0u) return;  // uniform
         uint32_t off = 0;
         for (int pp = 0; pp < parts; ++pp) {
             const uint32_t c = min(__hip_atomic_load(&sp.cnt[(int64_t)q * p.groups + pp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
@@ -917,7 +949,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
 }
 
 template <int D16>
-inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int batch, int parts, uint32_t* done,
+inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int batch, int parts, const SeedUpload& up,
                                 hipStream_t stream)
 {
     static bool lds_set = false;
@@ -928,19 +960,18 @@ inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int 
         lds_set = true;
     }
     hipLaunchKernelGGL(seed_kernel<D16>, dim3(batch, parts), dim3(kSeedThreads), kSelectLdsBytes, stream, se, seed_items,
-                       done);
+                       up);
     return hipGetLastError();
 }
 
-// done: batch zeroed counters in device memory (one per query)
-inline hipError_t launch_seed(const SelectParams& se, int64_t seed_items, int batch, int parts, uint32_t* done,
+inline hipError_t launch_seed(const SelectParams& se, int64_t seed_items, int batch, int parts, const SeedUpload& up,
                               hipStream_t stream)
 {
     switch (se.scan.d) {
-        case 64: return launch_seed_t<4>(se, seed_items, batch, parts, done, stream);
-        case 128: return launch_seed_t<8>(se, seed_items, batch, parts, done, stream);
-        case 256: return launch_seed_t<16>(se, seed_items, batch, parts, done, stream);
-        default: return launch_seed_t<0>(se, seed_items, batch, parts, done, stream);
+        case 64: return launch_seed_t<4>(se, seed_items, batch, parts, up, stream);
+        case 128: return launch_seed_t<8>(se, seed_items, batch, parts, up, stream);
+        case 256: return launch_seed_t<16>(se, seed_items, batch, parts, up, stream);
+        default: return launch_seed_t<0>(se, seed_items, batch, parts, up, stream);
     }
 }
 
