@@ -11,9 +11,7 @@
 #include <cstdio>
 #include <cstring>
 #include <map>
-#include <atomic>
 #include <mutex>
-#include <random>
 #include <new>
 #include <vector>
 
@@ -87,17 +85,6 @@ constexpr int kStages = 16;
 Stage g_stage[kStages];
 int g_stage_next = 0;
 std::mutex g_stage_mu;
-
-// Per-call mark of the seed pass: starts from a random value and never repeats in a process.
-uint64_t next_epoch()
-{
-    static std::atomic<uint64_t> e{[] {
-        std::random_device rd;
-        return ((uint64_t)rd() << 32) ^ (uint64_t)rd() ^ 0x9E3779B97F4A7C15ULL;
-    }()};
-    uint64_t v = e.fetch_add(1, std::memory_order_relaxed);
-    return v ? v : e.fetch_add(1, std::memory_order_relaxed);
-}
 
 int stage_acquire(size_t bytes, Stage** out)
 {
@@ -677,9 +664,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     se.q_taupos = tab(at_taupos);
     se.q_prow = tab(at_qprow);
     bool mfma_started = false;  // the first MFMA launch builds the resident-query image
+    int seed_parts = 1;         // slices per query of the seed pass (one threshold each)
     for (int lv = 0; lv < plan.n_levels; ++lv) {
         const st::Level& L_ = plan.level[lv];
-        se.first = lv == 0;
+        se.first = lv == 0 || (lv == 1 && plan.level[0].seed);  // no candidate list from before
         se.last = lv == plan.n_levels - 1;
         se.scan.stamp_level = sp_m.stamp_level = sp_d.stamp_level = lv < 8 ? lv : 7;
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
@@ -688,8 +676,6 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             up.src = (const int32_t*)stage->dev_view;
             up.dst = (int32_t*)(ws + L.meta);
             up.words = (int32_t)(blob.bytes() / 4);
-            up.epoch = next_epoch();
-            up.flags = (uint64_t*)(ws + L.seed_flags);
             st::SelectParams se_seed = se;  // the seed pass reads its tables from the pinned copy
             auto host_tab = [&](size_t at) { return (const int32_t*)((const char*)stage->dev_view + at); };
             se_seed.q_prow = host_tab(at_qprow);
@@ -697,7 +683,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             se_seed.q_taupos = host_tab(at_taupos);
             se_seed.scan.grp_row_off = host_tab(at_all_row_off);
             se_seed.scan.grp_rows = host_tab(at_all_rows);
-            ST_HIP(st::launch_seed(se_seed, L_.end, batch, st::seed_parts(batch, L.k_pad), up, stream));
+            seed_parts = st::seed_parts(batch, L.k_pad);
+            ST_HIP(st::launch_seed(se_seed, L_.end, batch, seed_parts, up, stream));
             ST_HIP(hipEventRecord(stage->ev, stream));
             continue;
         }
@@ -707,6 +694,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             q->seg_items = L_.seg_items;
             q->seg_per_visit = L_.seg_per_visit;
             q->use_tau = lv > 0;
+            q->tau_parts = (lv == 1 && plan.level[0].seed) ? seed_parts : 1;
         }
         // past the first level a visit is one segment per wavefront of the workgroup
         if (lv > 0 && mp.waves > L_.seg_per_visit) sp_m.seg_per_visit = mp.waves;
@@ -728,7 +716,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         if (set_dot.n) {
             TimedLaunch t(0, stream);
             hipLaunchKernelGGL(st::scan_wavedot_kernel, dim3(plan.groups), dim3(st::kScanThreads),
-                               (size_t)batch * 4, stream, sp_d);
+                               (size_t)((batch + 1) & ~1) * 4 + (size_t)batch * 8, stream, sp_d);
             ST_HIP(hipGetLastError());
         }
         se.regions = regions;

@@ -55,7 +55,7 @@ struct MfmaParams {
     int8_t* img_q;               // [S][rows_local][d]   swizzled as in LDS
     float* img_sq;               // [S][rows_local]
     int32_t* img_qrow;           // [S][rows_local]
-    uint64_t* img_tau;           // [S][rows_local / T]  written by the selection kernel
+    uint64_t* img_tau;           // [S][rows_local / T][kTauParts]  written by the selection kernel (entry 0) or the seed pass
     int32_t first_level;         // 1: build the resident state from the tables and write the image
     int32_t multi_block;         // 1: some filter group holds more than one query block in a row of workgroups
     int32_t waves;               // wavefronts per workgroup: 4 or 8
@@ -243,7 +243,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         if (tid < n_imgrow) {
             v_qrow = mp.img_qrow[y * mp.rows_local + tid];
             v_sq = mp.img_sq[y * mp.rows_local + tid];
-            v_tau = mp.img_tau[y * (mp.rows_local / TT) + tid / TT];
+            v_tau = ~0ULL;
+            for (int pp = 0; pp < p.tau_parts; ++pp)
+                v_tau = min(v_tau, mp.img_tau[(int64_t)(y * (mp.rows_local / TT) + tid / TT) * kTauParts + pp]);
         }
         if (tid < n_prow) s_prow[tid] = v_prow;
         if (tid <= p.n_groups) {
@@ -286,7 +288,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
             s_qrow[lr] = grow;
             s_sq[lr] = grow >= 0 ? p.qscale[grow] : 0.0f;
-            const uint64_t t64 = (grow >= 0 && p.use_tau) ? p.tau[grow / TT] : 0ULL;
+            uint64_t t64 = 0ULL;
+            if (grow >= 0 && p.use_tau) {
+                t64 = ~0ULL;
+                for (int pp = 0; pp < p.tau_parts; ++pp) t64 = min(t64, p.tau[(int64_t)(grow / TT) * kTauParts + pp]);
+            }
             s_tauf[lr] = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
             if ((lr % TT) == 0) {
                 s_cnt[lr / TT] = 0;
@@ -317,7 +323,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             const int grow = mp.img_qrow[y * mp.rows_local + lr];
             s_qrow[lr] = grow;
             s_sq[lr] = mp.img_sq[y * mp.rows_local + lr];
-            const uint64_t t64 = mp.img_tau[y * (mp.rows_local / TT) + lr / TT];
+            uint64_t t64 = ~0ULL;
+            for (int pp = 0; pp < p.tau_parts; ++pp)
+                t64 = min(t64, mp.img_tau[(int64_t)(y * (mp.rows_local / TT) + lr / TT) * kTauParts + pp]);
             s_tauf[lr] = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
             if ((lr % TT) == 0) {
                 s_cnt[lr / TT] = 0;

@@ -94,6 +94,9 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
         p.level[p.n_levels++] = Level{0, n0, seg0, cap / seg0, 0};
     }
     int64_t cur = n0;
+    // The seed pass only leaves a threshold behind (no candidate list): the level after it starts
+    // over at item 0, with the growth still counted from the prefix the threshold comes from.
+    int64_t next_begin = seed_items > 0 ? 0 : n0;
     // expected admissions per region in a level that grows the scanned prefix by `grow` are
     // K*(grow-1)/g_eff; aim at cap/4.  Never grow by less than 2x (extreme K with few sharing
     // workgroups): regions may then overflow and the slow exact path takes those queries.
@@ -114,9 +117,10 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
         // large segments fill the 16-item MFMA tiles best; shrink them only when the level would
         // otherwise occupy fewer than about eight wavefronts per compute unit
         int32_t seg = seg_cap;
-        while (seg > 64 && (nxt - cur) / seg < 2048) seg >>= 1;
-        p.level[p.n_levels++] = Level{cur, nxt, seg, 4, 0};  // one segment per wavefront of the workgroup
+        while (seg > 64 && (nxt - next_begin) / seg < 2048) seg >>= 1;
+        p.level[p.n_levels++] = Level{next_begin, nxt, seg, 4, 0};  // one segment per wavefront of the workgroup
         cur = nxt;
+        next_begin = nxt;
     }
     *out = p;
     return 0;
@@ -169,7 +173,7 @@ inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_ca
 // Byte offsets of the pieces of the device workspace.
 struct Layout {
     size_t meta, meta_bytes;  // uploaded group tables
-    size_t tau;               // uint64 [B]       admission threshold per query
+    size_t tau;               // uint64 [B][8]    admission threshold per query (seed pass: one per slice, the minimum counts)
     size_t ovf;               // uint32 [B]       1 = a candidate region overflowed
     size_t topk_keys;         // uint64 [B][K]    running top-K, sorted
     size_t topk_cnt;          // uint32 [B]
@@ -178,7 +182,6 @@ struct Layout {
     size_t gath;              // uint64 [B][K + G*cap]  contiguous copy for selection
     size_t srt;               // uint64 [B][Kpad]       only when Kpad > kLdsSortMax
     size_t img_q, img_sq, img_qrow, img_tau;  // resident-query image of the MFMA scorer
-    size_t seed_flags;        // uint64 [B][9]    seed pass: slice completion marks and the merge claim
     size_t img_rows;          // rows the image has room for
     size_t total;
     int64_t gath_cap;
@@ -199,7 +202,7 @@ inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 1
     auto take = [&](size_t bytes) { size_t o = off; off = (size_t)round_up((int64_t)(off + bytes), 256); return o; };
     L.meta_bytes = meta_bound_bytes(batch);
     L.meta = take(L.meta_bytes);
-    L.tau = take((size_t)batch * 8);
+    L.tau = take((size_t)batch * 8 * 8);
     L.ovf = take((size_t)batch * 4);
     L.topk_keys = take((size_t)batch * K * 8);
     L.topk_cnt = take((size_t)batch * 4);
@@ -215,8 +218,7 @@ inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 1
     L.img_q = take(L.img_rows * d);
     L.img_sq = take(L.img_rows * 4);
     L.img_qrow = take(L.img_rows * 4);
-    L.img_tau = take(L.img_rows * 8);
-    L.seed_flags = take((size_t)batch * 9 * 8);
+    L.img_tau = take(L.img_rows * 8 * 8);
     L.total = off;
     return L;
 }

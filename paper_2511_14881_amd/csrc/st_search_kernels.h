@@ -12,6 +12,8 @@ namespace st {
 constexpr int kScanThreads = 256;
 constexpr int kFilterBatch = 16;  // distinct filters handled per pass over a segment
 
+constexpr int kTauParts = 8;  // thresholds per query (the seed pass leaves one per slice; readers take the minimum)
+
 struct ScanParams {
     // Bloom index
     const uint64_t* bloom;
@@ -39,7 +41,8 @@ struct ScanParams {
     int32_t seg_items;
     int32_t seg_per_visit;       // consecutive segments a workgroup takes before striding on
     int32_t use_tau;
-    const uint64_t* tau;         // [B]
+    const uint64_t* tau;         // [B][kTauParts]
+    int32_t tau_parts;           // entries of tau in use per query
     // output regions
     uint64_t* cand;              // [B][G][cap]
     uint32_t* cnt;               // [B][G]
@@ -88,13 +91,22 @@ __device__ inline void admit(const ScanParams& p, uint32_t* cnt_l, int q, uint64
 // Scan with the wavefront dot-product scorer: one lane per passing item, v_dot4 over the row.
 __global__ __launch_bounds__(kScanThreads) void scan_wavedot_kernel(ScanParams p)
 {
-    extern __shared__ uint32_t cnt_l[];  // [batch] candidates admitted by this workgroup
+    extern __shared__ uint32_t cnt_l[];  // [batch] candidates admitted by this workgroup, then [batch] 64-bit thresholds
     __shared__ uint64_t s_mask[kFilterBatch][kTileWords];
     __shared__ uint16_t s_list[kFilterBatch][kTileItems];
     __shared__ int s_listcnt[kFilterBatch];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    for (int q = tid; q < p.batch; q += kScanThreads) cnt_l[q] = 0;
+    uint64_t* tau_l = reinterpret_cast<uint64_t*>(cnt_l + ((p.batch + 1) & ~1));
+    for (int q = tid; q < p.batch; q += kScanThreads) {
+        cnt_l[q] = 0;
+        uint64_t t = 0;
+        if (p.use_tau) {
+            t = ~0ULL;
+            for (int pp = 0; pp < p.tau_parts; ++pp) t = min(t, p.tau[(int64_t)q * kTauParts + pp]);
+        }
+        tau_l[q] = t;
+    }
     __syncthreads();
 
     const int seg_words = p.seg_items >> 6;
@@ -151,7 +163,7 @@ __global__ __launch_bounds__(kScanThreads) void scan_wavedot_kernel(ScanParams p
                         const float s = pair_score(p, q, row, s_i);
                         if (active) {
                             const uint64_t key = make_key(s, (uint32_t)item);
-                            if (!p.use_tau || key >= p.tau[q]) admit(p, cnt_l, q, key);
+                            if (key >= tau_l[q]) admit(p, cnt_l, q, key);
                         }
                     }
                 }
@@ -510,7 +522,7 @@ struct SelectParams {
     int64_t gath_cap;
     uint64_t* srt;          // [B][k_pad] or null (sort in LDS)
     int32_t K, k_pad;
-    uint64_t* tau;          // [B] out
+    uint64_t* tau;          // [B][kTauParts] out (entry 0; the seed pass writes one per slice)
     uint64_t* tau_img;      // thresholds in the order of the scorer's resident query image, or null
     const int32_t* q_taupos;  // [B] position of each query in tau_img (-1: none)
     const int32_t* q_prow;    // [B][kSeedRows + 1] first signature rows of each query's filter (-1 padded), then their count
@@ -676,10 +688,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         if (tid == 0) {
             const uint64_t t64 = kth;
             p.topk_cnt[q] = (uint32_t)n_out;
-            p.tau[q] = t64;
+            p.tau[(int64_t)q * kTauParts] = t64;
             if (p.tau_img) {
                 const int pos = p.q_taupos[q];
-                if (pos >= 0) p.tau_img[pos] = t64;
+                if (pos >= 0) p.tau_img[(int64_t)pos * kTauParts] = t64;
             }
         }
     } else {
@@ -695,22 +707,20 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
 
 // Seed pass for small batches: the prefix [0, seed_items) of the corpus is scanned per query by
 // `parts` workgroups, each on its own slice -- Bloom test of every word at once, compaction, one
-// lane per passing item for the int8 dot products (Sec. 4.2), top-K of the slice (Algorithm 1
-// phase 4).  The workgroup that finishes a query's last slice merges the slices' lists.  The pass
-// leaves the running top-K and the admission threshold exactly as the first cooperative level
-// and its selection would, in one launch.
+// lane per passing item for the int8 dot products (Sec. 4.2), radix select of the slice's keys
+// (Algorithm 1 phase 4 on the prefix).  Its only product is an admission threshold per query for
+// the first cooperative level, which then scans the whole range from item 0.
 constexpr int kSeedThreads = 512;
 constexpr int kSeedRows = 8;       // signature rows per query in the seed kernel's row table
-constexpr int kSeedMaxParts = 8;
+constexpr int kSeedMaxParts = kTauParts;
 static_assert(kSeedItems / 64 <= kSeedThreads, "one Bloom word per thread");
 
-// Slices per query: enough workgroups to occupy the chip, whole 1024-item tiles per slice, and all
-// slice results (parts * k_pad keys) together within the LDS key buffer of the merge.
+// Slices per query: enough workgroups to occupy the chip, whole 1024-item tiles per slice.
 inline int seed_parts(int batch, int k_pad)
 {
     int parts = 1;
-    while (parts < kSeedMaxParts && batch * parts < 256 && 2 * parts * k_pad <= kLdsKeys &&
-           kSeedItems / (2 * parts) >= kTileItems)
+    (void)k_pad;
+    while (parts < kSeedMaxParts && batch * parts < 256 && kSeedItems / (2 * parts) >= kTileItems)
         parts *= 2;
     return parts;
 }
@@ -718,14 +728,11 @@ inline int seed_parts(int batch, int k_pad)
 // The seed pass is the first kernel of a search, so it also brings the call's table blob to the
 // device: its own tables are read from the caller-side pinned copy (the table pointers in p that it
 // uses point there), and the workgroups copy the blob, a share each, to where the later kernels
-// expect it.  flags[batch][kSeedMaxParts + 1] need no initialisation: a slice marks its result with
-// the call's epoch, a value no earlier content of the workspace equals.
+// expect it.
 struct SeedUpload {
     const int32_t* src;  // pinned host memory, device-visible
     int32_t* dst;        // table area of the workspace
     int32_t words;
-    uint64_t epoch;
-    uint64_t* flags;
 };
 
 // D16 = d / 16 for d in {64, 128, 256} (item rows staged in registers, two items per thread in
@@ -758,8 +765,8 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     const int64_t begin = part * part_items;
     const int64_t n = n_all - begin < part_items ? (n_all - begin > 0 ? n_all - begin : 0) : part_items;  // items of this slice
     const int n_words = (int)((n + 63) >> 6);  // <= NT: one word per thread
-    // per query: [parts][pstride] slice results, then room for the keys of slices too large for LDS.
-    // A slice with few passing items publishes all of their keys, a larger one its own top-K.
+    // per query: [parts][pstride] scratch for the selection of slices too large for LDS, then room
+    // for their keys
     const int pshare = kLdsKeys / parts;
     const int pstride = p.K > pshare ? p.K : pshare;
     uint64_t* gpart = p.gath + (int64_t)q * p.gath_cap;
@@ -871,79 +878,33 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     __syncthreads();
     ST_STAMP(sp.stamps, 16, slot, 3);
 
-    uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
-    int n_out;
+    // This slice's share of the threshold: its ceil(K / parts)-th best key.  With every slice
+    // holding that many keys at or above its own value, the prefix holds at least K keys at or
+    // above the smallest of them, so the minimum over the slices is a valid admission threshold
+    // (0 = this slice has too few passing items: no threshold).  Nothing else is carried over: the
+    // level after the seed pass scans the prefix again.
+    const int rank = (p.K + parts - 1) / parts;
+    int rank_pad = 1;
+    while (rank_pad < rank) rank_pad <<= 1;
     uint64_t kth = 0;
-    const bool publish_all = parts > 1 && total <= (uint32_t)pshare;
-    if (publish_all) {
-        n_out = (int)total;
-        sorted = s_keys;
-    } else if (in_lds && !p.srt) {
-        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, parts == 1 && p.last, kth,
-                         sp.stamps, 16, slot, 9);
+    if (in_lds) {
+        (void)lds_topk(s_keys, (int)total, rank, s_sorted, rank_pad, s_hist, s_misc, s_red, false, kth, sp.stamps, 16, slot, 9);
     } else {
-        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
-        kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
+        uint64_t* sorted = gpart + (int64_t)part * pstride;  // K <= pstride entries of scratch
+        const int n_out = wg_topk(gkeys, (int64_t)total, rank, sorted, rank_pad, s_hist, s_misc, s_red);
+        kth = n_out == rank ? sorted[rank - 1] : 0ULL;
     }
     ST_STAMP(sp.stamps, 16, slot, 4);
-
-    if (parts > 1) {
-        // Publish this slice's list; the workgroup that completes the query merges all of them.
-        // Every store and load of the exchange is an agent-scope atomic (written through to, and
-        // read from, the level all compute dies share), and each thread waits for its stores
-        // before the slice is marked done: no cache-wide write-back or invalidate is needed.
-        for (int i = tid; i < n_out; i += NT)
-            __hip_atomic_store(&gpart[(int64_t)part * pstride + i], sorted[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (tid == 0)
-            __hip_atomic_store(&sp.cnt[(int64_t)q * p.groups + part], (uint32_t)n_out, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        // mark this slice done, then look at all marks: the workgroup whose mark lands last sees
-        // every other mark.  Two that finish together may both see all, so the merge is claimed
-        // with an exchange on one more word: only the first to put the epoch there goes on.
-        if (tid == 0) {
-            uint64_t* fq = up.flags + (int64_t)q * (kSeedMaxParts + 1);
-            __hip_atomic_store(&fq[part], up.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            uint32_t all = 1;
-            for (int pp = 0; pp < parts; ++pp)
-                all &= __hip_atomic_load(&fq[pp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == up.epoch ? 1u : 0u;
-            if (all)
-                all = __hip_atomic_exchange(&fq[kSeedMaxParts], up.epoch, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != up.epoch ? 1u : 0u;
-            s_misc[5] = all;
+    if (tid == 0) {
+        p.tau[(int64_t)q * kTauParts + part] = kth;
+        if (p.tau_img) {
+            const int pos = p.q_taupos[q];
+            if (pos >= 0) p.tau_img[(int64_t)pos * kTauParts + part] = kth;
         }
-        __syncthreads();
-        ST_STAMP(sp.stamps, 16, slot, 5);
-        if (s_misc[5] == 0u) return;  // uniform
-        uint32_t off = 0;
-        for (int pp = 0; pp < parts; ++pp) {
-            const uint32_t c = min(__hip_atomic_load(&sp.cnt[(int64_t)q * p.groups + pp], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT),
-                                   (uint32_t)pstride);
-            for (uint32_t i = tid; i < c; i += NT)
-                s_keys[off + i] = __hip_atomic_load(&gpart[(int64_t)pp * pstride + i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            off += c;
+        if (part == 0) {
+            p.ovf[q] = 0u;
+            p.topk_cnt[q] = 0u;
         }
-        __syncthreads();
-        ST_STAMP(sp.stamps, 16, slot, 6);
-        n_out = lds_topk(s_keys, (int)off, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
-        sorted = s_sorted;
-        ST_STAMP(sp.stamps, 16, slot, 7);
-    }
-    if (tid == 0) p.ovf[q] = 0u;
-    if (!p.last) {
-        for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
-        if (tid == 0) {
-            const uint64_t t64 = kth;
-            p.topk_cnt[q] = (uint32_t)n_out;
-            p.tau[q] = t64;
-            if (p.tau_img) {
-                const int pos = p.q_taupos[q];
-                if (pos >= 0) p.tau_img[pos] = t64;
-            }
-        }
-    } else {
-        write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
-                     p.out_count + q);
     }
     ST_STAMP(sp.stamps, 16, slot, 8);
 }

@@ -56,14 +56,20 @@ def test_schedule_covers_the_corpus_once(n, B, K, q_split):
     assert groups == 1024 and cap in (64, 128, 256, 512)
     assert groups * cap >= 2 * K + 2048
     assert levels[0, 0] == 0 and levels[-1, 1] == n
+    seeded = levels[0, 2] == 0 and n > 0
     for i, (b, e, seg) in enumerate(levels):
         assert e >= b and seg % 64 == 0 and seg <= 2048  # seg = items a workgroup takes per visit
-        if i:
+        if i == 1 and seeded:
+            # the seed pass only yields thresholds: the level after it starts over at item 0
+            assert b == 0 and e > levels[0, 1]
+        elif i:
             assert b == levels[i - 1, 1] and e > b and b % 1024 == 0
     b, e, seg = levels[0]
-    if seg == 0:
+    if seeded:
         # small batch, large corpus: the prefix is scanned by the per-query seed kernel
         assert B <= 128 and n >= 8 * 32768 and e == 32768
+    elif n == 0:
+        assert len(levels) == 1
     else:
         # level 0: `cap` items per workgroup at most, so its regions cannot overflow
         assert seg == cap and (e - b + seg - 1) // seg <= groups // q_split
