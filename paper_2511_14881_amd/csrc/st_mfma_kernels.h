@@ -63,6 +63,11 @@ struct MfmaParams {
     int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_tq, lds_thr, lds_scl, lds_total;
 };
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load; the set-up barrier of the scan would then sit out the HBM latency of
+// the first Bloom words, which are requested before it and needed only after.
+__device__ inline void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+
 // chunk swizzle: keeps 16 consecutive rows of d bytes on distinct LDS banks when the 16 lanes
 // of a quarter-wave read the same 16-byte chunk of each
 template <int KS>
@@ -117,6 +122,16 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 0);
     const int l16 = lane & 15, kg = lane >> 4;
+    // Plain search: tau / s_q per row, so that a pair can only be admitted if dot * s_i reaches it.
+    // +inf marks padding rows (never admitted), -inf rows that cannot be culled (no threshold yet,
+    // tau <= 0, or a quotient outside the range the bound is valid for).
+    auto tq_of = [](float tf, float sq) -> float {
+        const float inf = __builtin_inff();
+        if (tf == inf) return inf;
+        if (!(tf > 0.0f)) return -inf;
+        const float tq = tf / sq;
+        return (tq > 0.0f && tq < inf) ? tq : -inf;
+    };
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
     uint64_t* s_queue = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
     float* s_tq = reinterpret_cast<float*>(lds + mp.lds_tq);                                    // [rows_local] tau / s_q per row
@@ -264,7 +279,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         if (tid < n_imgrow) {
             s_qrow[tid] = v_qrow;
             s_sq[tid] = v_sq;
-            s_tauf[tid] = v_qrow >= 0 ? (v_tau ? key_score(v_tau) : -__builtin_inff()) : __builtin_inff();
+            const float tf = v_qrow >= 0 ? (v_tau ? key_score(v_tau) : -__builtin_inff()) : __builtin_inff();
+            s_tauf[tid] = tf;
+            if (!WEIGHTED) s_tq[tid] = tq_of(tf, v_sq);
             if ((tid % TT) == 0) {
                 s_cnt[tid / TT] = 0;
                 s_tau64[tid / TT] = v_tau;
@@ -283,31 +300,56 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         }
     }
     if (mp.first_level) {
-        for (int lr = tid; lr < mp.rows_local; lr += kThreads) {
+        // Resident state straight from the tables.  Two dependent reads per entry (row index, then
+        // the row's data); as above, all reads of one stage are issued before anything is stored.
+        auto row_of = [&](int lr) -> int {
             const int b = (lr >> 4) * S + y;
-            const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
-            s_qrow[lr] = grow;
-            s_sq[lr] = grow >= 0 ? p.qscale[grow] : 0.0f;
+            return (lr < mp.rows_local && b < mp.n_blocks) ? mp.blk_row[b * 16 + (lr & 15)] : -1;
+        };
+        const int n_piece_t = mp.rows_local * CH;
+        for (int lr0 = 0, i0 = 0; lr0 < mp.rows_local || i0 < n_piece_t; lr0 += kThreads, i0 += 8 * kThreads) {
+            const int lr = lr0 + tid;
+            const int grow = row_of(lr);
+            int grow_p[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + tid + u * kThreads;
+                grow_p[u] = i < n_piece_t ? row_of(i / CH) : -1;
+            }
+            const float sq = grow >= 0 ? p.qscale[grow] : 0.0f;
             uint64_t t64 = 0ULL;
             if (grow >= 0 && p.use_tau) {
                 t64 = ~0ULL;
                 for (int pp = 0; pp < p.tau_parts; ++pp) t64 = min(t64, p.tau[(int64_t)(grow / TT) * kTauParts + pp]);
             }
-            s_tauf[lr] = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
-            if ((lr % TT) == 0) {
-                s_cnt[lr / TT] = 0;
-                s_tau64[lr / TT] = t64;
+            int4 v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + tid + u * kThreads;
+                v[u] = make_int4(0, 0, 0, 0);
+                if (grow_p[u] >= 0) v[u] = reinterpret_cast<const int4*>(p.queries + (int64_t)grow_p[u] * D)[i % CH];
+            }
+            if (lr < mp.rows_local) {
+                s_qrow[lr] = grow;
+                s_sq[lr] = sq;
+                const float tf = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
+                s_tauf[lr] = tf;
+                if (!WEIGHTED) s_tq[lr] = tq_of(tf, sq);
+                if ((lr % TT) == 0) {
+                    s_cnt[lr / TT] = 0;
+                    s_tau64[lr / TT] = t64;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int i = i0 + tid + u * kThreads;
+                if (i < n_piece_t) {
+                    const int r = i / CH, c = i % CH;
+                    *reinterpret_cast<int4*>(s_q + r * D + ((c ^ swz<KS>(r)) << 4)) = v[u];
+                }
             }
         }
-        for (int i = tid; i < mp.rows_local * CH; i += kThreads) {
-            const int lr = i / CH, c = i - lr * CH;
-            const int b = (lr >> 4) * S + y;
-            const int grow = b < mp.n_blocks ? mp.blk_row[b * 16 + (lr & 15)] : -1;
-            int4 v = make_int4(0, 0, 0, 0);
-            if (grow >= 0) v = reinterpret_cast<const int4*>(p.queries + (int64_t)grow * D)[c];
-            *reinterpret_cast<int4*>(s_q + lr * D + ((c ^ swz<KS>(lr)) << 4)) = v;
-        }
-        __syncthreads();
+        lds_barrier();
         if (blockIdx.x == 0) {  // publish the image for the later levels
             int4* gq = reinterpret_cast<int4*>(mp.img_q + (int64_t)y * mp.rows_local * D);
             for (int i = tid; i < mp.rows_local * CH; i += kThreads) gq[i] = reinterpret_cast<const int4*>(s_q)[i];
@@ -322,36 +364,20 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         for (int lr = tid + kThreads; lr < mp.rows_local; lr += kThreads) {
             const int grow = mp.img_qrow[y * mp.rows_local + lr];
             s_qrow[lr] = grow;
-            s_sq[lr] = mp.img_sq[y * mp.rows_local + lr];
+            const float sq = mp.img_sq[y * mp.rows_local + lr];
+            s_sq[lr] = sq;
             uint64_t t64 = ~0ULL;
             for (int pp = 0; pp < p.tau_parts; ++pp)
                 t64 = min(t64, mp.img_tau[(int64_t)(y * (mp.rows_local / TT) + lr / TT) * kTauParts + pp]);
-            s_tauf[lr] = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
+            const float tf = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
+            s_tauf[lr] = tf;
+            if (!WEIGHTED) s_tq[lr] = tq_of(tf, sq);
             if ((lr % TT) == 0) {
                 s_cnt[lr / TT] = 0;
                 s_tau64[lr / TT] = t64;
             }
         }
-        __syncthreads();
-    }
-
-    // Plain search: tau / s_q per row, so that a pair can only be admitted if dot * s_i reaches it.
-    // +inf marks padding rows (never admitted), -inf rows that cannot be culled (no threshold yet,
-    // tau <= 0, or a quotient outside the range the bound is valid for).
-    if (!WEIGHTED) {
-        for (int lr = tid; lr < mp.rows_local; lr += kThreads) {
-            const float tf = s_tauf[lr];
-            const float inf = __builtin_inff();
-            float tq = -inf;
-            if (tf == inf) {
-                tq = inf;
-            } else if (tf > 0.0f) {
-                tq = tf / s_sq[lr];
-                if (!(tq > 0.0f && tq < inf)) tq = -inf;
-            }
-            s_tq[lr] = tq;
-        }
-        __syncthreads();
+        lds_barrier();
     }
 
     // lane constants of the MFMA operand reads: byte offset of this lane's chunk k inside a
