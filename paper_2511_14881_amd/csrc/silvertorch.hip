@@ -542,11 +542,11 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     // selection kernel stores each query's threshold in the resident-query image
     mp.q_split = std::max(mp.q_split, 1);
     const int32_t rows_local = ((mp.n_blocks + mp.q_split - 1) / mp.q_split) * 16;
-    std::vector<int32_t> prow((size_t)set_mfma.n * st::kPrefetchRows + 1, -1), q_taupos(batch, -1);
+    std::vector<int32_t> prow((size_t)set_mfma.n * st::kPrefetchStride + 1, -1), q_taupos(batch, -1);
     for (int32_t g = 0; g < set_mfma.n; ++g) {
         const int32_t nr = set_mfma.row_off[g + 1] - set_mfma.row_off[g];
-        for (int32_t r = 0; r < nr && r < st::kPrefetchRows; ++r)
-            prow[(size_t)g * st::kPrefetchRows + r] = set_mfma.rows[set_mfma.row_off[g] + r];
+        for (int32_t r = 0; r < nr && r < st::kPrefetchStride; ++r)
+            prow[(size_t)g * st::kPrefetchStride + r] = set_mfma.rows[set_mfma.row_off[g] + r];
         if (g < st::kMfmaFilterBatch) {
             for (int32_t r = 0; r < nr && r < st::kPrefetchRows; ++r)
                 mp.prow_pack[g][r / 4] |= (uint64_t)(uint16_t)set_mfma.rows[set_mfma.row_off[g] + r] << (16 * (r % 4));

@@ -29,7 +29,8 @@ namespace st {
 typedef int v4i __attribute__((ext_vector_type(4)));
 
 constexpr int kMfmaFilterBatch = 8;        // distinct filters handled per pass over a segment
-constexpr int kPrefetchRows = 8;           // signature rows per filter whose next-segment words are prefetched
+constexpr int kPrefetchRows = 8;           // signature rows per filter prefetched by 4-wavefront workgroups, and resident in the kernel arguments
+constexpr int kPrefetchStride = 16;        // rows per filter in the prefetch table; 8-wavefront workgroups prefetch all of them
 constexpr int kMfmaQueryLds = 64 * 1024;   // LDS bytes for resident query rows per workgroup
 constexpr int kMfmaMinRows = 4;            // a group needs this many query rows to go to MFMA
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
@@ -44,7 +45,7 @@ struct MfmaParams {
     int32_t n_blocks;            // all groups
     int32_t q_split;             // S: gridDim.y; block b belongs to y = b % S, local index b / S
     int32_t rows_local;          // 16 * blocks per y (max over y)
-    const int32_t* prow;         // [groups][kPrefetchRows] first signature rows of each filter, -1 padded
+    const int32_t* prow;         // [groups][kPrefetchStride] first signature rows of each filter, -1 padded
     // The same rows for the first batch of filters, resident in the kernel arguments so that the
     // very first Bloom words can be requested before anything has been read from memory:
     // row r of filter g is bits [16*(r%4), +16) of prow_pack[g][r/4]; prow_n holds the row counts.
@@ -101,18 +102,20 @@ template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW>
 __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
     constexpr int kThreads = NW * 64;
+    constexpr int PR = NW == 8 ? kPrefetchStride : kPrefetchRows;  // rows prefetched per filter (register budget)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int D = KS * 64;
     constexpr int CH = D / 16;  // 16-byte chunks per row
     constexpr int FB = kMfmaFilterBatch;
-    constexpr int NB = KS == 1 ? 4 : (KS == 2 ? ST_NB2 : 2);  // ring slots (units with rows in flight)
+    // ring slots (units with rows in flight)
+    constexpr int NB = KS == 1 ? 4 : (KS == 2 ? ST_NB2 : 2);
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
     uint64_t* s_tau64 = reinterpret_cast<uint64_t*>(lds + mp.lds_tau64);    // [rows_local / TT]
     int* s_qrow = reinterpret_cast<int*>(lds + mp.lds_qrow);
     uint32_t* s_cnt = reinterpret_cast<uint32_t*>(lds + mp.lds_cnt);
-    int* s_prow = reinterpret_cast<int*>(lds + mp.lds_prow);                // [groups][kPrefetchRows]
+    int* s_prow = reinterpret_cast<int*>(lds + mp.lds_prow);                // [groups][kPrefetchStride]
     int* s_glrow = reinterpret_cast<int*>(lds + mp.lds_blkoff);             // [groups] first local query row of the group
     int* s_gnblk = s_glrow + p.n_groups;                                    // [groups] local 16-row blocks of the group
     int* s_rowoff = reinterpret_cast<int*>(lds + mp.lds_rowoff);            // [groups + 1]
@@ -161,9 +164,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     // Bloom words: lane (gi * SW + w) owns word w of filter gi of the stage's batch.
     const bool pair_lane = lane < FB * SW;
     const int pr_gi = lane / SW, pr_w = lane - pr_gi * SW;
-    uint64_t pre[kPrefetchRows];
+    uint64_t pre[PR];
+    int pre_valid = 0;  // rows of the current stage that were prefetched (the first stage gets kPrefetchRows from the kernel arguments)
 #pragma unroll
-    for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
+    for (int r = 0; r < PR; ++r) pre[r] = ~0ULL;
     auto prefetch_issue = [&](int t) {
         if (!pair_lane || t >= n_stages) return;
         const int g = stage_batch(t) * FB + pr_gi;
@@ -172,8 +176,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         if (gw * 64 >= item_lim) return;
         const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
-        for (int r = 0; r < kPrefetchRows; ++r) {
-            const int row = s_prow[g * kPrefetchRows + r];
+        for (int r = 0; r < PR; ++r) {
+            const int row = s_prow[g * kPrefetchStride + r];
             pre[r] = row >= 0 ? base[(int64_t)row * kTileWords] : ~0ULL;
         }
     };
@@ -201,11 +205,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         const int64_t left = item_lim - first;
         uint64_t mask = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
 #pragma unroll
-        for (int r = 0; r < kPrefetchRows; ++r) mask &= pre[r];
+        for (int r = 0; r < PR; ++r) mask &= pre[r];
         const int r0 = s_rowoff[g], nr = s_rowoff[g + 1] - r0;
-        if (nr > kPrefetchRows) {  // long filters: the remaining rows, not prefetched
+        if (nr > pre_valid) {  // long filters: the remaining rows, not prefetched
             const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
-            for (int r = kPrefetchRows; r < nr; ++r) mask &= base[(int64_t)p.grp_rows[r0 + r] * kTileWords];
+            for (int r = pre_valid; r < nr; ++r) mask &= base[(int64_t)p.grp_rows[r0 + r] * kTileWords];
         }
         return mask;
     };
@@ -237,7 +241,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     // memory round trip each.  The first share of every table (all of it for ordinary sizes) is
     // therefore requested up front, into registers, and stored afterwards; loops take what is left.
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 10);
-    const int n_prow = p.n_groups * kPrefetchRows;
+    const int n_prow = p.n_groups * kPrefetchStride;
     const int n_piece = mp.first_level ? 0 : mp.rows_local * CH;   // 16-byte pieces of the query image
     const int n_imgrow = mp.first_level ? 0 : mp.rows_local;
     const int4* gq = reinterpret_cast<const int4*>(mp.img_q + (int64_t)y * mp.rows_local * D);
@@ -395,9 +399,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
 
         // (1) + (2): mask word of my pair, then the set bits of each filter's words, in item
         // order, into the filter's list
+        pre_valid = t == 0 ? kPrefetchRows : PR;
         uint64_t mask = prefetch_mask(t);
 #pragma unroll
-        for (int r = 0; r < kPrefetchRows; ++r) pre[r] = ~0ULL;
+        for (int r = 0; r < PR; ++r) pre[r] = ~0ULL;
         prefetch_issue(t + 1);
         if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 2);
         const int c = __popcll(mask);
@@ -696,18 +701,23 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         // Every load in the loop is unconditional (requests past the end repeat the last unit):
         // only then is the number of loads between a unit's request and its use a constant the
         // compiler can wait on.
-        UnitRegs<KS> ring[NB];
         if (n_units > 0) {
+            UnitRegs<KS> r0, r1, r2, r3;  // the ring, as separate variables (an array would be indexed through memory)
+            auto step = [&](UnitRegs<KS>& r, int u) {
+                if (u < n_units) unit_compute(r);
+                unit_load(r);
+            };
             gen_seek(0);
-#pragma unroll
-            for (int k = 0; k < NB; ++k) unit_load(ring[k]);
+            unit_load(r0);
+            unit_load(r1);
+            if (NB > 2) unit_load(r2);
+            if (NB > 3) unit_load(r3);
+            if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
             for (int base = 0; base < n_units; base += NB) {
-#pragma unroll
-                for (int k = 0; k < NB; ++k) {
-                    if (base + k < n_units) unit_compute(ring[k]);
-                    unit_load(ring[k]);
-                    if (t == 0 && base == 0 && k == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
-                }
+                step(r0, base);
+                step(r1, base + 1);
+                if (NB > 2) step(r2, base + 2);
+                if (NB > 3) step(r3, base + 3);
             }
             if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 5);
             while (qn > 0) drain();
@@ -781,7 +791,7 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, in
     mp->lds_cnt = take((mp->rows_local / n_tasks + 1) * 4);
     mp->lds_list = take(waves * kMfmaFilterBatch * kMfmaSegItems);
     mp->lds_queue = take(waves * kQueueSlots * 8);
-    mp->lds_prow = take(n_groups * kPrefetchRows * 4);
+    mp->lds_prow = take(n_groups * kPrefetchStride * 4);
     mp->lds_blkoff = take((2 * n_groups + 2) * 4);
     mp->lds_rowoff = take((n_groups + 1) * 4);
     mp->lds_tq = take(mp->rows_local * 4);

@@ -192,7 +192,7 @@ inline size_t meta_bound_bytes(int32_t batch)
 {
     // group tables (rows: at most 64 per query, twice: all groups and the per-scorer copies),
     // query lists, offsets, MFMA block tables (at most 16*(T/16 + 1) rows per query), slack
-    return (size_t)round_up(4096 + (size_t)batch * 776, 256);
+    return (size_t)round_up(4096 + (size_t)batch * 840, 256);
 }
 
 inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 16, int32_t n_tasks = 1)
