@@ -388,7 +388,9 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
 #pragma unroll
             for (int j = 0; j < kTopkRegs; ++j)
                 if (j < ne && kr[j] && (kr[j] & prefix_mask) == prefix) atomicAdd(&hist[(kr[j] >> shift) & 255], 1u);
-            uint32_t* stale = s_hist3 + ((pass + 2) % 3) * 256;  // used two passes from now
+            // clear the next pass's histogram: its last readers (two passes ago) were done before the
+            // previous barrier, whereas the one scanned in the previous pass may still be being read
+            uint32_t* stale = s_hist3 + ((pass + 1) % 3) * 256;
             if (tid < 256) stale[tid] = 0;
             __syncthreads();
             // every wavefront: lane l owns digits 255-4l .. 252-4l (descending)
