@@ -517,8 +517,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     mp.n_blocks = (int32_t)(blk_row.size() / 16);
     mp.q_split = 1;
     mp.waves = 4;
+    mp.region_slots = 1;
+    int mfma_wgs = 1;  // workgroups of the MFMA scan a compute unit holds at once
     if (set_mfma.n) {
-        st::mfma_choose_config(mp.n_blocks, d, n_tasks, set_mfma.n, 32, &mp.q_split, &mp.waves);
+        st::mfma_choose_config(mp.n_blocks, d, n_tasks, set_mfma.n, 32, &mp.q_split, &mp.waves, &mfma_wgs);
         if (mp.q_split < 1) return fail(ST_EINVAL, "query batch too large for the resident-query scorer");
     }
 
@@ -704,9 +706,23 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         const int64_t n_visit = (n_seg + sp_m.seg_per_visit - 1) / sp_m.seg_per_visit;
         int32_t regions = plan.groups;
         if (set_mfma.n) {
-            int32_t gx = plan.groups / mp.q_split;
-            if (!set_dot.n && n_visit < gx) gx = (int32_t)std::max<int64_t>(n_visit, 1);
-            regions = set_dot.n ? plan.groups : gx * mp.q_split;
+            const int32_t per_row = plan.groups / mp.q_split;  // regions of one row of the grid
+            int32_t gx = per_row;
+            mp.region_slots = 1;
+            if (!set_dot.n) {
+                // only as many workgroups as are resident at once; each takes several regions
+                const int32_t resident = st::pow2_ceil(st::kComputeUnits * mfma_wgs / mp.q_split + 1) / 2;
+                if (resident >= 1 && resident < gx) gx = resident;
+                if (n_visit < gx) gx = (int32_t)std::max<int64_t>(n_visit, 1);
+                const int64_t want = std::min<int64_t>(per_row / gx, (n_visit + gx - 1) / gx);
+                mp.region_slots = (int32_t)std::max<int64_t>(1, std::min<int64_t>(want, st::kMaxRegionSlots));
+                // the first level needs a region per visit (no region can then overflow)
+                if (lv == 0 && (int64_t)gx * mp.region_slots < n_visit) {
+                    gx = (int32_t)std::min<int64_t>(per_row, std::max<int64_t>(n_visit, 1));
+                    mp.region_slots = 1;
+                }
+            }
+            regions = set_dot.n ? plan.groups : gx * mp.region_slots * mp.q_split;
             st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n, mp.waves);
             mp.first_level = mfma_started ? 0 : 1;
             mfma_started = true;

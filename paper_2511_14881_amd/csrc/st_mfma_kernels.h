@@ -36,6 +36,7 @@ constexpr int kMfmaMinRows = 4;            // a group needs this many query rows
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
 constexpr int kMfmaSegItems = 256;         // items per wavefront segment, at most (4 mask words x 8 filters = 32 lanes)
 constexpr int kQueueSlots = 128;           // queued admissions per wavefront (drained whenever 64 are waiting)
+constexpr int kMaxRegionSlots = 8;         // candidate regions one workgroup may fill in a launch
 
 inline constexpr int mfma_max_seg_items(int) { return kMfmaSegItems; }
 
@@ -60,6 +61,10 @@ struct MfmaParams {
     int32_t first_level;         // 1: build the resident state from the tables and write the image
     int32_t multi_block;         // 1: some filter group holds more than one query block in a row of workgroups
     int32_t waves;               // wavefronts per workgroup: 4 or 8
+    // A launch holds only as many workgroups as the device keeps resident; each owns region_slots
+    // candidate regions (x + j * gridDim.x within its row of the grid) and rotates through them
+    // visit by visit, so that the regions fill as evenly as with one workgroup per region.
+    int32_t region_slots;
     // dynamic LDS layout (byte offsets)
     int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_tq, lds_thr, lds_scl, lds_total;
 };
@@ -122,7 +127,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
-    const int wg_lin = blockIdx.x + y * gridDim.x;  // region index in [0, groups)
+    const int wg_lin = blockIdx.x + y * gridDim.x;  // workgroup index (timeline probe only)
+    (void)wg_lin;
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 0);
     const int l16 = lane & 15, kg = lane >> 4;
     // Plain search: tau / s_q per row, so that a pair can only be admitted if dot * s_i reaches it.
@@ -142,8 +148,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     float* s_scl = reinterpret_cast<float*>(lds + mp.lds_scl) + wave * kMfmaSegItems;           // wave-private [seg] item scales
 
     // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
-    // workgroup; inside a visit wavefront w takes segments w, w + 4, ...  Stages of a wavefront
-    // are numbered (visit, segment slot, filter batch).
+    // workgroup.  wpv wavefronts share a visit (wavefront sl of them takes segments sl, sl + wpv,
+    // ...); when a visit has fewer segments than the workgroup has wavefronts, NW / wpv visits
+    // are in progress at once.  Stages of a wavefront are numbered (visit, segment slot, filter
+    // batch).
     const int seg_items = p.seg_items;
     const int SW = seg_items >> 6;  // mask words per segment (1, 2 or 4)
     const int spv = p.seg_per_visit;
@@ -151,14 +159,20 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     const int n_seg = (int)((p.item_end - p.item_begin + seg_items - 1) / seg_items);
     const int n_visit = (n_seg + spv - 1) / spv;
     const int n_batches = (p.n_groups + FB - 1) / FB;
-    const int slots = wave < spv ? (spv - wave + NW - 1) / NW : 0;  // my segments per visit
-    const int my_visits = (int)blockIdx.x < n_visit ? (n_visit - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
+    const int wpv = spv < NW ? spv : NW, cv = NW / wpv;
+    const int vl = wave / wpv, sl = wave - vl * wpv;
+    const int slots = (spv - sl + wpv - 1) / wpv;  // my segments per visit
+    const int wg_visits = (int)blockIdx.x < n_visit ? (n_visit - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
+    const int my_visits = vl < wg_visits ? (wg_visits - vl + cv - 1) / cv : 0;
     const int per_visit = slots * n_batches;
     const int n_stages = my_visits * per_visit;
+    auto stage_visit = [&](int t) { return vl + cv * (t / per_visit); };  // among the workgroup's visits
     auto stage_seg = [&](int t) {  // segment index of stage t (may lie past the level's end: no items there)
-        const int v = t / per_visit, r = t - v * per_visit;
-        return ((int)blockIdx.x + v * (int)gridDim.x) * spv + wave + (r / n_batches) * NW;
+        const int r = t % per_visit;
+        return ((int)blockIdx.x + stage_visit(t) * (int)gridDim.x) * spv + sl + (r / n_batches) * wpv;
     };
+    const int R = mp.region_slots;
+    const int nq_pad = mp.rows_local / TT + 1;  // counters per region slot
     auto stage_batch = [&](int t) { return (t % per_visit) % n_batches; };
 
     // Bloom words: lane (gi * SW + w) owns word w of filter gi of the stage's batch.
@@ -286,13 +300,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             const float tf = v_qrow >= 0 ? (v_tau ? key_score(v_tau) : -__builtin_inff()) : __builtin_inff();
             s_tauf[tid] = tf;
             if (!WEIGHTED) s_tq[tid] = tq_of(tf, v_sq);
-            if ((tid % TT) == 0) {
-                s_cnt[tid / TT] = 0;
-                s_tau64[tid / TT] = v_tau;
-            }
+            if ((tid % TT) == 0) s_tau64[tid / TT] = v_tau;
         }
     }
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 11);
+    for (int i = tid; i < R * nq_pad; i += kThreads) s_cnt[i] = 0;
     for (int i = tid + kThreads; i < n_prow; i += kThreads) s_prow[i] = mp.prow[i];
     for (int g = tid + kThreads; g <= p.n_groups; g += kThreads) {
         s_rowoff[g] = p.grp_row_off[g];
@@ -339,10 +351,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 const float tf = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
                 s_tauf[lr] = tf;
                 if (!WEIGHTED) s_tq[lr] = tq_of(tf, sq);
-                if ((lr % TT) == 0) {
-                    s_cnt[lr / TT] = 0;
-                    s_tau64[lr / TT] = t64;
-                }
+                if ((lr % TT) == 0) s_tau64[lr / TT] = t64;
             }
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
@@ -376,10 +385,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             const float tf = grow >= 0 ? (t64 ? key_score(t64) : -__builtin_inff()) : __builtin_inff();
             s_tauf[lr] = tf;
             if (!WEIGHTED) s_tq[lr] = tq_of(tf, sq);
-            if ((lr % TT) == 0) {
-                s_cnt[lr / TT] = 0;
-                s_tau64[lr / TT] = t64;
-            }
+            if ((lr % TT) == 0) s_tau64[lr / TT] = t64;
         }
         lds_barrier();
     }
@@ -396,6 +402,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
         const int nf = min(FB, p.n_groups - g0);
+        const int slot = stage_visit(t) % R;  // candidate region of this visit
+        const int region = (int)blockIdx.x + slot * (int)gridDim.x + y * (int)gridDim.x * R;
+        uint32_t* cnt_s = s_cnt + slot * nq_pad;
 
         // (1) + (2): mask word of my pair, then the set bits of each filter's words, in item
         // order, into the filter's list
@@ -539,9 +548,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 const uint64_t key = make_key(score, (uint32_t)(item0 + it));
                 const int grow = s_qrow[srow];
                 if (grow >= 0 && key >= s_tau64[srow / TT]) {
-                    const uint32_t at = atomicAdd(&s_cnt[srow / TT], 1u);
+                    const uint32_t at = atomicAdd(&cnt_s[srow / TT], 1u);
                     if (at < (uint32_t)p.cap) {
-                        uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + wg_lin) * p.cap + at;
+                        uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + region) * p.cap + at;
                         asm volatile("global_store_dwordx2 %0, %1, off\n\ts_waitcnt vmcnt(0)" : : "v"(dst), "v"(key) : "memory");
                     }
                 }
@@ -733,10 +742,13 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         if (grow < 0) continue;
         const int q = grow / TT;
         const int b = i >> 4;
-        uint32_t c = 0;
-        if (b % S == y) c = s_cnt[((b / S) * 16 + (i & 15)) / TT];
-        p.cnt[(int64_t)q * p.groups + wg_lin] = c < (uint32_t)p.cap ? c : (uint32_t)p.cap;
-        if (c > (uint32_t)p.cap) p.ovf[q] = 1u;
+        for (int j = 0; j < R; ++j) {
+            uint32_t c = 0;
+            if (b % S == y) c = s_cnt[j * nq_pad + ((b / S) * 16 + (i & 15)) / TT];
+            const int region = (int)blockIdx.x + j * (int)gridDim.x + y * (int)gridDim.x * R;
+            p.cnt[(int64_t)q * p.groups + region] = c < (uint32_t)p.cap ? c : (uint32_t)p.cap;
+            if (c > (uint32_t)p.cap) p.ovf[q] = 1u;
+        }
     }
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 9);
 }
@@ -746,35 +758,54 @@ inline bool mfma_shape_ok(int d, int n_tasks)
     return (d == 64 || d == 128 || d == 256 || d == 512) && (n_tasks == 1 || n_tasks == 2 || n_tasks == 4);
 }
 
-// LDS one workgroup needs with the resident queries split S ways and `waves` wavefronts.
-inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves);
+// LDS one workgroup needs with the resident queries split S ways, `waves` wavefronts and
+// `slots` candidate regions.
+inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves, int slots);
+
+// Candidate regions per workgroup when a compute unit holds `wgs` workgroups: all regions are
+// shared out among the workgroups that are resident at once.
+inline int mfma_region_slots(int wgs)
+{
+    const int resident = kComputeUnits * wgs;
+    int r = (scan_groups() + resident - 1) / resident;
+    return r < 1 ? 1 : (r > kMaxRegionSlots ? kMaxRegionSlots : r);
+}
 
 // Chooses the split S of the resident queries over rows of workgroups (every row scans the
 // corpus for its share of the queries) and the wavefronts per workgroup.  Cost model: passes
 // over the corpus divided by the wavefronts a compute unit holds at once (160 KB of LDS; at most
 // 16 wavefronts for d <= 128 and 8 above, from the register budget).  Ties go to fewer passes.
-inline void mfma_choose_config(int n_blocks, int d, int n_tasks, int n_groups, int max_split, int* out_S, int* out_waves)
+inline void mfma_choose_config(int n_blocks, int d, int n_tasks, int n_groups, int max_split, int* out_S, int* out_waves,
+                               int* out_wgs)
 {
     const int wave_cap = d <= 128 ? 16 : 8;
     double best = 1e30;
-    int best_S = 0, best_w = 4;
+    int best_S = 0, best_w = 4, best_wgs = 1;
     for (int S = 1; S <= max_split; S <<= 1) {
         for (int waves = 4; waves <= 8; waves += 4) {
-            const int lds = mfma_lds_bytes(n_blocks, S, d, n_tasks, n_groups, waves);
-            if (lds > 160 * 1024) continue;
-            int wgs = (160 * 1024) / lds;
-            if (wgs * waves > wave_cap) wgs = wave_cap / waves;
+            // workgroups per compute unit; fewer of them means more region slots each, which
+            // takes a little more LDS: settle from the pessimistic side
+            int wgs = 0;
+            for (int slots = kMaxRegionSlots; slots >= 1; --slots) {
+                const int lds = mfma_lds_bytes(n_blocks, S, d, n_tasks, n_groups, waves, slots);
+                if (lds > 160 * 1024) continue;
+                int w = (160 * 1024) / lds;
+                if (w * waves > wave_cap) w = wave_cap / waves;
+                if (w >= 1 && mfma_region_slots(w) <= slots) wgs = w;
+            }
             if (wgs < 1) continue;
             const double cost = (double)S / (double)(wgs * waves);
             if (cost < best * 0.999) {
                 best = cost;
                 best_S = S;
                 best_w = waves;
+                best_wgs = wgs;
             }
         }
     }
     *out_S = best_S;  // 0: not even the largest split fits
     *out_waves = best_w;
+    *out_wgs = best_wgs;
 }
 
 inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, int waves)
@@ -788,7 +819,7 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, in
     mp->lds_tauf = take(mp->rows_local * 4);
     mp->lds_tau64 = take((mp->rows_local / n_tasks + 1) * 8);
     mp->lds_qrow = take(mp->rows_local * 4);
-    mp->lds_cnt = take((mp->rows_local / n_tasks + 1) * 4);
+    mp->lds_cnt = take(mp->region_slots * (mp->rows_local / n_tasks + 1) * 4);
     mp->lds_list = take(waves * kMfmaFilterBatch * kMfmaSegItems);
     mp->lds_queue = take(waves * kQueueSlots * 8);
     mp->lds_prow = take(n_groups * kPrefetchStride * 4);
@@ -800,11 +831,12 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, in
     mp->lds_total = off;
 }
 
-inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves)
+inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves, int slots)
 {
     MfmaParams t;
     t.n_blocks = n_blocks;
     t.q_split = S;
+    t.region_slots = slots;
     mfma_lds_layout(&t, d, n_tasks, n_groups, waves);
     return t.lds_total;
 }

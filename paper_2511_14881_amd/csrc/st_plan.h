@@ -14,7 +14,8 @@
 
 namespace st {
 
-constexpr int kScanGroups = 1024;    // persistent workgroups of the scan kernel (4 per CU on MI355X)
+constexpr int kComputeUnits = 256;   // MI355X
+constexpr int kScanGroups = 1024;    // candidate regions per query (one per scan workgroup at 4 workgroups per CU)
 constexpr int kMaxScanGroups = 2048;
 constexpr int kMaxLevels = 32;
 constexpr int kMaxSegItems = 512;    // items one workgroup takes per step, at most
