@@ -398,11 +398,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     for (int k = 0; k < KS; ++k) a_off[k] = l16 * D + (((kg + 4 * k) ^ swz<KS>(l16)) << 4);
 
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 1);
+    int thr_E = -1000;  // exponent the wavefront's integer bounds were built for (none yet)
     for (int t = 0; t < n_stages; ++t) {
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
         const int g0 = stage_batch(t) * FB;
         const int nf = min(FB, p.n_groups - g0);
-        const int slot = stage_visit(t) % R;  // candidate region of this visit
+        const int slot = R == 1 ? 0 : stage_visit(t) % R;  // candidate region of this visit
         const int region = (int)blockIdx.x + slot * (int)gridDim.x + y * (int)gridDim.x * R;
         uint32_t* cnt_s = s_cnt + slot * nq_pad;
 
@@ -450,7 +451,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         // ceil(s_i * 2^(31-E)) and every row gets the integer bound floor(tau / s_q * 2^-(E+1)),
         // shaved by more than all roundings involved.  A pair can only be admitted if
         // mulhi(dot, factor) reaches the bound of its row, which costs two integer instructions per
-        // pair; the exact fp32 arithmetic runs when an entry is drained from the queue.
+        // pair; the exact fp32 arithmetic runs when an entry is drained from the queue.  The bounds
+        // depend on the segment through E only and are rebuilt when E changes (rarely: scales of
+        // neighbouring segments are of one magnitude).
         float fix_scale = 0.0f;  // 2^(31-E); 0: no cull in this segment
         {
             const float4 sc4 = pre_sc;
@@ -467,7 +470,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 }
                 fix_scale = cull ? ldexpf(1.0f, 31 - E) : 0.0f;
                 const float thr_scale = ldexpf(0.99999618530273f, -(E + 1));  // (1 - 2^-18) * 2^-(E+1)
-                for (int row = lane; row < mp.rows_local; row += 64) {
+                const int e_code = cull ? E : 1000;
+                const bool rebuild = e_code != thr_E;
+                thr_E = e_code;
+                for (int row = lane; rebuild && row < mp.rows_local; row += 64) {
                     const float tq = s_tq[row];
                     int thr = (int)0x80000000;  // no bound
                     if (tq == __builtin_inff())

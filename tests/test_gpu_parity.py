@@ -298,6 +298,36 @@ def test_loose_threshold_admits_most_pairs_of_a_later_level(B):
     check_search(w, 2000, label=f"loose threshold B={B}")
 
 
+@pytest.mark.parametrize("kind", ["loguniform", "tiny", "mixed"])
+@pytest.mark.parametrize("B", [8, 40])
+def test_wide_range_of_scales_keeps_the_exact_ranking(kind, B):
+    # admission is tested against a bound derived from the threshold and the two scales; the
+    # ranking must stay the exact fp32 one whatever the magnitudes (also where the scale of an
+    # item is so small that the bound is not trusted and the item takes the exact test alone)
+    n, d = 200_000, 64
+    w = ragged_workload(91, n, d, B, 40, 3, 256, 2)
+    rng = np.random.default_rng(5)
+    if kind == "loguniform":
+        isc = np.exp(rng.uniform(np.log(1e-3), np.log(1e3), n))
+        qsc = np.exp(rng.uniform(np.log(1e-3), np.log(1e3), B))
+    elif kind == "tiny":
+        isc = rng.choice([1e-35, 3e-33, 1e-39], n)
+        qsc = rng.uniform(0.5e6, 1.5e6, B)
+    else:
+        isc = rng.uniform(0.5, 1.5, n)
+        pick = rng.uniform(0, 1, n)
+        isc[pick < 0.02] = 1e-39
+        isc[(pick >= 0.02) & (pick < 0.04)] = 1e-35
+        isc[(pick >= 0.04) & (pick < 0.06)] = 1e-20
+        isc[(pick >= 0.06) & (pick < 0.065)] = 1e20
+        qsc = rng.uniform(0.5, 1.5, B)
+        qsc[0] = 1e-32
+    w.item_scale = torch.from_numpy(isc.astype(np.float32))
+    w.query_scale = torch.from_numpy(qsc.astype(np.float32))
+    w.filt_ids, w.filt_offsets = np.full(B, 7, np.uint64), np.arange(B + 1, dtype=np.int64)
+    check_search(w, 300, label=f"scales {kind} B={B}")
+
+
 def test_results_are_deterministic():
     cfg = S.scaled(S.CONFIGS["mid"], 80_000)
     w = S.make_workload(cfg)
