@@ -130,14 +130,16 @@ def main():
     ms_per_step = elapsed * 1e3 / args.steps
 
     # per-kernel durations, HIP events on the launch stream around every kernel of K more steps
-    levels, groups, cap = st.st_search_plan(cfg.n_items, cfg.batch, cfg.top_k)
-    st.st_timing_begin(args.steps * (3 * len(levels) + 1) + 8)
+    # room for three kernels per level; the library may add levels when it splits the query rows
+    plan_levels, _, _ = st.st_search_plan(cfg.n_items, cfg.batch * T, cfg.top_k)
+    st.st_timing_begin(args.steps * 3 * (len(plan_levels) + 6) + 8)
     for _ in range(args.steps):
         step()
     torch.cuda.synchronize()
     timing = st.st_timing_end()
     scan_ms, scan_n = timing["scan"]
     scan_ms_per_step = scan_ms / args.steps
+    n_levels = timing["select"][1] // args.steps  # one selection (or seed) launch per level
 
     stats = union_and_rows(st, bloom, w)
     n_words = (cfg.n_items + 63) // 64
@@ -209,7 +211,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": cfg.name, "n_items": cfg.n_items, "d": cfg.d, "batch": cfg.batch,
                    "n_tasks": cfg.n_tasks, "m_bits": cfg.m_bits, "k_hashes": cfg.k_hashes,
-                   "filter_terms": cfg.n_terms, "top_k": cfg.top_k, "levels": len(levels),
+                   "filter_terms": cfg.n_terms, "top_k": cfg.top_k, "levels": n_levels,
                    "scoring_path": args.path, "distinct_filters": stats["distinct_filters"],
                    "union_selectivity": stats["union_items"] / max(cfg.n_items, 1),
                    "mean_filter_selectivity": float(np.mean(stats["per_filter_sel"]))},
