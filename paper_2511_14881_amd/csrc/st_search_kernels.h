@@ -641,9 +641,33 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     const uint32_t total = n_prev + all;
     ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 1);
     const bool in_lds = total <= (uint32_t)kLdsKeys;
+    // More candidates than LDS holds, result sorted in LDS: the candidates are narrowed down where
+    // they lie (below), not copied.
+    const bool narrow = !in_lds && !p.srt;
     uint64_t* gkeys = p.gath + (int64_t)q * p.gath_cap;
-    {
-        // each thread copies the entries of its own regions (loads independent of each other)
+    // f(key) for every candidate of the query: each thread walks its own regions (loads independent
+    // of each other), then the running top-K
+    auto for_each_key = [&](auto&& f) {
+        for (int j = 0; j < per; ++j) {
+            const int w = tid * per + j;
+            if (w < R) {
+                const uint32_t c = min(cq[w], (uint32_t)p.cap);
+                const uint64_t* src = p.cand + ((int64_t)q * p.groups + w) * p.cap;
+                for (uint32_t i0 = 0; i0 < c; i0 += 4) {
+                    uint64_t v[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (i0 + u < c) v[u] = src[i0 + u];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (i0 + u < c) f(v[u]);
+                }
+            }
+        }
+        for (int i = tid; i < (int)n_prev; i += NT) f(p.topk_keys[(int64_t)q * p.K + i]);
+    };
+    if (!narrow) {
+        // contiguous copy: regions in order after the running top-K
         uint32_t off = n_prev + wbase + incl - mine;
         for (int j = 0; j < per; ++j) {
             const int w = tid * per + j;
@@ -665,11 +689,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
                 off += c;
             }
         }
-    }
-    for (int i = tid; i < (int)n_prev; i += NT) {
-        const uint64_t v = p.topk_keys[(int64_t)q * p.K + i];
-        if (in_lds) s_keys[i] = v;
-        else gkeys[i] = v;
+        for (int i = tid; i < (int)n_prev; i += NT) {
+            const uint64_t v = p.topk_keys[(int64_t)q * p.K + i];
+            if (in_lds) s_keys[i] = v;
+            else gkeys[i] = v;
+        }
     }
     __syncthreads();
     ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 2);
@@ -677,7 +701,79 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
     uint64_t kth = 0;  // K-th best key so far (0: fewer than K candidates yet)
-    if (in_lds && !p.srt) {
+    if (narrow) {
+        // Radix passes from the top, 12 bits each, over the candidates where they lie, until the
+        // keys at or above the bucket that holds the K-th fit in LDS; those are collected and the
+        // selection finishes there.  Scores of one query share most of their leading bits only up
+        // to the exponent, so one pass is the rule.
+        constexpr int kBins = 4096;
+        static_assert(kBins * 4 <= kLdsSortMax * 8, "histogram borrows the sort buffer");
+        uint32_t* hist = reinterpret_cast<uint32_t*>(s_sorted);
+        uint64_t prefix = 0, pmask = 0;
+        uint32_t want = (uint32_t)p.K, above = 0;  // above: keys over the prefix bucket (all kept)
+        uint64_t bound = 0;
+        uint32_t keep = 0;
+        for (int shift = 52;;) {
+            for (int i = tid; i < kBins; i += NT) hist[i] = 0;
+            __syncthreads();
+            for_each_key([&](uint64_t key) {
+                if ((key & pmask) == prefix) atomicAdd(&hist[(uint32_t)(key >> shift) & (kBins - 1)], 1u);
+            });
+            __syncthreads();
+            // thread t owns bins 4095-8t .. 4088-8t (descending); running count from the top
+            constexpr int kPer = kBins / NT;
+            uint32_t h[kPer], sum = 0;
+#pragma unroll
+            for (int j = 0; j < kPer; ++j) { h[j] = hist[kBins - 1 - kPer * tid - j]; sum += h[j]; }
+            uint32_t inc = sum;
+            for (int o = 1; o < 64; o <<= 1) {
+                const uint32_t v = __shfl_up(inc, o);
+                if (lane >= o) inc += v;
+            }
+            if (lane == 63) s_wsum[wv] = inc;
+            __syncthreads();
+            uint32_t base = 0;
+            for (int w = 0; w < wv; ++w) base += s_wsum[w];
+            uint32_t before = base + inc - sum;  // keys of the bucket in bins above mine
+            if (before < want && want <= before + sum) {  // exactly one thread
+#pragma unroll
+                for (int j = 0; j < kPer; ++j) {
+                    if (want > before && want <= before + h[j]) {
+                        s_misc[0] = (uint32_t)(kBins - 1 - kPer * tid - j);
+                        s_misc[1] = want - before;   // rank inside that bin
+                        s_misc[3] = before;          // keys of the bucket in the bins above it
+                        s_misc[5] = before + h[j];   // ... and including it
+                    }
+                    before += h[j];
+                }
+            }
+            __syncthreads();
+            const uint32_t digit = s_misc[0], rest = s_misc[1], gt = s_misc[3], ge = s_misc[5];
+            __syncthreads();
+            if (above + ge <= (uint32_t)kLdsKeys || shift == 0) {
+                bound = prefix | ((uint64_t)digit << shift);
+                keep = above + ge;
+                break;
+            }
+            above += gt;
+            prefix |= (uint64_t)digit << shift;
+            pmask |= (uint64_t)(kBins - 1) << shift;
+            want = rest;
+            shift = shift >= 12 ? shift - 12 : 0;  // the last window overlaps bits already fixed
+        }
+        if (tid == 0) s_misc[2] = 0;
+        __syncthreads();
+        for_each_key([&](uint64_t key) {
+            if (key >= bound) {
+                const uint32_t slot = atomicAdd(&s_misc[2], 1u);
+                if (slot < (uint32_t)kLdsKeys) s_keys[slot] = key;
+            }
+        });
+        __syncthreads();
+        keep = keep < (uint32_t)kLdsKeys ? keep : (uint32_t)kLdsKeys;  // keys are distinct: never cut
+        n_out = lds_topk(s_keys, (int)keep, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
+                         1, q, 9);
+    } else if (in_lds && !p.srt) {
         n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
                          1, q, 9);
     } else {
