@@ -524,7 +524,13 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         if (mp.q_split < 1) return fail(ST_EINVAL, "query batch too large for the resident-query scorer");
     }
 
-    const int32_t seg_cap = set_mfma.n ? st::mfma_max_seg_items(d) : st::kMaxSegItems;
+    // 512-item segments fill the 16-item units better and halve the per-segment work, where the
+    // larger per-wavefront lists leave as many workgroups on a compute unit
+    mp.seg_stride = 256;
+    if (set_mfma.n && st::mfma_lds_bytes(mp.n_blocks, mp.q_split, d, n_tasks, set_mfma.n, mp.waves,
+                                         st::mfma_region_slots(mfma_wgs), st::kMfmaSegItems) * mfma_wgs <= 160 * 1024)
+        mp.seg_stride = st::kMfmaSegItems;
+    const int32_t seg_cap = set_mfma.n ? mp.seg_stride : st::kMaxSegItems;
     st::Plan plan;
     if (st::make_plan(n_items, K, mp.q_split, seg_cap, batch * n_tasks, &plan) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");

@@ -34,11 +34,10 @@ constexpr int kPrefetchStride = 16;        // rows per filter in the prefetch ta
 constexpr int kMfmaQueryLds = 64 * 1024;   // LDS bytes for resident query rows per workgroup
 constexpr int kMfmaMinRows = 4;            // a group needs this many query rows to go to MFMA
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
-constexpr int kMfmaSegItems = 256;         // items per wavefront segment, at most (4 mask words x 8 filters = 32 lanes)
+constexpr int kMfmaSegItems = 512;         // items per wavefront segment, at most (8 mask words x 8 filters = 64 lanes)
 constexpr int kQueueSlots = 128;           // queued admissions per wavefront (drained whenever 64 are waiting)
 constexpr int kMaxRegionSlots = 8;         // candidate regions one workgroup may fill in a launch
 
-inline constexpr int mfma_max_seg_items(int) { return kMfmaSegItems; }
 
 struct MfmaParams {
     const int32_t* grp_blk_off;  // [F+1] first 16-row block of each group
@@ -65,6 +64,7 @@ struct MfmaParams {
     // candidate regions (x + j * gridDim.x within its row of the grid) and rotates through them
     // visit by visit, so that the regions fill as evenly as with one workgroup per region.
     int32_t region_slots;
+    int32_t seg_stride;          // items the per-wavefront LDS lists are laid out for (256 or 512, >= seg_items)
     // dynamic LDS layout (byte offsets)
     int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_tq, lds_thr, lds_scl, lds_total;
 };
@@ -107,6 +107,10 @@ template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW>
 __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
     constexpr int kThreads = NW * 64;
+    // The variant for small batches (one query block per filter, four wavefronts) is only launched
+    // with one region per workgroup and 256-item segments: both are compile-time facts there.
+    constexpr bool LEAN = !MULTI && NW == 4;
+    const int seg_stride = LEAN ? 256 : mp.seg_stride;
     constexpr int PR = NW == 8 ? kPrefetchStride : kPrefetchRows;  // rows prefetched per filter (register budget)
     extern __shared__ __attribute__((aligned(16))) unsigned char lds[];
     constexpr int D = KS * 64;
@@ -141,11 +145,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         const float tq = tf / sq;
         return (tq > 0.0f && tq < inf) ? tq : -inf;
     };
-    uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * kMfmaSegItems;  // wave-private [FB][seg]
+    // Passing items of each filter, in item order, as the low 8 bits of their place in the segment:
+    // entries of the upper half of a 512-item segment follow those of the lower half, so the
+    // number of lower-half entries per filter restores the ninth bit.
+    uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * seg_stride;  // wave-private [FB][seg]
     uint64_t* s_queue = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
     float* s_tq = reinterpret_cast<float*>(lds + mp.lds_tq);                                    // [rows_local] tau / s_q per row
     int* s_thr = reinterpret_cast<int*>(lds + mp.lds_thr) + wave * mp.rows_local;               // wave-private [rows_local]
-    float* s_scl = reinterpret_cast<float*>(lds + mp.lds_scl) + wave * kMfmaSegItems;           // wave-private [seg] item scales
+    float* s_scl = reinterpret_cast<float*>(lds + mp.lds_scl) + wave * seg_stride;              // wave-private [seg] item scales
 
     // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
     // workgroup.  wpv wavefronts share a visit (wavefront sl of them takes segments sl, sl + wpv,
@@ -153,7 +160,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     // are in progress at once.  Stages of a wavefront are numbered (visit, segment slot, filter
     // batch).
     const int seg_items = p.seg_items;
-    const int SW = seg_items >> 6;  // mask words per segment (1, 2 or 4)
+    const int SW = seg_items >> 6;  // mask words per segment (1, 2, 4 or 8)
     const int spv = p.seg_per_visit;
     const int64_t item_lim = p.item_end < p.n_items ? p.item_end : p.n_items;
     const int n_seg = (int)((p.item_end - p.item_begin + seg_items - 1) / seg_items);
@@ -171,7 +178,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         const int r = t % per_visit;
         return ((int)blockIdx.x + stage_visit(t) * (int)gridDim.x) * spv + sl + (r / n_batches) * wpv;
     };
-    const int R = mp.region_slots;
+    const int R = LEAN ? 1 : mp.region_slots;
     const int nq_pad = mp.rows_local / TT + 1;  // counters per region slot
     auto stage_batch = [&](int t) { return (t % per_visit) % n_batches; };
 
@@ -195,19 +202,26 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             pre[r] = row >= 0 ? base[(int64_t)row * kTileWords] : ~0ULL;
         }
     };
-    // item scales of a stage's segment: lane l fetches items 4l .. 4l+3 (zero past the end)
-    float4 pre_sc = make_float4(0.f, 0.f, 0.f, 0.f);
+    // item scales of a stage's segment: lane l fetches items 4l .. 4l+3 and, in a 512-item
+    // segment, 256+4l .. 256+4l+3 (zero past the end)
+    float4 pre_sc = make_float4(0.f, 0.f, 0.f, 0.f), pre_sc2 = pre_sc;
+    auto scale_fetch = [&](int64_t i0) -> float4 {
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (i0 + 3 < item_lim) {
+            v = *reinterpret_cast<const float4*>(p.iscale + i0);
+        } else {
+            if (i0 < item_lim) v.x = p.iscale[i0];
+            if (i0 + 1 < item_lim) v.y = p.iscale[i0 + 1];
+            if (i0 + 2 < item_lim) v.z = p.iscale[i0 + 2];
+        }
+        return v;
+    };
     auto scale_issue = [&](int t) {
-        pre_sc = make_float4(0.f, 0.f, 0.f, 0.f);
+        pre_sc = pre_sc2 = make_float4(0.f, 0.f, 0.f, 0.f);
         if (t >= n_stages || 4 * lane >= seg_items) return;
         const int64_t i0 = p.item_begin + (int64_t)stage_seg(t) * seg_items + 4 * lane;
-        if (i0 + 3 < item_lim) {
-            pre_sc = *reinterpret_cast<const float4*>(p.iscale + i0);
-        } else {
-            if (i0 < item_lim) pre_sc.x = p.iscale[i0];
-            if (i0 + 1 < item_lim) pre_sc.y = p.iscale[i0 + 1];
-            if (i0 + 2 < item_lim) pre_sc.z = p.iscale[i0 + 2];
-        }
+        pre_sc = scale_fetch(i0);
+        if (!LEAN && seg_items > 256) pre_sc2 = scale_fetch(i0 + 256);
     };
     auto prefetch_mask = [&](int t) -> uint64_t {  // mask word of my (filter, word) pair for stage t
         if (!pair_lane) return 0ULL;
@@ -423,7 +437,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         }
         {
             int pos = incl - c;
-            uint8_t* list = s_list + pr_gi * kMfmaSegItems;
+            uint8_t* list = s_list + pr_gi * seg_stride;
             while (mask) {
                 const int b = __ffsll((long long)mask) - 1;
                 mask &= mask - 1;
@@ -433,7 +447,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         // list size of filter gi -> lane gi; 16-item units per filter and their running sum
         // (the shuffle runs in every lane: a lane switched off would read as 0 for the others)
         const int last_word = __shfl(incl, (lane * SW + SW - 1) & 63);
+        const int low_words = LEAN ? last_word : __shfl(incl, (lane * SW + (SW > 4 ? 3 : SW - 1)) & 63);  // entries of the lower 256 items
         const int gcount = lane < nf ? last_word : 0;
+        const int glow = lane < nf ? low_words : 0;
         const int gunits = (gcount + 15) >> 4;
         int ucum = gunits;  // inclusive over filters
         for (int o = 1; o < FB; o <<= 1) {
@@ -456,11 +472,13 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         // neighbouring segments are of one magnitude).
         float fix_scale = 0.0f;  // 2^(31-E); 0: no cull in this segment
         {
-            const float4 sc4 = pre_sc;
+            const float4 sc4 = pre_sc, sc4b = pre_sc2;
             scale_issue(t + 1);
             if (4 * lane < seg_items) *reinterpret_cast<float4*>(s_scl + 4 * lane) = sc4;
+            if (!LEAN && seg_items > 256) *reinterpret_cast<float4*>(s_scl + 256 + 4 * lane) = sc4b;
             if (!WEIGHTED && n_units > 0) {
                 float smax = fmaxf(fmaxf(sc4.x, sc4.y), fmaxf(sc4.z, sc4.w));
+                smax = fmaxf(smax, fmaxf(fmaxf(sc4b.x, sc4b.y), fmaxf(sc4b.z, sc4b.w)));
                 for (int o = 32; o > 0; o >>= 1) smax = fmaxf(smax, __shfl_xor(smax, o));
                 int E = 0;
                 bool cull = smax > 0.0f && smax < __builtin_inff();
@@ -487,7 +505,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
 
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
-        // contracted: uniform bases + 32-bit lane offsets (the segment spans at most 256 * D bytes)
+        // contracted: uniform bases + 32-bit lane offsets (the segment spans at most 512 * D bytes)
         const char* seg_rows = reinterpret_cast<const char*>(p.items + item0 * D) + kg * 16;
         int qn = 0;          // queued admissions (uniform)
         int cur_lrow = -1;   // query block whose A operand (and per-row constants) sit in registers
@@ -497,16 +515,18 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
 
         // unit generator: (gen_gi, gen_b0) is the next unit to request; it stays on the last unit
         // once all have been produced, so that requests past the end are harmless repeats
-        int gen_gi = 0, gen_b0 = 0, gen_n = 0, gen_left = 0;
+        int gen_gi = 0, gen_b0 = 0, gen_n = 0, gen_low = 0, gen_left = 0;
         auto gen_seek = [&](int u) {  // position on unit u (cold)
             gen_gi = __popcll(ballot(lane < nf && ucum <= u));
             gen_b0 = (u - (__builtin_amdgcn_readlane(ucum, gen_gi) - __builtin_amdgcn_readlane(gunits, gen_gi))) << 4;
             gen_n = __builtin_amdgcn_readlane(gcount, gen_gi);
+            gen_low = __builtin_amdgcn_readlane(glow, gen_gi);
             gen_left = n_units - 1 - u;
         };
         auto unit_load = [&](UnitRegs<KS>& w) {
             const int li = gen_b0 + l16;
-            const int idx = (int)s_list[gen_gi * kMfmaSegItems + min(li, gen_n - 1)];
+            const int at = min(li, gen_n - 1);
+            const int idx = (int)s_list[gen_gi * seg_stride + at] + (!LEAN && at >= gen_low ? 256 : 0);
             w.item = li < gen_n ? idx : -1;
             w.gi = gen_gi;
             const uint32_t off = (uint32_t)(idx * D);
@@ -525,6 +545,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                     ++gen_gi;
                     gen_b0 = 0;
                     gen_n = __builtin_amdgcn_readlane(gcount, gen_gi);
+                    gen_low = __builtin_amdgcn_readlane(glow, gen_gi);
                 }
             }
         };
@@ -544,8 +565,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             const int base = qn > 64 ? qn - 64 : 0;
             if (base + lane < qn) {
                 const uint64_t e = s_queue[base + lane];
-                const int srow = (int)((uint32_t)e >> 8);  // local row of the query's first task
-                const int it = (int)(e & 255u);
+                const int srow = (int)((uint32_t)e >> 9);  // local row of the query's first task
+                const int it = (int)(e & 511u);
                 float score;
                 if (WEIGHTED)
                     score = __uint_as_float((uint32_t)(e >> 32));
@@ -612,7 +633,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                     if ((m >> lane) & 1ULL) {
                         const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32),
                                                                     __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                        s_queue[pos] = ((uint64_t)val[r] << 32) | (uint32_t)(((lrow + 4 * kg + r) << 8) | w.item);
+                        s_queue[pos] = ((uint64_t)val[r] << 32) | (uint32_t)(((lrow + 4 * kg + r) << 9) | w.item);
                     }
                     qn += __popcll(m);
                     if (qn >= 64) drain();
@@ -766,7 +787,7 @@ inline bool mfma_shape_ok(int d, int n_tasks)
 
 // LDS one workgroup needs with the resident queries split S ways, `waves` wavefronts and
 // `slots` candidate regions.
-inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves, int slots);
+inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves, int slots, int seg_stride = 256);
 
 // Candidate regions per workgroup when a compute unit holds `wgs` workgroups: all regions are
 // shared out among the workgroups that are resident at once.
@@ -826,23 +847,24 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, in
     mp->lds_tau64 = take((mp->rows_local / n_tasks + 1) * 8);
     mp->lds_qrow = take(mp->rows_local * 4);
     mp->lds_cnt = take(mp->region_slots * (mp->rows_local / n_tasks + 1) * 4);
-    mp->lds_list = take(waves * kMfmaFilterBatch * kMfmaSegItems);
+    mp->lds_list = take(waves * kMfmaFilterBatch * mp->seg_stride);
     mp->lds_queue = take(waves * kQueueSlots * 8);
     mp->lds_prow = take(n_groups * kPrefetchStride * 4);
     mp->lds_blkoff = take((2 * n_groups + 2) * 4);
     mp->lds_rowoff = take((n_groups + 1) * 4);
     mp->lds_tq = take(mp->rows_local * 4);
     mp->lds_thr = take(waves * mp->rows_local * 4);
-    mp->lds_scl = take(waves * kMfmaSegItems * 4);
+    mp->lds_scl = take(waves * mp->seg_stride * 4);
     mp->lds_total = off;
 }
 
-inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves, int slots)
+inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups, int waves, int slots, int seg_stride)
 {
     MfmaParams t;
     t.n_blocks = n_blocks;
     t.q_split = S;
     t.region_slots = slots;
+    t.seg_stride = seg_stride;
     mfma_lds_layout(&t, d, n_tasks, n_groups, waves);
     return t.lds_total;
 }
@@ -865,14 +887,14 @@ inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp,
 // gx = workgroups per row of the grid (at most groups / q_split); region index = x + y * gx
 inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
-    if (sp.seg_items > mfma_max_seg_items(sp.d) || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
+    if (sp.seg_items > mp.seg_stride || mp.seg_stride > kMfmaSegItems || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
     const int ks = sp.d / 64, tt = sp.n_tasks;
 #define ST_CASE(K_, T_)                                                                                          \
     if (ks == K_ && tt == T_) {                                                                                  \
         if (mp.waves == 8)                                                                                       \
             return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true, 8>(sp, mp, gx, stream)                   \
                                : launch_scan_mfma_t<K_, T_, false, true, 8>(sp, mp, gx, stream);                 \
-        if (mp.multi_block)                                                                                      \
+        if (mp.multi_block || mp.region_slots != 1 || mp.seg_stride != 256)                                      \
             return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true, 4>(sp, mp, gx, stream)                   \
                                : launch_scan_mfma_t<K_, T_, false, true, 4>(sp, mp, gx, stream);                 \
         return sp.weighted ? launch_scan_mfma_t<K_, T_, true, false, 4>(sp, mp, gx, stream)                      \
