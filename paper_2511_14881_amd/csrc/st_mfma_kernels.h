@@ -154,11 +154,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     int* s_thr = reinterpret_cast<int*>(lds + mp.lds_thr) + wave * mp.rows_local;               // wave-private [rows_local]
     float* s_scl = reinterpret_cast<float*>(lds + mp.lds_scl) + wave * seg_stride;              // wave-private [seg] item scales
 
-    // ---- per-wavefront schedule.  A visit is seg_per_visit consecutive segments owned by one
-    // workgroup.  wpv wavefronts share a visit (wavefront sl of them takes segments sl, sl + wpv,
-    // ...); when a visit has fewer segments than the workgroup has wavefronts, NW / wpv visits
-    // are in progress at once.  Stages of a wavefront are numbered (visit, segment slot, filter
-    // batch).
+    // ---- schedule.  A visit is seg_per_visit consecutive segments; workgroup x owns visits x,
+    // x + gridDim.x, ...  Its segments, in that order, are numbered 0, 1, ...; wavefront w starts on
+    // number w and draws every further one from a counter in LDS, so that no wavefront of the
+    // workgroup idles while another still has segments queued.  A stage is one (segment, filter
+    // batch) of a wavefront.
     const int seg_items = p.seg_items;
     const int SW = seg_items >> 6;  // mask words per segment (1, 2, 4 or 8)
     const int spv = p.seg_per_visit;
@@ -166,21 +166,29 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     const int n_seg = (int)((p.item_end - p.item_begin + seg_items - 1) / seg_items);
     const int n_visit = (n_seg + spv - 1) / spv;
     const int n_batches = (p.n_groups + FB - 1) / FB;
-    const int wpv = spv < NW ? spv : NW, cv = NW / wpv;
-    const int vl = wave / wpv, sl = wave - vl * wpv;
-    const int slots = (spv - sl + wpv - 1) / wpv;  // my segments per visit
     const int wg_visits = (int)blockIdx.x < n_visit ? (n_visit - (int)blockIdx.x + (int)gridDim.x - 1) / (int)gridDim.x : 0;
-    const int my_visits = vl < wg_visits ? (wg_visits - vl + cv - 1) / cv : 0;
-    const int per_visit = slots * n_batches;
-    const int n_stages = my_visits * per_visit;
-    auto stage_visit = [&](int t) { return vl + cv * (t / per_visit); };  // among the workgroup's visits
-    auto stage_seg = [&](int t) {  // segment index of stage t (may lie past the level's end: no items there)
-        const int r = t % per_visit;
-        return ((int)blockIdx.x + stage_visit(t) * (int)gridDim.x) * spv + sl + (r / n_batches) * wpv;
-    };
+    const int wg_segs = wg_visits * spv;  // the last visit of the level may hold fewer: those have no items
     const int R = LEAN ? 1 : mp.region_slots;
     const int nq_pad = mp.rows_local / TT + 1;  // counters per region slot
-    auto stage_batch = [&](int t) { return (t % per_visit) % n_batches; };
+    uint32_t* s_work = s_cnt + R * nq_pad;      // next segment number of the workgroup
+    struct Stage {
+        int num;    // segment number within the workgroup (>= wg_segs: none, the work has run out)
+        int batch;  // filter batch
+    };
+    auto stage_ok = [&](const Stage& st) { return st.num < wg_segs; };
+    auto stage_visit = [&](const Stage& st) { return st.num / spv; };  // among the workgroup's visits
+    auto stage_seg = [&](const Stage& st) {  // segment index in the level (may lie past its end: no items there)
+        const int i = st.num / spv;
+        return ((int)blockIdx.x + i * (int)gridDim.x) * spv + (st.num - i * spv);
+    };
+    auto stage_next = [&](const Stage& st) -> Stage {
+        if (!stage_ok(st)) return st;
+        if (st.batch + 1 < n_batches) return Stage{st.num, st.batch + 1};
+        uint32_t v = 0;
+        if (lane == 0) v = atomicAdd(s_work, 1u);
+        return Stage{__builtin_amdgcn_readfirstlane((int)v), 0};
+    };
+    Stage cur{wave, 0};
 
     // Bloom words: lane (gi * SW + w) owns word w of filter gi of the stage's batch.
     const bool pair_lane = lane < FB * SW;
@@ -189,11 +197,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     int pre_valid = 0;  // rows of the current stage that were prefetched (the first stage gets kPrefetchRows from the kernel arguments)
 #pragma unroll
     for (int r = 0; r < PR; ++r) pre[r] = ~0ULL;
-    auto prefetch_issue = [&](int t) {
-        if (!pair_lane || t >= n_stages) return;
-        const int g = stage_batch(t) * FB + pr_gi;
+    auto prefetch_issue = [&](const Stage& st) {
+        if (!pair_lane || !stage_ok(st)) return;
+        const int g = st.batch * FB + pr_gi;
         if (g >= p.n_groups) return;
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(t) * seg_items) >> 6) + pr_w;
+        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(st) * seg_items) >> 6) + pr_w;
         if (gw * 64 >= item_lim) return;
         const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
@@ -216,18 +224,18 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         }
         return v;
     };
-    auto scale_issue = [&](int t) {
+    auto scale_issue = [&](const Stage& st) {
         pre_sc = pre_sc2 = make_float4(0.f, 0.f, 0.f, 0.f);
-        if (t >= n_stages || 4 * lane >= seg_items) return;
-        const int64_t i0 = p.item_begin + (int64_t)stage_seg(t) * seg_items + 4 * lane;
+        if (!stage_ok(st) || 4 * lane >= seg_items) return;
+        const int64_t i0 = p.item_begin + (int64_t)stage_seg(st) * seg_items + 4 * lane;
         pre_sc = scale_fetch(i0);
         if (!LEAN && seg_items > 256) pre_sc2 = scale_fetch(i0 + 256);
     };
-    auto prefetch_mask = [&](int t) -> uint64_t {  // mask word of my (filter, word) pair for stage t
+    auto prefetch_mask = [&](const Stage& st) -> uint64_t {  // mask word of my (filter, word) pair for the stage
         if (!pair_lane) return 0ULL;
-        const int g = stage_batch(t) * FB + pr_gi;
+        const int g = st.batch * FB + pr_gi;
         if (g >= p.n_groups) return 0ULL;
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(t) * seg_items) >> 6) + pr_w;
+        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(st) * seg_items) >> 6) + pr_w;
         const int64_t first = gw * 64;
         if (first >= item_lim) return 0ULL;
         const int64_t left = item_lim - first;
@@ -242,7 +250,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         return mask;
     };
     // ---- first Bloom words: rows from the kernel arguments, requested before any table is read
-    if (pair_lane && n_stages > 0) {
+    if (pair_lane && stage_ok(cur)) {
         uint64_t lo = 0, hi = 0;
         int nr = 0;
 #pragma unroll
@@ -252,7 +260,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 hi = mp.prow_pack[g][1];
                 nr = (int)((mp.prow_n >> (8 * g)) & 255);
             }
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(0) * seg_items) >> 6) + pr_w;
+        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(cur) * seg_items) >> 6) + pr_w;
         if (pr_gi < p.n_groups && gw * 64 < item_lim) {
             const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
@@ -262,7 +270,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             }
         }
     }
-    scale_issue(0);
+    scale_issue(cur);
 
     // ---- workgroup-wide set-up: tables and resident queries into LDS.  The compiler keeps a
     // global load behind the LDS stores that precede it, so a copy loop per table would pay one
@@ -319,6 +327,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     }
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 11);
     for (int i = tid; i < R * nq_pad; i += kThreads) s_cnt[i] = 0;
+    if (tid == 0) *s_work = (uint32_t)NW;  // numbers 0 .. NW-1 are the wavefronts' first segments
     for (int i = tid + kThreads; i < n_prow; i += kThreads) s_prow[i] = mp.prow[i];
     for (int g = tid + kThreads; g <= p.n_groups; g += kThreads) {
         s_rowoff[g] = p.grp_row_off[g];
@@ -413,22 +422,23 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
 
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 1);
     int thr_E = -1000;  // exponent the wavefront's integer bounds were built for (none yet)
-    for (int t = 0; t < n_stages; ++t) {
-        const int64_t item0 = p.item_begin + (int64_t)stage_seg(t) * seg_items;
-        const int g0 = stage_batch(t) * FB;
+    for (bool first = true; stage_ok(cur); first = false) {
+        const int64_t item0 = p.item_begin + (int64_t)stage_seg(cur) * seg_items;
+        const int g0 = cur.batch * FB;
         const int nf = min(FB, p.n_groups - g0);
-        const int slot = R == 1 ? 0 : stage_visit(t) % R;  // candidate region of this visit
+        const int slot = R == 1 ? 0 : stage_visit(cur) % R;  // candidate region of this visit
         const int region = (int)blockIdx.x + slot * (int)gridDim.x + y * (int)gridDim.x * R;
         uint32_t* cnt_s = s_cnt + slot * nq_pad;
 
         // (1) + (2): mask word of my pair, then the set bits of each filter's words, in item
         // order, into the filter's list
-        pre_valid = t == 0 ? kPrefetchRows : PR;
-        uint64_t mask = prefetch_mask(t);
+        pre_valid = first ? kPrefetchRows : PR;
+        uint64_t mask = prefetch_mask(cur);
+        const Stage nxt = stage_next(cur);
 #pragma unroll
         for (int r = 0; r < PR; ++r) pre[r] = ~0ULL;
-        prefetch_issue(t + 1);
-        if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 2);
+        prefetch_issue(nxt);
+        if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 2);
         const int c = __popcll(mask);
         int incl = c;  // running count over the words of my filter
         for (int o = 1; o < SW; o <<= 1) {
@@ -460,7 +470,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         // first local query row and local block count of filter gi -> lane gi
         const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
         const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;
-        if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 3);
+        if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 3);
 
         // Item scales of the segment into LDS.  Plain search: their maximum fixes a power of two
         // 2^E above every scale of the segment; the lane's scale becomes the fixed-point factor
@@ -473,7 +483,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         float fix_scale = 0.0f;  // 2^(31-E); 0: no cull in this segment
         {
             const float4 sc4 = pre_sc, sc4b = pre_sc2;
-            scale_issue(t + 1);
+            scale_issue(nxt);
             if (4 * lane < seg_items) *reinterpret_cast<float4*>(s_scl + 4 * lane) = sc4;
             if (!LEAN && seg_items > 256) *reinterpret_cast<float4*>(s_scl + 256 + 4 * lane) = sc4b;
             if (!WEIGHTED && n_units > 0) {
@@ -748,17 +758,18 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             unit_load(r1);
             if (NB > 2) unit_load(r2);
             if (NB > 3) unit_load(r3);
-            if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
+            if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
             for (int base = 0; base < n_units; base += NB) {
                 step(r0, base);
                 step(r1, base + 1);
                 if (NB > 2) step(r2, base + 2);
                 if (NB > 3) step(r3, base + 3);
             }
-            if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 5);
+            if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 5);
             while (qn > 0) drain();
         }
-        if (t == 0) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 6);
+        if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 6);
+        cur = nxt;
     }
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 7);
     __syncthreads();
@@ -846,7 +857,7 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, in
     mp->lds_tauf = take(mp->rows_local * 4);
     mp->lds_tau64 = take((mp->rows_local / n_tasks + 1) * 8);
     mp->lds_qrow = take(mp->rows_local * 4);
-    mp->lds_cnt = take(mp->region_slots * (mp->rows_local / n_tasks + 1) * 4);
+    mp->lds_cnt = take((mp->region_slots * (mp->rows_local / n_tasks + 1) + 1) * 4);  // + the segment counter
     mp->lds_list = take(waves * kMfmaFilterBatch * mp->seg_stride);
     mp->lds_queue = take(waves * kQueueSlots * 8);
     mp->lds_prow = take(n_groups * kPrefetchStride * 4);
