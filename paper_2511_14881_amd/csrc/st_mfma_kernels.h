@@ -667,11 +667,28 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         auto row_sq = [&](int lrow) { return *reinterpret_cast<const float4*>(s_sq + lrow + 4 * kg); };
         auto row_tf = [&](int lrow) { return *reinterpret_cast<const float4*>(s_tauf + lrow + 4 * kg); };
         auto row_thr = [&](int lrow) { return *reinterpret_cast<const int4*>(s_thr + lrow + 4 * kg); };
-        // the test of one block, from the per-row constants in LDS
-        auto block_test = [&](int lrow, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid, uint32_t (&val)[4],
+        // the per-row constants of one block (read from LDS together with its A operand, well before
+        // the accumulators they are compared with exist) and the test that uses them
+        struct RowK {
+            float4 sq, tf;  // weighted search
+            int4 thr;       // plain search
+        };
+        auto row_k = [&](int lrow) -> RowK {
+            RowK k;
+            k.sq = k.tf = make_float4(0.f, 0.f, 0.f, 0.f);
+            k.thr = make_int4(0, 0, 0, 0);
+            if (WEIGHTED) {
+                k.sq = row_sq(lrow);
+                k.tf = row_tf(lrow);
+            } else {
+                k.thr = row_thr(lrow);
+            }
+            return k;
+        };
+        auto block_test = [&](const RowK& k, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid, uint32_t (&val)[4],
                               uint64_t (&hits)[4]) -> bool {
-            if (WEIGHTED) return block_scores(row_sq(lrow), row_tf(lrow), acc, w, valid, val, hits);
-            return block_cull(row_thr(lrow), acc, w, valid, val, hits);
+            if (WEIGHTED) return block_scores(k.sq, k.tf, acc, w, valid, val, hits);
+            return block_cull(k.thr, acc, w, valid, val, hits);
         };
         // Contracts one unit with the query blocks of its filter group, two blocks per round (the
         // operands of both are read before either is used).  A group of a single block keeps its
@@ -701,7 +718,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             }
             if (!MULTI) return;
             int j = 0;
-            if (NW == 8) {  // four blocks per round: independent chains, the registers allow it at 8 wavefronts
+            if (NW == 8 && KS <= 2) {  // four blocks per round: independent chains, where the registers allow it
                 for (; j + 4 <= nblk; j += 4) {
                     const int l0 = lrow0 + 16 * j;
                     v4i a0[KS], a1[KS], a2[KS], a3[KS];
@@ -711,11 +728,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                     block_a(l0 + 16, a1);
                     block_a(l0 + 32, a2);
                     block_a(l0 + 48, a3);
+                    const RowK k0 = row_k(l0), k1 = row_k(l0 + 16), k2 = row_k(l0 + 32), k3 = row_k(l0 + 48);
                     const v4i c0 = block_mfma(a0, w), c1 = block_mfma(a1, w), c2 = block_mfma(a2, w), c3 = block_mfma(a3, w);
-                    const bool y0 = block_test(l0, c0, w, valid, v0, h0);
-                    const bool y1 = block_test(l0 + 16, c1, w, valid, v1, h1);
-                    const bool y2 = block_test(l0 + 32, c2, w, valid, v2, h2);
-                    const bool y3 = block_test(l0 + 48, c3, w, valid, v3, h3);
+                    const bool y0 = block_test(k0, c0, w, valid, v0, h0);
+                    const bool y1 = block_test(k1, c1, w, valid, v1, h1);
+                    const bool y2 = block_test(k2, c2, w, valid, v2, h2);
+                    const bool y3 = block_test(k3, c3, w, valid, v3, h3);
                     if (y0) block_push(l0, w, valid, v0, h0);
                     if (y1) block_push(l0 + 16, w, valid, v1, h1);
                     if (y2) block_push(l0 + 32, w, valid, v2, h2);
@@ -729,9 +747,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 uint64_t h0[4], h1[4];
                 block_a(l0, a0);
                 block_a(l0 + 16, a1);
+                const RowK k0 = row_k(l0), k1 = row_k(l0 + 16);
                 const v4i c0 = block_mfma(a0, w), c1 = block_mfma(a1, w);
-                const bool y0 = block_test(l0, c0, w, valid, v0, h0);
-                const bool y1 = block_test(l0 + 16, c1, w, valid, v1, h1);
+                const bool y0 = block_test(k0, c0, w, valid, v0, h0);
+                const bool y1 = block_test(k1, c1, w, valid, v1, h1);
                 if (y0) block_push(l0, w, valid, v0, h0);
                 if (y1) block_push(l0 + 16, w, valid, v1, h1);
             }
@@ -740,8 +759,9 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 uint32_t val[4];
                 uint64_t hits[4];
                 block_a(lrow0 + 16 * j, a);
+                const RowK k = row_k(lrow0 + 16 * j);
                 const v4i acc = block_mfma(a, w);
-                if (block_test(lrow0 + 16 * j, acc, w, valid, val, hits)) block_push(lrow0 + 16 * j, w, valid, val, hits);
+                if (block_test(k, acc, w, valid, val, hits)) block_push(lrow0 + 16 * j, w, valid, val, hits);
             }
         };
         // Every load in the loop is unconditional (requests past the end repeat the last unit):
