@@ -117,7 +117,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     constexpr int CH = D / 16;  // 16-byte chunks per row
     constexpr int FB = kMfmaFilterBatch;
     // ring slots (units with rows in flight)
-    constexpr int NB = KS == 1 ? 4 : (KS == 2 ? ST_NB2 : 2);
+    // 8-wavefront workgroups contract two units at a time with each query block (the A operand and
+    // the per-row constants are read from LDS once for both: LDS bandwidth, not the matrix cores,
+    // bounds the loop when a filter group holds many query blocks); their ring holds two pairs.
+    constexpr bool PAIRS = NW == 8 && KS <= 2;
+    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? ST_NB2 : 2));
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
@@ -764,6 +768,44 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 if (block_test(k, acc, w, valid, val, hits)) block_push(lrow0 + 16 * j, w, valid, val, hits);
             }
         };
+        // Two units of one filter group at once: every block's operands serve both.
+        auto unit_compute2 = [&](const UnitRegs<KS>& w0, const UnitRegs<KS>& w1) {
+            const int lrow0 = __builtin_amdgcn_readlane(glrow, w0.gi);
+            const int nblk = __builtin_amdgcn_readlane(gnblk, w0.gi);
+            const uint64_t valid0 = ballot(w0.item >= 0), valid1 = ballot(w1.item >= 0);
+            int j = 0;
+            for (; j + 2 <= nblk; j += 2) {
+                const int l0 = lrow0 + 16 * j;
+                v4i a0[KS], a1[KS];
+                uint32_t v00[4], v01[4], v10[4], v11[4];
+                uint64_t h00[4], h01[4], h10[4], h11[4];
+                block_a(l0, a0);
+                block_a(l0 + 16, a1);
+                const RowK k0 = row_k(l0), k1 = row_k(l0 + 16);
+                const v4i c00 = block_mfma(a0, w0), c01 = block_mfma(a0, w1), c10 = block_mfma(a1, w0), c11 = block_mfma(a1, w1);
+                const bool y00 = block_test(k0, c00, w0, valid0, v00, h00);
+                const bool y01 = block_test(k0, c01, w1, valid1, v01, h01);
+                const bool y10 = block_test(k1, c10, w0, valid0, v10, h10);
+                const bool y11 = block_test(k1, c11, w1, valid1, v11, h11);
+                if (y00) block_push(l0, w0, valid0, v00, h00);
+                if (y01) block_push(l0, w1, valid1, v01, h01);
+                if (y10) block_push(l0 + 16, w0, valid0, v10, h10);
+                if (y11) block_push(l0 + 16, w1, valid1, v11, h11);
+            }
+            for (; j < nblk; ++j) {
+                const int l0 = lrow0 + 16 * j;
+                v4i a[KS];
+                uint32_t v0[4], v1[4];
+                uint64_t h0[4], h1[4];
+                block_a(l0, a);
+                const RowK k = row_k(l0);
+                const v4i c0 = block_mfma(a, w0), c1 = block_mfma(a, w1);
+                const bool y0 = block_test(k, c0, w0, valid0, v0, h0);
+                const bool y1 = block_test(k, c1, w1, valid1, v1, h1);
+                if (y0) block_push(l0, w0, valid0, v0, h0);
+                if (y1) block_push(l0, w1, valid1, v1, h1);
+            }
+        };
         // Every load in the loop is unconditional (requests past the end repeat the last unit):
         // only then is the number of loads between a unit's request and its use a constant the
         // compiler can wait on.
@@ -773,6 +815,16 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 if (u < n_units) unit_compute(r);
                 unit_load(r);
             };
+            auto step2 = [&](UnitRegs<KS>& ra, UnitRegs<KS>& rb, int u) {
+                if (u + 1 < n_units && ra.gi == rb.gi && __builtin_amdgcn_readlane(gnblk, ra.gi) > 1) {
+                    unit_compute2(ra, rb);
+                } else {
+                    if (u < n_units) unit_compute(ra);
+                    if (u + 1 < n_units) unit_compute(rb);
+                }
+                unit_load(ra);
+                unit_load(rb);
+            };
             gen_seek(0);
             unit_load(r0);
             unit_load(r1);
@@ -780,10 +832,15 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             if (NB > 3) unit_load(r3);
             if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
             for (int base = 0; base < n_units; base += NB) {
-                step(r0, base);
-                step(r1, base + 1);
-                if (NB > 2) step(r2, base + 2);
-                if (NB > 3) step(r3, base + 3);
+                if (PAIRS) {
+                    step2(r0, r1, base);
+                    step2(r2, r3, base + 2);
+                } else {
+                    step(r0, base);
+                    step(r1, base + 1);
+                    if (NB > 2) step(r2, base + 2);
+                    if (NB > 3) step(r3, base + 3);
+                }
             }
             if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 5);
             while (qn > 0) drain();
