@@ -149,6 +149,15 @@ int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t
                    const int64_t* dev_pair_item, const int32_t* dev_pair_query, int64_t n_pairs,
                    int32_t* dev_out_dot, float* dev_out_score, void* hip_stream);
 
+/* Diagnostic: byte offset, inside a workspace laid out for these sizes (the arguments of
+ * st_search_workspace_bytes), of the per-query overflow flags: uint32 [batch], valid once a
+ * search on that workspace has completed.  1 = one of the query's candidate regions overflowed
+ * in some level and the query was recomputed by the slow exact path (Algorithm 1 phases 3-4 are
+ * then evaluated for that query alone, over the whole corpus); results are exact either way, the
+ * flag only tells that the fast path did not hold.  Negative st_status on bad sizes. */
+int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks,
+                                        int32_t K);
+
 /* Host-side description of how a search of these sizes is scheduled (pure arithmetic, no
  * GPU): writes up to max_levels rows of 3 int64 {item_begin, item_end, segment_items} and
  * returns the number of levels, or a negative st_status.  The corpus is scanned once, in

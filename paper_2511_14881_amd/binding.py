@@ -21,6 +21,7 @@ EXPORTS = [
     "st_bloom_layout_bytes", "st_bloom_n_items", "st_bloom_export_signatures", "st_bloom_mask",
     "st_search_workspace_bytes", "st_search", "st_search_multitask", "st_score_pairs",
     "st_search_plan", "st_set_scoring_path", "st_timing_begin", "st_timing_end",
+    "st_search_overflow_flags_offset",
 ]
 
 
@@ -57,6 +58,8 @@ def lib() -> C.CDLL:
         L.st_bloom_mask.argtypes = [p, p, p, i32, p, p]
         L.st_search_workspace_bytes.restype = i64
         L.st_search_workspace_bytes.argtypes = [i64, i32, i32, i32, i32]
+        L.st_search_overflow_flags_offset.restype = i64
+        L.st_search_overflow_flags_offset.argtypes = [i64, i32, i32, i32, i32]
         L.st_search.restype = C.c_int
         L.st_search.argtypes = [p, p, p, i64, i32, p, p, i32, p, p, i32, p, p, p, p, i64, p]
         L.st_search_multitask.restype = C.c_int
@@ -185,6 +188,10 @@ def st_search_workspace_bytes(n_items: int, d: int, batch: int, n_tasks: int, K:
     return _check(lib().st_search_workspace_bytes(n_items, d, batch, n_tasks, K))
 
 
+def st_search_overflow_flags_offset(n_items: int, d: int, batch: int, n_tasks: int, K: int) -> int:
+    return _check(lib().st_search_overflow_flags_offset(n_items, d, batch, n_tasks, K))
+
+
 def st_search_plan(n_items: int, batch: int, K: int, q_split: int = 1):
     levels = np.zeros((32, 3), dtype=np.int64)
     caps = np.zeros(2, dtype=np.int64)
@@ -213,10 +220,17 @@ class SearchBuffers:
 
     def __init__(self, n_items: int, d: int, batch: int, n_tasks: int, K: int):
         self.nbytes = st_search_workspace_bytes(n_items, d, batch, n_tasks, K)
+        self._ovf = (st_search_overflow_flags_offset(n_items, d, batch, n_tasks, K), batch)
         self.workspace = torch.empty(self.nbytes, dtype=torch.uint8, device="cuda")
         self.ids = torch.empty((batch, K), dtype=torch.int64, device="cuda")
         self.scores = torch.empty((batch, K), dtype=torch.float32, device="cuda")
         self.count = torch.empty(batch, dtype=torch.int32, device="cuda")
+
+    def overflow_flags(self):
+        """int32 [batch] view: 1 where the last search on these buffers had to recompute the query
+        by the slow exact path (read after the stream has synchronised)."""
+        off, batch = self._ovf
+        return self.workspace[off:off + 4 * batch].view(torch.int32)
 
 
 def st_search(bloom: BloomIndex, items, item_scale, queries, query_scale, filt_ids, filt_offsets,

@@ -449,6 +449,18 @@ int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int
     return (int64_t)st::make_layout(p, batch, K, d, n_tasks).total;
 }
 
+int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K)
+{
+    const int64_t total = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
+    if (total < 0) return total;
+    st::Plan p;
+    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p) != 0)
+        return fail(ST_EINVAL, "no schedule for these sizes");
+    return (int64_t)st::make_layout(p, batch, K, d, n_tasks).ovf;
+}
+
+static int32_t plan_groups_per_row(int32_t q_split) { return st::scan_groups() / std::max(q_split, 1); }
+
 static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
                        int64_t n_items, int32_t d, const int8_t* dev_queries, const float* dev_query_scale,
                        int32_t batch, int32_t n_tasks, const float* host_task_weight,
@@ -532,7 +544,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         mp.seg_stride = st::kMfmaSegItems;
     const int32_t seg_cap = set_mfma.n ? mp.seg_stride : st::kMaxSegItems;
     st::Plan plan;
-    if (st::make_plan(n_items, K, mp.q_split, seg_cap, batch * n_tasks, &plan) != 0)
+    // wavefronts that scan a level side by side: the resident workgroups of one row of the grid
+    const int32_t scan_waves = set_mfma.n ? std::max(1, std::min(plan_groups_per_row(mp.q_split), st::kComputeUnits * mfma_wgs / mp.q_split)) * mp.waves
+                                          : st::scan_groups() * (st::kScanThreads / 64);
+    if (st::make_plan(n_items, K, mp.q_split, seg_cap, batch * n_tasks, &plan, scan_waves) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
     if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1) != 0)
@@ -704,11 +719,19 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             q->use_tau = lv > 0;
             q->tau_parts = (lv == 1 && plan.level[0].seed) ? seed_parts : 1;
         }
-        // past the first level a visit is one segment per wavefront of the workgroup
-        if (lv > 0 && mp.waves > L_.seg_per_visit) sp_m.seg_per_visit = mp.waves;
+        const int64_t n_seg = (L_.end - L_.begin + L_.seg_items - 1) / L_.seg_items;
+        // workgroups of the MFMA scan that are resident at once, per row of the grid
+        const int32_t resident = std::max(1, st::pow2_ceil(st::kComputeUnits * mfma_wgs / mp.q_split + 1) / 2);
+        // Past the first level a visit is one segment per wavefront of the workgroup; a level with
+        // fewer segments than that gives every resident workgroup takes shorter visits instead, so
+        // that all of them (and with them all of their candidate regions) take part.
+        if (lv > 0 && mp.waves > L_.seg_per_visit) {
+            sp_m.seg_per_visit = mp.waves;
+            if (set_mfma.n && !set_dot.n && n_seg < (int64_t)resident * mp.waves)
+                sp_m.seg_per_visit = (int32_t)std::max<int64_t>(1, (n_seg + resident - 1) / resident);
+        }
         // workgroups with work: one visit (seg_per_visit segments) per step; launching no more
         // keeps idle workgroups from staging queries, and the selection reads only their regions
-        const int64_t n_seg = (L_.end - L_.begin + L_.seg_items - 1) / L_.seg_items;
         const int64_t n_visit = (n_seg + sp_m.seg_per_visit - 1) / sp_m.seg_per_visit;
         int32_t regions = plan.groups;
         if (set_mfma.n) {
@@ -717,10 +740,13 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             mp.region_slots = 1;
             if (!set_dot.n) {
                 // only as many workgroups as are resident at once; each takes several regions
-                const int32_t resident = st::pow2_ceil(st::kComputeUnits * mfma_wgs / mp.q_split + 1) / 2;
-                if (resident >= 1 && resident < gx) gx = resident;
+                if (resident < gx) gx = resident;
                 if (n_visit < gx) gx = (int32_t)std::max<int64_t>(n_visit, 1);
-                const int64_t want = std::min<int64_t>(per_row / gx, (n_visit + gx - 1) / gx);
+                // the first level needs exactly one visit per region; later levels spread each
+                // workgroup's candidates, segment by segment, over the regions the layout leaves it
+                // (as many as the LDS budget of the chosen configuration was sized for)
+                const int64_t want = lv == 0 ? std::min<int64_t>(per_row / gx, (n_visit + gx - 1) / gx)
+                                             : std::min<int64_t>(per_row / gx, st::mfma_region_slots(mfma_wgs));
                 mp.region_slots = (int32_t)std::max<int64_t>(1, std::min<int64_t>(want, st::kMaxRegionSlots));
                 // the first level needs a region per visit (no region can then overflow)
                 if (lv == 0 && (int64_t)gx * mp.region_slots < n_visit) {

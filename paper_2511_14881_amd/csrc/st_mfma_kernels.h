@@ -430,7 +430,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(cur) * seg_items;
         const int g0 = cur.batch * FB;
         const int nf = min(FB, p.n_groups - g0);
-        const int slot = R == 1 ? 0 : stage_visit(cur) % R;  // candidate region of this visit
+        // candidate region: one per visit on the first level (a region then holds the candidates of
+        // at most `cap` items and cannot overflow), afterwards the workgroup's regions take turns
+        // segment by segment, which spreads the load over all of them even in a short level
+        const int slot = R == 1 ? 0 : (p.use_tau ? cur.num : stage_visit(cur)) % R;
         const int region = (int)blockIdx.x + slot * (int)gridDim.x + y * (int)gridDim.x * R;
         uint32_t* cnt_s = s_cnt + slot * nq_pad;
 

@@ -74,8 +74,10 @@ inline int64_t seed_items_for(int64_t n_items, int32_t batch_rows)
     return (batch_rows <= kSeedMaxRows && n_items >= 8 * (int64_t)kSeedItems) ? kSeedItems : 0;
 }
 
+// `waves` = wavefronts that scan one level side by side (per row of workgroups): it sizes the
+// segments of a level.
 inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, int32_t seg_cap, int64_t seed_items,
-                       Plan* out)
+                       int32_t waves, Plan* out)
 {
     Plan p;
     p.groups = scan_groups();
@@ -115,10 +117,29 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
         int64_t nxt = want >= (double)n_items ? n_items : (int64_t)want;
         if (nxt < n_items) nxt = nxt / 1024 * 1024;
         if (nxt <= cur) nxt = cur + 1024 < n_items ? cur + 1024 : n_items;
-        // large segments fill the 16-item MFMA tiles best; shrink them only when the level would
-        // otherwise occupy fewer than about eight wavefronts per compute unit
+        // Segment size: a wavefront's share of the level is ceil(segments / waves) segments, each
+        // costing a fixed part (the memory round trips of a stage, worth about 256 items of
+        // streaming) plus its items; the size with the smallest product wins, larger on ties
+        // (large segments also fill the 16-item MFMA tiles best).
+        // A segment's candidates go to one region, and about K * (grow - 1) candidates per query are
+        // expected in the level: sizes that leave fewer segments than four times that many over
+        // the region capacity are passed over (down to the smallest size).
         int32_t seg = seg_cap;
-        while (seg > 64 && (nxt - next_begin) / seg < 2048) seg >>= 1;
+        {
+            const int64_t span = nxt - next_begin;
+            const double admitted = (double)K * ((double)nxt / (double)(cur > 0 ? cur : 1) - 1.0);
+            const int64_t min_seg_count = (int64_t)(4.0 * admitted / (double)cap) + 1;
+            int64_t best = -1;
+            for (int32_t c = seg_cap; c >= 64; c >>= 1) {
+                const int64_t n_seg = (span + c - 1) / c;
+                if (n_seg < min_seg_count && c > 64) continue;
+                const int64_t cost = ((n_seg + waves - 1) / waves) * (256 + c);
+                if (best < 0 || cost < best) {
+                    best = cost;
+                    seg = c;
+                }
+            }
+        }
         p.level[p.n_levels++] = Level{next_begin, nxt, seg, 4, 0};  // one segment per wavefront of the workgroup
         cur = nxt;
         next_begin = nxt;
@@ -139,7 +160,7 @@ inline int choose_cap(int64_t n_items, int32_t K)
         // the slow exact path appends into a buffer of K + groups*cap keys, a tile at a time
         if ((int64_t)scan_groups() * cap < 2 * (int64_t)K + 2048) continue;
         Plan p;
-        if (make_levels(n_items, K, cap, scan_groups(), kMaxSegItems, 0, &p) != 0) continue;
+        if (make_levels(n_items, K, cap, scan_groups(), kMaxSegItems, 0, 2048, &p) != 0) continue;
         best = cap;
         if (p.n_levels <= 6) break;
     }
@@ -161,14 +182,15 @@ inline int seg_limit(int32_t seg_cap)
     return e > 0 && e < seg_cap ? e : seg_cap;
 }
 
-inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, Plan* out)
+inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, Plan* out,
+                     int32_t waves = 2048)
 {
     const int cap = choose_cap(n_items, K);
     if (cap < 0 || q_split < 1 || scan_groups() % q_split) return -1;
     // the seed pass borrows the candidate regions and the gather buffer of a query as scratch
     const bool seed_fits = K <= kLdsSortMax && (int64_t)scan_groups() * cap >= 2 * (int64_t)kSeedItems;
     const int64_t seed = seed_fits ? seed_items_for(n_items, batch_rows) : 0;
-    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_limit(seg_cap), seed, out);
+    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_limit(seg_cap), seed, waves < 1 ? 1 : waves, out);
 }
 
 // Byte offsets of the pieces of the device workspace.

@@ -33,8 +33,11 @@ def oracle_index(w, m=None, k=None):
                          k or cfg.k_hashes)
 
 
-def check_search(w, K, sigs=None, queries=None, path=0, label=""):
-    """Runs the GPU search on the whole batch and compares the chosen queries with the oracle."""
+def check_search(w, K, sigs=None, queries=None, path=0, label="", fast_path_only=False, slow_path=None):
+    """Runs the GPU search on the whole batch and compares the chosen queries with the oracle.
+    fast_path_only: also require that no query fell back to the slow exact path (a schedule that
+    overflows candidate regions on an ordinary workload is a performance bug, not a wrong result).
+    slow_path: (queries that must have fallen back, queries that must not have)."""
     cfg = w.cfg
     say(f"[parity] {label or cfg.name}: N={cfg.n_items} d={cfg.d} B={cfg.batch} T={cfg.n_tasks} "
         f"m={cfg.m_bits} k={cfg.k_hashes} K={K} path={path}")
@@ -42,15 +45,23 @@ def check_search(w, K, sigs=None, queries=None, path=0, label=""):
     items, iscale, foff, fids, q, qs = dev
     bloom = st.st_bloom_build(foff, fids, cfg.n_items, cfg.m_bits, cfg.k_hashes)
     old = st.st_set_scoring_path(path)
+    buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, max(cfg.n_tasks, 1), K)
     try:
         if cfg.n_tasks > 0:
             ids, scores, count = st.st_search_multitask(bloom, items, iscale, q, qs, w.task_weight,
-                                                        w.filt_ids, w.filt_offsets, K)
+                                                        w.filt_ids, w.filt_offsets, K, buffers=buf)
         else:
-            ids, scores, count = st.st_search(bloom, items, iscale, q, qs, w.filt_ids, w.filt_offsets, K)
+            ids, scores, count = st.st_search(bloom, items, iscale, q, qs, w.filt_ids, w.filt_offsets, K,
+                                              buffers=buf)
         torch.cuda.synchronize()
     finally:
         st.st_set_scoring_path(old)
+    if fast_path_only:
+        slow = np.nonzero(_np(buf.overflow_flags()))[0]
+        assert slow.size == 0, f"queries {slow[:8].tolist()}... took the slow exact path"
+    if slow_path is not None:
+        flags = _np(buf.overflow_flags())
+        assert all(flags[b] == 1 for b in slow_path[0]) and all(flags[b] == 0 for b in slow_path[1]), flags
     ids, scores, count = _np(ids), _np(scores), _np(count)
     if sigs is None:
         sigs = oracle_index(w)
@@ -205,7 +216,7 @@ def test_mid_config_full_size_every_query():
     # the configuration bench.py times, at full size, all 64 queries against the oracle
     cfg = S.CONFIGS["mid"]
     w = S.make_workload(cfg, device="cuda")
-    check_search(w, cfg.top_k)
+    check_search(w, cfg.top_k, fast_path_only=True)
 
 
 @pytest.mark.parametrize("name", ["large", "multi", "mfma"])
@@ -215,7 +226,7 @@ def test_big_configs_full_size_sampled_queries(name):
     cfg = S.CONFIGS[name]
     w = S.make_workload(cfg, device="cuda")
     step = max(cfg.batch // 64, 1)
-    check_search(w, cfg.top_k, queries=range(0, cfg.batch, step))
+    check_search(w, cfg.top_k, queries=range(0, cfg.batch, step), fast_path_only=True)
 
 
 @pytest.mark.parametrize("d,T,all_pass", [(128, 0, False), (128, 0, True), (64, 2, False), (48, 0, False), (256, 4, False)])
@@ -280,7 +291,7 @@ def test_rising_scores_overflow_the_regions_and_take_the_exact_slow_path():
     w.item_scale = (0.5 + torch.arange(n, dtype=torch.float32) / n).contiguous()
     w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
     for path in (1, 2):
-        ids, _, _ = check_search(w, 50, path=path, label="rising scores")
+        ids, _, _ = check_search(w, 50, path=path, label="rising scores", slow_path=([0], [1]))
         assert ids[0, 0] == n - 1 and ids[1, 0] == 0
 
 
