@@ -572,12 +572,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         // the local row, the item's place in the segment and the aggregated score (weighted
         // search) or the int32 dot product (plain search, rescaled here).
         //
-        // The store of a drained candidate is written in assembly and waited for on the spot.
-        // On this target loads and stores share one outstanding-operation counter; a store the
-        // compiler knows of, possibly pending, turns every later wait for a unit's rows into a
-        // wait for all younger loads as well, which would flatten the row pipeline.  This way the
-        // compiler keeps counting loads only (its waits stay exact: everything older has
-        // completed once the store has), and the full wait is paid only when a drain happens.
+        // The store of a drained candidate is written in assembly.  On this target loads and stores
+        // share one outstanding-operation counter; a store the compiler knows of, possibly pending,
+        // turns every later wait for a unit's rows into a wait for all younger loads as well, which
+        // would flatten the row pipeline.  This way the compiler keeps counting loads only.  A store
+        // it does not know of can only make one of its waits last longer, never end early: a wait
+        // for "at most n operations outstanding" is met once enough operations have completed, the
+        // loads complete in the order they were issued, so the load waited for is among them with
+        // or without the store.  (Nothing in the kernel reads the stored keys back.)
         auto drain = [&]() {  // takes the last (up to) 64 queued entries; the order inside a region is free
             const int base = qn > 64 ? qn - 64 : 0;
             if (base + lane < qn) {
@@ -595,7 +597,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                     const uint32_t at = atomicAdd(&cnt_s[srow / TT], 1u);
                     if (at < (uint32_t)p.cap) {
                         uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + region) * p.cap + at;
-                        asm volatile("global_store_dwordx2 %0, %1, off\n\ts_waitcnt vmcnt(0)" : : "v"(dst), "v"(key) : "memory");
+                        asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(dst), "v"(key) : "memory");
                     }
                 }
             }
