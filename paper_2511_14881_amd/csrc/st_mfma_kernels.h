@@ -103,9 +103,12 @@ struct UnitRegs {
 // MULTI = some filter group holds more than one 16-row query block in a row of workgroups.
 // NW = wavefronts per workgroup: 4, or 8 when the resident queries leave room for one workgroup
 // per compute unit only (twice the wavefronts then share one query image).
-template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW>
+// ADMIT = first level with one segment per region (8-wavefront workgroups only): no threshold
+// exists yet, every passing pair is a candidate and goes straight to its region.
+template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW, bool ADMIT = false>
 __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
+    static_assert(!ADMIT || NW == 8, "the first-level variant exists for 8-wavefront workgroups");
     constexpr int kThreads = NW * 64;
     // The variant for small batches (one query block per filter, four wavefronts) is only launched
     // with one region per workgroup and 256-item segments: both are compile-time facts there.
@@ -702,6 +705,47 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         // Contracts one unit with the query blocks of its filter group, two blocks per round (the
         // operands of both are read before either is used).  A group of a single block keeps its
         // A operand and per-row constants in registers from one unit to the next.
+        // First level with one segment per region: there is no threshold and every pair is a
+        // candidate, so the queue and its counters are bypassed.  An item's place in its filter's
+        // list is its place in the region of each of the filter's queries (the 16 lanes of a quarter
+        // wavefront write 16 consecutive keys of one query), and the list length is the fill count.
+        auto unit_admit_all = [&](const UnitRegs<KS>& w, int u) {
+            const int lrow0 = __builtin_amdgcn_readlane(glrow, w.gi);
+            const int nblk = __builtin_amdgcn_readlane(gnblk, w.gi);
+            const int n = __builtin_amdgcn_readlane(gcount, w.gi);
+            const int pos = ((u - (__builtin_amdgcn_readlane(ucum, w.gi) - __builtin_amdgcn_readlane(gunits, w.gi))) << 4) + l16;
+            for (int j = 0; j < nblk; ++j) {
+                const int lrow = lrow0 + 16 * j;
+                v4i a[KS];
+                block_a(lrow, a);
+                const v4i acc = block_mfma(a, w);
+                const float4 sq4 = row_sq(lrow);
+                const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
+                float sc[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si);
+                if (WEIGHTED) {
+#pragma unroll
+                    for (int q0 = 0; q0 < 4; q0 += TT) {
+                        float agg = 0.0f;
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
+                        sc[q0] = agg;
+                    }
+                }
+#pragma unroll
+                for (int r = 0; r < 4; r += TT) {
+                    const int row = lrow + 4 * kg + r;
+                    const int grow = s_qrow[row];
+                    if (w.item >= 0 && grow >= 0) {
+                        const uint64_t key = make_key(sc[r], (uint32_t)(item0 + w.item));
+                        uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + region) * p.cap + pos;
+                        asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(dst), "v"(key) : "memory");  // as in drain()
+                        if (pos == n - 1) cnt_s[row / TT] = (uint32_t)n;
+                    }
+                }
+            }
+        };
         auto unit_compute = [&](const UnitRegs<KS>& w) {
             const int lrow0 = __builtin_amdgcn_readlane(glrow, w.gi);
             const int nblk = __builtin_amdgcn_readlane(gnblk, w.gi);
@@ -817,7 +861,12 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         if (n_units > 0) {
             UnitRegs<KS> r0, r1, r2, r3;  // the ring, as separate variables (an array would be indexed through memory)
             auto step = [&](UnitRegs<KS>& r, int u) {
-                if (u < n_units) unit_compute(r);
+                if (u < n_units) {
+                    if (ADMIT)
+                        unit_admit_all(r, u);
+                    else
+                        unit_compute(r);
+                }
                 unit_load(r);
             };
             auto step2 = [&](UnitRegs<KS>& ra, UnitRegs<KS>& rb, int u) {
@@ -837,7 +886,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             if (NB > 3) unit_load(r3);
             if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
             for (int base = 0; base < n_units; base += NB) {
-                if (PAIRS) {
+                if (PAIRS && !ADMIT) {
                     step2(r0, r1, base);
                     step2(r2, r3, base + 2);
                 } else {
@@ -962,18 +1011,18 @@ inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups,
     return t.lds_total;
 }
 
-template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW>
+template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW, bool ADMIT = false>
 inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
     static int max_set = 0;  // largest dynamic LDS size this instantiation has been allowed
     if (mp.lds_total > max_set) {
-        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW>),
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW, ADMIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, mp.lds_total);
         if (e != hipSuccess) return e;
         max_set = mp.lds_total;
     }
     const dim3 grid((unsigned)gx, (unsigned)mp.q_split);
-    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW>), grid, dim3(NW * 64), (size_t)mp.lds_total, stream, sp, mp);
+    hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW, ADMIT>), grid, dim3(NW * 64), (size_t)mp.lds_total, stream, sp, mp);
     return hipGetLastError();
 }
 
@@ -982,21 +1031,27 @@ inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, i
 {
     if (sp.seg_items > mp.seg_stride || mp.seg_stride > kMfmaSegItems || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
     const int ks = sp.d / 64, tt = sp.n_tasks;
+    // first level, one segment per region: every pair is a candidate and is stored directly
+    const bool admit = !sp.use_tau && sp.seg_per_visit == 1 && sp.seg_items <= sp.cap;
+// plain search has one task per query (several tasks always come with weights)
+#define ST_ARM(K_, T_, W_, M_, N_, A_)                                                                           \
+    ((W_ || T_ == 1) ? launch_scan_mfma_t<K_, (W_ || T_ == 1) ? T_ : 1, W_, M_, N_, A_>(sp, mp, gx, stream)       \
+                     : hipErrorInvalidValue)
 #define ST_CASE(K_, T_)                                                                                          \
     if (ks == K_ && tt == T_) {                                                                                  \
+        if (mp.waves == 8 && admit)                                                                              \
+            return sp.weighted ? ST_ARM(K_, T_, true, true, 8, true) : ST_ARM(K_, T_, false, true, 8, true);     \
         if (mp.waves == 8)                                                                                       \
-            return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true, 8>(sp, mp, gx, stream)                   \
-                               : launch_scan_mfma_t<K_, T_, false, true, 8>(sp, mp, gx, stream);                 \
+            return sp.weighted ? ST_ARM(K_, T_, true, true, 8, false) : ST_ARM(K_, T_, false, true, 8, false);   \
         if (mp.multi_block || mp.region_slots != 1 || mp.seg_stride != 256)                                      \
-            return sp.weighted ? launch_scan_mfma_t<K_, T_, true, true, 4>(sp, mp, gx, stream)                   \
-                               : launch_scan_mfma_t<K_, T_, false, true, 4>(sp, mp, gx, stream);                 \
-        return sp.weighted ? launch_scan_mfma_t<K_, T_, true, false, 4>(sp, mp, gx, stream)                      \
-                           : launch_scan_mfma_t<K_, T_, false, false, 4>(sp, mp, gx, stream);                    \
+            return sp.weighted ? ST_ARM(K_, T_, true, true, 4, false) : ST_ARM(K_, T_, false, true, 4, false);   \
+        return sp.weighted ? ST_ARM(K_, T_, true, false, 4, false) : ST_ARM(K_, T_, false, false, 4, false);     \
     }
     ST_CASE(1, 1) ST_CASE(1, 2) ST_CASE(1, 4)
     ST_CASE(2, 1) ST_CASE(2, 2) ST_CASE(2, 4)
     ST_CASE(4, 1) ST_CASE(4, 2) ST_CASE(4, 4)
     ST_CASE(8, 1) ST_CASE(8, 2) ST_CASE(8, 4)
+#undef ST_ARM
 #undef ST_CASE
     return hipErrorInvalidValue;
 }
