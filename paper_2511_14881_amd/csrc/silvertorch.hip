@@ -675,6 +675,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     se.srt = L.k_pad > st::kLdsSortMax ? (uint64_t*)(ws + L.srt) : nullptr;
     se.K = K;
     se.k_pad = L.k_pad;
+    // more queries than compute units: a smaller key buffer lets two selection workgroups share one
+    se.lds_keys = batch > st::kComputeUnits ? st::kLdsKeysDense : st::kLdsKeys;
     se.tau = (uint64_t*)(ws + L.tau);
     se.ovf = sp.ovf;
     se.out_ids = dev_out_ids;
@@ -776,7 +778,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                                            hipFuncAttributeMaxDynamicSharedMemorySize, st::kSelectLdsBytes));
                 lds_set = true;
             }
-            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), st::kSelectLdsBytes, stream, se);
+            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads),
+                               (size_t)st::select_lds_bytes(se.lds_keys), stream, se);
         }
         ST_HIP(hipGetLastError());
     }

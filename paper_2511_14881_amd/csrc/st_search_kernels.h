@@ -529,6 +529,7 @@ struct SelectParams {
     const int32_t* q_taupos;  // [B] position of each query in tau_img (-1: none)
     const int32_t* q_prow;    // [B][kSeedRows + 1] first signature rows of each query's filter (-1 padded), then their count
     uint32_t* ovf;          // [B]
+    int32_t lds_keys;       // candidates per query the selection gathers in LDS (<= kLdsKeys; sizes its LDS)
     int32_t first, last;
     int64_t* out_ids;       // [B][K]
     float* out_scores;
@@ -591,12 +592,17 @@ __device__ inline void rescue_query(const SelectParams& r, int q, uint64_t* s_so
 // of the query's regions overflowed.
 static_assert(kLdsSortMax * 8 >= kLdsKeys * 2, "the sort buffer doubles as the seed kernel's 16-bit item list");
 constexpr int kSelectLdsBytes = kLdsKeys * 8 + kLdsSortMax * 8 + 3 * 256 * 4 + 64 * 8 + 64 * 4;
+// Key capacity for batches that need more than one workgroup per compute unit: two selection
+// workgroups then fit the 160 KB of LDS side by side.
+constexpr int kLdsKeysDense = 7168;
+inline int select_lds_bytes(int lds_keys) { return kSelectLdsBytes - (kLdsKeys - lds_keys) * 8; }
 
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char sel_lds[];
-    uint64_t* s_keys = reinterpret_cast<uint64_t*>(sel_lds);                       // [kLdsKeys]
-    uint64_t* s_sorted = s_keys + kLdsKeys;                                        // [kLdsSortMax]
+    const int lds_keys = p.lds_keys;
+    uint64_t* s_keys = reinterpret_cast<uint64_t*>(sel_lds);                       // [lds_keys]
+    uint64_t* s_sorted = s_keys + lds_keys;                                        // [kLdsSortMax]
     uint64_t* s_red = s_sorted + kLdsSortMax;                                      // [32]
     uint64_t* s_mask = s_red + 32;                                                 // [16]
     uint32_t* s_hist = reinterpret_cast<uint32_t*>(s_mask + 16);                   // [3][256]
@@ -640,7 +646,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     }
     const uint32_t total = n_prev + all;
     ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 1);
-    const bool in_lds = total <= (uint32_t)kLdsKeys;
+    const bool in_lds = total <= (uint32_t)lds_keys;
     // More candidates than LDS holds, result sorted in LDS: the candidates are narrowed down where
     // they lie (below), not copied.
     const bool narrow = !in_lds && !p.srt;
@@ -750,7 +756,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
             __syncthreads();
             const uint32_t digit = s_misc[0], rest = s_misc[1], gt = s_misc[3], ge = s_misc[5];
             __syncthreads();
-            if (above + ge <= (uint32_t)kLdsKeys || shift == 0) {
+            if (above + ge <= (uint32_t)lds_keys || shift == 0) {
                 bound = prefix | ((uint64_t)digit << shift);
                 keep = above + ge;
                 break;
@@ -766,11 +772,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         for_each_key([&](uint64_t key) {
             if (key >= bound) {
                 const uint32_t slot = atomicAdd(&s_misc[2], 1u);
-                if (slot < (uint32_t)kLdsKeys) s_keys[slot] = key;
+                if (slot < (uint32_t)lds_keys) s_keys[slot] = key;
             }
         });
         __syncthreads();
-        keep = keep < (uint32_t)kLdsKeys ? keep : (uint32_t)kLdsKeys;  // keys are distinct: never cut
+        keep = keep < (uint32_t)lds_keys ? keep : (uint32_t)lds_keys;  // keys are distinct: never cut
         n_out = lds_topk(s_keys, (int)keep, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
                          1, q, 9);
     } else if (in_lds && !p.srt) {
