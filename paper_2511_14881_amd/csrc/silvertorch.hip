@@ -701,6 +701,17 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             up.src = (const int32_t*)stage->dev_view;
             up.dst = (int32_t*)(ws + L.meta);
             up.words = (int32_t)(blob.bytes() / 4);
+            up.img_q = nullptr;
+            if (set_mfma.n) {  // the seed pass stages the scorer's query image as well
+                up.img_q = mp.img_q;
+                up.img_sq = mp.img_sq;
+                up.img_qrow = mp.img_qrow;
+                up.blk_row = (const int32_t*)((const char*)stage->dev_view + at_blk_row);
+                up.n_blocks = mp.n_blocks;
+                up.q_split = mp.q_split;
+                up.rows_local = rows_local;
+                mfma_started = true;
+            }
             st::SelectParams se_seed = se;  // the seed pass reads its tables from the pinned copy
             auto host_tab = [&](size_t at) { return (const int32_t*)((const char*)stage->dev_view + at); };
             se_seed.q_prow = host_tab(at_qprow);

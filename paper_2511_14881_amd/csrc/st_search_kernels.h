@@ -837,6 +837,14 @@ struct SeedUpload {
     const int32_t* src;  // pinned host memory, device-visible
     int32_t* dst;        // table area of the workspace
     int32_t words;
+    // Resident-query image of the MFMA scorer (null: none).  The seed pass also writes it, in the
+    // layout that scorer keeps in LDS, so that the scan that follows stages its queries with one
+    // memory round trip instead of two (row table, then rows).
+    int8_t* img_q;             // [q_split][rows_local][d], 16-byte chunks swizzled as in LDS
+    float* img_sq;             // [q_split][rows_local]
+    int32_t* img_qrow;         // [q_split][rows_local]  global query row or -1 (padding)
+    const int32_t* blk_row;    // [n_blocks * 16] query row of every block row, pinned host memory
+    int32_t n_blocks, q_split, rows_local;
 };
 
 // D16 = d / 16 for d in {64, 128, 256} (item rows staged in registers, two items per thread in
@@ -863,6 +871,43 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         const int share = (up.words + n_wg - 1) / n_wg;
         const int w0 = slot * share;
         for (int i = tid; i < share && w0 + i < up.words; i += NT) up.dst[w0 + i] = up.src[w0 + i];
+    }
+    if (up.img_q && wv == NT / 64 - 1) {  // the last wavefront: the first ones hold the Bloom words of the slice
+        const int l = lane, T = sp.n_tasks, d = sp.d, nch = d >> 4;
+        const int sh = nch >= 16 ? 0 : (nch == 8 ? 1 : 2), smask = (nch < 16 ? nch : 16) - 1;  // the scorer's chunk swizzle
+        const int rows_q = up.rows_local / T;  // queries per row of scan workgroups
+        if (part == 0) {
+            const int pos = p.q_taupos[q];
+            if (pos >= 0) {
+                const int yy = pos / rows_q, lr0 = (pos - yy * rows_q) * T;
+                for (int i = l; i < T * nch; i += 64) {
+                    const int t = i / nch, c = i - t * nch, lr = lr0 + t;
+                    const int64_t grow = (int64_t)q * T + t;
+                    const int64_t ir = (int64_t)yy * up.rows_local + lr;
+                    const int4 v = reinterpret_cast<const int4*>(sp.queries + grow * d)[c];
+                    *reinterpret_cast<int4*>(up.img_q + ir * d + ((c ^ ((lr >> sh) & smask)) << 4)) = v;
+                    if (c == 0) {
+                        up.img_sq[ir] = sp.qscale[grow];
+                        up.img_qrow[ir] = (int)grow;
+                    }
+                }
+            }
+        }
+        // padding rows of the image, dealt out over the workgroups
+        const int n_rows = up.rows_local * up.q_split, n_wg = (int)(gridDim.x * gridDim.y);
+        for (int ir = slot; ir < n_rows; ir += n_wg) {
+            const int yy = ir / up.rows_local, lr = ir - yy * up.rows_local;
+            const int b = (lr >> 4) * up.q_split + yy;
+            const int grow = b < up.n_blocks ? up.blk_row[b * 16 + (lr & 15)] : -1;
+            if (grow < 0) {
+                for (int c = l; c < nch; c += 64)
+                    *reinterpret_cast<int4*>(up.img_q + (int64_t)ir * d + (c << 4)) = make_int4(0, 0, 0, 0);
+                if (l == 0) {
+                    up.img_sq[ir] = 0.0f;
+                    up.img_qrow[ir] = -1;
+                }
+            }
+        }
     }
     const int64_t n_all = seed_items < sp.n_items ? seed_items : sp.n_items;
     const int64_t part_items = seed_items / parts;  // whole tiles
