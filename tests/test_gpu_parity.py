@@ -255,6 +255,18 @@ def test_ragged_sizes_and_filters(n, d, B, K, T, path):
         assert (ids[b, count[b]:] == -1).all() and np.isneginf(scores[b, count[b]:]).all()
 
 
+@pytest.mark.parametrize("K,B", [(5000, 6), (16384, 2)])
+def test_top_k_above_the_lds_sort_size(K, B):
+    # K above 2048: the running top-K is sorted in global memory and several levels feed it
+    n = 300_000
+    w = ragged_workload(31 + K, n, 64, B, 12, 4, 100, 3)
+    w.filt_ids = np.array([3], dtype=np.uint64)           # query 0 filtered, the others take every item
+    w.filt_offsets = np.array([0] + [1] * B, dtype=np.int64)
+    levels, _, _ = st.st_search_plan(n, B, K)
+    assert len(levels) >= 2
+    check_search(w, K, label=f"K={K}")
+
+
 def test_empty_corpus_and_no_passing_items():
     w = ragged_workload(5, 500, 16, 3, 10, 3, 4096, 2)
     w.filt_ids = np.array([10**15, 10**15 + 16, 10**15 + 32], dtype=np.uint64)  # ids no item holds
