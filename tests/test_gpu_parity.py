@@ -267,6 +267,15 @@ def test_top_k_above_the_lds_sort_size(K, B):
     check_search(w, K, label=f"K={K}")
 
 
+@pytest.mark.parametrize("B,T,d", [(48, 0, 64), (24, 2, 128), (300, 0, 64)])
+def test_many_distinct_filters_through_the_mfma_scorer(B, T, d):
+    # more filter groups than one pass of the MFMA scan holds (8), most of them with one or two
+    # queries: several filter batches per segment, single-block groups, padding rows
+    n = 120_000
+    w = ragged_workload(500 + B, n, d, B, 30, 4, 128, 2, T=T)
+    check_search(w, 64, path=2, label=f"many filters B={B} T={T} d={d}")
+
+
 def test_empty_corpus_and_no_passing_items():
     w = ragged_workload(5, 500, 16, 3, 10, 3, 4096, 2)
     w.filt_ids = np.array([10**15, 10**15 + 16, 10**15 + 32], dtype=np.uint64)  # ids no item holds
