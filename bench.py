@@ -72,6 +72,9 @@ def main():
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 wavefront dot, 2 MFMA")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
+    ap.add_argument("--distinct-filters", action="store_true",
+                    help="stress variant of the workload: the filter pool is as large as the batch, so "
+                         "(almost) every query carries its own filter; reported as its own workload name")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy, as the known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -90,6 +93,8 @@ def main():
         sys.exit(2)
     st.lib()  # fail loudly if the HIP library is missing
     cfg = synth.CONFIGS[args.config]
+    if args.distinct_filters:
+        cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
     t0 = time.time()
     w = synth.make_workload(cfg, device="cuda")
     torch.cuda.synchronize()
@@ -155,7 +160,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = json.load(open(tpath)).get(args.config)
+            traffic = None if args.distinct_filters else json.load(open(tpath)).get(args.config)
         except Exception:
             traffic = None
 

@@ -181,6 +181,26 @@ def test_mid_recipe_small(n, path):
     check_search(S.make_workload(cfg), cfg.top_k, path=path)
 
 
+def test_mid_recipe_with_literal_feature_ids():
+    # correctness-only variant of the input recipe: rank r gets id r - 1 (popular ids are then
+    # XOR-neighbours, which the hash family h_j(f) = splitmix64(f ^ j) must not trip over)
+    cfg = S.scaled(S.CONFIGS["mid"], 100_003, scatter_ids=False)
+    check_search(S.make_workload(cfg), cfg.top_k)
+
+
+@pytest.mark.parametrize("name,n", [("mid", 200_000), ("multi", 120_000)])
+def test_all_distinct_filters_stress_batch(name, n):
+    # every query of the batch carries its own filter (pool = batch): no query rows to share, so
+    # the groups go to the wavefront dot-product scorer (or ride along in the MFMA scan)
+    base = S.CONFIGS[name]
+    cfg = S.scaled(base, n, pool=base.batch)
+    w = S.make_workload(cfg)
+    fo = w.filt_offsets
+    assert len({tuple(w.filt_ids[fo[b]:fo[b + 1]]) for b in range(base.batch)}) > base.batch // 2
+    for path in (0, 2):
+        check_search(w, cfg.top_k, path=path, label=f"{name} with {base.batch} distinct filters")
+
+
 @pytest.mark.parametrize("path", PATHS)
 def test_multitask_recipe_small(path):
     cfg = S.scaled(S.CONFIGS["multi"], 60_000, batch=16)
