@@ -740,8 +740,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         // that all of them (and with them all of their candidate regions) take part.
         if (lv > 0 && mp.waves > L_.seg_per_visit) {
             sp_m.seg_per_visit = mp.waves;
-            if (set_mfma.n && !set_dot.n && n_seg < (int64_t)resident * mp.waves)
-                sp_m.seg_per_visit = (int32_t)std::max<int64_t>(1, (n_seg + resident - 1) / resident);
+            // (with the second scorer in the same search every region has its own workgroup)
+            const int64_t wgs = set_dot.n ? plan.groups / mp.q_split : resident;
+            if (set_mfma.n && n_seg < wgs * mp.waves)
+                sp_m.seg_per_visit = (int32_t)std::max<int64_t>(1, (n_seg + wgs - 1) / wgs);
         }
         // workgroups with work: one visit (seg_per_visit segments) per step; launching no more
         // keeps idle workgroups from staging queries, and the selection reads only their regions
