@@ -391,6 +391,40 @@ def test_results_are_deterministic():
         assert np.array_equal(x, y)
 
 
+def test_concurrent_searches_on_two_streams():
+    # two host threads, each with its own stream, workspace and outputs, share one index
+    import threading
+    cfg = S.scaled(S.CONFIGS["mid"], 150_000)
+    w = S.make_workload(cfg, device="cuda")
+    bloom = st.st_bloom_build(w.feat_offsets, w.feat_ids, cfg.n_items, cfg.m_bits, cfg.k_hashes)
+    ref = [t.clone() for t in st.st_search(bloom, w.items, w.item_scale, w.queries, w.query_scale,
+                                           w.filt_ids, w.filt_offsets, cfg.top_k)]
+    torch.cuda.synchronize()
+    errors = []
+
+    def worker(i):
+        try:
+            stream = torch.cuda.Stream()
+            buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, 1, cfg.top_k)
+            for _ in range(30):
+                ids, scores, count = st.st_search(bloom, w.items, w.item_scale, w.queries, w.query_scale,
+                                                  w.filt_ids, w.filt_offsets, cfg.top_k, buffers=buf, stream=stream)
+            stream.synchronize()
+            for a, b in zip((ids, scores, count), ref):
+                if not torch.equal(a, b):
+                    errors.append(f"thread {i}: results differ")
+        except Exception as e:  # noqa: BLE001
+            errors.append(f"thread {i}: {e!r}")
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    bloom.free()
+
+
 # ------------------------------------------------------------------ search: argument errors
 def test_error_paths_return_codes():
     w = ragged_workload(9, 2000, 16, 2, 10, 3, 64, 2)
