@@ -551,7 +551,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     st::Plan plan;
     // wavefronts that scan a level side by side: the resident workgroups of one row of the grid
     const int32_t scan_waves = set_mfma.n ? std::max(1, std::min(plan_groups_per_row(mp.q_split), st::kComputeUnits * mfma_wgs / mp.q_split)) * mp.waves
-                                          : st::scan_groups() * (st::kScanThreads / 64);
+                                          : st::scan_groups();  // (a whole workgroup shares a segment there)
     if (st::make_plan(n_items, K, mp.q_split, seg_cap, batch * n_tasks, &plan, scan_waves) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
@@ -750,6 +750,9 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             if (set_mfma.n && n_seg < wgs * mp.waves)
                 sp_m.seg_per_visit = (int32_t)std::max<int64_t>(1, (n_seg + wgs - 1) / wgs);
         }
+        // the same for the wavefront-dot scorer, whose workgroups take a visit's segments in turn
+        if (lv > 0 && n_seg < (int64_t)plan.groups * L_.seg_per_visit)
+            sp_d.seg_per_visit = (int32_t)std::max<int64_t>(1, (n_seg + plan.groups - 1) / plan.groups);
         // workgroups with work: one visit (seg_per_visit segments) per step; launching no more
         // keeps idle workgroups from staging queries, and the selection reads only their regions
         const int64_t n_visit = (n_seg + sp_m.seg_per_visit - 1) / sp_m.seg_per_visit;

@@ -83,7 +83,14 @@ __device__ inline uint64_t bloom_mask_word(const uint64_t* __restrict__ bloom, i
     const int64_t left = n_items - first;
     uint64_t mask = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
     const uint64_t* base = bloom + ((gw >> 4) * (int64_t)m_bits) * kTileWords + (gw & 15);
-    for (int r = 0; r < n_rows; ++r) mask &= base[(int64_t)rows[r] * kTileWords];
+    // four independent loads at a time, so that their latencies overlap
+    int r = 0;
+    for (; r + 4 <= n_rows; r += 4) {
+        const uint64_t a = base[(int64_t)rows[r] * kTileWords], b = base[(int64_t)rows[r + 1] * kTileWords];
+        const uint64_t c = base[(int64_t)rows[r + 2] * kTileWords], e = base[(int64_t)rows[r + 3] * kTileWords];
+        mask &= (a & b) & (c & e);
+    }
+    for (; r < n_rows; ++r) mask &= base[(int64_t)rows[r] * kTileWords];
     return mask;
 }
 

@@ -80,6 +80,29 @@ __device__ inline float pair_score(const ScanParams& p, int q, const int8_t* ite
     return agg;
 }
 
+// Dot products of the item row this lane holds with NR query rows whose addresses are the same in
+// every lane: the item row is read once, the query chunks come through the scalar cache (the
+// queries are read-only for the whole search, which the constant address space tells the compiler).
+constexpr int kRowBlock = 8;
+template <int NR>
+__device__ inline void dot_block(const int4* item, const int8_t* queries, const int64_t (&qoff)[kRowBlock],
+                                 int chunks, int (&acc)[kRowBlock])
+{
+    typedef int Int4 __attribute__((ext_vector_type(4)));
+    typedef const Int4 __attribute__((address_space(4))) * ConstRow;
+    constexpr int kUnroll = NR > 4 ? 2 : 4;  // chunks in flight: bounded by the scalar registers
+#pragma unroll kUnroll
+    for (int c = 0; c < chunks; ++c) {
+        const int4 v = item[c];
+#pragma unroll
+        for (int r = 0; r < NR; ++r) {
+            const ConstRow qr = (ConstRow)(uintptr_t)(queries + qoff[r]);
+            const Int4 qv = qr[c];
+            acc[r] = dot16(v, make_int4(qv.x, qv.y, qv.z, qv.w), acc[r]);
+        }
+    }
+}
+
 // Admission of a candidate into this workgroup's region for query q.
 __device__ inline void admit(const ScanParams& p, uint32_t* cnt_l, int q, uint64_t key)
 {
@@ -147,7 +170,9 @@ __global__ __launch_bounds__(kScanThreads) void scan_wavedot_kernel(ScanParams p
                 if (lane == 0) s_listcnt[gi] = total;
             }
             __syncthreads();
-            // (3) score the passing items against the queries of the filter's group
+            // (3) score the passing items against the queries of the filter's group: a lane holds
+            // one item row and takes up to eight query rows per pass over it
+            const int qpp = p.n_tasks >= kRowBlock ? 1 : kRowBlock / p.n_tasks;  // queries per pass
             for (int gi = 0; gi < nf; ++gi) {
                 const int n = s_listcnt[gi];
                 const int g = g0 + gi;
@@ -156,14 +181,46 @@ __global__ __launch_bounds__(kScanThreads) void scan_wavedot_kernel(ScanParams p
                     const int li = b0 + lane;
                     const bool active = li < n;
                     const int64_t item = item0 + (active ? (int)s_list[gi][li] : (int)s_list[gi][0]);
-                    const int8_t* row = p.items + item * p.d;
+                    const int4* row = reinterpret_cast<const int4*>(p.items + item * p.d);
                     const float s_i = p.iscale[item];
-                    for (int qi = qb; qi < qe; ++qi) {
-                        const int q = p.grp_q[qi];
-                        const float s = pair_score(p, q, row, s_i);
-                        if (active) {
-                            const uint64_t key = make_key(s, (uint32_t)item);
-                            if (key >= tau_l[q]) admit(p, cnt_l, q, key);
+                    for (int q0 = qb; q0 < qe; q0 += qpp) {
+                        const int nq = min(qpp, qe - q0);
+                        const int nr = nq * p.n_tasks;
+                        // rows past the pass's last one repeat row 0 (their sums are not used)
+                        int64_t qoff[kRowBlock];
+#pragma unroll
+                        for (int r = 0; r < kRowBlock; ++r) {
+                            const int rr = r < nr ? r : 0;
+                            const int j = rr / p.n_tasks, t = rr - j * p.n_tasks;
+                            qoff[r] = ((int64_t)p.grp_q[q0 + j] * p.n_tasks + t) * p.d;
+                        }
+                        int acc[kRowBlock];
+#pragma unroll
+                        for (int r = 0; r < kRowBlock; ++r) acc[r] = 0;
+                        if (nr == 1) dot_block<1>(row, p.queries, qoff, p.d >> 4, acc);
+                        else if (nr == 2) dot_block<2>(row, p.queries, qoff, p.d >> 4, acc);
+                        else if (nr <= 4) dot_block<4>(row, p.queries, qoff, p.d >> 4, acc);
+                        else dot_block<kRowBlock>(row, p.queries, qoff, p.d >> 4, acc);
+                        // rows in order: the tasks of a query are consecutive, and its aggregate
+                        // is complete after the last of them
+                        float agg = 0.0f;
+                        int t = 0, j = 0;
+#pragma unroll
+                        for (int r = 0; r < kRowBlock; ++r) {
+                            if (r < nr) {
+                                const int q = p.grp_q[q0 + j];
+                                const float st = rescale(acc[r], p.qscale[(int64_t)q * p.n_tasks + t], s_i);
+                                agg = p.weighted ? __fmaf_rn(p.w[t], st, agg) : st;
+                                if (++t == p.n_tasks) {
+                                    if (active) {
+                                        const uint64_t key = make_key(agg, (uint32_t)item);
+                                        if (key >= tau_l[q]) admit(p, cnt_l, q, key);
+                                    }
+                                    agg = 0.0f;
+                                    t = 0;
+                                    ++j;
+                                }
+                            }
                         }
                     }
                 }
