@@ -14,6 +14,8 @@
  *   - scoring only the items whose mask bit is 1, then ArgTopK  [Sec. 4.3, Alg. 1 phases 3-4,
  *                                                                 every item in scope = all clusters probed]
  *   - the weighted-sum form of the Value Model over T tasks     [Sec. 5.2]
+ *   - boolean filter expressions (AND / OR / NOT) over per-feature
+ *     Bloom results, as an operation array run on a stack       [Sec. 4 query form, Sec. 4.3]
  *
  * Constants the paper leaves open are fixed by the build's problem statement:
  *   hash  h_j(f) = splitmix64(f XOR j) mod m,  j = 0..k-1
@@ -29,7 +31,9 @@
  * Pins (tests/test_oracle_pins.py): published splitmix64 outputs, brute force
  * on raw id sets, no-false-negative and false-positive-rate closed form,
  * numpy int32 matmul + stable argsort, exact rational arithmetic for the
- * rescale and the fused multiply-add chain.
+ * rescale and the fused multiply-add chain; for the expressions a recursive
+ * evaluation of the expression tree on the per-feature masks, the raw id sets
+ * of a hand-written corpus, and De Morgan's laws.
  */
 #include <math.h>
 #include <stdint.h>
@@ -209,6 +213,136 @@ int sto_search(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
         }
         out_count[b] = (int32_t)keep;
         free(qb); free(cand);
+    }
+    return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Boolean filter expressions.  [Sec. 4: a query is a conjunction of OR-groups of
+ * feature = value terms; Sec. 4.3: per-feature Bloom results and operators are stored in an
+ * operation array that is processed in order with a stack]
+ *
+ * A program is n entries in postfix order.  ops[i] is one of
+ *   STO_LEAF (0)  push "item passes the Bloom test of the single feature id ids[i]"
+ *                 (all k hash bits of that id are set in VB_i; Eq. 4 with a one-element Q)
+ *   STO_AND  (1)  pop two results, push their conjunction
+ *   STO_OR   (2)  pop two results, push their disjunction
+ *   STO_NOT  (3)  pop one result, push its negation
+ * ids[i] is read for leaves only.  A well-formed program never pops an empty stack and leaves
+ * exactly one result; the empty program (n == 0) passes every item.
+ *
+ * A Bloom leaf can be true for an item that lacks the feature (false positive), so a program
+ * without NOT can only pass too many items, while under a NOT the error turns round: an item
+ * that lacks the feature may be rejected.
+ */
+enum { STO_LEAF = 0, STO_AND = 1, STO_OR = 2, STO_NOT = 3 };
+#define STO_MAX_EXPR_DEPTH 64
+
+/* Largest stack depth the program reaches, or -1 if it is ill-formed (unknown operator,
+ * pop from an empty stack, more or less than one result left, deeper than the oracle's stack). */
+int32_t sto_expr_depth(const int32_t* ops, int64_t n)
+{
+    int32_t depth = 0, deepest = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (ops[i] == STO_LEAF) {
+            ++depth;
+        } else if (ops[i] == STO_AND || ops[i] == STO_OR) {
+            if (depth < 2) return -1;
+            --depth;
+        } else if (ops[i] == STO_NOT) {
+            if (depth < 1) return -1;
+        } else {
+            return -1;
+        }
+        if (depth > deepest) deepest = depth;
+    }
+    if (n > 0 && depth != 1) return -1;
+    if (deepest > STO_MAX_EXPR_DEPTH) return -1;
+    return deepest;
+}
+
+/* Value of a (well-formed) program for the item whose signature is vb. */
+static int expr_pass(const int32_t* ops, const uint64_t* ids, int64_t n, const uint64_t* vb, int32_t m, int32_t k)
+{
+    int stack[STO_MAX_EXPR_DEPTH];
+    int top = 0;
+    if (n == 0) return 1;
+    for (int64_t i = 0; i < n; ++i) {
+        if (ops[i] == STO_LEAF) {
+            int all = 1;
+            for (int32_t j = 0; j < k; ++j) {
+                int64_t bit = sto_bit_index(ids[i], j, m);
+                if (!((vb[bit / 64] >> (bit % 64)) & 1)) all = 0;
+            }
+            stack[top++] = all;
+        } else if (ops[i] == STO_NOT) {
+            stack[top - 1] = !stack[top - 1];
+        } else {
+            int rhs = stack[--top];
+            int lhs = stack[--top];
+            stack[top++] = ops[i] == STO_AND ? (lhs && rhs) : (lhs || rhs);
+        }
+    }
+    return stack[0];
+}
+
+/* mask bit i = value of the program for item i; bits at or past n_items are 0 (also under a
+ * NOT).  Returns 0, or -1 for an ill-formed program (mask untouched). */
+int sto_expr_mask(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
+                  const int32_t* ops, const uint64_t* ids, int64_t n_ops, uint64_t* mask)
+{
+    if (sto_expr_depth(ops, n_ops) < 0) return -1;
+    int64_t W = sig_words(m);
+    int64_t n_words = (n_items + 63) / 64;
+    for (int64_t w = 0; w < n_words; ++w) mask[w] = 0;
+    for (int64_t i = 0; i < n_items; ++i)
+        if (expr_pass(ops, ids, n_ops, sigs + i * W, m, k)) mask[i / 64] |= 1ULL << (i % 64);
+    return 0;
+}
+
+/*
+ * Filtered top-K where query b's filter is the program
+ * (expr_ops, expr_ids)[expr_offsets[b] .. expr_offsets[b+1]); everything else as in sto_search.
+ * Returns 0, -1 when memory runs out, -2 for an ill-formed program.
+ */
+int sto_search_expr(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
+                    const int8_t* items, const float* item_scale, int32_t d,
+                    const int8_t* queries, const float* query_scale, int32_t batch,
+                    int32_t n_tasks, const float* task_weight,
+                    const int32_t* expr_ops, const uint64_t* expr_ids, const int64_t* expr_offsets, int32_t K,
+                    int64_t* out_ids, float* out_scores, int32_t* out_count)
+{
+    int64_t W = sig_words(m);
+    int failed = 0;
+    for (int32_t b = 0; b < batch; ++b)
+        if (sto_expr_depth(expr_ops + expr_offsets[b], expr_offsets[b + 1] - expr_offsets[b]) < 0) return -2;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < batch; ++b) {
+        sto_cand* cand = (sto_cand*)malloc((size_t)(n_items > 0 ? n_items : 1) * sizeof(sto_cand));
+        if (!cand) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        const int32_t* ops = expr_ops + expr_offsets[b];
+        const uint64_t* ids = expr_ids + expr_offsets[b];
+        int64_t n_ops = expr_offsets[b + 1] - expr_offsets[b];
+        int64_t n = 0;
+        for (int64_t i = 0; i < n_items; ++i) {
+            if (!expr_pass(ops, ids, n_ops, sigs + i * W, m, k)) continue;
+            cand[n].score = sto_pair_score(queries, query_scale, n_tasks, task_weight, b,
+                                           items + i * (int64_t)d, item_scale[i], d);
+            cand[n].id = i;
+            ++n;
+        }
+        qsort(cand, (size_t)n, sizeof(sto_cand), cand_cmp);
+        int64_t keep = n < K ? n : K;
+        for (int64_t r = 0; r < K; ++r) {
+            out_ids[(int64_t)b * K + r] = r < keep ? cand[r].id : -1;
+            out_scores[(int64_t)b * K + r] = r < keep ? cand[r].score : -INFINITY;
+        }
+        out_count[b] = (int32_t)keep;
+        free(cand);
     }
     return failed ? -1 : 0;
 }

@@ -53,6 +53,13 @@ def lib() -> C.CDLL:
         L.sto_search.restype = C.c_int
         L.sto_search.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, p, C.c_int32, p, p,
                                  C.c_int32, C.c_int32, p, p, p, C.c_int32, p, p, p]
+        L.sto_expr_depth.restype = C.c_int32
+        L.sto_expr_depth.argtypes = [p, C.c_int64]
+        L.sto_expr_mask.restype = C.c_int
+        L.sto_expr_mask.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, p, C.c_int64, p]
+        L.sto_search_expr.restype = C.c_int
+        L.sto_search_expr.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, p, C.c_int32, p, p,
+                                      C.c_int32, C.c_int32, p, p, p, p, C.c_int32, p, p, p]
         L.sto_num_threads.restype = C.c_int32
         L.sto_num_threads.argtypes = []
         _lib = L
@@ -157,6 +164,63 @@ def search(sigs, m, k, items, item_scale, queries, query_scale, filt_ids, filt_o
     rc = lib().sto_search(_ptr(sigs), n, m, k, _ptr(items), _ptr(item_scale), d, _ptr(queries),
                           _ptr(query_scale), B, T, _ptr(w), _ptr(fid), _ptr(foff), K,
                           _ptr(ids), _ptr(scores), _ptr(count))
+    if rc != 0:
+        raise MemoryError("oracle ran out of memory")
+    return ids, scores, count
+
+
+LEAF, AND, OR, NOT = 0, 1, 2, 3  # operation codes of a filter program (postfix order)
+
+
+def expr_depth(ops) -> int:
+    """Deepest stack a program reaches, -1 if it is ill-formed."""
+    ops = _arr(ops, np.int32)
+    return int(lib().sto_expr_depth(_ptr(ops), ops.size))
+
+
+def expr_mask(sigs: np.ndarray, m: int, k: int, ops, ids) -> np.ndarray:
+    """1 bit per item for one filter program (ops, ids in postfix order)."""
+    n = sigs.shape[0]
+    ops = _arr(ops, np.int32)
+    ids = _arr(ids, np.uint64)
+    assert ops.size == ids.size
+    mask = np.zeros((n + 63) // 64, dtype=np.uint64)
+    sigs = _arr(sigs, np.uint64)
+    if lib().sto_expr_mask(_ptr(sigs), n, m, k, _ptr(ops), _ptr(ids), ops.size, _ptr(mask)) != 0:
+        raise ValueError("ill-formed filter program")
+    return mask
+
+
+def search_expr(sigs, m, k, items, item_scale, queries, query_scale, expr_ops, expr_ids, expr_offsets, K,
+                task_weight=None):
+    """Filtered top-K with one filter program per query; otherwise as ``search``."""
+    items = _arr(items, np.int8)
+    item_scale = _arr(item_scale, np.float32)
+    queries = _arr(queries, np.int8)
+    query_scale = _arr(query_scale, np.float32)
+    eops = _arr(expr_ops, np.int32)
+    eids = _arr(expr_ids, np.uint64)
+    eoff = _arr(expr_offsets, np.int64)
+    n, d = items.shape
+    if task_weight is None:
+        assert queries.ndim == 2 and queries.shape[1] == d
+        B, T, w = queries.shape[0], 1, None
+    else:
+        assert queries.ndim == 3 and queries.shape[2] == d
+        B, T = queries.shape[0], queries.shape[1]
+        w = _arr(task_weight, np.float32)
+        assert w.size == T
+    assert query_scale.size == B * T and eoff.size == B + 1 and sigs.shape[0] == n
+    assert eops.size == eids.size == eoff[-1]
+    ids = np.empty((B, K), dtype=np.int64)
+    scores = np.empty((B, K), dtype=np.float32)
+    count = np.empty(B, dtype=np.int32)
+    sigs = _arr(sigs, np.uint64)
+    rc = lib().sto_search_expr(_ptr(sigs), n, m, k, _ptr(items), _ptr(item_scale), d, _ptr(queries),
+                               _ptr(query_scale), B, T, _ptr(w), _ptr(eops), _ptr(eids), _ptr(eoff), K,
+                               _ptr(ids), _ptr(scores), _ptr(count))
+    if rc == -2:
+        raise ValueError("ill-formed filter program")
     if rc != 0:
         raise MemoryError("oracle ran out of memory")
     return ids, scores, count
