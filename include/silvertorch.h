@@ -52,6 +52,14 @@ typedef enum st_status {
 #define ST_MAX_TASKS 8
 #define ST_MAX_TOP_K 16384
 #define ST_MAX_DIM 4096         /* d, a multiple of 16 */
+#define ST_MAX_EXPR_OPS 256     /* entries of one filter program */
+#define ST_MAX_EXPR_DEPTH 16    /* results a filter program may hold on its stack at once */
+
+/* operations of a filter program (st_bloom_mask_expr, st_search_expr) */
+#define ST_OP_LEAF 0            /* push: the item passes the Bloom test of one feature id */
+#define ST_OP_AND 1             /* pop two results, push their conjunction */
+#define ST_OP_OR 2              /* pop two results, push their disjunction */
+#define ST_OP_NOT 3             /* pop one result, push its negation */
 
 /* Thread-local text of the last failure in the calling thread ("" if none). */
 const char* st_last_error(void);
@@ -168,6 +176,47 @@ int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batc
 int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_split,
                        int64_t* out_levels, int32_t max_levels, int64_t* out_caps);
 
+/* ------------------------------------------------------------------ filter expressions
+ * Filters with AND, OR and NOT (Sec. 4: a query is the embedding search AND OR-groups of
+ * feature = value terms; Sec. 4.3: per-feature Bloom results and operators in an operation
+ * array that is run in order on a stack).  A program is a sequence of entries in postfix order
+ * (operands before their operator): host_expr_ops[i] is an ST_OP_* code and host_expr_ids[i]
+ * the feature id of an ST_OP_LEAF entry (ignored for operators).  A leaf is true for an item
+ * when all k hash bits of the id are set in the item's signature (Eq. 4 with one id), so a
+ * conjunction of leaves is exactly the filter st_search takes.  Program p occupies entries
+ * [host_expr_offsets[p], host_expr_offsets[p+1]); an empty program passes every item.
+ * ST_EINVAL for an ill-formed program: unknown code, an operator without operands, more or
+ * fewer than one result left, more than ST_MAX_EXPR_OPS entries, stack deeper than
+ * ST_MAX_EXPR_DEPTH.  Bloom false positives make a leaf pass too many items; under a NOT
+ * the error turns round (too few).
+ *
+ * Parity/debug export (Sec. 4.3: 1 bit per item), like st_bloom_mask:
+ * dev_mask[n_exprs][ceil(n_items/64)], bits at or past n_items are 0.  Allocates a small
+ * table and synchronises hip_stream before returning. */
+int st_bloom_mask_expr(const st_bloom* bloom, const int32_t* host_expr_ops,
+                       const uint64_t* host_expr_ids, const int64_t* host_expr_offsets,
+                       int32_t n_exprs, uint64_t* dev_mask, void* hip_stream);
+
+/* Workspace of st_search_expr: that of st_search / st_search_multitask plus one mask row per
+ * query and the program tables; n_expr_entries = host_expr_offsets[batch] of the call (or an
+ * upper bound, at most batch * ST_MAX_EXPR_OPS).  Pure host arithmetic. */
+int64_t st_search_expr_workspace_bytes(int64_t n_items, int32_t d, int32_t batch,
+                                       int32_t n_tasks, int32_t K, int64_t n_expr_entries);
+
+/* st_search (host_task_weight == NULL, n_tasks == 1) or st_search_multitask (weights given)
+ * where query b's filter is program b.  One kernel evaluates every distinct program of the
+ * batch into a 1-bit-per-item mask in the workspace (Sec. 4.3: the search takes a bit mask
+ * from the Bloom index); the fused scan then tests one mask row per query group instead of
+ * the signature rows.  Arguments, outputs, ordering, asynchrony and errors as for st_search;
+ * the host arrays may be reused when the call returns. */
+int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
+                   int64_t n_items, int32_t d, const int8_t* dev_queries,
+                   const float* dev_query_scale, int32_t batch, int32_t n_tasks,
+                   const float* host_task_weight, const int32_t* host_expr_ops,
+                   const uint64_t* host_expr_ids, const int64_t* host_expr_offsets, int32_t K,
+                   int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
+                   void* dev_workspace, int64_t workspace_bytes, void* hip_stream);
+
 /* Search scheduling knobs, mainly for tests: path = 0 auto, 1 force the wavefront
  * dot-product scorer, 2 force the int8 MFMA scorer where it applies.  Returns the old value. */
 int32_t st_set_scoring_path(int32_t path);
@@ -176,8 +225,8 @@ int32_t st_set_scoring_path(int32_t path);
  * search entry points launch is bracketed by two HIP events recorded on the caller's stream
  * (up to max_launches launches; not thread safe, one measuring thread at a time).
  * st_timing_end waits for the recorded events and returns, per kernel kind (0 = scan,
- * 1 = select, 2 = slow exact path), the summed elapsed milliseconds in host_out_ms[3] and the
- * number of launches in host_out_launches[3]. */
+ * 1 = select, 2 = slow exact path, 3 = filter expressions), the summed elapsed milliseconds in
+ * host_out_ms[4] and the number of launches in host_out_launches[4]. */
 int st_timing_begin(int32_t max_launches);
 int st_timing_end(double* host_out_ms, int64_t* host_out_launches);
 

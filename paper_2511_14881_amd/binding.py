@@ -21,8 +21,11 @@ EXPORTS = [
     "st_bloom_layout_bytes", "st_bloom_n_items", "st_bloom_export_signatures", "st_bloom_mask",
     "st_search_workspace_bytes", "st_search", "st_search_multitask", "st_score_pairs",
     "st_search_plan", "st_set_scoring_path", "st_timing_begin", "st_timing_end",
-    "st_search_overflow_flags_offset",
+    "st_search_overflow_flags_offset", "st_bloom_mask_expr", "st_search_expr_workspace_bytes",
+    "st_search_expr",
 ]
+
+ST_OP_LEAF, ST_OP_AND, ST_OP_OR, ST_OP_NOT = 0, 1, 2, 3  # operations of a filter program
 
 
 class StError(RuntimeError):
@@ -75,6 +78,12 @@ def lib() -> C.CDLL:
         L.st_timing_begin.argtypes = [i32]
         L.st_timing_end.restype = C.c_int
         L.st_timing_end.argtypes = [p, p]
+        L.st_bloom_mask_expr.restype = C.c_int
+        L.st_bloom_mask_expr.argtypes = [p, p, p, p, i32, p, p]
+        L.st_search_expr_workspace_bytes.restype = i64
+        L.st_search_expr_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i64]
+        L.st_search_expr.restype = C.c_int
+        L.st_search_expr.argtypes = [p, p, p, i64, i32, p, p, i32, i32, p, p, p, p, i32, p, p, p, p, i64, p]
         _lib = L
     return _lib
 
@@ -208,18 +217,22 @@ def st_timing_begin(max_launches: int) -> None:
 
 
 def st_timing_end():
-    """{'scan'|'select'|'rescue': (total_ms, launches)}"""
-    ms = np.zeros(3, dtype=np.float64)
-    n = np.zeros(3, dtype=np.int64)
+    """{'scan'|'select'|'rescue'|'expr': (total_ms, launches)}"""
+    ms = np.zeros(4, dtype=np.float64)
+    n = np.zeros(4, dtype=np.int64)
     _check(lib().st_timing_end(_hptr(ms), _hptr(n)))
-    return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(("scan", "select", "rescue"))}
+    return {k: (float(ms[i]), int(n[i])) for i, k in enumerate(("scan", "select", "rescue", "expr"))}
 
 
 class SearchBuffers:
-    """Workspace and outputs for repeated searches of one shape."""
+    """Workspace and outputs for repeated searches of one shape.  n_expr_entries: room for filter
+    programs of that many entries per batch (st_search_expr); None for the plain searches."""
 
-    def __init__(self, n_items: int, d: int, batch: int, n_tasks: int, K: int):
-        self.nbytes = st_search_workspace_bytes(n_items, d, batch, n_tasks, K)
+    def __init__(self, n_items: int, d: int, batch: int, n_tasks: int, K: int, n_expr_entries: int | None = None):
+        if n_expr_entries is None:
+            self.nbytes = st_search_workspace_bytes(n_items, d, batch, n_tasks, K)
+        else:
+            self.nbytes = _check(lib().st_search_expr_workspace_bytes(n_items, d, batch, n_tasks, K, n_expr_entries))
         self._ovf = (st_search_overflow_flags_offset(n_items, d, batch, n_tasks, K), batch)
         self.workspace = torch.empty(self.nbytes, dtype=torch.uint8, device="cuda")
         self.ids = torch.empty((batch, K), dtype=torch.int64, device="cuda")
@@ -272,6 +285,63 @@ def st_search_multitask(bloom: BloomIndex, items, item_scale, queries, query_sca
                                      _dptr(queries), _dptr(query_scale), B, T, _hptr(w), _hptr(ids),
                                      _hptr(off), K, _dptr(buf.ids), _dptr(buf.scores), _dptr(buf.count),
                                      _dptr(buf.workspace), buf.nbytes, _stream(stream)))
+    return buf.ids, buf.scores, buf.count
+
+
+def _programs(expr_ops, expr_ids, expr_offsets, n: int):
+    ops = np.ascontiguousarray(np.asarray(expr_ops, dtype=np.int32))
+    ids = np.asarray(expr_ids)
+    if ids.dtype != np.dtype(np.uint64):
+        ids = ids.astype(np.uint64)
+    ids = np.ascontiguousarray(ids)
+    off = np.ascontiguousarray(np.asarray(expr_offsets, dtype=np.int64))
+    if off.size != n + 1 or ops.size != ids.size or (off.size and ops.size < off[-1]):
+        raise ValueError("filter program arrays do not match their offsets")
+    return ops, ids, off
+
+
+def st_bloom_mask_expr(bloom: BloomIndex, expr_ops, expr_ids, expr_offsets, stream=None) -> torch.Tensor:
+    n_e = len(expr_offsets) - 1
+    ops, ids, off = _programs(expr_ops, expr_ids, expr_offsets, n_e)
+    out = torch.zeros((n_e, (bloom.n_items + 63) // 64), dtype=torch.int64, device="cuda")
+    _check(lib().st_bloom_mask_expr(C.c_void_p(bloom.handle), _hptr(ops), _hptr(ids), _hptr(off), n_e,
+                                    _dptr(out), _stream(stream)))
+    return out
+
+
+def st_search_expr_workspace_bytes(n_items: int, d: int, batch: int, n_tasks: int, K: int,
+                                   n_expr_entries: int) -> int:
+    return _check(lib().st_search_expr_workspace_bytes(n_items, d, batch, n_tasks, K, n_expr_entries))
+
+
+def st_search_expr(bloom: BloomIndex, items, item_scale, queries, query_scale, expr_ops, expr_ids,
+                   expr_offsets, K: int, task_weight=None, buffers: SearchBuffers | None = None, stream=None):
+    """queries [B, d] (task_weight None) or [B, T, d] with T weights; query b's filter is program b."""
+    _need(items, torch.int8, "items")
+    _need(item_scale, torch.float32, "item_scale")
+    _need(queries, torch.int8, "queries")
+    _need(query_scale, torch.float32, "query_scale")
+    n, d = items.shape
+    B = queries.shape[0]
+    if task_weight is None:
+        if queries.dim() != 2 or queries.shape[1] != d:
+            raise ValueError("queries must be [B, d]")
+        T, w = 1, None
+    else:
+        if queries.dim() != 3 or queries.shape[2] != d:
+            raise ValueError("queries must be [B, T, d]")
+        T = queries.shape[1]
+        w = np.ascontiguousarray(np.asarray(task_weight, dtype=np.float32))
+        if w.size != T:
+            raise ValueError("shape mismatch")
+    if query_scale.numel() != B * T or item_scale.numel() != n:
+        raise ValueError("shape mismatch")
+    ops, ids, off = _programs(expr_ops, expr_ids, expr_offsets, B)
+    buf = buffers or SearchBuffers(n, d, B, T, K, n_expr_entries=int(off[-1]))
+    _check(lib().st_search_expr(C.c_void_p(bloom.handle), _dptr(items), _dptr(item_scale), n, d, _dptr(queries),
+                                _dptr(query_scale), B, T, None if w is None else _hptr(w), _hptr(ops),
+                                _hptr(ids), _hptr(off), K, _dptr(buf.ids), _dptr(buf.scores), _dptr(buf.count),
+                                _dptr(buf.workspace), buf.nbytes, _stream(stream)))
     return buf.ids, buf.scores, buf.count
 
 

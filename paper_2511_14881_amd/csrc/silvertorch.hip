@@ -48,7 +48,7 @@ int g_scoring_path = 0;  // 0 auto, 1 wavefront dot product, 2 MFMA where it app
 struct Timing {
     bool on = false;
     std::vector<hipEvent_t> ev;  // pairs: [2i] before, [2i+1] after launch i
-    std::vector<int> kind;       // 0 scan, 1 select, 2 rescue
+    std::vector<int> kind;       // 0 scan, 1 select, 2 rescue, 3 filter expressions
     size_t used = 0;             // launches recorded
     size_t dropped = 0;
 };
@@ -210,6 +210,102 @@ SetAt add_set(Blob& blob, const GroupSet& s)
     return at;
 }
 
+// Filter programs of a batch (Sec. 4.3: operation array run on a stack) as device tables for
+// the expression kernel, and the queries grouped by distinct program.
+struct ExprTables {
+    std::vector<int32_t> prog_off{0}, code, leaf_rows;
+    int32_t n_exprs = 0;
+};
+
+// Stack discipline of one program: every operator finds its operands, one result is left
+// (an empty program is the filter that passes everything), depth and length within the limits.
+int check_program(const int32_t* ops, int64_t n, int32_t index)
+{
+    if (n > ST_MAX_EXPR_OPS) return fail(ST_EINVAL, "filter program %d has %lld entries (limit %d)", index, (long long)n, ST_MAX_EXPR_OPS);
+    int depth = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        switch (ops[i]) {
+        case ST_OP_LEAF:
+            if (++depth > ST_MAX_EXPR_DEPTH) return fail(ST_EINVAL, "filter program %d needs a stack deeper than %d", index, ST_MAX_EXPR_DEPTH);
+            break;
+        case ST_OP_AND:
+        case ST_OP_OR:
+            if (depth < 2) return fail(ST_EINVAL, "filter program %d: operator at entry %lld lacks operands", index, (long long)i);
+            --depth;
+            break;
+        case ST_OP_NOT:
+            if (depth < 1) return fail(ST_EINVAL, "filter program %d: NOT at entry %lld lacks an operand", index, (long long)i);
+            break;
+        default:
+            return fail(ST_EINVAL, "filter program %d: unknown operation %d at entry %lld", index, ops[i], (long long)i);
+        }
+    }
+    if (n > 0 && depth != 1) return fail(ST_EINVAL, "filter program %d leaves %d results", index, depth);
+    return ST_OK;
+}
+
+// groups == nullptr: one expression per program, in order (mask export).  Otherwise equal
+// programs share an expression, and group g tests row g of the evaluated masks.
+int build_programs(const int32_t* ops, const uint64_t* ids, const int64_t* off, int32_t n, int32_t m_bits,
+                   int32_t k_hashes, ExprTables* tab, Groups* groups)
+{
+    if (off[0] != 0) return fail(ST_EINVAL, "host_expr_offsets[0] must be 0");
+    for (int32_t b = 0; b < n; ++b)
+        if (off[b + 1] < off[b]) return fail(ST_EINVAL, "program offsets decrease at %d", b);
+    if (off[n] > 0 && (!ops || !ids)) return fail(ST_EINVAL, "program arrays are null");
+    std::map<std::pair<std::vector<int32_t>, std::vector<uint64_t>>, int32_t> index;
+    std::vector<std::vector<int32_t>> members;
+    if (groups) groups->q2grp.assign(n, 0);
+    for (int32_t b = 0; b < n; ++b) {
+        const int64_t len = off[b + 1] - off[b];
+        const int rc = check_program(ops + off[b], len, b);
+        if (rc != ST_OK) return rc;
+        int32_t e = -1;
+        if (groups) {
+            std::vector<int32_t> o(ops + off[b], ops + off[b + 1]);
+            std::vector<uint64_t> f(ids + off[b], ids + off[b + 1]);
+            for (int64_t i = 0; i < len; ++i)
+                if (o[i] != ST_OP_LEAF) f[i] = 0;  // ids of operators are not part of the program
+            auto key = std::make_pair(std::move(o), std::move(f));
+            auto it = index.find(key);
+            if (it != index.end()) e = it->second;
+            else index.emplace(std::move(key), tab->n_exprs);
+        }
+        if (e < 0) {
+            e = tab->n_exprs++;
+            for (int64_t i = off[b]; i < off[b + 1]; ++i) {
+                tab->code.push_back(ops[i]);
+                for (int j = 0; j < k_hashes; ++j)
+                    tab->leaf_rows.push_back(ops[i] == ST_OP_LEAF ? (int32_t)st::bloom_bit(ids[i], j, (uint32_t)m_bits) : 0);
+            }
+            tab->prog_off.push_back((int32_t)tab->code.size());
+            members.emplace_back();
+        }
+        members[e].push_back(b);
+        if (groups) groups->q2grp[b] = e;
+    }
+    if (groups) {
+        groups->n_groups = tab->n_exprs;
+        groups->row_off.assign(1, 0);
+        groups->q_off.assign(1, 0);
+        groups->rows.clear();
+        groups->q_list.clear();
+        for (int32_t g = 0; g < tab->n_exprs; ++g) {
+            groups->rows.push_back(g);
+            groups->row_off.push_back(g + 1);
+            groups->q_list.insert(groups->q_list.end(), members[g].begin(), members[g].end());
+            groups->q_off.push_back((int32_t)groups->q_list.size());
+        }
+    }
+    return ST_OK;
+}
+
+// Bytes of the device copy of the tables: offsets, then operators, then leaf rows.
+size_t expr_table_bytes(int64_t n_programs, int64_t n_entries, int32_t k_hashes)
+{
+    return (size_t)st::round_up((n_programs + 1 + n_entries * (1 + (int64_t)k_hashes) + 4) * 4, 256);
+}
+
 }  // namespace
 
 struct st_bloom {
@@ -254,7 +350,7 @@ int st_timing_end(double* out_ms, int64_t* out_launches)
 {
     if (!out_ms || !out_launches) return fail(ST_EINVAL, "null argument");
     g_timing.on = false;
-    for (int k = 0; k < 3; ++k) { out_ms[k] = 0.0; out_launches[k] = 0; }
+    for (int k = 0; k < 4; ++k) { out_ms[k] = 0.0; out_launches[k] = 0; }
     for (size_t i = 0; i < g_timing.used; ++i) {
         ST_HIP(hipEventSynchronize(g_timing.ev[2 * i + 1]));
         float ms = 0.f;
@@ -466,10 +562,14 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                        int32_t batch, int32_t n_tasks, const float* host_task_weight,
                        const uint64_t* host_filt_ids, const int64_t* host_filt_offsets, int32_t K,
                        int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
-                       void* dev_workspace, int64_t workspace_bytes, void* hip_stream)
+                       void* dev_workspace, int64_t workspace_bytes, void* hip_stream,
+                       const Groups* expr_groups = nullptr, const uint64_t* expr_rows = nullptr,
+                       int32_t expr_row_count = 0)
 {
+    // expr_groups: the filters were evaluated beforehand into expr_row_count mask rows at
+    // expr_rows, laid out like a Bloom index; each group then tests the one row it names
     if (!bloom) return fail(ST_EINVAL, "bloom is null");
-    if (!dev_queries || !dev_query_scale || !host_filt_offsets || !dev_out_ids || !dev_out_scores ||
+    if (!dev_queries || !dev_query_scale || (!host_filt_offsets && !expr_groups) || !dev_out_ids || !dev_out_scores ||
         !dev_out_count || !dev_workspace)
         return fail(ST_EINVAL, "null argument");
     if (n_items != bloom->n_items)
@@ -482,8 +582,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     if (((uintptr_t)dev_workspace & 255) || ((uintptr_t)dev_items & 15) || ((uintptr_t)dev_queries & 15) ||
         ((uintptr_t)dev_item_scale & 15))
         return fail(ST_EINVAL, "misaligned buffer (workspace 256 B; items, item scales and queries 16 B)");
-    if (host_filt_offsets[0] != 0) return fail(ST_EINVAL, "host_filt_offsets[0] must be 0");
-    if (host_filt_offsets[batch] > 0 && !host_filt_ids) return fail(ST_EINVAL, "host_filt_ids is null");
+    if (!expr_groups) {
+        if (host_filt_offsets[0] != 0) return fail(ST_EINVAL, "host_filt_offsets[0] must be 0");
+        if (host_filt_offsets[batch] > 0 && !host_filt_ids) return fail(ST_EINVAL, "host_filt_ids is null");
+    }
     const bool weighted = host_task_weight != nullptr;
     if (weighted)
         for (int t = 0; t < n_tasks; ++t)
@@ -491,7 +593,11 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     hipStream_t stream = (hipStream_t)hip_stream;
 
     Groups groups;
-    int rc = build_groups(host_filt_ids, host_filt_offsets, batch, bloom->m_bits, bloom->k_hashes, &groups);
+    int rc = ST_OK;
+    if (expr_groups)
+        groups = *expr_groups;
+    else
+        rc = build_groups(host_filt_ids, host_filt_offsets, batch, bloom->m_bits, bloom->k_hashes, &groups);
     if (rc != ST_OK) return rc;
 
     // split the groups between the two scorers: MFMA where scoring is a real dense contraction
@@ -618,8 +724,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
 
     st::ScanParams sp;
     memset(&sp, 0, sizeof(sp));
-    sp.bloom = bloom->dev;
-    sp.m_bits = bloom->m_bits;
+    sp.bloom = expr_groups ? expr_rows : bloom->dev;
+    sp.m_bits = expr_groups ? expr_row_count : bloom->m_bits;
     sp.items = dev_items;
     sp.iscale = dev_item_scale;
     sp.n_items = n_items;
@@ -829,6 +935,112 @@ int st_search_multitask(const st_bloom* bloom, const int8_t* dev_items, const fl
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch,
                        n_tasks, host_task_weight, host_filt_ids, host_filt_offsets, K, dev_out_ids,
                        dev_out_scores, dev_out_count, dev_workspace, workspace_bytes, hip_stream);
+}
+
+int st_bloom_mask_expr(const st_bloom* bloom, const int32_t* host_expr_ops, const uint64_t* host_expr_ids,
+                       const int64_t* host_expr_offsets, int32_t n_exprs, uint64_t* dev_mask, void* hip_stream)
+{
+    if (!bloom || !host_expr_offsets || !dev_mask) return fail(ST_EINVAL, "null argument");
+    if (n_exprs < 0 || n_exprs > 65535) return fail(ST_EINVAL, "n_exprs=%d out of range", n_exprs);
+    ExprTables tab;
+    int rc = build_programs(host_expr_ops, host_expr_ids, host_expr_offsets, n_exprs, bloom->m_bits, bloom->k_hashes,
+                            &tab, nullptr);
+    if (rc != ST_OK) return rc;
+    if (n_exprs == 0 || bloom->n_items == 0) return ST_OK;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    tab.code.push_back(0);       // (never empty, so that data() is a real address)
+    tab.leaf_rows.push_back(0);
+    int32_t* d_tab = nullptr;
+    const size_t n_off = tab.prog_off.size(), n_code = tab.code.size(), n_rows = tab.leaf_rows.size();
+    ST_HIP(hipMalloc((void**)&d_tab, (n_off + n_code + n_rows) * 4));
+    auto body = [&]() -> int {
+        ST_HIP(hipMemcpyAsync(d_tab, tab.prog_off.data(), n_off * 4, hipMemcpyHostToDevice, stream));
+        ST_HIP(hipMemcpyAsync(d_tab + n_off, tab.code.data(), n_code * 4, hipMemcpyHostToDevice, stream));
+        ST_HIP(hipMemcpyAsync(d_tab + n_off + n_code, tab.leaf_rows.data(), n_rows * 4, hipMemcpyHostToDevice, stream));
+        const int64_t n_words = (bloom->n_items + 63) / 64;
+        dim3 grid((unsigned)((n_words + 255) / 256), (unsigned)n_exprs);
+        hipLaunchKernelGGL(st::bloom_expr_kernel, grid, dim3(256), 0, stream, bloom->dev, bloom->m_bits,
+                           bloom->k_hashes, bloom->n_items, n_words, d_tab, d_tab + n_off, d_tab + n_off + n_code, 0,
+                           dev_mask);
+        ST_HIP(hipGetLastError());
+        ST_HIP(hipStreamSynchronize(stream));
+        return ST_OK;
+    };
+    rc = body();
+    (void)hipFree(d_tab);
+    return rc;
+}
+
+int64_t st_search_expr_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K,
+                                       int64_t n_expr_entries)
+{
+    const int64_t base = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
+    if (base < 0) return base;
+    if (n_expr_entries < 0 || n_expr_entries > (int64_t)batch * ST_MAX_EXPR_OPS)
+        return fail(ST_EINVAL, "n_expr_entries=%lld out of range", (long long)n_expr_entries);
+    const int64_t n_tiles = (n_items + st::kTileItems - 1) / st::kTileItems;
+    // the search's own workspace, one mask row per query (every program distinct), the tables
+    return st::round_up(base, 256) + n_tiles * batch * st::kTileWords * 8 +
+           (int64_t)expr_table_bytes(batch, n_expr_entries, ST_MAX_K_HASHES);
+}
+
+int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale, int64_t n_items,
+                   int32_t d, const int8_t* dev_queries, const float* dev_query_scale, int32_t batch,
+                   int32_t n_tasks, const float* host_task_weight, const int32_t* host_expr_ops,
+                   const uint64_t* host_expr_ids, const int64_t* host_expr_offsets, int32_t K,
+                   int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count, void* dev_workspace,
+                   int64_t workspace_bytes, void* hip_stream)
+{
+    if (!bloom || !host_expr_offsets || !dev_workspace) return fail(ST_EINVAL, "null argument");
+    if (!host_task_weight && n_tasks != 1) return fail(ST_EINVAL, "n_tasks=%d needs host_task_weight", n_tasks);
+    const int64_t base = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
+    if (base < 0) return (int)base;
+    if (n_items != bloom->n_items)
+        return fail(ST_EINVAL, "n_items=%lld but the index holds %lld", (long long)n_items, (long long)bloom->n_items);
+    if ((uintptr_t)dev_workspace & 255) return fail(ST_EINVAL, "misaligned workspace (256 B)");
+    ExprTables tab;
+    Groups groups;
+    int rc = build_programs(host_expr_ops, host_expr_ids, host_expr_offsets, batch, bloom->m_bits, bloom->k_hashes,
+                            &tab, &groups);
+    if (rc != ST_OK) return rc;
+    const int64_t need = st_search_expr_workspace_bytes(n_items, d, batch, n_tasks, K, host_expr_offsets[batch]);
+    if (need < 0) return (int)need;
+    if (workspace_bytes < need)
+        return fail(ST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t n_tiles = (n_items + st::kTileItems - 1) / st::kTileItems;
+    char* ws = (char*)dev_workspace;
+    uint64_t* mask_rows = (uint64_t*)(ws + st::round_up(base, 256));
+    int32_t* d_tab = (int32_t*)((char*)mask_rows + n_tiles * batch * st::kTileWords * 8);
+
+    if (n_tiles > 0) {
+        // tables through a pinned slot (asynchronous copy), then one launch evaluates every
+        // distinct program into its row of the mask index
+        const size_t n_off = tab.prog_off.size(), n_code = tab.code.size(), n_rows = tab.leaf_rows.size();
+        const size_t bytes = (n_off + n_code + n_rows) * 4;
+        if (bytes > expr_table_bytes(batch, host_expr_offsets[batch], ST_MAX_K_HASHES))
+            return fail(ST_EINVAL, "program tables exceed their workspace slot");
+        Stage* stage = nullptr;
+        rc = stage_acquire(bytes, &stage);
+        if (rc != ST_OK) return rc;
+        int32_t* h = (int32_t*)stage->host;
+        memcpy(h, tab.prog_off.data(), n_off * 4);
+        if (n_code) memcpy(h + n_off, tab.code.data(), n_code * 4);
+        if (n_rows) memcpy(h + n_off + n_code, tab.leaf_rows.data(), n_rows * 4);
+        ST_HIP(hipMemcpyAsync(d_tab, stage->host, bytes, hipMemcpyHostToDevice, stream));
+        ST_HIP(hipEventRecord(stage->ev, stream));
+        stage->in_flight = true;
+        const int64_t n_words = n_tiles * st::kTileWords;  // whole tiles: the pad words become 0
+        dim3 grid((unsigned)((n_words + 255) / 256), (unsigned)tab.n_exprs);
+        TimedLaunch t(3, stream);
+        hipLaunchKernelGGL(st::bloom_expr_kernel, grid, dim3(256), 0, stream, bloom->dev, bloom->m_bits,
+                           bloom->k_hashes, n_items, n_words, d_tab, d_tab + n_off, d_tab + n_off + n_code,
+                           tab.n_exprs, mask_rows);
+        ST_HIP(hipGetLastError());
+    }
+    return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, n_tasks,
+                       host_task_weight, nullptr, nullptr, K, dev_out_ids, dev_out_scores, dev_out_count,
+                       dev_workspace, base, hip_stream, &groups, mask_rows, tab.n_exprs);
 }
 
 int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t d, const int8_t* dev_queries,

@@ -110,4 +110,60 @@ __global__ __launch_bounds__(256) void bloom_mask_kernel(const uint64_t* __restr
     out[(int64_t)f * n_words + gw] = bloom_mask_word(bloom, m_bits, gw, n_items, rows + r0, r1 - r0);
 }
 
+// Boolean filter expressions over per-feature Bloom results (Sec. 4: a query is a conjunction of
+// OR-groups of feature = value terms, possibly negated; Sec. 4.3: the per-feature results and the
+// operators sit in an operation array that is run in order on a stack).  One thread per 64-item
+// word and expression: a leaf pushes the AND of the k signature rows of its feature, NOT / AND /
+// OR work on the top of the stack, which lives in LDS (one column per thread, so the dynamic
+// depth costs no register indexing).  The host has checked every program: depth <= kExprDepth,
+// no pop from an empty stack, one result left.
+//   code[i]       operator of entry i (0 leaf, 1 and, 2 or, 3 not)
+//   leaf_rows     k_hashes rows per entry (read for leaves only), entry-major
+//   prog_off      [n_exprs + 1] entries of each expression; an empty one passes every item
+//   out_tile_rows > 0: the result becomes row e of a bit-sliced index of that many rows in the
+//                 layout above (the scan kernels read it like a Bloom index whose "signature bit"
+//                 e is the whole expression); 0: plain [n_exprs][n_words] masks (Sec. 4.3: 1 bit
+//                 per item)
+constexpr int kExprDepth = 16;
+__global__ __launch_bounds__(256) void bloom_expr_kernel(const uint64_t* __restrict__ bloom, int32_t m_bits,
+                                                         int32_t k_hashes, int64_t n_items, int64_t n_words,
+                                                         const int32_t* __restrict__ prog_off,
+                                                         const int32_t* __restrict__ code,
+                                                         const int32_t* __restrict__ leaf_rows,
+                                                         int32_t out_tile_rows, uint64_t* __restrict__ out)
+{
+    __shared__ uint64_t s_stack[kExprDepth][256];
+    const int tid = threadIdx.x;
+    const int64_t gw = (int64_t)blockIdx.x * 256 + tid;
+    const int e = blockIdx.y;
+    if (gw >= n_words) return;  // (no barrier below: a thread's stack column is its own)
+    const int64_t first = gw * 64;
+    const int64_t left = n_items - first;
+    const uint64_t valid = left >= 64 ? ~0ULL : (left > 0 ? ((1ULL << left) - 1ULL) : 0ULL);
+    const uint64_t* base = bloom + ((gw >> 4) * (int64_t)m_bits) * kTileWords + (gw & 15);
+    const int i0 = prog_off[e], i1 = prog_off[e + 1];
+    int top = 0;
+    for (int i = i0; i < i1; ++i) {
+        const int op = code[i];
+        if (op == 0) {
+            uint64_t w = ~0ULL;
+            const int32_t* rows = leaf_rows + (int64_t)i * k_hashes;
+            for (int j = 0; j < k_hashes; ++j) w &= base[(int64_t)rows[j] * kTileWords];
+            s_stack[top++][tid] = w;
+        } else if (op == 3) {
+            s_stack[top - 1][tid] = ~s_stack[top - 1][tid];
+        } else {
+            const uint64_t rhs = s_stack[--top][tid];
+            const uint64_t lhs = s_stack[top - 1][tid];
+            s_stack[top - 1][tid] = op == 1 ? (lhs & rhs) : (lhs | rhs);
+        }
+    }
+    // bits past the last item stay 0, also under a NOT
+    const uint64_t res = (i1 > i0 ? s_stack[0][tid] : ~0ULL) & valid;
+    if (out_tile_rows > 0)
+        out[((gw >> 4) * (int64_t)out_tile_rows + e) * kTileWords + (gw & 15)] = res;
+    else
+        out[(int64_t)e * n_words + gw] = res;
+}
+
 }  // namespace st

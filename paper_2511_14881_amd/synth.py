@@ -279,3 +279,37 @@ def make_workload(cfg: Config, device="cpu") -> Workload:
     pool = choose_filter_pool(cfg, sample)
     fid, foff = gen_filters(cfg, pool)
     return Workload(cfg, items, item_scale, off, ids, q, qs, w, fid, foff, pool)
+
+
+# operation codes of a filter program (postfix order), as the library's header defines them
+OP_LEAF, OP_AND, OP_OR, OP_NOT = 0, 1, 2, 3
+
+
+def gen_filter_programs(cfg: Config, pool: int = 8, with_not: bool = True):
+    """Per-query filters of the paper's query form (Sec. 4): a broad term AND an OR-group of two
+    narrower terms, every second program of the pool also AND NOT a further term.  Terms come
+    from the 32 most frequent ids.  Returns (ops int32 [sum], ids uint64 [sum], offsets int64
+    [B+1], programs) with programs[p] = (ops, ids) of pool entry p; query b uses entry
+    u64(filters, 2^21 + b) mod pool."""
+    head = [int(rank_to_id(r, cfg.vocab, cfg.scatter_ids)) for r in range(32)] if cfg.zipf_s > 0 else \
+           [int(x) % cfg.vocab for x in range(32)]
+    z = _lsr(rand_u64(cfg.seed, S_FILTERS, _arange(3 << 20, (3 << 20) + 4 * pool, "cpu")), 11).reshape(pool, 4).tolist()
+    programs = []
+    for p in range(pool):
+        a = head[z[p][0] % 4]
+        b = head[2 + z[p][1] % 14]
+        c = head[2 + (z[p][1] % 14 + 1 + z[p][2] % 13) % 14]  # differs from b
+        ops = [OP_LEAF, OP_LEAF, OP_LEAF, OP_OR, OP_AND]
+        ids = [a, b, c, 0, 0]
+        if with_not and p % 2 == 1:
+            ops += [OP_LEAF, OP_NOT, OP_AND]
+            ids += [head[z[p][3] % 8], 0, 0]
+        programs.append((ops, ids))
+    pick = (_lsr(rand_u64(cfg.seed, S_FILTERS, _arange(2 << 20, (2 << 20) + cfg.batch, "cpu")), 11) % pool).tolist()
+    all_ops, all_ids, off = [], [], [0]
+    for b in range(cfg.batch):
+        all_ops.extend(programs[pick[b]][0])
+        all_ids.extend(programs[pick[b]][1])
+        off.append(len(all_ops))
+    return (np.asarray(all_ops, dtype=np.int32), np.asarray(all_ids, dtype=np.uint64),
+            np.asarray(off, dtype=np.int64), programs)

@@ -89,6 +89,19 @@ def test_workspace_size_and_argument_checks():
         assert st.last_error()
 
 
+def test_expression_workspace_adds_mask_rows_and_tables():
+    base = st.st_search_workspace_bytes(1_000_000, 128, 64, 1, 100)
+    a = st.st_search_expr_workspace_bytes(1_000_000, 128, 64, 1, 100, 0)
+    # one 128-byte line per query and 1024-item tile, plus the (here nearly empty) tables
+    assert a >= base + 977 * 64 * 128 and a - base - 977 * 64 * 128 < 4096
+    b = st.st_search_expr_workspace_bytes(1_000_000, 128, 64, 1, 100, 64 * 8)
+    assert b > a and b - a <= 64 * 8 * 17 * 4 + 256
+    for bad in [(-1, 128, 64, 1, 100, 0), (1000, 128, 64, 1, 100, -1), (1000, 128, 64, 1, 100, 64 * 256 + 1)]:
+        with pytest.raises(st.StError) as e:
+            st.st_search_expr_workspace_bytes(*bad)
+        assert e.value.code == st.ST_EINVAL
+
+
 def test_null_arguments_are_rejected_without_touching_a_gpu():
     lib = st.lib()
     assert lib.st_bloom_free(None) == 0
@@ -96,5 +109,8 @@ def test_null_arguments_are_rejected_without_touching_a_gpu():
     assert lib.st_bloom_build(None, None, 0, 64, 2, None, None) == st.ST_EINVAL
     assert lib.st_search(None, None, None, 0, 16, None, None, 1, None, None, 1, None, None, None, None, 0,
                          None) == st.ST_EINVAL
+    assert lib.st_bloom_mask_expr(None, None, None, None, 0, None, None) == st.ST_EINVAL
+    assert lib.st_search_expr(None, None, None, 0, 16, None, None, 1, 1, None, None, None, None, 1, None, None,
+                              None, None, 0, None) == st.ST_EINVAL
     assert lib.st_score_pairs(None, None, 16, None, None, None, None, 0, None, None, None) == st.ST_EINVAL
     assert lib.st_set_scoring_path(0) in (0, 1, 2)
