@@ -63,6 +63,37 @@ def union_and_rows(st, bloom, w):
             "passing_pairs": passing_pairs, "per_filter_sel": [p / max(w.cfg.n_items, 1) for p in per_filter]}
 
 
+def union_and_rows_programs(st, bloom, w, prog):
+    """The same ingredients for a batch whose filters are programs (ops, ids, offsets): signature
+    rows read by the leaves of each distinct program, plus one mask row written and read per
+    distinct program (counted as 2 rows each)."""
+    import torch
+    ops, ids, off = prog
+    seen, progs, q2p = {}, [], []
+    for b in range(w.cfg.batch):
+        key = (tuple(ops[off[b]:off[b + 1]].tolist()), tuple(ids[off[b]:off[b + 1]].tolist()))
+        if key not in seen:
+            seen[key] = len(progs)
+            progs.append(key)
+        q2p.append(seen[key])
+    p_ops = np.array([o for p in progs for o in p[0]], dtype=np.int32)
+    p_ids = np.array([i for p in progs for i in p[1]], dtype=np.uint64)
+    p_off = np.concatenate([[0], np.cumsum([len(p[0]) for p in progs])]).astype(np.int64)
+    masks = st.st_bloom_mask_expr(bloom, p_ops, p_ids, p_off)
+    torch.cuda.synchronize()
+
+    def popcount(t):
+        return int(torch.from_numpy(np.unpackbits(t.cpu().numpy().view(np.uint8))).sum())
+
+    union = masks[0].clone()
+    for j in range(1, masks.shape[0]):
+        union |= masks[j]
+    per = [popcount(masks[j]) for j in range(masks.shape[0])]
+    rows = sum(w.cfg.k_hashes * sum(1 for o in p[0] if o == 0) + 2 for p in progs)
+    return {"distinct_filters": len(progs), "rows_touched": rows, "union_items": popcount(union),
+            "passing_pairs": sum(per[j] for j in q2p), "per_filter_sel": [p / max(w.cfg.n_items, 1) for p in per]}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -75,6 +106,10 @@ def main():
     ap.add_argument("--distinct-filters", action="store_true",
                     help="stress variant of the workload: the filter pool is as large as the batch, so "
                          "(almost) every query carries its own filter; reported as its own workload name")
+    ap.add_argument("--filter-programs", action="store_true",
+                    help="variant of the workload: every query's filter is a boolean program of the "
+                         "paper's query form (a term AND an OR-group, every second one AND NOT a term), run "
+                         "through st_search_expr; reported as its own workload name")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy, as the known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -95,6 +130,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if args.distinct_filters:
         cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
+    if args.filter_programs:
+        cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+filter-programs")
     t0 = time.time()
     w = synth.make_workload(cfg, device="cuda")
     torch.cuda.synchronize()
@@ -105,11 +142,18 @@ def main():
     bloom = st.st_bloom_build(w.feat_offsets, w.feat_ids, cfg.n_items, cfg.m_bits, cfg.k_hashes)
     torch.cuda.synchronize()
     build_s = time.time() - t0
-    buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, T, cfg.top_k)
+    prog = None
+    if args.filter_programs:
+        prog = synth.gen_filter_programs(cfg)[:3]
+    buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, T, cfg.top_k,
+                           n_expr_entries=None if prog is None else int(prog[2][-1]))
     st.st_set_scoring_path(args.path)
 
     def step():
-        if cfg.n_tasks > 0:
+        if prog is not None:
+            st.st_search_expr(bloom, w.items, w.item_scale, w.queries, w.query_scale, prog[0], prog[1], prog[2],
+                              cfg.top_k, task_weight=w.task_weight, buffers=buf)
+        elif cfg.n_tasks > 0:
             st.st_search_multitask(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.task_weight,
                                    w.filt_ids, w.filt_offsets, cfg.top_k, buffers=buf)
         else:
@@ -146,7 +190,7 @@ def main():
     scan_ms_per_step = scan_ms / args.steps
     n_levels = timing["select"][1] // args.steps  # one selection (or seed) launch per level
 
-    stats = union_and_rows(st, bloom, w)
+    stats = union_and_rows(st, bloom, w) if prog is None else union_and_rows_programs(st, bloom, w, prog)
     n_words = (cfg.n_items + 63) // 64
     a_bytes = (stats["rows_touched"] * n_words * 8 + stats["union_items"] * (cfg.d + 4)
                + cfg.batch * T * cfg.d + cfg.batch * cfg.top_k * 12)
@@ -160,7 +204,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = None if args.distinct_filters else json.load(open(tpath)).get(args.config)
+            traffic = None if (args.distinct_filters or args.filter_programs) else json.load(open(tpath)).get(args.config)
         except Exception:
             traffic = None
 
@@ -177,6 +221,7 @@ def main():
         "algorithmic_ops_per_step": a_ops,
         "select_ms_per_step": timing["select"][0] / args.steps,
         "rescue_ms_per_step": timing["rescue"][0] / args.steps,
+        "filter_expr_ms_per_step": timing["expr"][0] / args.steps,
     })
 
     cpu = None
@@ -197,8 +242,13 @@ def main():
         reps, spent = 0, 0.0
         while spent < args.cpu_seconds and reps < 1000:
             t0 = time.perf_counter()
-            O.search(sigs, cfg.m_bits, cfg.k_hashes, items, isc, q, qs, fi, fo, cfg.top_k,
-                     task_weight=w.task_weight)
+            if prog is not None:
+                po = prog[2][: b_s + 1]
+                O.search_expr(sigs, cfg.m_bits, cfg.k_hashes, items, isc, q, qs, prog[0][: int(po[-1])],
+                              prog[1][: int(po[-1])], po, cfg.top_k, task_weight=w.task_weight)
+            else:
+                O.search(sigs, cfg.m_bits, cfg.k_hashes, items, isc, q, qs, fi, fo, cfg.top_k,
+                         task_weight=w.task_weight)
             spent += time.perf_counter() - t0
             reps += 1
         per_batch = spent / reps

@@ -217,6 +217,9 @@ struct ExprTables {
     int32_t n_exprs = 0;
 };
 
+static_assert(ST_MAX_EXPR_OPS <= st::kExprOps && ST_MAX_EXPR_DEPTH <= st::kExprDepth &&
+              ST_MAX_K_HASHES <= st::kExprHashes, "the expression kernel's LDS tables follow the limits");
+
 // Stack discipline of one program: every operator finds its operands, one result is left
 // (an empty program is the filter that passes everything), depth and length within the limits.
 int check_program(const int32_t* ops, int64_t n, int32_t index)
@@ -1027,16 +1030,24 @@ int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* 
         memcpy(h, tab.prog_off.data(), n_off * 4);
         if (n_code) memcpy(h + n_off, tab.code.data(), n_code * 4);
         if (n_rows) memcpy(h + n_off + n_code, tab.leaf_rows.data(), n_rows * 4);
-        ST_HIP(hipMemcpyAsync(d_tab, stage->host, bytes, hipMemcpyHostToDevice, stream));
-        ST_HIP(hipEventRecord(stage->ev, stream));
-        stage->in_flight = true;
+        // small tables are read by the kernel straight from the pinned slot (each workgroup fetches
+        // its program once); larger ones are copied to the workspace first
+        const int32_t* t_dev = (const int32_t*)stage->dev_view;
+        if (bytes > 64 * 1024) {
+            ST_HIP(hipMemcpyAsync(d_tab, stage->host, bytes, hipMemcpyHostToDevice, stream));
+            t_dev = d_tab;
+        }
         const int64_t n_words = n_tiles * st::kTileWords;  // whole tiles: the pad words become 0
         dim3 grid((unsigned)((n_words + 255) / 256), (unsigned)tab.n_exprs);
-        TimedLaunch t(3, stream);
-        hipLaunchKernelGGL(st::bloom_expr_kernel, grid, dim3(256), 0, stream, bloom->dev, bloom->m_bits,
-                           bloom->k_hashes, n_items, n_words, d_tab, d_tab + n_off, d_tab + n_off + n_code,
-                           tab.n_exprs, mask_rows);
+        {
+            TimedLaunch t(3, stream);
+            hipLaunchKernelGGL(st::bloom_expr_kernel, grid, dim3(256), 0, stream, bloom->dev, bloom->m_bits,
+                               bloom->k_hashes, n_items, n_words, t_dev, t_dev + n_off, t_dev + n_off + n_code,
+                               tab.n_exprs, mask_rows);
+        }
         ST_HIP(hipGetLastError());
+        ST_HIP(hipEventRecord(stage->ev, stream));
+        stage->in_flight = true;
     }
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, n_tasks,
                        host_task_weight, nullptr, nullptr, K, dev_out_ids, dev_out_scores, dev_out_count,

@@ -125,6 +125,8 @@ __global__ __launch_bounds__(256) void bloom_mask_kernel(const uint64_t* __restr
 //                 e is the whole expression); 0: plain [n_exprs][n_words] masks (Sec. 4.3: 1 bit
 //                 per item)
 constexpr int kExprDepth = 16;
+constexpr int kExprOps = 256;    // entries of one program, at most
+constexpr int kExprHashes = 16;  // rows of a leaf, at most
 __global__ __launch_bounds__(256) void bloom_expr_kernel(const uint64_t* __restrict__ bloom, int32_t m_bits,
                                                          int32_t k_hashes, int64_t n_items, int64_t n_words,
                                                          const int32_t* __restrict__ prog_off,
@@ -133,21 +135,28 @@ __global__ __launch_bounds__(256) void bloom_expr_kernel(const uint64_t* __restr
                                                          int32_t out_tile_rows, uint64_t* __restrict__ out)
 {
     __shared__ uint64_t s_stack[kExprDepth][256];
+    __shared__ int32_t s_code[kExprOps];
+    __shared__ int32_t s_rows[kExprOps * kExprHashes];
     const int tid = threadIdx.x;
     const int64_t gw = (int64_t)blockIdx.x * 256 + tid;
     const int e = blockIdx.y;
+    // the workgroup's program, fetched once (the tables may sit in pinned host memory: one round
+    // trip for the whole workgroup instead of one per entry)
+    const int i0 = prog_off[e], n_ops = prog_off[e + 1] - i0;
+    for (int i = tid; i < n_ops; i += 256) s_code[i] = code[i0 + i];
+    for (int i = tid; i < n_ops * k_hashes; i += 256) s_rows[i] = leaf_rows[(int64_t)i0 * k_hashes + i];
+    __syncthreads();
     if (gw >= n_words) return;  // (no barrier below: a thread's stack column is its own)
     const int64_t first = gw * 64;
     const int64_t left = n_items - first;
     const uint64_t valid = left >= 64 ? ~0ULL : (left > 0 ? ((1ULL << left) - 1ULL) : 0ULL);
     const uint64_t* base = bloom + ((gw >> 4) * (int64_t)m_bits) * kTileWords + (gw & 15);
-    const int i0 = prog_off[e], i1 = prog_off[e + 1];
     int top = 0;
-    for (int i = i0; i < i1; ++i) {
-        const int op = code[i];
+    for (int i = 0; i < n_ops; ++i) {
+        const int op = s_code[i];
         if (op == 0) {
             uint64_t w = ~0ULL;
-            const int32_t* rows = leaf_rows + (int64_t)i * k_hashes;
+            const int32_t* rows = s_rows + i * k_hashes;
             for (int j = 0; j < k_hashes; ++j) w &= base[(int64_t)rows[j] * kTileWords];
             s_stack[top++][tid] = w;
         } else if (op == 3) {
@@ -159,7 +168,7 @@ __global__ __launch_bounds__(256) void bloom_expr_kernel(const uint64_t* __restr
         }
     }
     // bits past the last item stay 0, also under a NOT
-    const uint64_t res = (i1 > i0 ? s_stack[0][tid] : ~0ULL) & valid;
+    const uint64_t res = (n_ops > 0 ? s_stack[0][tid] : ~0ULL) & valid;
     if (out_tile_rows > 0)
         out[((gw >> 4) * (int64_t)out_tile_rows + e) * kTileWords + (gw & 15)] = res;
     else
