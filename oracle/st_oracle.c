@@ -14,6 +14,8 @@
  *   - scoring only the items whose mask bit is 1, then ArgTopK  [Sec. 4.3, Alg. 1 phases 3-4,
  *                                                                 every item in scope = all clusters probed]
  *   - the weighted-sum form of the Value Model over T tasks     [Sec. 5.2]
+ *   - cluster probing in front of the filter and the scoring (IVF): centroid
+ *     scores, the n_p best clusters, filter and scoring inside them [Sec. 4.2, Alg. 1 phases 1-4]
  *   - boolean filter expressions (AND / OR / NOT) over per-feature
  *     Bloom results, as an operation array run on a stack       [Sec. 4 query form, Sec. 4.3]
  *
@@ -33,7 +35,10 @@
  * numpy int32 matmul + stable argsort, exact rational arithmetic for the
  * rescale and the fused multiply-add chain; for the expressions a recursive
  * evaluation of the expression tree on the per-feature masks, the raw id sets
- * of a hand-written corpus, and De Morgan's laws.
+ * of a hand-written corpus, and De Morgan's laws; for the probing a numpy
+ * argsort of the centroid scores with the probed ranges masked by hand, the
+ * all-clusters-probed case against the plain search, and the paper's
+ * probed-fraction arithmetic.
  */
 #include <math.h>
 #include <stdint.h>
@@ -343,6 +348,94 @@ int sto_search_expr(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
         }
         out_count[b] = (int32_t)keep;
         free(cand);
+    }
+    return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Cluster probing (IVF).  [Sec. 4.2: probe the clusters closest to the query, top-K inside
+ * them; Sec. 4.3 / Alg. 1: phase 1 scores the centroids and keeps the n_p best clusters,
+ * phase 2 runs the Bloom filter only over the item ranges of those clusters, phase 3 scores
+ * the items that pass, phase 4 takes the top K over all probed clusters]
+ *
+ * Items are stored cluster by cluster: cluster c holds items
+ * [cluster_offsets[c], cluster_offsets[c+1]), offsets non-decreasing from 0 to n_items (empty
+ * clusters allowed).  Centroids are int8 rows with an fp32 scale like the items, and a
+ * centroid's score for query b is the same expression as an item's: rescale(dot, s_q, s_c).
+ * Clusters are ranked by (score descending, cluster id ascending), the first
+ * min(n_probe, n_clusters) are probed.  Single-task queries only (the paper probes with one
+ * user embedding).  out_probes[batch][n_probe] receives the probed cluster ids in rank order
+ * (-1 past n_clusters) when not NULL.
+ * Returns 0, -1 out of memory, -2 ill-formed program.
+ */
+typedef struct { float score; int32_t id; } sto_ccand;
+
+static int ccand_cmp(const void* pa, const void* pb)
+{
+    const sto_ccand* a = (const sto_ccand*)pa;
+    const sto_ccand* b = (const sto_ccand*)pb;
+    if (a->score > b->score) return -1;
+    if (a->score < b->score) return 1;
+    if (a->id < b->id) return -1;
+    if (a->id > b->id) return 1;
+    return 0;
+}
+
+int sto_search_ivf(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
+                   const int8_t* items, const float* item_scale, int32_t d,
+                   const int8_t* centroids, const float* centroid_scale, const int64_t* cluster_offsets,
+                   int32_t n_clusters, int32_t n_probe,
+                   const int8_t* queries, const float* query_scale, int32_t batch,
+                   const int32_t* expr_ops, const uint64_t* expr_ids, const int64_t* expr_offsets, int32_t K,
+                   int64_t* out_ids, float* out_scores, int32_t* out_count, int32_t* out_probes)
+{
+    int64_t W = sig_words(m);
+    int failed = 0;
+    for (int32_t b = 0; b < batch; ++b)
+        if (sto_expr_depth(expr_ops + expr_offsets[b], expr_offsets[b + 1] - expr_offsets[b]) < 0) return -2;
+    int32_t np = n_probe < n_clusters ? n_probe : n_clusters;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t b = 0; b < batch; ++b) {
+        sto_cand* cand = (sto_cand*)malloc((size_t)(n_items > 0 ? n_items : 1) * sizeof(sto_cand));
+        sto_ccand* cl = (sto_ccand*)malloc((size_t)(n_clusters > 0 ? n_clusters : 1) * sizeof(sto_ccand));
+        if (!cand || !cl) {
+#pragma omp atomic write
+            failed = 1;
+            free(cand); free(cl);
+            continue;
+        }
+        const int8_t* q = queries + (int64_t)b * d;
+        /* phase 1: centroid scores, best n_p clusters */
+        for (int32_t c = 0; c < n_clusters; ++c) {
+            cl[c].score = sto_rescale(sto_dot(q, centroids + (int64_t)c * d, d), query_scale[b], centroid_scale[c]);
+            cl[c].id = c;
+        }
+        qsort(cl, (size_t)n_clusters, sizeof(sto_ccand), ccand_cmp);
+        if (out_probes)
+            for (int32_t j = 0; j < n_probe; ++j) out_probes[(int64_t)b * n_probe + j] = j < np ? cl[j].id : -1;
+        const int32_t* ops = expr_ops + expr_offsets[b];
+        const uint64_t* ids = expr_ids + expr_offsets[b];
+        int64_t n_ops = expr_offsets[b + 1] - expr_offsets[b];
+        int64_t n = 0;
+        for (int32_t j = 0; j < np; ++j) {
+            int32_t c = cl[j].id;
+            /* phases 2 and 3 inside the cluster's item range */
+            for (int64_t i = cluster_offsets[c]; i < cluster_offsets[c + 1]; ++i) {
+                if (!expr_pass(ops, ids, n_ops, sigs + i * W, m, k)) continue;
+                cand[n].score = sto_rescale(sto_dot(q, items + i * (int64_t)d, d), query_scale[b], item_scale[i]);
+                cand[n].id = i;
+                ++n;
+            }
+        }
+        /* phase 4 */
+        qsort(cand, (size_t)n, sizeof(sto_cand), cand_cmp);
+        int64_t keep = n < K ? n : K;
+        for (int64_t r = 0; r < K; ++r) {
+            out_ids[(int64_t)b * K + r] = r < keep ? cand[r].id : -1;
+            out_scores[(int64_t)b * K + r] = r < keep ? cand[r].score : -INFINITY;
+        }
+        out_count[b] = (int32_t)keep;
+        free(cand); free(cl);
     }
     return failed ? -1 : 0;
 }

@@ -60,6 +60,9 @@ def lib() -> C.CDLL:
         L.sto_search_expr.restype = C.c_int
         L.sto_search_expr.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, p, C.c_int32, p, p,
                                       C.c_int32, C.c_int32, p, p, p, p, C.c_int32, p, p, p]
+        L.sto_search_ivf.restype = C.c_int
+        L.sto_search_ivf.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, p, C.c_int32, p, p, p, C.c_int32,
+                                     C.c_int32, p, p, C.c_int32, p, p, p, C.c_int32, p, p, p, p]
         L.sto_num_threads.restype = C.c_int32
         L.sto_num_threads.argtypes = []
         _lib = L
@@ -224,6 +227,41 @@ def search_expr(sigs, m, k, items, item_scale, queries, query_scale, expr_ops, e
     if rc != 0:
         raise MemoryError("oracle ran out of memory")
     return ids, scores, count
+
+
+def search_ivf(sigs, m, k, items, item_scale, centroids, centroid_scale, cluster_offsets, n_probe,
+               queries, query_scale, expr_ops, expr_ids, expr_offsets, K):
+    """Probe the n_probe best clusters per query, filter and score inside them, top-K.
+    Returns (ids [B,K], scores [B,K], count [B], probes int32 [B,n_probe])."""
+    items = _arr(items, np.int8)
+    item_scale = _arr(item_scale, np.float32)
+    cent = _arr(centroids, np.int8)
+    cs = _arr(centroid_scale, np.float32)
+    coff = _arr(cluster_offsets, np.int64)
+    queries = _arr(queries, np.int8)
+    query_scale = _arr(query_scale, np.float32)
+    eops = _arr(expr_ops, np.int32)
+    eids = _arr(expr_ids, np.uint64)
+    eoff = _arr(expr_offsets, np.int64)
+    n, d = items.shape
+    n_c = cent.shape[0]
+    B = queries.shape[0]
+    assert queries.ndim == 2 and queries.shape[1] == d and cent.shape[1] == d
+    assert cs.size == n_c and coff.size == n_c + 1 and coff[0] == 0 and coff[-1] == n
+    assert query_scale.size == B and eoff.size == B + 1 and eops.size == eids.size == eoff[-1]
+    ids = np.empty((B, K), dtype=np.int64)
+    scores = np.empty((B, K), dtype=np.float32)
+    count = np.empty(B, dtype=np.int32)
+    probes = np.empty((B, n_probe), dtype=np.int32)
+    sigs = _arr(sigs, np.uint64)
+    rc = lib().sto_search_ivf(_ptr(sigs), n, m, k, _ptr(items), _ptr(item_scale), d, _ptr(cent), _ptr(cs),
+                              _ptr(coff), n_c, n_probe, _ptr(queries), _ptr(query_scale), B, _ptr(eops),
+                              _ptr(eids), _ptr(eoff), K, _ptr(ids), _ptr(scores), _ptr(count), _ptr(probes))
+    if rc == -2:
+        raise ValueError("ill-formed filter program")
+    if rc != 0:
+        raise MemoryError("oracle ran out of memory")
+    return ids, scores, count, probes
 
 
 def num_threads() -> int:
