@@ -52,6 +52,8 @@ typedef enum st_status {
 #define ST_MAX_TASKS 8
 #define ST_MAX_TOP_K 16384
 #define ST_MAX_DIM 4096         /* d, a multiple of 16 */
+#define ST_MAX_CLUSTERS 65536   /* clusters of st_search_ivf */
+#define ST_MAX_PROBES 2048      /* clusters probed per query */
 #define ST_MAX_EXPR_OPS 256     /* entries of one filter program */
 #define ST_MAX_EXPR_DEPTH 16    /* results a filter program may hold on its stack at once */
 
@@ -216,6 +218,33 @@ int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* 
                    const uint64_t* host_expr_ids, const int64_t* host_expr_offsets, int32_t K,
                    int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
                    void* dev_workspace, int64_t workspace_bytes, void* hip_stream);
+
+/* ------------------------------------------------------------------ cluster probing (IVF)
+ * The co-designed search of Sec. 4.3 / Algorithm 1 in its four phases: (1) score every
+ * centroid against the query and keep the n_probe best clusters, (2) run the filter only over
+ * the item ranges of those clusters, (3) score the items that pass, (4) top-K over all probed
+ * clusters.  Items must be stored cluster by cluster: cluster c is the item range
+ * [dev_cluster_offsets[c], dev_cluster_offsets[c+1]) (int64 [n_clusters+1], device memory,
+ * non-decreasing from 0 to n_items; empty clusters allowed; ranges are clipped to the corpus).
+ * dev_centroids [n_clusters, d] int8 (16-byte aligned) with dev_centroid_scale [n_clusters] fp32:
+ * a centroid's score is the item score expression ((float)dot * s_q) * s_c; clusters rank by
+ * score descending, then id ascending; min(n_probe, n_clusters) are probed.  Queries are
+ * single-task ([batch, d]); filters are programs as for st_search_expr (a conjunction is its
+ * leaves ANDed).  dev_out_probes (int32 [batch, n_probe], may be NULL) receives the probed
+ * cluster ids in rank order, -1 past n_clusters.  With n_probe >= n_clusters the result is that
+ * of st_search_expr.  1 <= n_clusters <= ST_MAX_CLUSTERS, 1 <= n_probe <= ST_MAX_PROBES.
+ * Everything else (outputs, ordering, workspace ownership, asynchrony, errors) as for st_search. */
+int64_t st_search_ivf_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t K,
+                                      int32_t n_clusters, int32_t n_probe, int64_t n_expr_entries);
+int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
+                  int64_t n_items, int32_t d, const int8_t* dev_centroids,
+                  const float* dev_centroid_scale, const int64_t* dev_cluster_offsets,
+                  int32_t n_clusters, int32_t n_probe, const int8_t* dev_queries,
+                  const float* dev_query_scale, int32_t batch, const int32_t* host_expr_ops,
+                  const uint64_t* host_expr_ids, const int64_t* host_expr_offsets, int32_t K,
+                  int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
+                  int32_t* dev_out_probes, void* dev_workspace, int64_t workspace_bytes,
+                  void* hip_stream);
 
 /* Search scheduling knobs, mainly for tests: path = 0 auto, 1 force the wavefront
  * dot-product scorer, 2 force the int8 MFMA scorer where it applies.  Returns the old value. */

@@ -22,7 +22,7 @@ EXPORTS = [
     "st_search_workspace_bytes", "st_search", "st_search_multitask", "st_score_pairs",
     "st_search_plan", "st_set_scoring_path", "st_timing_begin", "st_timing_end",
     "st_search_overflow_flags_offset", "st_bloom_mask_expr", "st_search_expr_workspace_bytes",
-    "st_search_expr",
+    "st_search_expr", "st_search_ivf_workspace_bytes", "st_search_ivf",
 ]
 
 ST_OP_LEAF, ST_OP_AND, ST_OP_OR, ST_OP_NOT = 0, 1, 2, 3  # operations of a filter program
@@ -84,6 +84,11 @@ def lib() -> C.CDLL:
         L.st_search_expr_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i64]
         L.st_search_expr.restype = C.c_int
         L.st_search_expr.argtypes = [p, p, p, i64, i32, p, p, i32, i32, p, p, p, p, i32, p, p, p, p, i64, p]
+        L.st_search_ivf_workspace_bytes.restype = i64
+        L.st_search_ivf_workspace_bytes.argtypes = [i64, i32, i32, i32, i32, i32, i64]
+        L.st_search_ivf.restype = C.c_int
+        L.st_search_ivf.argtypes = [p, p, p, i64, i32, p, p, p, i32, i32, p, p, i32, p, p, p, i32, p, p, p, p, p,
+                                    i64, p]
         _lib = L
     return _lib
 
@@ -343,6 +348,48 @@ def st_search_expr(bloom: BloomIndex, items, item_scale, queries, query_scale, e
                                 _hptr(ids), _hptr(off), K, _dptr(buf.ids), _dptr(buf.scores), _dptr(buf.count),
                                 _dptr(buf.workspace), buf.nbytes, _stream(stream)))
     return buf.ids, buf.scores, buf.count
+
+
+def st_search_ivf_workspace_bytes(n_items: int, d: int, batch: int, K: int, n_clusters: int, n_probe: int,
+                                  n_expr_entries: int) -> int:
+    return _check(lib().st_search_ivf_workspace_bytes(n_items, d, batch, K, n_clusters, n_probe, n_expr_entries))
+
+
+class IvfBuffers(SearchBuffers):
+    """Workspace and outputs of st_search_ivf for one shape."""
+
+    def __init__(self, n_items: int, d: int, batch: int, K: int, n_clusters: int, n_probe: int, n_expr_entries: int):
+        super().__init__(n_items, d, batch, 1, K)
+        self.nbytes = st_search_ivf_workspace_bytes(n_items, d, batch, K, n_clusters, n_probe, n_expr_entries)
+        self.workspace = torch.empty(self.nbytes, dtype=torch.uint8, device="cuda")
+        self.probes = torch.empty((batch, n_probe), dtype=torch.int32, device="cuda")
+
+
+def st_search_ivf(bloom: BloomIndex, items, item_scale, centroids, centroid_scale, cluster_offsets, n_probe: int,
+                  queries, query_scale, expr_ops, expr_ids, expr_offsets, K: int,
+                  buffers: IvfBuffers | None = None, stream=None):
+    """Returns (ids, scores, count, probes); cluster_offsets int64 [n_clusters + 1] on the device."""
+    _need(items, torch.int8, "items")
+    _need(item_scale, torch.float32, "item_scale")
+    _need(centroids, torch.int8, "centroids")
+    _need(centroid_scale, torch.float32, "centroid_scale")
+    _need(cluster_offsets, torch.int64, "cluster_offsets")
+    _need(queries, torch.int8, "queries")
+    _need(query_scale, torch.float32, "query_scale")
+    n, d = items.shape
+    n_c = centroids.shape[0]
+    B = queries.shape[0]
+    if (queries.dim() != 2 or queries.shape[1] != d or centroids.shape[1] != d or query_scale.numel() != B
+            or item_scale.numel() != n or centroid_scale.numel() != n_c or cluster_offsets.numel() != n_c + 1):
+        raise ValueError("shape mismatch")
+    ops, ids, off = _programs(expr_ops, expr_ids, expr_offsets, B)
+    buf = buffers or IvfBuffers(n, d, B, K, n_c, n_probe, int(off[-1]))
+    _check(lib().st_search_ivf(C.c_void_p(bloom.handle), _dptr(items), _dptr(item_scale), n, d, _dptr(centroids),
+                               _dptr(centroid_scale), _dptr(cluster_offsets), n_c, n_probe, _dptr(queries),
+                               _dptr(query_scale), B, _hptr(ops), _hptr(ids), _hptr(off), K, _dptr(buf.ids),
+                               _dptr(buf.scores), _dptr(buf.count), _dptr(buf.probes), _dptr(buf.workspace),
+                               buf.nbytes, _stream(stream)))
+    return buf.ids, buf.scores, buf.count, buf.probes
 
 
 def st_score_pairs(items, item_scale, queries, query_scale, pair_item, pair_query, stream=None):

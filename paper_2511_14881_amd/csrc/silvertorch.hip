@@ -17,6 +17,7 @@
 
 #include "st_bloom_kernels.h"
 #include "st_mfma_kernels.h"
+#include "st_ivf_kernels.h"
 #include "st_plan.h"
 #include "st_search_kernels.h"
 
@@ -535,7 +536,7 @@ int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_spli
     return p.n_levels;
 }
 
-int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K)
+static int64_t search_ws_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K, int32_t min_cap)
 {
     if (n_items < 0 || n_items >= (1LL << 31)) return fail(ST_EINVAL, "n_items=%lld out of range", (long long)n_items);
     if (d < 16 || d > ST_MAX_DIM || d % 16) return fail(ST_EINVAL, "d=%d must be a multiple of 16 in [16, %d]", d, ST_MAX_DIM);
@@ -543,9 +544,14 @@ int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int
     if (n_tasks < 1 || n_tasks > ST_MAX_TASKS) return fail(ST_EINVAL, "n_tasks=%d out of range", n_tasks);
     if (K < 1 || K > ST_MAX_TOP_K) return fail(ST_EINVAL, "K=%d out of range", K);
     st::Plan p;
-    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p) != 0)
+    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p, 2048, min_cap) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     return (int64_t)st::make_layout(p, batch, K, d, n_tasks).total;
+}
+
+int64_t st_search_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K)
+{
+    return search_ws_bytes(n_items, d, batch, n_tasks, K, 64);
 }
 
 int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K)
@@ -567,8 +573,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                        int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
                        void* dev_workspace, int64_t workspace_bytes, void* hip_stream,
                        const Groups* expr_groups = nullptr, const uint64_t* expr_rows = nullptr,
-                       int32_t expr_row_count = 0)
+                       int32_t expr_row_count = 0, bool allow_seed = true, int32_t min_cap = 64)
 {
+    // allow_seed = false: no seed pass (its threshold comes from a prefix of the corpus, which says
+    // nothing when the passing items sit in a few item ranges, as after cluster probing)
     // expr_groups: the filters were evaluated beforehand into expr_row_count mask rows at
     // expr_rows, laid out like a Bloom index; each group then tests the one row it names
     if (!bloom) return fail(ST_EINVAL, "bloom is null");
@@ -578,7 +586,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     if (n_items != bloom->n_items)
         return fail(ST_EINVAL, "n_items=%lld but the index holds %lld", (long long)n_items, (long long)bloom->n_items);
     if (n_items > 0 && (!dev_items || !dev_item_scale)) return fail(ST_EINVAL, "null corpus");
-    const int64_t need = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
+    const int64_t need = search_ws_bytes(n_items, d, batch, n_tasks, K, min_cap);
     if (need < 0) return (int)need;
     if (workspace_bytes < need)
         return fail(ST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
@@ -661,10 +669,11 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     // wavefronts that scan a level side by side: the resident workgroups of one row of the grid
     const int32_t scan_waves = set_mfma.n ? std::max(1, std::min(plan_groups_per_row(mp.q_split), st::kComputeUnits * mfma_wgs / mp.q_split)) * mp.waves
                                           : st::scan_groups();  // (a whole workgroup shares a segment there)
-    if (st::make_plan(n_items, K, mp.q_split, seg_cap, batch * n_tasks, &plan, scan_waves) != 0)
+    if (st::make_plan(n_items, K, mp.q_split, seg_cap, allow_seed ? batch * n_tasks : st::kSeedMaxRows + 1, &plan, scan_waves,
+                      min_cap) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
-    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1) != 0)
+    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1, 2048, min_cap) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     const st::Layout L = st::make_layout(plan1, batch, K, d, n_tasks);  // layout depends on sizes only
 
@@ -808,6 +817,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         const st::Level& L_ = plan.level[lv];
         se.first = lv == 0 || (lv == 1 && plan.level[0].seed);  // no candidate list from before
         se.last = lv == plan.n_levels - 1;
+        se.may_overflow = lv > 0;
         se.scan.stamp_level = sp_m.stamp_level = sp_d.stamp_level = lv < 8 ? lv : 7;
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
@@ -974,10 +984,10 @@ int st_bloom_mask_expr(const st_bloom* bloom, const int32_t* host_expr_ops, cons
     return rc;
 }
 
-int64_t st_search_expr_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K,
-                                       int64_t n_expr_entries)
+static int64_t expr_ws_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K,
+                             int64_t n_expr_entries, int32_t min_cap)
 {
-    const int64_t base = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
+    const int64_t base = search_ws_bytes(n_items, d, batch, n_tasks, K, min_cap);
     if (base < 0) return base;
     if (n_expr_entries < 0 || n_expr_entries > (int64_t)batch * ST_MAX_EXPR_OPS)
         return fail(ST_EINVAL, "n_expr_entries=%lld out of range", (long long)n_expr_entries);
@@ -985,6 +995,12 @@ int64_t st_search_expr_workspace_bytes(int64_t n_items, int32_t d, int32_t batch
     // the search's own workspace, one mask row per query (every program distinct), the tables
     return st::round_up(base, 256) + n_tiles * batch * st::kTileWords * 8 +
            (int64_t)expr_table_bytes(batch, n_expr_entries, ST_MAX_K_HASHES);
+}
+
+int64_t st_search_expr_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K,
+                                       int64_t n_expr_entries)
+{
+    return expr_ws_bytes(n_items, d, batch, n_tasks, K, n_expr_entries, 64);
 }
 
 int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale, int64_t n_items,
@@ -1052,6 +1068,128 @@ int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* 
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, n_tasks,
                        host_task_weight, nullptr, nullptr, K, dev_out_ids, dev_out_scores, dev_out_count,
                        dev_workspace, base, hip_stream, &groups, mask_rows, tab.n_exprs);
+}
+
+// Region capacity of the probing search: the largest, so that the first level (every pair
+// admitted) is long enough to give every query a threshold although its passing items sit in a few
+// item ranges, and a dense range cannot overflow a region.
+static constexpr int32_t kIvfCap = 512;
+
+int64_t st_search_ivf_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t K, int32_t n_clusters,
+                                      int32_t n_probe, int64_t n_expr_entries)
+{
+    const int64_t base = expr_ws_bytes(n_items, d, batch, 1, K, n_expr_entries, kIvfCap);
+    if (base < 0) return base;
+    if (n_clusters < 1 || n_clusters > ST_MAX_CLUSTERS) return fail(ST_EINVAL, "n_clusters=%d out of range", n_clusters);
+    if (n_probe < 1 || n_probe > ST_MAX_PROBES) return fail(ST_EINVAL, "n_probe=%d out of range", n_probe);
+    // centroid keys and probed cluster ids behind the expression search's workspace
+    return st::round_up(base, 256) + st::round_up((int64_t)batch * n_clusters * 8, 256) +
+           st::round_up((int64_t)batch * n_probe * 4, 256);
+}
+
+int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale, int64_t n_items,
+                  int32_t d, const int8_t* dev_centroids, const float* dev_centroid_scale,
+                  const int64_t* dev_cluster_offsets, int32_t n_clusters, int32_t n_probe,
+                  const int8_t* dev_queries, const float* dev_query_scale, int32_t batch,
+                  const int32_t* host_expr_ops, const uint64_t* host_expr_ids, const int64_t* host_expr_offsets,
+                  int32_t K, int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
+                  int32_t* dev_out_probes, void* dev_workspace, int64_t workspace_bytes, void* hip_stream)
+{
+    if (!bloom || !host_expr_offsets || !dev_workspace || !dev_centroids || !dev_centroid_scale ||
+        !dev_cluster_offsets || !dev_queries || !dev_query_scale)
+        return fail(ST_EINVAL, "null argument");
+    const int64_t base = search_ws_bytes(n_items, d, batch, 1, K, kIvfCap);
+    if (base < 0) return (int)base;
+    if (n_items != bloom->n_items)
+        return fail(ST_EINVAL, "n_items=%lld but the index holds %lld", (long long)n_items, (long long)bloom->n_items);
+    if (((uintptr_t)dev_workspace & 255) || ((uintptr_t)dev_centroids & 15) || ((uintptr_t)dev_queries & 15))
+        return fail(ST_EINVAL, "misaligned buffer (workspace 256 B; centroids and queries 16 B)");
+    ExprTables tab;
+    int rc = build_programs(host_expr_ops, host_expr_ids, host_expr_offsets, batch, bloom->m_bits, bloom->k_hashes,
+                            &tab, nullptr);  // one program per query, in order
+    if (rc != ST_OK) return rc;
+    const int64_t expr_ws = expr_ws_bytes(n_items, d, batch, 1, K, host_expr_offsets[batch], kIvfCap);
+    const int64_t need = st_search_ivf_workspace_bytes(n_items, d, batch, K, n_clusters, n_probe, host_expr_offsets[batch]);
+    if (need < 0) return (int)need;
+    if (workspace_bytes < need)
+        return fail(ST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t n_tiles = (n_items + st::kTileItems - 1) / st::kTileItems;
+    char* ws = (char*)dev_workspace;
+    uint64_t* mask_rows = (uint64_t*)(ws + st::round_up(base, 256));
+    int32_t* d_tab = (int32_t*)((char*)mask_rows + n_tiles * batch * st::kTileWords * 8);
+    char* tail = ws + st::round_up(expr_ws, 256);
+
+    st::IvfParams ip;
+    memset(&ip, 0, sizeof(ip));
+    ip.queries = dev_queries;
+    ip.qscale = dev_query_scale;
+    ip.centroids = dev_centroids;
+    ip.cscale = dev_centroid_scale;
+    ip.cluster_off = dev_cluster_offsets;
+    ip.d = d;
+    ip.n_clusters = n_clusters;
+    ip.n_probe = n_probe;
+    ip.k_pad = st::pow2_ceil(std::min(n_probe, n_clusters));
+    ip.batch = batch;
+    ip.n_items = n_items;
+    ip.keys = (uint64_t*)tail;
+    ip.probes = (int32_t*)(tail + st::round_up((int64_t)batch * n_clusters * 8, 256));
+    ip.user_probes = dev_out_probes;
+
+    // every query is its own filter group: its probed clusters are its own
+    Groups groups;
+    groups.n_groups = batch;
+    groups.row_off.assign(1, 0);
+    groups.q_off.assign(1, 0);
+    for (int32_t b = 0; b < batch; ++b) {
+        groups.rows.push_back(b);
+        groups.row_off.push_back(b + 1);
+        groups.q_list.push_back(b);
+        groups.q_off.push_back(b + 1);
+        groups.q2grp.push_back(b);
+    }
+
+    {   // phase 1: centroid scores and the n_probe best clusters of every query
+        TimedLaunch t(3, stream);
+        hipLaunchKernelGGL(st::ivf_probe_kernel, dim3(batch), dim3(st::kProbeThreads), st::probe_lds_bytes(ip.k_pad),
+                           stream, ip);
+    }
+    ST_HIP(hipGetLastError());
+    if (n_tiles > 0) {
+        const size_t n_off = tab.prog_off.size(), n_code = tab.code.size(), n_rows = tab.leaf_rows.size();
+        const size_t bytes = (n_off + n_code + n_rows) * 4;
+        if (bytes > expr_table_bytes(batch, host_expr_offsets[batch], ST_MAX_K_HASHES))
+            return fail(ST_EINVAL, "program tables exceed their workspace slot");
+        Stage* stage = nullptr;
+        rc = stage_acquire(bytes, &stage);
+        if (rc != ST_OK) return rc;
+        int32_t* h = (int32_t*)stage->host;
+        memcpy(h, tab.prog_off.data(), n_off * 4);
+        if (n_code) memcpy(h + n_off, tab.code.data(), n_code * 4);
+        if (n_rows) memcpy(h + n_off + n_code, tab.leaf_rows.data(), n_rows * 4);
+        const int32_t* t_dev = (const int32_t*)stage->dev_view;
+        if (bytes > 64 * 1024) {
+            ST_HIP(hipMemcpyAsync(d_tab, stage->host, bytes, hipMemcpyHostToDevice, stream));
+            t_dev = d_tab;
+        }
+        {   // phase 2: the filter over the probed ranges only, into zeroed mask rows
+            TimedLaunch t(3, stream);
+            const int64_t n_mask_words = n_tiles * batch * st::kTileWords;
+            hipLaunchKernelGGL(st::fill_zero_kernel, dim3((unsigned)std::min<int64_t>((n_mask_words + 255) / 256, 4096)),
+                               dim3(256), 0, stream, mask_rows, n_mask_words);
+            hipLaunchKernelGGL(st::ivf_mask_kernel, dim3((unsigned)n_probe, (unsigned)batch), dim3(256), 0, stream,
+                               bloom->dev, bloom->m_bits, bloom->k_hashes, ip, t_dev, t_dev + n_off,
+                               t_dev + n_off + n_code, mask_rows);
+        }
+        ST_HIP(hipGetLastError());
+        ST_HIP(hipEventRecord(stage->ev, stream));
+        stage->in_flight = true;
+    }
+    // phases 3 and 4
+    return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, 1, nullptr,
+                       nullptr, nullptr, K, dev_out_ids, dev_out_scores, dev_out_count, dev_workspace, base,
+                       hip_stream, &groups, mask_rows, batch, false, kIvfCap);
 }
 
 int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t d, const int8_t* dev_queries,

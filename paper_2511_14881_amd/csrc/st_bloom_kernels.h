@@ -127,6 +127,32 @@ __global__ __launch_bounds__(256) void bloom_mask_kernel(const uint64_t* __restr
 constexpr int kExprDepth = 16;
 constexpr int kExprOps = 256;    // entries of one program, at most
 constexpr int kExprHashes = 16;  // rows of a leaf, at most
+
+// One program on one 64-item word: s_code / s_rows hold the program (LDS), base points at word w
+// of row 0 of the word's tile, column tid of s_stack is this thread's stack.  Returns the raw
+// result (all ones for the empty program); the caller masks the bits that are not items.
+__device__ inline uint64_t expr_eval_word(const int32_t* s_code, const int32_t* s_rows, int n_ops, int k_hashes,
+                                          const uint64_t* __restrict__ base, uint64_t (*s_stack)[256], int tid)
+{
+    int top = 0;
+    for (int i = 0; i < n_ops; ++i) {
+        const int op = s_code[i];
+        if (op == 0) {
+            uint64_t w = ~0ULL;
+            const int32_t* rows = s_rows + i * k_hashes;
+            for (int j = 0; j < k_hashes; ++j) w &= base[(int64_t)rows[j] * kTileWords];
+            s_stack[top++][tid] = w;
+        } else if (op == 3) {
+            s_stack[top - 1][tid] = ~s_stack[top - 1][tid];
+        } else {
+            const uint64_t rhs = s_stack[--top][tid];
+            const uint64_t lhs = s_stack[top - 1][tid];
+            s_stack[top - 1][tid] = op == 1 ? (lhs & rhs) : (lhs | rhs);
+        }
+    }
+    return n_ops > 0 ? s_stack[0][tid] : ~0ULL;
+}
+
 __global__ __launch_bounds__(256) void bloom_expr_kernel(const uint64_t* __restrict__ bloom, int32_t m_bits,
                                                          int32_t k_hashes, int64_t n_items, int64_t n_words,
                                                          const int32_t* __restrict__ prog_off,
@@ -151,24 +177,9 @@ __global__ __launch_bounds__(256) void bloom_expr_kernel(const uint64_t* __restr
     const int64_t left = n_items - first;
     const uint64_t valid = left >= 64 ? ~0ULL : (left > 0 ? ((1ULL << left) - 1ULL) : 0ULL);
     const uint64_t* base = bloom + ((gw >> 4) * (int64_t)m_bits) * kTileWords + (gw & 15);
-    int top = 0;
-    for (int i = 0; i < n_ops; ++i) {
-        const int op = s_code[i];
-        if (op == 0) {
-            uint64_t w = ~0ULL;
-            const int32_t* rows = s_rows + i * k_hashes;
-            for (int j = 0; j < k_hashes; ++j) w &= base[(int64_t)rows[j] * kTileWords];
-            s_stack[top++][tid] = w;
-        } else if (op == 3) {
-            s_stack[top - 1][tid] = ~s_stack[top - 1][tid];
-        } else {
-            const uint64_t rhs = s_stack[--top][tid];
-            const uint64_t lhs = s_stack[top - 1][tid];
-            s_stack[top - 1][tid] = op == 1 ? (lhs & rhs) : (lhs | rhs);
-        }
-    }
+    const uint64_t raw = expr_eval_word(s_code, s_rows, n_ops, k_hashes, base, s_stack, tid);
     // bits past the last item stay 0, also under a NOT
-    const uint64_t res = (n_ops > 0 ? s_stack[0][tid] : ~0ULL) & valid;
+    const uint64_t res = raw & valid;
     if (out_tile_rows > 0)
         out[((gw >> 4) * (int64_t)out_tile_rows + e) * kTileWords + (gw & 15)] = res;
     else

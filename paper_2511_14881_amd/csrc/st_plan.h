@@ -152,11 +152,12 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
 // every passing pair of groups * cap items, so its cost grows with the capacity; later levels
 // grow by at most cap * groups / (4K).  The smallest capacity that keeps the schedule at six
 // levels or fewer (every workgroup sharing every query) is taken, else the largest.
-inline int choose_cap(int64_t n_items, int32_t K)
+inline int choose_cap(int64_t n_items, int32_t K, int32_t min_cap = 64)
 {
     static const int32_t caps[] = {64, 128, 256, 512};
     int best = -1;
     for (int32_t cap : caps) {
+        if (cap < min_cap) continue;
         // the slow exact path appends into a buffer of K + groups*cap keys, a tile at a time
         if ((int64_t)scan_groups() * cap < 2 * (int64_t)K + 2048) continue;
         Plan p;
@@ -182,10 +183,13 @@ inline int seg_limit(int32_t seg_cap)
     return e > 0 && e < seg_cap ? e : seg_cap;
 }
 
+// min_cap: smallest region capacity to consider.  Searches whose passing items sit in a few dense
+// item ranges (cluster probing) ask for the largest: a long first level that admits everything
+// then gives every query a threshold, and a dense range cannot overflow a region.
 inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, Plan* out,
-                     int32_t waves = 2048)
+                     int32_t waves = 2048, int32_t min_cap = 64)
 {
-    const int cap = choose_cap(n_items, K);
+    const int cap = choose_cap(n_items, K, min_cap);
     if (cap < 0 || q_split < 1 || scan_groups() % q_split) return -1;
     // the seed pass borrows the candidate regions and the gather buffer of a query as scratch
     const bool seed_fits = K <= kLdsSortMax && (int64_t)scan_groups() * cap >= 2 * (int64_t)kSeedItems;

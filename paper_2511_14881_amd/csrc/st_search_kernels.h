@@ -588,6 +588,7 @@ struct SelectParams {
     uint32_t* ovf;          // [B]
     int32_t lds_keys;       // candidates per query the selection gathers in LDS (<= kLdsKeys; sizes its LDS)
     int32_t first, last;
+    int32_t may_overflow;   // 0: the level's regions cannot overflow (every pair admitted, one visit per region): the flag is reset
     int64_t* out_ids;       // [B][K]
     float* out_scores;
     int32_t* out_count;
@@ -671,8 +672,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     // counts are clamped to what the buffers can hold, whatever the memory says
     uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
     n_prev = n_prev < (uint32_t)p.K ? n_prev : (uint32_t)p.K;
-    const bool overflowed = !p.first && p.ovf[q] != 0u;
-    if (p.first && tid == 0) p.ovf[q] = 0u;
+    // (the level after a seed pass has no list from before but admits by threshold: its regions
+    // can overflow like any later level's, and the seed pass has reset the flag)
+    const bool overflowed = p.may_overflow && p.ovf[q] != 0u;
+    if (!p.may_overflow && tid == 0) p.ovf[q] = 0u;
     if (p.last && overflowed) {  // uniform over the workgroup
         rescue_query(p, q, s_sorted, s_hist, s_misc, s_red, s_mask, &s_misc[4]);
         return;

@@ -313,3 +313,21 @@ def gen_filter_programs(cfg: Config, pool: int = 8, with_not: bool = True):
         off.append(len(all_ops))
     return (np.asarray(all_ops, dtype=np.int32), np.asarray(all_ids, dtype=np.uint64),
             np.asarray(off, dtype=np.int64), programs)
+
+
+S_CLUSTERS = 11  # random stream of the cluster layout and the centroids
+
+
+def gen_clusters(cfg: Config, n_clusters: int, device="cpu"):
+    """A cluster layout for the probing search: the corpus cut into n_clusters contiguous ranges
+    at sorted random positions (so sizes vary, a few clusters may be empty), centroids drawn from
+    the item family with scales U(0.5, 1.5).  No clustering is trained: the probing cost and the
+    exactness of the result do not depend on where the centroids are.  Returns (centroids int8
+    [n_c, d], scales fp32 [n_c], offsets int64 [n_c + 1])."""
+    cent = gen_int8(cfg.seed, S_CLUSTERS, n_clusters, cfg.d, cfg.item_dist, device)
+    cs = gen_scale(cfg.seed, S_CLUSTERS + 1, n_clusters, device)
+    z = _lsr(rand_u64(cfg.seed, S_CLUSTERS + 2, _arange(0, max(n_clusters - 1, 0), "cpu")), 11)
+    cuts = torch.sort(z % (cfg.n_items + 1)).values if n_clusters > 1 else torch.zeros(0, dtype=torch.int64)
+    off = torch.cat([torch.zeros(1, dtype=torch.int64), cuts.to(torch.int64),
+                     torch.full((1,), cfg.n_items, dtype=torch.int64)]).to(device)
+    return cent, cs, off

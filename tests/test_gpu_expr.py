@@ -165,3 +165,60 @@ def test_query_form_recipe_mid_full_size():
             seen.add(key)
             sel.append(b)
     check_expr_search(w, programs, cfg.top_k, label="mid query form, full size", queries=sel, fast_path_only=True)
+
+
+# ------------------------------------------------------------------ cluster probing (IVF)
+def check_ivf(w, programs_per_query, n_clusters, n_probe, K, queries=None, path=0, label="", fast_path_only=False):
+    cfg = w.cfg
+    ops, ids, off = pack(programs_per_query)
+    say(f"[ivf] {label or cfg.name}: N={cfg.n_items} d={cfg.d} B={cfg.batch} K={K} clusters={n_clusters} "
+        f"probes={n_probe} path={path}")
+    cent, cs, coff = S.gen_clusters(cfg, n_clusters)
+    items, iscale, foff, fids, q, qs = [t.cuda() for t in (w.items, w.item_scale, w.feat_offsets, w.feat_ids,
+                                                         w.queries, w.query_scale)]
+    bloom = st.st_bloom_build(foff, fids, cfg.n_items, cfg.m_bits, cfg.k_hashes)
+    buf = st.IvfBuffers(cfg.n_items, cfg.d, cfg.batch, K, n_clusters, n_probe, int(off[-1]))
+    old = st.st_set_scoring_path(path)
+    try:
+        g = st.st_search_ivf(bloom, items, iscale, cent.cuda(), cs.cuda(), coff.cuda(), n_probe, q, qs, ops, ids, off,
+                             K, buffers=buf)
+        torch.cuda.synchronize()
+    finally:
+        st.st_set_scoring_path(old)
+    if fast_path_only:
+        slow = np.nonzero(_np(buf.overflow_flags()))[0]
+        assert slow.size == 0, f"queries {slow[:8].tolist()}... took the slow exact path"
+    g_ids, g_scores, g_count, g_probes = [_np(t) for t in g]
+    sigs = oracle_index(w)
+    sel = list(range(cfg.batch)) if queries is None else list(queries)
+    s_ops, s_ids, s_off = pack([programs_per_query[b] for b in sel])
+    oi, os_, oc, op = O.search_ivf(sigs, cfg.m_bits, cfg.k_hashes, _np(w.items), _np(w.item_scale), _np(cent),
+                                   _np(cs), _np(coff), n_probe, _np(w.queries)[sel], _np(w.query_scale)[sel],
+                                   s_ops, s_ids, s_off, K)
+    for j, b in enumerate(sel):
+        assert np.array_equal(g_probes[b], op[j]), f"query {b}: probed clusters differ"
+        assert g_count[b] == oc[j], f"query {b}: count {g_count[b]} vs oracle {oc[j]}"
+        bad = np.nonzero(g_ids[b] != oi[j])[0]
+        assert bad.size == 0, f"query {b}: first id mismatch at rank {bad[0]}: gpu {g_ids[b][bad[0]]} vs {oi[j][bad[0]]}"
+        assert np.array_equal(g_scores[b].view(np.uint32), os_[j].view(np.uint32)), f"query {b}: score bits differ"
+    bloom.free()
+
+
+@pytest.mark.parametrize("path", [0, 1, 2])
+@pytest.mark.parametrize("n,d,B,n_c,n_p,K", [(3000, 64, 9, 7, 3, 20), (70_001, 128, 33, 300, 40, 100),
+                                             (20_000, 64, 12, 50, 50, 30), (50_000, 128, 20, 2000, 1, 64),
+                                             (40_000, 32, 5, 3, 8, 50)])
+def test_probing_search_matches_oracle(n, d, B, n_c, n_p, K, path):
+    w = ragged_workload(500 + n, n, d, B, 24, 6, 128, 3)
+    programs = random_programs(n + B + 1, B, 24, depth=3)
+    check_ivf(w, programs, n_c, n_p, K, path=path, label=f"ragged n={n}")
+
+
+def test_probing_search_mid_recipe_scaled_and_full():
+    for n, step in ((200_000, 4), (1_000_000, 9)):
+        cfg = S.scaled(S.CONFIGS["mid"], n)
+        w = S.make_workload(cfg)
+        ops, ids, off, pool = S.gen_filter_programs(cfg)
+        programs = [(ops[off[b]:off[b + 1]].tolist(), ids[off[b]:off[b + 1]].tolist()) for b in range(cfg.batch)]
+        check_ivf(w, programs, 1024, 64, cfg.top_k, queries=range(0, cfg.batch, step), label=f"mid@{n}",
+                  fast_path_only=True)

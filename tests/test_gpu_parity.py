@@ -451,3 +451,21 @@ def test_error_paths_return_codes():
     st.st_search(bloom, items, isc, q, qs, w.filt_ids, w.filt_offsets, 10, buffers=buf)
     torch.cuda.synchronize()
     bloom.free()
+
+
+def test_overflow_in_the_level_after_the_seed_pass_is_caught():
+    # The seed pass looks at the first 32768 items only.  Here no item of that prefix passes the
+    # filter of the even queries, so their threshold stays open and the one level after the seed
+    # pass admits a whole dense block of passing items: far more than the candidate regions hold.
+    # Those queries must be flagged and recomputed by the slow exact path, not silently truncated.
+    n, d, B, K = 300_000, 64, 6, 50
+    w = ragged_workload(91, n, d, B, 30, 3, 128, 3)
+    off = np.arange(n + 1, dtype=np.int64)
+    ids = np.full(n, 2000, dtype=np.int64)
+    ids[100_000:160_000] = 1000
+    filters = [[1000] if b % 2 == 0 else [2000] for b in range(B)]
+    w.feat_offsets, w.feat_ids = torch.from_numpy(off), torch.from_numpy(ids)
+    w.filt_ids = np.array([x for f in filters for x in f], dtype=np.uint64)
+    w.filt_offsets = np.arange(B + 1, dtype=np.int64)
+    w.pool = filters
+    check_search(w, K, label="dense block behind an empty prefix", slow_path=([0, 2, 4], []))
