@@ -94,6 +94,49 @@ def union_and_rows_programs(st, bloom, w, prog):
             "passing_pairs": sum(per[j] for j in q2p), "per_filter_sel": [p / max(w.cfg.n_items, 1) for p in per]}
 
 
+def stats_ivf(st, bloom, w, prog, coff, probes, n_clusters):
+    """Ingredients for the probing search: passing items per query = program mask AND probed
+    ranges; bytes of phases 1-2 = centroid table and keys, signature rows over the probed words
+    only, and the per-query mask rows (zeroed, then read by the scan)."""
+    import torch
+    cfg = w.cfg
+    base = union_and_rows_programs(st, bloom, w, prog)  # per-program masks are recomputed below, cheaply
+    ops, ids, off = prog
+    seen, progs, q2p = {}, [], []
+    for b in range(cfg.batch):
+        key = (tuple(ops[off[b]:off[b + 1]].tolist()), tuple(ids[off[b]:off[b + 1]].tolist()))
+        if key not in seen:
+            seen[key] = len(progs)
+            progs.append(key)
+        q2p.append(seen[key])
+    p_ops = np.array([o for p in progs for o in p[0]], dtype=np.int32)
+    p_ids = np.array([i for p in progs for i in p[1]], dtype=np.uint64)
+    p_off = np.concatenate([[0], np.cumsum([len(p[0]) for p in progs])]).astype(np.int64)
+    masks = st.st_bloom_mask_expr(bloom, p_ops, p_ids, p_off)  # [E][n_words] int64
+    shifts = torch.arange(64, device="cuda", dtype=torch.int64)
+    cluster_of = torch.bucketize(torch.arange(cfg.n_items, device="cuda"), coff[1:], right=True).clamp_(max=n_clusters - 1)
+    union = torch.zeros(cfg.n_items, dtype=torch.bool, device="cuda")
+    passing_pairs, probed_words, leaf_row_words = 0, 0, 0
+    sizes = (coff[1:] - coff[:-1])
+    for b in range(cfg.batch):
+        pr = probes[b][probes[b] >= 0].long()
+        probed = torch.zeros(n_clusters, dtype=torch.bool, device="cuda")
+        probed[pr] = True
+        in_probe = probed[cluster_of]
+        bits = ((masks[q2p[b]].unsqueeze(1) >> shifts) & 1).reshape(-1)[: cfg.n_items].bool()
+        pb = bits & in_probe
+        union |= pb
+        passing_pairs += int(pb.sum())
+        words_b = int(((sizes[pr] + 63) // 64 + 1).sum())
+        probed_words += words_b
+        leaf_row_words += words_b * cfg.k_hashes * sum(1 for o in progs[q2p[b]][0] if o == 0)
+    n_words = (cfg.n_items + 63) // 64
+    extra = n_clusters * (cfg.d + 4) + 2 * cfg.batch * n_clusters * 8 + leaf_row_words * 8 + 2 * cfg.batch * n_words * 8
+    return {"distinct_filters": cfg.batch, "rows_touched": 0, "extra_bytes": extra, "union_items": int(union.sum()),
+            "passing_pairs": passing_pairs, "per_filter_sel": base["per_filter_sel"],
+            "probed_item_fraction": float(probed_words * 64) / max(cfg.n_items * cfg.batch, 1)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -110,6 +153,10 @@ def main():
                     help="variant of the workload: every query's filter is a boolean program of the "
                          "paper's query form (a term AND an OR-group, every second one AND NOT a term), run "
                          "through st_search_expr; reported as its own workload name")
+    ap.add_argument("--ivf", default="",
+                    help="variant of the workload: N_CLUSTERS:N_PROBE, e.g. 1024:64 -- the corpus cut into "
+                         "clusters, every query probes its N_PROBE best ones (st_search_ivf) with the filter "
+                         "programs of --filter-programs; single-task workloads only")
     ap.add_argument("--copy-probe", action="store_true",
                     help="also run one plain 256 MiB device copy, as the known-size reference for "
                          "scaling rocprofv3's FETCH_SIZE / WRITE_SIZE counters")
@@ -130,7 +177,15 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if args.distinct_filters:
         cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
-    if args.filter_programs:
+    ivf = None
+    if args.ivf:
+        ivf = tuple(int(x) for x in args.ivf.split(":"))
+        if cfg.n_tasks > 0 or len(ivf) != 2:
+            print("bench.py: --ivf takes N_CLUSTERS:N_PROBE and a single-task workload", file=sys.stderr)
+            sys.exit(2)
+        args.filter_programs = True
+        cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+ivf%d:%d" % ivf)
+    elif args.filter_programs:
         cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+filter-programs")
     t0 = time.time()
     w = synth.make_workload(cfg, device="cuda")
@@ -145,12 +200,19 @@ def main():
     prog = None
     if args.filter_programs:
         prog = synth.gen_filter_programs(cfg)[:3]
-    buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, T, cfg.top_k,
-                           n_expr_entries=None if prog is None else int(prog[2][-1]))
+    if ivf:
+        cent, cscale, coff = synth.gen_clusters(cfg, ivf[0], device="cuda")
+        buf = st.IvfBuffers(cfg.n_items, cfg.d, cfg.batch, cfg.top_k, ivf[0], ivf[1], int(prog[2][-1]))
+    else:
+        buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, T, cfg.top_k,
+                               n_expr_entries=None if prog is None else int(prog[2][-1]))
     st.st_set_scoring_path(args.path)
 
     def step():
-        if prog is not None:
+        if ivf:
+            st.st_search_ivf(bloom, w.items, w.item_scale, cent, cscale, coff, ivf[1], w.queries, w.query_scale,
+                             prog[0], prog[1], prog[2], cfg.top_k, buffers=buf)
+        elif prog is not None:
             st.st_search_expr(bloom, w.items, w.item_scale, w.queries, w.query_scale, prog[0], prog[1], prog[2],
                               cfg.top_k, task_weight=w.task_weight, buffers=buf)
         elif cfg.n_tasks > 0:
@@ -190,10 +252,13 @@ def main():
     scan_ms_per_step = scan_ms / args.steps
     n_levels = timing["select"][1] // args.steps  # one selection (or seed) launch per level
 
-    stats = union_and_rows(st, bloom, w) if prog is None else union_and_rows_programs(st, bloom, w, prog)
+    if ivf:
+        stats = stats_ivf(st, bloom, w, prog, coff, buf.probes, ivf[0])
+    else:
+        stats = union_and_rows(st, bloom, w) if prog is None else union_and_rows_programs(st, bloom, w, prog)
     n_words = (cfg.n_items + 63) // 64
     a_bytes = (stats["rows_touched"] * n_words * 8 + stats["union_items"] * (cfg.d + 4)
-               + cfg.batch * T * cfg.d + cfg.batch * cfg.top_k * 12)
+               + cfg.batch * T * cfg.d + cfg.batch * cfg.top_k * 12 + stats.get("extra_bytes", 0))
     a_ops = 2.0 * cfg.d * T * stats["passing_pairs"]
     stream_all = cfg.n_items * (cfg.d + 4) + cfg.n_items * cfg.m_bits // 8
     achieved_gbs = a_bytes / (scan_ms_per_step * 1e-3) / 1e9 if scan_ms_per_step > 0 else 0.0
@@ -242,7 +307,12 @@ def main():
         reps, spent = 0, 0.0
         while spent < args.cpu_seconds and reps < 1000:
             t0 = time.perf_counter()
-            if prog is not None:
+            if ivf:
+                po = prog[2][: b_s + 1]
+                O.search_ivf(sigs, cfg.m_bits, cfg.k_hashes, items, isc, cent.cpu().numpy(), cscale.cpu().numpy(),
+                             np.minimum(coff.cpu().numpy(), n_s), ivf[1], q, qs, prog[0][: int(po[-1])],
+                             prog[1][: int(po[-1])], po, cfg.top_k)
+            elif prog is not None:
                 po = prog[2][: b_s + 1]
                 O.search_expr(sigs, cfg.m_bits, cfg.k_hashes, items, isc, q, qs, prog[0][: int(po[-1])],
                               prog[1][: int(po[-1])], po, cfg.top_k, task_weight=w.task_weight)
@@ -269,7 +339,8 @@ def main():
                    "filter_terms": cfg.n_terms, "top_k": cfg.top_k, "levels": n_levels,
                    "scoring_path": args.path, "distinct_filters": stats["distinct_filters"],
                    "union_selectivity": stats["union_items"] / max(cfg.n_items, 1),
-                   "mean_filter_selectivity": float(np.mean(stats["per_filter_sel"]))},
+                   "mean_filter_selectivity": float(np.mean(stats["per_filter_sel"])),
+                   **({"probed_item_fraction": stats["probed_item_fraction"]} if ivf else {})},
         "items_scanned_per_s": cfg.n_items / (ms_per_step * 1e-3),
         "item_query_pairs_per_s": cfg.n_items * cfg.batch / (ms_per_step * 1e-3),
         "bloom_build_items_per_s": cfg.n_items / build_s if build_s > 0 else None,

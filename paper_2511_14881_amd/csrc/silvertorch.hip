@@ -1178,7 +1178,7 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
             const int64_t n_mask_words = n_tiles * batch * st::kTileWords;
             hipLaunchKernelGGL(st::fill_zero_kernel, dim3((unsigned)std::min<int64_t>((n_mask_words + 255) / 256, 4096)),
                                dim3(256), 0, stream, mask_rows, n_mask_words);
-            hipLaunchKernelGGL(st::ivf_mask_kernel, dim3((unsigned)n_probe, (unsigned)batch), dim3(256), 0, stream,
+            hipLaunchKernelGGL(st::ivf_mask_kernel, dim3((unsigned)((n_probe + st::kMaskProbes - 1) / st::kMaskProbes), (unsigned)batch), dim3(256), 0, stream,
                                bloom->dev, bloom->m_bits, bloom->k_hashes, ip, t_dev, t_dev + n_off,
                                t_dev + n_off + n_code, mask_rows);
         }

@@ -4,7 +4,7 @@
 // Phase 1 (ivf_probe_kernel): one workgroup per query scores every centroid like an item
 // (int8 dot, two fp32 multiplies), and an exact top-n_p by (score descending, cluster id
 // ascending) gives the probed clusters.
-// Phase 2 (ivf_mask_kernel): one workgroup per (query, probed cluster) runs the query's filter
+// Phase 2 (ivf_mask_kernel): 32 threads per (query, probed cluster) run the query's filter
 // program only over the words of that cluster's range and ORs the result into the query's row of
 // a bit-sliced mask index (zeroed beforehand), laid out like the Bloom index.  Phases 3-4 are the
 // ordinary fused scan and selection reading that mask index: items outside the probed ranges have
@@ -60,8 +60,11 @@ __global__ __launch_bounds__(kProbeThreads) void ivf_probe_kernel(IvfParams p)
     }
 }
 
-// grid (n_probe, batch).  prog_off / code / leaf_rows as for bloom_expr_kernel, one program per
-// query.  mask_rows: bit-sliced index with `batch` rows; row b belongs to query b.
+// grid (ceil(n_probe / kMaskProbes), batch): a workgroup takes kMaskProbes probed clusters of one
+// query, 32 threads per cluster (a cluster of a thousand items is 16 words).  prog_off / code /
+// leaf_rows as for bloom_expr_kernel, one program per query.  mask_rows: bit-sliced index with
+// `batch` rows; row b belongs to query b.
+constexpr int kMaskProbes = 8;
 __global__ __launch_bounds__(256) void ivf_mask_kernel(const uint64_t* __restrict__ bloom, int32_t m_bits,
                                                        int32_t k_hashes, IvfParams p,
                                                        const int32_t* __restrict__ prog_off,
@@ -73,19 +76,24 @@ __global__ __launch_bounds__(256) void ivf_mask_kernel(const uint64_t* __restric
     __shared__ int32_t s_code[kExprOps];
     __shared__ int32_t s_rows[kExprOps * kExprHashes];
     const int tid = threadIdx.x, b = blockIdx.y;
-    const int32_t c = p.probes[(int64_t)b * p.n_probe + blockIdx.x];
-    if (c < 0) return;  // the whole workgroup: fewer clusters than probes
-    // the range, kept inside the corpus whatever the offsets say
-    int64_t lo = p.cluster_off[c], hi = p.cluster_off[c + 1];
-    lo = lo < 0 ? 0 : (lo > p.n_items ? p.n_items : lo);
-    hi = hi < lo ? lo : (hi > p.n_items ? p.n_items : hi);
-    if (lo >= hi) return;  // empty cluster (uniform)
+    const int sub = tid >> 5, wl = tid & 31;
+    const int j = (int)blockIdx.x * kMaskProbes + sub;
+    const int32_t c = j < p.n_probe ? p.probes[(int64_t)b * p.n_probe + j] : -1;
+    // the range, kept inside the corpus whatever the offsets say (empty when there is no cluster)
+    int64_t lo = 0, hi = 0;
+    if (c >= 0) {
+        lo = p.cluster_off[c];
+        hi = p.cluster_off[c + 1];
+        lo = lo < 0 ? 0 : (lo > p.n_items ? p.n_items : lo);
+        hi = hi < lo ? lo : (hi > p.n_items ? p.n_items : hi);
+    }
     const int i0 = prog_off[b], n_ops = prog_off[b + 1] - i0;
     for (int i = tid; i < n_ops; i += 256) s_code[i] = code[i0 + i];
     for (int i = tid; i < n_ops * k_hashes; i += 256) s_rows[i] = leaf_rows[(int64_t)i0 * k_hashes + i];
-    __syncthreads();
+    __syncthreads();  // the only barrier: threads without work may leave below
+    if (lo >= hi) return;
     const int64_t w_first = lo >> 6, w_last = (hi - 1) >> 6;
-    for (int64_t gw = w_first + tid; gw <= w_last; gw += 256) {
+    for (int64_t gw = w_first + wl; gw <= w_last; gw += 32) {
         // bits of this word that belong to [lo, hi)
         const int64_t first = gw * 64;
         uint64_t in = ~0ULL;
