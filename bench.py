@@ -153,6 +153,9 @@ def main():
                     help="variant of the workload: every query's filter is a boolean program of the "
                          "paper's query form (a term AND an OR-group, every second one AND NOT a term), run "
                          "through st_search_expr; reported as its own workload name")
+    ap.add_argument("--top-k", type=int, default=0,
+                    help="variant of the workload: another K (the paper's pre-filter sizes are O(10,000)); "
+                         "reported as its own workload name")
     ap.add_argument("--ivf", default="",
                     help="variant of the workload: N_CLUSTERS:N_PROBE, e.g. 1024:64 -- the corpus cut into "
                          "clusters, every query probes its N_PROBE best ones (st_search_ivf) with the filter "
@@ -177,6 +180,8 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if args.distinct_filters:
         cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
+    if args.top_k > 0:
+        cfg = synth.scaled(cfg, cfg.n_items, top_k=args.top_k, name=cfg.name + "+K%d" % args.top_k)
     ivf = None
     if args.ivf:
         ivf = tuple(int(x) for x in args.ivf.split(":"))
@@ -269,7 +274,8 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            traffic = None if (args.distinct_filters or args.filter_programs) else json.load(open(tpath)).get(args.config)
+            variant = args.distinct_filters or args.filter_programs or args.top_k > 0
+            traffic = None if variant else json.load(open(tpath)).get(args.config)
         except Exception:
             traffic = None
 

@@ -912,14 +912,19 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         se.regions = regions;
         {
             TimedLaunch t(1, stream);
+            // K above the LDS sort size: the final ordering of k_pad keys runs in LDS where they fit
+            const size_t big_bytes = (size_t)L.k_pad * 8;
+            constexpr size_t kBigSortMax = 128 * 1024;
+            se.big_sort = (se.srt && big_bytes <= kBigSortMax) ? 1 : 0;
             static bool lds_set = false;
             if (!lds_set) {
                 ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&st::select_kernel),
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, st::kSelectLdsBytes));
+                                           hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)std::max<size_t>(st::kSelectLdsBytes, kBigSortMax)));
                 lds_set = true;
             }
-            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads),
-                               (size_t)st::select_lds_bytes(se.lds_keys), stream, se);
+            const size_t lds = std::max<size_t>((size_t)st::select_lds_bytes(se.lds_keys), se.big_sort ? big_bytes : 0);
+            hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), lds, stream, se);
         }
         ST_HIP(hipGetLastError());
     }

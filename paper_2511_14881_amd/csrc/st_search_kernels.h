@@ -247,17 +247,26 @@ __global__ __launch_bounds__(kScanThreads) void scan_wavedot_kernel(ScanParams p
 // needed -- then the keys at or above it are collected and a bitonic network orders them.
 // All threads of the workgroup must call it; uses s_hist (256 words), s_misc (8 words) and
 // s_red (2 x 8 64-bit words) of LDS.
+// With want_sorted = false the bitonic network is skipped: sorted[0 .. min(n,K)) then holds the
+// best keys in no particular order (a caller that only carries the set forward needs no order),
+// and *kth_out, if given, receives the K-th best key (0 if n < K) in either mode.
 __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* sorted, int k_pad,
-                              uint32_t* s_hist, uint32_t* s_misc, uint64_t* s_red)
+                              uint32_t* s_hist, uint32_t* s_misc, uint64_t* s_red, bool want_sorted = true,
+                              uint64_t* kth_out = nullptr)
 {
     const int tid = threadIdx.x, nt = blockDim.x;
     const int n_out = n < (int64_t)K ? (int)n : K;
+    uint64_t low = ~0ULL;  // smallest key this thread put into sorted[]
     // power-of-two size the sorting network runs on
     int P = 1;
     while (P < n_out) P <<= 1;
     if (P > k_pad) P = k_pad;
     if (n <= (int64_t)K) {
-        for (int i = tid; i < P; i += nt) sorted[i] = i < n_out ? buf[i] : 0ULL;
+        for (int i = tid; i < P; i += nt) {
+            const uint64_t key = i < n_out ? buf[i] : 0ULL;
+            sorted[i] = key;
+            if (i < n_out && key < low) low = key;
+        }
     } else {
         // bits shared by every key need no pass: find the highest byte in which two keys differ
         uint64_t lo = ~0ULL, hi = 0ULL;
@@ -330,11 +339,25 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
             if (key >= kth) {
                 const uint32_t slot = atomicAdd(&s_misc[2], 1u);
                 if (slot < (uint32_t)P) sorted[slot] = key;
+                if (key < low) low = key;
             }
         }
         for (int i = K + tid; i < P; i += nt) sorted[i] = 0ULL;
     }
     __syncthreads();
+    if (kth_out) {
+        // the K-th best key is the smallest one kept (keys are distinct), when there are K of them
+        for (int o = 32; o > 0; o >>= 1) {
+            const uint64_t l2 = __shfl_xor((unsigned long long)low, o);
+            low = l2 < low ? l2 : low;
+        }
+        if ((tid & 63) == 0) s_red[tid >> 6] = low;
+        __syncthreads();
+        for (int w = 0; w < (nt >> 6); ++w) low = s_red[w] < low ? s_red[w] : low;
+        *kth_out = n_out == K ? low : 0ULL;
+        __syncthreads();
+    }
+    if (!want_sorted) return n_out;
     if (P <= nt) {
         // few keys: every thread ranks its key against all the others (no barriers per stage);
         // padding zeros tie among themselves and are ordered by position
@@ -588,6 +611,7 @@ struct SelectParams {
     uint32_t* ovf;          // [B]
     int32_t lds_keys;       // candidates per query the selection gathers in LDS (<= kLdsKeys; sizes its LDS)
     int32_t first, last;
+    int32_t big_sort;       // 1: K above the LDS sort size and the launch's LDS holds k_pad keys (see the kernel)
     int32_t may_overflow;   // 0: the level's regions cannot overflow (every pair admitted, one visit per region): the flag is reset
     int64_t* out_ids;       // [B][K]
     float* out_scores;
@@ -842,6 +866,33 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     } else if (in_lds && !p.srt) {
         n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
                          1, q, 9);
+    } else if (p.big_sort) {
+        // Large K: the set is carried from level to level unordered (only its K-th key is needed);
+        // the last level orders it in LDS, which holds all k_pad keys once the selection's own
+        // buffers are no longer in use.
+        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red, false, &kth);
+        if (p.last) {
+            uint64_t* big = reinterpret_cast<uint64_t*>(sel_lds);  // [k_pad]: the launch sized the LDS for it
+            int P = 1;
+            while (P < n_out) P <<= 1;
+            __syncthreads();
+            for (int i = tid; i < P; i += NT) big[i] = i < n_out ? sorted[i] : 0ULL;
+            __syncthreads();
+            for (int k2 = 2; k2 <= P; k2 <<= 1) {
+                for (int j = k2 >> 1; j > 0; j >>= 1) {
+                    for (int i = tid; i < P; i += NT) {
+                        const int x = i ^ j;
+                        if (x > i) {
+                            const uint64_t a = big[i], b = big[x];
+                            const bool desc = (i & k2) == 0;
+                            if (desc ? (a < b) : (a > b)) { big[i] = b; big[x] = a; }
+                        }
+                    }
+                    __syncthreads();
+                }
+            }
+            sorted = big;
+        }
     } else {
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
         kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
