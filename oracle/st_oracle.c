@@ -14,6 +14,7 @@
  *   - scoring only the items whose mask bit is 1, then ArgTopK  [Sec. 4.3, Alg. 1 phases 3-4,
  *                                                                 every item in scope = all clusters probed]
  *   - the weighted-sum form of the Value Model over T tasks     [Sec. 5.2]
+ *   - publish-time int8 quantisation with one global scale      [Sec. 4.2]
  *   - cluster probing in front of the filter and the scoring (IVF): centroid
  *     scores, the n_p best clusters, filter and scoring inside them [Sec. 4.2, Alg. 1 phases 1-4]
  *   - boolean filter expressions (AND / OR / NOT) over per-feature
@@ -438,6 +439,37 @@ int sto_search_ivf(const uint64_t* sigs, int64_t n_items, int32_t m, int32_t k,
         free(cand); free(cl);
     }
     return failed ? -1 : 0;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Publish-time quantisation.  [Sec. 4.2: global min / max over all embeddings, scaled to the
+ * int8 range, integer representations assigned]
+ * Reading: one scale for the whole table, symmetric about zero so that zero maps to zero and
+ * inner products need no offset terms: a = max(|min|, |max|), s = a / 127 (1 when the table is
+ * all zero), q = round-half-even(x / s) kept inside [-127, 127].  Every row then has the
+ * scale s, which is what row_scale receives (the search takes per-row scales).  minmax[0..1]
+ * receive the global min and max (0, 0 for an empty table).  Values must be finite.
+ */
+void sto_quantize_global(const float* x, int64_t n_rows, int32_t d, int8_t* q, float* row_scale, float* minmax)
+{
+    int64_t n = n_rows * (int64_t)d;
+    float mn = n > 0 ? x[0] : 0.0f, mx = mn;
+    for (int64_t i = 1; i < n; ++i) {
+        if (x[i] < mn) mn = x[i];
+        if (x[i] > mx) mx = x[i];
+    }
+    float a = fabsf(mn) > fabsf(mx) ? fabsf(mn) : fabsf(mx);
+    volatile float s = a > 0.0f ? a / 127.0f : 1.0f;
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float r = x[i] / s;
+        float v = nearbyintf(r);  /* default rounding mode: ties to even */
+        if (v > 127.0f) v = 127.0f;
+        if (v < -127.0f) v = -127.0f;
+        q[i] = (int8_t)v;
+    }
+    for (int64_t i = 0; i < n_rows; ++i) row_scale[i] = s;
+    minmax[0] = mn;
+    minmax[1] = mx;
 }
 
 /* Threads sto_search uses (for reporting the CPU baseline honestly). */

@@ -63,6 +63,8 @@ def lib() -> C.CDLL:
         L.sto_search_ivf.restype = C.c_int
         L.sto_search_ivf.argtypes = [p, C.c_int64, C.c_int32, C.c_int32, p, p, C.c_int32, p, p, p, C.c_int32,
                                      C.c_int32, p, p, C.c_int32, p, p, p, C.c_int32, p, p, p, p]
+        L.sto_quantize_global.restype = None
+        L.sto_quantize_global.argtypes = [p, C.c_int64, C.c_int32, p, p, p]
         L.sto_num_threads.restype = C.c_int32
         L.sto_num_threads.argtypes = []
         _lib = L
@@ -262,6 +264,17 @@ def search_ivf(sigs, m, k, items, item_scale, centroids, centroid_scale, cluster
     if rc != 0:
         raise MemoryError("oracle ran out of memory")
     return ids, scores, count, probes
+
+
+def quantize_global(x):
+    """fp32 [N, d] -> (int8 [N, d], row scales fp32 [N], (min, max))."""
+    x = _arr(x, np.float32)
+    assert x.ndim == 2
+    q = np.empty(x.shape, dtype=np.int8)
+    rs = np.empty(x.shape[0], dtype=np.float32)
+    mm = np.empty(2, dtype=np.float32)
+    lib().sto_quantize_global(_ptr(x), x.shape[0], x.shape[1], _ptr(q), _ptr(rs), _ptr(mm))
+    return q, rs, (float(mm[0]), float(mm[1]))
 
 
 def num_threads() -> int:
