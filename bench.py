@@ -137,6 +137,65 @@ def stats_ivf(st, bloom, w, prog, coff, probes, n_clusters):
             "probed_item_fraction": float(probed_words * 64) / max(cfg.n_items * cfg.batch, 1)}
 
 
+def quantize_bench(args, cfg, torch, st):
+    """Publish-time quantisation of an fp32 [n_items, d] table: two passes (min / max, then codes),
+    9 bytes per value of algorithmic traffic."""
+    n, d = cfg.n_items, cfg.d
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20251114)
+    x = torch.randn((n, d), generator=gen, device="cuda", dtype=torch.float32)
+    q = torch.empty((n, d), dtype=torch.int8, device="cuda")
+    rs = torch.empty(n, dtype=torch.float32, device="cuda")
+    mm = torch.empty(2, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(2, dtype=torch.int32, device="cuda")
+    import ctypes as C
+    stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+    def step():
+        rc = st.lib().st_quantize_global(C.c_void_p(x.data_ptr()), n, d, C.c_void_p(q.data_ptr()), C.c_void_p(rs.data_ptr()),
+                                         C.c_void_p(mm.data_ptr()), C.c_void_p(scratch.data_ptr()), stream)
+        if rc != 0:
+            raise RuntimeError(st.last_error())
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    st.st_timing_begin(args.steps * 2 + 8)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    k_ms = st.st_timing_end()["scan"][0] / args.steps
+    a_bytes = 9 * n * d + 4 * n
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import st_oracle as O
+        n_s = min(n, 2_000_000)
+        xs = x[:n_s].cpu().numpy()
+        reps, spent = 0, 0.0
+        while spent < args.cpu_seconds and reps < 100:
+            t0 = time.perf_counter()
+            O.quantize_global(xs)
+            spent += time.perf_counter() - t0
+            reps += 1
+        cpu = {"value": n_s / (spent / reps), "unit": "items/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n_s} rows, {reps} repetitions, {spent:.1f} s"}
+    print(json.dumps({
+        "metric": "int8 quantisation items/sec", "value": n / (ms * 1e-3), "unit": "items/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name + "+quantize", "n_items": n, "d": d},
+        "roofline": {"bound": "hbm", "achieved": a_bytes / (k_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": a_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "quant_minmax + quant_apply", "kernel_ms_per_step": k_ms,
+                     "algorithmic_bytes_per_step": a_bytes},
+        "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -153,6 +212,9 @@ def main():
                     help="variant of the workload: every query's filter is a boolean program of the "
                          "paper's query form (a term AND an OR-group, every second one AND NOT a term), run "
                          "through st_search_expr; reported as its own workload name")
+    ap.add_argument("--quantize", action="store_true",
+                    help="time the publish-time int8 quantisation (st_quantize_global) of an fp32 table of the "
+                         "workload's shape instead of the search; prints its own JSON line")
     ap.add_argument("--top-k", type=int, default=0,
                     help="variant of the workload: another K (the paper's pre-filter sizes are O(10,000)); "
                          "reported as its own workload name")
@@ -178,6 +240,9 @@ def main():
         sys.exit(2)
     st.lib()  # fail loudly if the HIP library is missing
     cfg = synth.CONFIGS[args.config]
+    if args.quantize:
+        quantize_bench(args, cfg, torch, st)
+        return
     if args.distinct_filters:
         cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
     if args.top_k > 0:

@@ -246,6 +246,22 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
                   int32_t* dev_out_probes, void* dev_workspace, int64_t workspace_bytes,
                   void* hip_stream);
 
+/* ------------------------------------------------------------------ publish-time quantisation
+ * Int8 quantisation of an embedding table with one global scale (Sec. 4.2: global min / max
+ * over all embeddings, scaled to the int8 range).  Reading: symmetric about zero, so that zero
+ * maps to zero and inner products need no offset terms: a = max(|min|, |max|), s = a / 127
+ * (s = 1 for an all-zero table), q = round-half-even(x / s) kept inside [-127, 127].
+ *   dev_x          [n_rows, d] fp32 row-major, 16-byte aligned, finite values
+ *   dev_q          [n_rows, d] int8 out, 16-byte aligned: the items / queries layout of st_search
+ *   dev_row_scale  [n_rows] fp32 out, every entry = s (the search takes per-row scales)
+ *   dev_minmax     [2] fp32 out: global min and max (0, 0 for an empty table)
+ *   dev_scratch8   8 bytes of device scratch, 8-byte aligned (the running min / max)
+ * 1 <= d <= ST_MAX_DIM (any d, not only multiples of 16), n_rows * d <= 2^40.  Three kernels on
+ * hip_stream, asynchronous, no allocation. */
+int st_quantize_global(const float* dev_x, int64_t n_rows, int32_t d, int8_t* dev_q,
+                       float* dev_row_scale, float* dev_minmax, void* dev_scratch8,
+                       void* hip_stream);
+
 /* Search scheduling knobs, mainly for tests: path = 0 auto, 1 force the wavefront
  * dot-product scorer, 2 force the int8 MFMA scorer where it applies.  Returns the old value. */
 int32_t st_set_scoring_path(int32_t path);

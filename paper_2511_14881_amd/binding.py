@@ -22,7 +22,7 @@ EXPORTS = [
     "st_search_workspace_bytes", "st_search", "st_search_multitask", "st_score_pairs",
     "st_search_plan", "st_set_scoring_path", "st_timing_begin", "st_timing_end",
     "st_search_overflow_flags_offset", "st_bloom_mask_expr", "st_search_expr_workspace_bytes",
-    "st_search_expr", "st_search_ivf_workspace_bytes", "st_search_ivf",
+    "st_search_expr", "st_search_ivf_workspace_bytes", "st_search_ivf", "st_quantize_global",
 ]
 
 ST_OP_LEAF, ST_OP_AND, ST_OP_OR, ST_OP_NOT = 0, 1, 2, 3  # operations of a filter program
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.st_search_ivf.restype = C.c_int
         L.st_search_ivf.argtypes = [p, p, p, i64, i32, p, p, p, i32, i32, p, p, i32, p, p, p, i32, p, p, p, p, p,
                                     i64, p]
+        L.st_quantize_global.restype = C.c_int
+        L.st_quantize_global.argtypes = [p, i64, i32, p, p, p, p, p]
         _lib = L
     return _lib
 
@@ -390,6 +392,20 @@ def st_search_ivf(bloom: BloomIndex, items, item_scale, centroids, centroid_scal
                                _dptr(buf.scores), _dptr(buf.count), _dptr(buf.probes), _dptr(buf.workspace),
                                buf.nbytes, _stream(stream)))
     return buf.ids, buf.scores, buf.count, buf.probes
+
+
+def st_quantize_global(x, stream=None):
+    """fp32 [N, d] CUDA tensor -> (int8 [N, d], row scales fp32 [N], minmax fp32 [2]) on the device."""
+    _need(x, torch.float32, "x")
+    if x.dim() != 2:
+        raise ValueError("x must be [N, d]")
+    n, d = x.shape
+    q = torch.empty((n, d), dtype=torch.int8, device="cuda")
+    rs = torch.empty(n, dtype=torch.float32, device="cuda")
+    mm = torch.empty(2, dtype=torch.float32, device="cuda")
+    scratch = torch.empty(2, dtype=torch.int32, device="cuda")
+    _check(lib().st_quantize_global(_dptr(x), n, d, _dptr(q), _dptr(rs), _dptr(mm), _dptr(scratch), _stream(stream)))
+    return q, rs, mm
 
 
 def st_score_pairs(items, item_scale, queries, query_scale, pair_item, pair_query, stream=None):

@@ -18,6 +18,7 @@
 #include "st_bloom_kernels.h"
 #include "st_mfma_kernels.h"
 #include "st_ivf_kernels.h"
+#include "st_quant_kernels.h"
 #include "st_plan.h"
 #include "st_search_kernels.h"
 
@@ -1195,6 +1196,35 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, 1, nullptr,
                        nullptr, nullptr, K, dev_out_ids, dev_out_scores, dev_out_count, dev_workspace, base,
                        hip_stream, &groups, mask_rows, batch, false, kIvfCap);
+}
+
+int st_quantize_global(const float* dev_x, int64_t n_rows, int32_t d, int8_t* dev_q, float* dev_row_scale,
+                       float* dev_minmax, void* dev_scratch8, void* hip_stream)
+{
+    if (n_rows < 0 || d < 1 || d > ST_MAX_DIM || n_rows > (1LL << 40) / d)
+        return fail(ST_EINVAL, "bad table size %lld x %d", (long long)n_rows, d);
+    if (!dev_minmax || !dev_scratch8 || (n_rows > 0 && (!dev_x || !dev_q || !dev_row_scale)))
+        return fail(ST_EINVAL, "null argument");
+    if (((uintptr_t)dev_x & 15) || ((uintptr_t)dev_q & 15) || ((uintptr_t)dev_scratch8 & 7))
+        return fail(ST_EINVAL, "misaligned buffer (table and output 16 B, scratch 8 B)");
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const int64_t n = n_rows * d;
+    uint32_t* mm = (uint32_t*)dev_scratch8;
+    // enough workgroups to fill the chip, each streaming many values
+    const unsigned grid = (unsigned)std::max<int64_t>(1, std::min<int64_t>((n / 16 + st::kQuantThreads - 1) / st::kQuantThreads,
+                                                                         st::kComputeUnits * 16));
+    hipLaunchKernelGGL(st::quant_init_kernel, dim3(1), dim3(64), 0, stream, mm);
+    if (n > 0) {
+        TimedLaunch t(0, stream);
+        hipLaunchKernelGGL(st::quant_minmax_kernel, dim3(grid), dim3(st::kQuantThreads), 0, stream, dev_x, n, mm);
+    }
+    {
+        TimedLaunch t(0, stream);
+        hipLaunchKernelGGL(st::quant_apply_kernel, dim3(grid), dim3(st::kQuantThreads), 0, stream, dev_x, n, n_rows, mm,
+                           dev_q, dev_row_scale, dev_minmax);
+    }
+    ST_HIP(hipGetLastError());
+    return ST_OK;
 }
 
 int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t d, const int8_t* dev_queries,
