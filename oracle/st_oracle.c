@@ -15,6 +15,7 @@
  *                                                                 every item in scope = all clusters probed]
  *   - the weighted-sum form of the Value Model over T tasks     [Sec. 5.2]
  *   - publish-time int8 quantisation with one global scale      [Sec. 4.2]
+ *   - Value Model formulas over per-task scores, as a postfix program [Sec. 5.2]
  *   - cluster probing in front of the filter and the scoring (IVF): centroid
  *     scores, the n_p best clusters, filter and scoring inside them [Sec. 4.2, Alg. 1 phases 1-4]
  *   - boolean filter expressions (AND / OR / NOT) over per-feature
@@ -470,6 +471,80 @@ void sto_quantize_global(const float* x, int64_t n_rows, int32_t d, int8_t* q, f
     for (int64_t i = 0; i < n_rows; ++i) row_scale[i] = s;
     minmax[0] = mn;
     minmax[1] = mx;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Value Model formulas.  [Sec. 5.2: per-task predictions are combined into one score by a
+ * user-defined formula with conditions, parsed into a tree and evaluated for many items]
+ * The tree arrives flattened in postfix order.  Entry i has code ops[i] & 255:
+ *   0 TASK   push the item's score of task (ops[i] >> 8)
+ *   1 CONST  push consts[i]
+ *   2 ADD  3 SUB  4 MUL  5 MIN  6 MAX      pop b, pop a, push a op b   (one fp32 rounding each)
+ *   7 GT     pop b, pop a, push (a > b ? 1.0f : 0.0f)
+ *   8 SELECT pop y, pop x, pop c, push (c != 0 ? x : y)                   (the conditions)
+ * One result must remain.  scores is [n, n_tasks] row-major, out is [n].
+ * Returns 0, or -1 for an ill-formed program (unknown code, missing operands, task out of
+ * range, more than one result, deeper than 16).
+ */
+enum { STO_VM_TASK = 0, STO_VM_CONST, STO_VM_ADD, STO_VM_SUB, STO_VM_MUL, STO_VM_MIN, STO_VM_MAX, STO_VM_GT, STO_VM_SELECT };
+
+int32_t sto_vm_depth(const int32_t* ops, int32_t n_ops, int32_t n_tasks)
+{
+    int32_t depth = 0, deepest = 0;
+    for (int32_t i = 0; i < n_ops; ++i) {
+        int32_t code = ops[i] & 255;
+        if (code == STO_VM_TASK) {
+            if ((ops[i] >> 8) < 0 || (ops[i] >> 8) >= n_tasks) return -1;
+            ++depth;
+        } else if (code == STO_VM_CONST) {
+            ++depth;
+        } else if (code >= STO_VM_ADD && code <= STO_VM_GT) {
+            if (depth < 2) return -1;
+            --depth;
+        } else if (code == STO_VM_SELECT) {
+            if (depth < 3) return -1;
+            depth -= 2;
+        } else {
+            return -1;
+        }
+        if (depth > deepest) deepest = depth;
+    }
+    if (depth != 1 || deepest > 16) return -1;
+    return deepest;
+}
+
+int sto_value_model(const float* scores, int64_t n, int32_t n_tasks, const int32_t* ops, const float* consts,
+                    int32_t n_ops, float* out)
+{
+    if (sto_vm_depth(ops, n_ops, n_tasks) < 0) return -1;
+    for (int64_t it = 0; it < n; ++it) {
+        volatile float st[16];
+        int top = 0;
+        for (int32_t i = 0; i < n_ops; ++i) {
+            int32_t code = ops[i] & 255;
+            if (code == STO_VM_TASK) {
+                st[top++] = scores[it * n_tasks + (ops[i] >> 8)];
+            } else if (code == STO_VM_CONST) {
+                st[top++] = consts[i];
+            } else if (code == STO_VM_SELECT) {
+                float y = st[--top], x = st[--top], c = st[--top];
+                st[top++] = c != 0.0f ? x : y;
+            } else {
+                float b = st[--top], a = st[--top], r;
+                switch (code) {
+                case STO_VM_ADD: r = a + b; break;
+                case STO_VM_SUB: r = a - b; break;
+                case STO_VM_MUL: r = a * b; break;
+                case STO_VM_MIN: r = a < b ? a : b; break;
+                case STO_VM_MAX: r = a > b ? a : b; break;
+                default: r = a > b ? 1.0f : 0.0f; break;
+                }
+                st[top++] = r;
+            }
+        }
+        out[it] = st[0];
+    }
+    return 0;
 }
 
 /* Threads sto_search uses (for reporting the CPU baseline honestly). */

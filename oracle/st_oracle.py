@@ -65,6 +65,10 @@ def lib() -> C.CDLL:
                                      C.c_int32, p, p, C.c_int32, p, p, p, C.c_int32, p, p, p, p]
         L.sto_quantize_global.restype = None
         L.sto_quantize_global.argtypes = [p, C.c_int64, C.c_int32, p, p, p]
+        L.sto_vm_depth.restype = C.c_int32
+        L.sto_vm_depth.argtypes = [p, C.c_int32, C.c_int32]
+        L.sto_value_model.restype = C.c_int
+        L.sto_value_model.argtypes = [p, C.c_int64, C.c_int32, p, p, C.c_int32, p]
         L.sto_num_threads.restype = C.c_int32
         L.sto_num_threads.argtypes = []
         _lib = L
@@ -275,6 +279,32 @@ def quantize_global(x):
     mm = np.empty(2, dtype=np.float32)
     lib().sto_quantize_global(_ptr(x), x.shape[0], x.shape[1], _ptr(q), _ptr(rs), _ptr(mm))
     return q, rs, (float(mm[0]), float(mm[1]))
+
+
+VM_TASK, VM_CONST, VM_ADD, VM_SUB, VM_MUL, VM_MIN, VM_MAX, VM_GT, VM_SELECT = range(9)
+
+
+def vm_task(t: int) -> int:
+    """Program entry that pushes the score of task t."""
+    return VM_TASK | (t << 8)
+
+
+def vm_depth(ops, n_tasks: int) -> int:
+    ops = _arr(ops, np.int32)
+    return int(lib().sto_vm_depth(_ptr(ops), ops.size, n_tasks))
+
+
+def value_model(scores, ops, consts) -> np.ndarray:
+    """scores fp32 [n, T]; postfix program (ops int32, consts fp32, same length) -> fp32 [n]."""
+    scores = _arr(scores, np.float32)
+    ops = _arr(ops, np.int32)
+    consts = _arr(consts, np.float32)
+    assert scores.ndim == 2 and ops.size == consts.size
+    out = np.empty(scores.shape[0], dtype=np.float32)
+    if lib().sto_value_model(_ptr(scores), scores.shape[0], scores.shape[1], _ptr(ops), _ptr(consts), ops.size,
+                             _ptr(out)) != 0:
+        raise ValueError("ill-formed value model program")
+    return out
 
 
 def num_threads() -> int:
