@@ -196,6 +196,63 @@ def quantize_bench(args, cfg, torch, st):
         "cpu_baseline": cpu}))
 
 
+def value_model_bench(args, cfg, torch, st):
+    """A formula with a condition over four task scores per item: if s2 > 0.5 then
+    0.4*s0 + 0.3*s1 + 0.2*s2 + 0.1*s3 else min(s0, s1) * 0.5.  20 bytes per item."""
+    n, T = cfg.n_items, 4
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(20251114)
+    scores = torch.rand((n, T), generator=gen, device="cuda", dtype=torch.float32)
+    out = torch.empty(n, dtype=torch.float32, device="cuda")
+    TASK = lambda t: 0 | (t << 8)
+    prog = [(TASK(2), 0), (1, 0.5), (7, 0),
+            (1, 0.4), (TASK(0), 0), (4, 0), (1, 0.3), (TASK(1), 0), (4, 0), (2, 0), (1, 0.2), (TASK(2), 0), (4, 0), (2, 0),
+            (1, 0.1), (TASK(3), 0), (4, 0), (2, 0),
+            (TASK(0), 0), (TASK(1), 0), (5, 0), (1, 0.5), (4, 0), (8, 0)]
+    ops = [p[0] for p in prog]
+    consts = [float(p[1]) for p in prog]
+
+    def step():
+        st.st_value_model(scores, ops, consts, out=out)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    st.st_timing_begin(args.steps + 8)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    k_ms = st.st_timing_end()["scan"][0] / args.steps
+    a_bytes = n * (4 * T + 4)
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import st_oracle as O
+        n_s = min(n, 2_000_000)
+        xs = scores[:n_s].cpu().numpy()
+        reps, spent = 0, 0.0
+        while spent < args.cpu_seconds and reps < 100:
+            t0 = time.perf_counter()
+            O.value_model(xs, ops, consts)
+            spent += time.perf_counter() - t0
+            reps += 1
+        cpu = {"value": n_s / (spent / reps), "unit": "items/s", "cores": 1, "kind": "oracle",
+               "sample": f"first {n_s} items, {reps} repetitions, {spent:.1f} s"}
+    print(json.dumps({
+        "metric": "value model items/sec", "value": n / (ms * 1e-3), "unit": "items/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": cfg.name + "+value-model", "n_items": n, "n_tasks": T, "formula_entries": len(ops)},
+        "roofline": {"bound": "hbm", "achieved": a_bytes / (k_ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": a_bytes / (k_ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "kernel": "value_model", "kernel_ms_per_step": k_ms, "algorithmic_bytes_per_step": a_bytes},
+        "cpu_baseline": cpu}))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -215,6 +272,9 @@ def main():
     ap.add_argument("--quantize", action="store_true",
                     help="time the publish-time int8 quantisation (st_quantize_global) of an fp32 table of the "
                          "workload's shape instead of the search; prints its own JSON line")
+    ap.add_argument("--value-model", action="store_true",
+                    help="time a Value Model formula (st_value_model) over n_items x 4 task scores instead of the "
+                         "search; prints its own JSON line")
     ap.add_argument("--top-k", type=int, default=0,
                     help="variant of the workload: another K (the paper's pre-filter sizes are O(10,000)); "
                          "reported as its own workload name")
@@ -242,6 +302,9 @@ def main():
     cfg = synth.CONFIGS[args.config]
     if args.quantize:
         quantize_bench(args, cfg, torch, st)
+        return
+    if args.value_model:
+        value_model_bench(args, cfg, torch, st)
         return
     if args.distinct_filters:
         cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")

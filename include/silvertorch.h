@@ -57,6 +57,20 @@ typedef enum st_status {
 #define ST_MAX_EXPR_OPS 256     /* entries of one filter program */
 #define ST_MAX_EXPR_DEPTH 16    /* results a filter program may hold on its stack at once */
 
+#define ST_MAX_VM_OPS 64        /* entries of a Value Model formula */
+#define ST_MAX_VM_DEPTH 16      /* values a formula may hold on its stack at once */
+
+/* operations of a Value Model formula (st_value_model): code = entry & 255 */
+#define ST_VM_TASK 0            /* push the item's score of task (entry >> 8) */
+#define ST_VM_CONST 1           /* push the entry's constant */
+#define ST_VM_ADD 2             /* pop b, pop a, push a + b (one fp32 rounding; likewise below) */
+#define ST_VM_SUB 3             /* a - b */
+#define ST_VM_MUL 4             /* a * b */
+#define ST_VM_MIN 5             /* a < b ? a : b */
+#define ST_VM_MAX 6             /* a > b ? a : b */
+#define ST_VM_GT 7              /* a > b ? 1.0f : 0.0f */
+#define ST_VM_SELECT 8          /* pop y, pop x, pop c, push c != 0 ? x : y */
+
 /* operations of a filter program (st_bloom_mask_expr, st_search_expr) */
 #define ST_OP_LEAF 0            /* push: the item passes the Bloom test of one feature id */
 #define ST_OP_AND 1             /* pop two results, push their conjunction */
@@ -261,6 +275,21 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
 int st_quantize_global(const float* dev_x, int64_t n_rows, int32_t d, int8_t* dev_q,
                        float* dev_row_scale, float* dev_minmax, void* dev_scratch8,
                        void* hip_stream);
+
+/* ------------------------------------------------------------------ Value Model formulas
+ * Combines the per-task scores of n items into one score each by a user formula with
+ * conditions (Sec. 5.2: formulas are parsed into a tree and a GPU kernel evaluates them for
+ * many items in parallel).  The tree is passed flattened in postfix order: host_ops[i] is an
+ * ST_VM_* code (ST_VM_TASK | task << 8 for a task's score), host_consts[i] the constant of an
+ * ST_VM_CONST entry (ignored otherwise, but finite).  The weighted sum of st_search_multitask
+ * is one such formula (with separately rounded multiply and add instead of its fused chain).
+ *   dev_task_scores [n, n_tasks] fp32 row-major; dev_out [n] fp32; 1 <= n_tasks <= 64
+ * ST_EINVAL for an ill-formed formula (unknown code, missing operands, task out of range, not
+ * exactly one result, more than ST_MAX_VM_OPS entries, deeper than ST_MAX_VM_DEPTH).
+ * One kernel on hip_stream, asynchronous, no allocation; the formula travels in its arguments. */
+int st_value_model(const float* dev_task_scores, int64_t n, int32_t n_tasks,
+                   const int32_t* host_ops, const float* host_consts, int32_t n_ops,
+                   float* dev_out, void* hip_stream);
 
 /* Search scheduling knobs, mainly for tests: path = 0 auto, 1 force the wavefront
  * dot-product scorer, 2 force the int8 MFMA scorer where it applies.  Returns the old value. */

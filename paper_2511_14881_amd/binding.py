@@ -22,7 +22,7 @@ EXPORTS = [
     "st_search_workspace_bytes", "st_search", "st_search_multitask", "st_score_pairs",
     "st_search_plan", "st_set_scoring_path", "st_timing_begin", "st_timing_end",
     "st_search_overflow_flags_offset", "st_bloom_mask_expr", "st_search_expr_workspace_bytes",
-    "st_search_expr", "st_search_ivf_workspace_bytes", "st_search_ivf", "st_quantize_global",
+    "st_search_expr", "st_search_ivf_workspace_bytes", "st_search_ivf", "st_quantize_global", "st_value_model",
 ]
 
 ST_OP_LEAF, ST_OP_AND, ST_OP_OR, ST_OP_NOT = 0, 1, 2, 3  # operations of a filter program
@@ -89,6 +89,8 @@ def lib() -> C.CDLL:
         L.st_search_ivf.restype = C.c_int
         L.st_search_ivf.argtypes = [p, p, p, i64, i32, p, p, p, i32, i32, p, p, i32, p, p, p, i32, p, p, p, p, p,
                                     i64, p]
+        L.st_value_model.restype = C.c_int
+        L.st_value_model.argtypes = [p, i64, i32, p, p, i32, p, p]
         L.st_quantize_global.restype = C.c_int
         L.st_quantize_global.argtypes = [p, i64, i32, p, p, p, p, p]
         _lib = L
@@ -406,6 +408,22 @@ def st_quantize_global(x, stream=None):
     scratch = torch.empty(2, dtype=torch.int32, device="cuda")
     _check(lib().st_quantize_global(_dptr(x), n, d, _dptr(q), _dptr(rs), _dptr(mm), _dptr(scratch), _stream(stream)))
     return q, rs, mm
+
+
+def st_value_model(task_scores, ops, consts, out=None, stream=None):
+    """task_scores fp32 [n, T] CUDA tensor; postfix formula (ops int32, consts fp32) -> fp32 [n]."""
+    _need(task_scores, torch.float32, "task_scores")
+    if task_scores.dim() != 2:
+        raise ValueError("task_scores must be [n, T]")
+    n, T = task_scores.shape
+    o = np.ascontiguousarray(np.asarray(ops, dtype=np.int32))
+    c = np.ascontiguousarray(np.asarray(consts, dtype=np.float32))
+    if o.size != c.size:
+        raise ValueError("ops and consts differ in length")
+    if out is None:
+        out = torch.empty(n, dtype=torch.float32, device="cuda")
+    _check(lib().st_value_model(_dptr(task_scores), n, T, _hptr(o), _hptr(c), o.size, _dptr(out), _stream(stream)))
+    return out
 
 
 def st_score_pairs(items, item_scale, queries, query_scale, pair_item, pair_query, stream=None):

@@ -19,6 +19,7 @@
 #include "st_mfma_kernels.h"
 #include "st_ivf_kernels.h"
 #include "st_quant_kernels.h"
+#include "st_vm_kernels.h"
 #include "st_plan.h"
 #include "st_search_kernels.h"
 
@@ -1222,6 +1223,59 @@ int st_quantize_global(const float* dev_x, int64_t n_rows, int32_t d, int8_t* de
         TimedLaunch t(0, stream);
         hipLaunchKernelGGL(st::quant_apply_kernel, dim3(grid), dim3(st::kQuantThreads), 0, stream, dev_x, n, n_rows, mm,
                            dev_q, dev_row_scale, dev_minmax);
+    }
+    ST_HIP(hipGetLastError());
+    return ST_OK;
+}
+
+int st_value_model(const float* dev_task_scores, int64_t n, int32_t n_tasks, const int32_t* host_ops,
+                   const float* host_consts, int32_t n_ops, float* dev_out, void* hip_stream)
+{
+    static_assert(ST_MAX_VM_OPS == st::kVmOps && ST_MAX_VM_DEPTH == st::kVmDepth, "formula limits follow the kernel");
+    if (n < 0 || n_tasks < 1 || n_tasks > 64) return fail(ST_EINVAL, "bad sizes");
+    if (!host_ops || !host_consts || (n > 0 && (!dev_task_scores || !dev_out))) return fail(ST_EINVAL, "null argument");
+    if (n_ops < 1 || n_ops > ST_MAX_VM_OPS) return fail(ST_EINVAL, "formula has %d entries (1 to %d)", n_ops, ST_MAX_VM_OPS);
+    st::VmProgram prog;
+    memset(&prog, 0, sizeof(prog));
+    prog.n_ops = n_ops;
+    int depth = 0, deepest = 0;
+    for (int32_t i = 0; i < n_ops; ++i) {
+        const int32_t code = host_ops[i] & 255;
+        switch (code) {
+        case ST_VM_TASK:
+            if ((host_ops[i] >> 8) < 0 || (host_ops[i] >> 8) >= n_tasks)
+                return fail(ST_EINVAL, "formula entry %d names task %d of %d", i, host_ops[i] >> 8, n_tasks);
+            ++depth;
+            break;
+        case ST_VM_CONST:
+            if (!std::isfinite(host_consts[i])) return fail(ST_EINVAL, "formula constant %d is not finite", i);
+            ++depth;
+            break;
+        case ST_VM_ADD: case ST_VM_SUB: case ST_VM_MUL: case ST_VM_MIN: case ST_VM_MAX: case ST_VM_GT:
+            if (depth < 2) return fail(ST_EINVAL, "formula entry %d lacks operands", i);
+            --depth;
+            break;
+        case ST_VM_SELECT:
+            if (depth < 3) return fail(ST_EINVAL, "formula entry %d lacks operands", i);
+            depth -= 2;
+            break;
+        default:
+            return fail(ST_EINVAL, "formula entry %d: unknown operation %d", i, code);
+        }
+        if (depth > ST_MAX_VM_DEPTH) return fail(ST_EINVAL, "formula needs a stack deeper than %d", ST_MAX_VM_DEPTH);
+        deepest = std::max(deepest, depth);
+        prog.ops[i] = host_ops[i];
+        prog.consts[i] = host_consts[i];
+    }
+    if (depth != 1) return fail(ST_EINVAL, "formula leaves %d results", depth);
+    if (n == 0) return ST_OK;
+    const int64_t quads = (n + st::kVmItems - 1) / st::kVmItems;
+    const unsigned grid = (unsigned)std::min<int64_t>((quads + st::kVmThreads - 1) / st::kVmThreads, st::kComputeUnits * 16);
+    {
+        TimedLaunch t(0, (hipStream_t)hip_stream);
+        hipLaunchKernelGGL(st::value_model_kernel, dim3(grid), dim3(st::kVmThreads),
+                           (size_t)deepest * st::kVmThreads * sizeof(float4), (hipStream_t)hip_stream,
+                           dev_task_scores, n, n_tasks, prog, dev_out);
     }
     ST_HIP(hipGetLastError());
     return ST_OK;
