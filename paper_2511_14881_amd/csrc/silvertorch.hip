@@ -628,11 +628,12 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             if (rows >= min_rows) blocks_big += (rows + 15) / 16;
         }
         if (blocks_big > 0 && blocks_all <= std::max<int64_t>(2 * blocks_big, blocks_big + 8)) min_rows = 1;
-        // likewise when the padded rows of all groups together still fit four rows of workgroups:
-        // one scan with mostly empty query blocks measured faster than the dot-product scorer's
-        // pass per small group (a batch where every query has its own filter: 0.15 vs 0.23 ms at
-        // 1M x 128)
-        if (groups.n_groups <= st::kMfmaMaxGroups && blocks_all * 16 * d <= 4 * (int64_t)st::kMfmaQueryLds) min_rows = 1;
+        // likewise, next to a dense group, when the padded rows of all groups together still fit four
+        // rows of workgroups.  With no dense group at all (every query its own filter, single task)
+        // the dot-product scorer takes the whole batch: 0.125 vs 0.152 ms of scan at 1M x 128, and
+        // 0.093 vs 0.169 ms behind cluster probing, where most (query, segment) lists are empty.
+        if (blocks_big > 0 && groups.n_groups <= st::kMfmaMaxGroups && blocks_all * 16 * d <= 4 * (int64_t)st::kMfmaQueryLds)
+            min_rows = 1;
     }
     GroupSet set_mfma, set_dot;
     std::vector<int32_t> blk_off{0}, blk_row;
