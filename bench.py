@@ -275,6 +275,9 @@ def main():
     ap.add_argument("--value-model", action="store_true",
                     help="time a Value Model formula (st_value_model) over n_items x 4 task scores instead of the "
                          "search; prints its own JSON line")
+    ap.add_argument("--batch", type=int, default=0,
+                    help="variant of the workload: another batch size (the paper's ANN runs use 16); "
+                         "reported as its own workload name")
     ap.add_argument("--top-k", type=int, default=0,
                     help="variant of the workload: another K (the paper's pre-filter sizes are O(10,000)); "
                          "reported as its own workload name")
@@ -310,6 +313,8 @@ def main():
         cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
     if args.top_k > 0:
         cfg = synth.scaled(cfg, cfg.n_items, top_k=args.top_k, name=cfg.name + "+K%d" % args.top_k)
+    if args.batch > 0:
+        cfg = synth.scaled(cfg, cfg.n_items, batch=args.batch, pool=min(cfg.pool, args.batch), name=cfg.name + "+B%d" % args.batch)
     ivf = None
     if args.ivf:
         ivf = tuple(int(x) for x in args.ivf.split(":"))
@@ -402,7 +407,7 @@ def main():
     tpath = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tpath):
         try:
-            variant = args.distinct_filters or args.filter_programs or args.top_k > 0
+            variant = args.distinct_filters or args.filter_programs or args.top_k > 0 or args.batch > 0
             traffic = None if variant else json.load(open(tpath)).get(args.config)
         except Exception:
             traffic = None

@@ -626,7 +626,7 @@ constexpr int kLdsKeys = kSelectLdsKeys;  // candidates per query gathered in LD
 
 // Slow exact path for a query whose candidate region overflowed in some level: rescans the whole
 // corpus for that query alone, keeping at most gath_cap keys and pruning to the best K whenever
-// the buffer cannot take another tile.  Called by the whole workgroup.
+// the buffer cannot take another round.  Called by the whole workgroup.
 __device__ inline void rescue_query(const SelectParams& r, int q, uint64_t* s_sorted, uint32_t* s_hist,
                                     uint32_t* s_misc, uint64_t* s_red, uint64_t* s_mask, uint32_t* s_n)
 {
@@ -639,9 +639,14 @@ __device__ inline void rescue_query(const SelectParams& r, int q, uint64_t* s_so
     uint64_t tau = 0;
     if (tid == 0) *s_n = 0;
     __syncthreads();
-    const int64_t n_tiles = (p.n_items + kTileItems - 1) / kTileItems;
-    for (int64_t tile = 0; tile < n_tiles; ++tile) {
-        if ((int64_t)*s_n + kTileItems > r.gath_cap) {  // uniform: *s_n is stable between barriers
+    // A thread owns one 64-item word per round and scores the items it admits itself: rounds of up to
+    // blockDim.x words, as many as the buffer is sure to hold beside the K keys kept (one tile at least).
+    const int64_t n_words = (p.n_items + 63) >> 6;
+    int64_t wpr = (r.gath_cap - r.K) / 64;
+    wpr = wpr > nt ? nt : (wpr < kTileWords ? kTileWords : wpr);
+    (void)s_mask;
+    for (int64_t w0 = 0; w0 < n_words; w0 += wpr) {
+        if ((int64_t)*s_n + wpr * 64 > r.gath_cap) {  // uniform: *s_n is stable between barriers
             const int n_out = wg_topk(buf, (int64_t)*s_n, r.K, sorted, r.k_pad, s_hist, s_misc, s_red);
             for (int i = tid; i < n_out; i += nt) buf[i] = sorted[i];
             tau = n_out == r.K ? sorted[r.K - 1] : 0ULL;
@@ -649,17 +654,16 @@ __device__ inline void rescue_query(const SelectParams& r, int q, uint64_t* s_so
             if (tid == 0) *s_n = (uint32_t)n_out;
             __syncthreads();
         }
-        if (tid < kTileWords)
-            s_mask[tid] = bloom_mask_word(p.bloom, p.m_bits, tile * kTileWords + tid, p.n_items,
-                                          p.grp_rows + r0, r1 - r0);
-        __syncthreads();
-        for (int loc = tid; loc < kTileItems; loc += nt) {
-            if ((s_mask[loc >> 6] >> (loc & 63)) & 1ULL) {
-                const int64_t item = tile * kTileItems + loc;
-                const float sc = pair_score(p, q, p.items + item * p.d, p.iscale[item]);
-                const uint64_t key = make_key(sc, (uint32_t)item);
-                if (key >= tau) buf[atomicAdd(s_n, 1u)] = key;
-            }
+        const int64_t gw = w0 + tid;
+        uint64_t m = 0;
+        if (tid < wpr && gw < n_words) m = bloom_mask_word(p.bloom, p.m_bits, gw, p.n_items, p.grp_rows + r0, r1 - r0);
+        while (m) {
+            const int bit = __ffsll((long long)m) - 1;
+            m &= m - 1;
+            const int64_t item = gw * 64 + bit;
+            const float sc = pair_score(p, q, p.items + item * p.d, p.iscale[item]);
+            const uint64_t key = make_key(sc, (uint32_t)item);
+            if (key >= tau) buf[atomicAdd(s_n, 1u)] = key;
         }
         __syncthreads();
     }
