@@ -1145,6 +1145,17 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
     ip.probes = (int32_t*)(tail + st::round_up((int64_t)batch * n_clusters * 8, 256));
     ip.user_probes = dev_out_probes;
 
+    // Few enough probes for one workgroup to lay out: phases 2-4 run per query over the probed
+    // ranges alone.  (A forced scoring path selects the scan-based route below instead, which also
+    // serves larger probe counts.)
+    const bool per_query = g_scoring_path == 0 && n_probe <= st::kQueryProbes;
+    if (per_query) {
+        if (!dev_out_ids || !dev_out_scores || !dev_out_count || (n_items > 0 && (!dev_items || !dev_item_scale)))
+            return fail(ST_EINVAL, "null argument");
+        if (((uintptr_t)dev_items & 15) || ((uintptr_t)dev_item_scale & 3))
+            return fail(ST_EINVAL, "misaligned buffer (items 16 B)");
+    }
+
     // every query is its own filter group: its probed clusters are its own
     Groups groups;
     groups.n_groups = batch;
@@ -1180,6 +1191,40 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
         if (bytes > 64 * 1024) {
             ST_HIP(hipMemcpyAsync(d_tab, stage->host, bytes, hipMemcpyHostToDevice, stream));
             t_dev = d_tab;
+        }
+        if (per_query) {
+            st::Plan plan1;
+            if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch, &plan1, 2048, kIvfCap) != 0)
+                return fail(ST_EINVAL, "no schedule for these sizes");
+            const st::Layout L = st::make_layout(plan1, batch, K, d, 1);
+            st::IvfQueryParams qp;
+            memset(&qp, 0, sizeof(qp));
+            qp.ivf = ip;
+            qp.bloom = bloom->dev;
+            qp.m_bits = bloom->m_bits;
+            qp.k_hashes = bloom->k_hashes;
+            qp.items = dev_items;
+            qp.iscale = dev_item_scale;
+            qp.prog_off = t_dev;
+            qp.code = t_dev + n_off;
+            qp.leaf_rows = t_dev + n_off + n_code;
+            qp.gath = (uint64_t*)(ws + L.gath);
+            qp.gath_cap = L.gath_cap;
+            qp.srt = L.k_pad > st::kLdsSortMax ? (uint64_t*)(ws + L.srt) : nullptr;
+            qp.K = K;
+            qp.k_pad = L.k_pad;
+            qp.out_ids = dev_out_ids;
+            qp.out_scores = dev_out_scores;
+            qp.out_count = dev_out_count;
+            qp.ovf = (uint32_t*)(ws + L.ovf);
+            {
+                TimedLaunch t(0, stream);
+                hipLaunchKernelGGL(st::ivf_query_kernel, dim3(batch), dim3(st::kQueryThreads), 0, stream, qp);
+            }
+            ST_HIP(hipGetLastError());
+            ST_HIP(hipEventRecord(stage->ev, stream));
+            stage->in_flight = true;
+            return ST_OK;
         }
         {   // phase 2: the filter over the probed ranges only, into zeroed mask rows
             TimedLaunch t(3, stream);

@@ -129,10 +129,11 @@ constexpr int kExprOps = 256;    // entries of one program, at most
 constexpr int kExprHashes = 16;  // rows of a leaf, at most
 
 // One program on one 64-item word: s_code / s_rows hold the program (LDS), base points at word w
-// of row 0 of the word's tile, column tid of s_stack is this thread's stack.  Returns the raw
+// of row 0 of the word's tile, column tid of s_stack (NT columns, one per thread) is this thread's stack.  Returns the raw
 // result (all ones for the empty program); the caller masks the bits that are not items.
+template <int NT>
 __device__ inline uint64_t expr_eval_word(const int32_t* s_code, const int32_t* s_rows, int n_ops, int k_hashes,
-                                          const uint64_t* __restrict__ base, uint64_t (*s_stack)[256], int tid)
+                                          const uint64_t* __restrict__ base, uint64_t (*s_stack)[NT], int tid)
 {
     int top = 0;
     for (int i = 0; i < n_ops; ++i) {

@@ -107,6 +107,179 @@ __global__ __launch_bounds__(256) void ivf_mask_kernel(const uint64_t* __restric
     }
 }
 
+// ------------------------------------------------------------------------------------------
+// Phases 2-4 in one kernel, for up to kQueryProbes probes: one workgroup per query walks the
+// words of its probed clusters (all of them laid end to end, one word per thread and round), runs
+// the filter program on each word, scores the items that pass itself (one v_dot4 row product per
+// set bit), appends their keys to the query's buffer and prunes the buffer to the best K whenever
+// it cannot take another round; the final selection writes the result rows.  The work is
+// proportional to the probed items, nothing is written for the rest of the corpus, and no
+// candidate can be lost (no regions, no thresholds from elsewhere).
+constexpr int kQueryThreads = 512;
+constexpr int kQueryProbes = 512;   // one probe per thread when the ranges are laid out
+
+struct IvfQueryParams {
+    IvfParams ivf;
+    const uint64_t* bloom;
+    int32_t m_bits, k_hashes;
+    const int8_t* items;
+    const float* iscale;
+    const int32_t *prog_off, *code, *leaf_rows;
+    uint64_t* gath;            // [batch][gath_cap] key buffer
+    int64_t gath_cap;
+    uint64_t* srt;             // [batch][k_pad] when k_pad > kLdsSortMax, else null
+    int32_t K, k_pad;
+    int64_t* out_ids;
+    float* out_scores;
+    int32_t* out_count;
+    uint32_t* ovf;             // [batch] "took the slow exact path" flags of the workspace: reset (this path has none)
+};
+
+__global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams p)
+{
+    __shared__ uint64_t s_stack[kExprDepth][kQueryThreads];
+    __shared__ int32_t s_code[kExprOps];
+    __shared__ int32_t s_rows[kExprOps * kExprHashes];
+    __shared__ uint64_t s_sorted[kLdsSortMax];
+    __shared__ int64_t s_lo[kQueryProbes], s_hi[kQueryProbes];
+    __shared__ uint32_t s_first[kQueryProbes + 1];  // first word (in the laid-out order) of each probe
+    __shared__ uint32_t s_hist[3 * 256], s_misc[8], s_wsum[kQueryThreads / 64];
+    __shared__ uint64_t s_red[32];
+    __shared__ int64_t s_word[kQueryThreads];  // first item of the word each thread evaluated this round
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, b = blockIdx.x;
+    const IvfParams& v = p.ivf;
+    static_assert(sizeof(s_stack) >= (size_t)kTopkRegs * kQueryThreads * 8, "the stack doubles as the final key buffer");
+
+    // the program, and the item ranges of the probed clusters (clipped to the corpus)
+    const int i0 = p.prog_off[b], n_ops = p.prog_off[b + 1] - i0;
+    for (int i = tid; i < n_ops; i += kQueryThreads) s_code[i] = p.code[i0 + i];
+    for (int i = tid; i < n_ops * p.k_hashes; i += kQueryThreads) s_rows[i] = p.leaf_rows[(int64_t)i0 * p.k_hashes + i];
+    uint32_t words = 0;
+    if (tid < kQueryProbes) {
+        int64_t lo = 0, hi = 0;
+        const int32_t c = tid < v.n_probe ? v.probes[(int64_t)b * v.n_probe + tid] : -1;
+        if (c >= 0) {
+            lo = v.cluster_off[c];
+            hi = v.cluster_off[c + 1];
+            lo = lo < 0 ? 0 : (lo > v.n_items ? v.n_items : lo);
+            hi = hi < lo ? lo : (hi > v.n_items ? v.n_items : hi);
+        }
+        s_lo[tid] = lo;
+        s_hi[tid] = hi;
+        words = hi > lo ? (uint32_t)(((hi - 1) >> 6) - (lo >> 6) + 1) : 0u;
+    }
+    // exclusive prefix sum of the word counts over the workgroup
+    uint32_t incl = words;
+    for (int o = 1; o < 64; o <<= 1) {
+        const uint32_t t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) s_wsum[wv] = incl;
+    if (tid == 0) {
+        s_misc[4] = 0;  // keys in the buffer
+        p.ovf[b] = 0u;
+    }
+    __syncthreads();
+    uint32_t base = 0, total = 0;
+    for (int w = 0; w < kQueryThreads / 64; ++w) {
+        const uint32_t t = s_wsum[w];
+        if (w < wv) base += t;
+        total += t;
+    }
+    if (tid < kQueryProbes) s_first[tid] = base + incl - words;
+    if (tid == 0) s_first[kQueryProbes] = total;
+    __syncthreads();
+
+    uint64_t* buf = p.gath + (int64_t)b * p.gath_cap;
+    uint64_t* sorted = p.srt ? p.srt + (int64_t)b * p.k_pad : s_sorted;
+    uint32_t* s_n = &s_misc[4];
+    int64_t qoff[kRowBlock];
+#pragma unroll
+    for (int r = 0; r < kRowBlock; ++r) qoff[r] = (int64_t)b * v.d;
+    const float sq = v.qscale[b];
+    uint64_t tau = 0;
+    // words per round: as many as the buffer is sure to hold beside the K keys kept
+    int64_t wpr = (p.gath_cap - p.K) / 64;
+    wpr = wpr > kQueryThreads ? kQueryThreads : (wpr < 1 ? 1 : wpr);
+    for (uint32_t w0 = 0; w0 < total; w0 += (uint32_t)wpr) {
+        if ((int64_t)*s_n + wpr * 64 > p.gath_cap) {  // uniform: *s_n is stable between barriers
+            const int n_out = wg_topk(buf, (int64_t)*s_n, p.K, sorted, p.k_pad, s_hist, s_misc, s_red, false, &tau);
+            for (int i = tid; i < n_out; i += kQueryThreads) buf[i] = sorted[i];
+            __syncthreads();
+            if (tid == 0) *s_n = (uint32_t)n_out;
+            __syncthreads();
+        }
+        const uint32_t wi = w0 + tid;
+        uint64_t m = 0;
+        int64_t first = 0;
+        if (tid < wpr && wi < total) {
+            // the probe this word belongs to: last j with s_first[j] <= wi
+            int a = 0, z = kQueryProbes;
+            while (z - a > 1) {
+                const int mid = (a + z) >> 1;
+                if (s_first[mid] <= wi) a = mid; else z = mid;
+            }
+            const int64_t lo = s_lo[a], hi = s_hi[a];
+            const int64_t gw = (lo >> 6) + (wi - s_first[a]);
+            first = gw * 64;
+            uint64_t in = ~0ULL;
+            if (first < lo) in &= ~0ULL << (lo - first);
+            if (first + 64 > hi) in &= ~0ULL >> (first + 64 - hi);
+            const uint64_t* wbase = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
+            m = expr_eval_word(s_code, s_rows, n_ops, p.k_hashes, wbase, s_stack, tid) & in;
+        }
+        // The wavefront's passing items, dealt out evenly over its lanes: every lane lists its set
+        // bits as (lane, bit) pairs in the wavefront's own columns of the stack (free once the words
+        // are evaluated; 16 rows x 64 columns x 8 bytes = 4096 pairs, the most 64 words can hold).
+        s_word[tid] = first;
+        const int cnt = __popcll(m);
+        int inc = cnt;
+        for (int o = 1; o < 64; o <<= 1) {
+            const int t = __shfl_up(inc, o);
+            if (lane >= o) inc += t;
+        }
+        const int wave_total = __shfl(inc, 63);
+        auto pair_at = [&](int e) -> uint16_t* {
+            return reinterpret_cast<uint16_t*>(&s_stack[e >> 8][wv * 64]) + (e & 255);
+        };
+        {
+            int e = inc - cnt;
+            uint64_t mm = m;
+            while (mm) {
+                const int bit = __ffsll((long long)mm) - 1;
+                mm &= mm - 1;
+                *pair_at(e++) = (uint16_t)((lane << 6) | bit);
+            }
+        }
+        __syncthreads();
+        for (int k = lane; k < wave_total; k += 64) {
+            const int pr = *pair_at(k);
+            const int64_t item = s_word[wv * 64 + (pr >> 6)] + (pr & 63);
+            // (query chunks through the scalar cache, item chunks four loads at a time)
+            int acc[kRowBlock] = {0, 0, 0, 0, 0, 0, 0, 0};
+            dot_block<1>(reinterpret_cast<const int4*>(p.items + item * v.d), v.queries, qoff, v.d >> 4, acc);
+            const float sc = rescale(acc[0], sq, p.iscale[item]);
+            const uint64_t key = make_key(sc, (uint32_t)item);
+            if (key >= tau) buf[atomicAdd(s_n, 1u)] = key;
+        }
+        __syncthreads();
+    }
+    // final selection: in LDS (the stack is free now) when the keys and the result fit there
+    const uint32_t n_keys = *s_n;
+    int n_out;
+    if (!p.srt && n_keys <= (uint32_t)(kTopkRegs * kQueryThreads)) {
+        uint64_t* s_keys = &s_stack[0][0];
+        __syncthreads();
+        for (uint32_t i = tid; i < n_keys; i += kQueryThreads) s_keys[i] = buf[i];
+        __syncthreads();
+        uint64_t kth;
+        n_out = lds_topk(s_keys, (int)n_keys, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, true, kth);
+    } else {
+        n_out = wg_topk(buf, (int64_t)n_keys, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
+    }
+    write_result(sorted, n_out, p.K, p.out_ids + (int64_t)b * p.K, p.out_scores + (int64_t)b * p.K, p.out_count + b);
+}
+
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint64_t* __restrict__ dst, int64_t n)
 {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = 0ULL;
