@@ -247,6 +247,8 @@ int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* 
  * leaves ANDed).  dev_out_probes (int32 [batch, n_probe], may be NULL) receives the probed
  * cluster ids in rank order, -1 past n_clusters.  With n_probe >= n_clusters the result is that
  * of st_search_expr.  1 <= n_clusters <= ST_MAX_CLUSTERS, 1 <= n_probe <= ST_MAX_PROBES.
+ * Up to 512 probes run as one kernel per batch over the probed ranges alone; more probes go
+ * through per-query mask rows and the fused scan of st_search_expr.
  * Everything else (outputs, ordering, workspace ownership, asynchrony, errors) as for st_search. */
 int64_t st_search_ivf_workspace_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t K,
                                       int32_t n_clusters, int32_t n_probe, int64_t n_expr_entries);

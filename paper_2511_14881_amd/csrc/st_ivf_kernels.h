@@ -1,14 +1,16 @@
-// Cluster probing in front of the fused search (Sec. 4.2; Sec. 4.3, Alg. 1 phases 1-2).
+// Cluster probing (Sec. 4.2; Sec. 4.3, Alg. 1).
 //
 // Items are stored cluster by cluster; cluster c is the item range [off[c], off[c+1]).
 // Phase 1 (ivf_probe_kernel): one workgroup per query scores every centroid like an item
 // (int8 dot, two fp32 multiplies), and an exact top-n_p by (score descending, cluster id
 // ascending) gives the probed clusters.
-// Phase 2 (ivf_mask_kernel): 32 threads per (query, probed cluster) run the query's filter
-// program only over the words of that cluster's range and ORs the result into the query's row of
-// a bit-sliced mask index (zeroed beforehand), laid out like the Bloom index.  Phases 3-4 are the
-// ordinary fused scan and selection reading that mask index: items outside the probed ranges have
-// mask bit 0 and are never loaded.
+// Phases 2-4, up to kQueryProbes probes (ivf_query_kernel): one workgroup per query filters and
+// scores the items of its probed ranges alone and selects the top K.
+// Phase 2, any number of probes (ivf_mask_kernel): 32 threads per (query, probed cluster) run the
+// query's filter program only over the words of that cluster's range and OR the result into the
+// query's row of a bit-sliced mask index (zeroed beforehand), laid out like the Bloom index; phases
+// 3-4 are then the ordinary fused scan and selection reading that mask index: items outside the
+// probed ranges have mask bit 0 and are never loaded.
 #pragma once
 #include "st_bloom_kernels.h"
 #include "st_search_kernels.h"
