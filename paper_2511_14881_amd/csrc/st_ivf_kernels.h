@@ -43,11 +43,16 @@ __global__ __launch_bounds__(kProbeThreads) void ivf_probe_kernel(IvfParams p)
     uint32_t* s_hist = reinterpret_cast<uint32_t*>(s_red + 2 * (kProbeThreads / 64));  // [256]
     uint32_t* s_misc = s_hist + 256;                                      // [8]
     const int tid = threadIdx.x, b = blockIdx.x;
-    const int8_t* q = p.queries + (int64_t)b * p.d;
     const float sq = p.qscale[b];
     uint64_t* keys = p.keys + (int64_t)b * p.n_clusters;
+    int64_t qoff[kRowBlock];
+#pragma unroll
+    for (int r = 0; r < kRowBlock; ++r) qoff[r] = (int64_t)b * p.d;
     for (int c = tid; c < p.n_clusters; c += kProbeThreads) {
-        const float s = rescale(dot_rows(p.centroids + (int64_t)c * p.d, q, p.d), sq, p.cscale[c]);
+        // (query chunks through the scalar cache, centroid chunks four loads at a time)
+        int acc[kRowBlock] = {0, 0, 0, 0, 0, 0, 0, 0};
+        dot_block<1>(reinterpret_cast<const int4*>(p.centroids + (int64_t)c * p.d), p.queries, qoff, p.d >> 4, acc);
+        const float s = rescale(acc[0], sq, p.cscale[c]);
         keys[c] = make_key(s, (uint32_t)c);
     }
     __threadfence_block();
