@@ -1092,7 +1092,7 @@ int64_t st_search_ivf_workspace_bytes(int64_t n_items, int32_t d, int32_t batch,
     if (n_probe < 1 || n_probe > ST_MAX_PROBES) return fail(ST_EINVAL, "n_probe=%d out of range", n_probe);
     // centroid keys and probed cluster ids behind the expression search's workspace
     return st::round_up(base, 256) + st::round_up((int64_t)batch * n_clusters * 8, 256) +
-           st::round_up((int64_t)batch * n_probe * 4, 256);
+           st::round_up((int64_t)batch * n_probe * 4, 256) + st::round_up((int64_t)batch * (1 + st::kQueryParts) * 4, 256);
 }
 
 int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale, int64_t n_items,
@@ -1144,6 +1144,8 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
     ip.keys = (uint64_t*)tail;
     ip.probes = (int32_t*)(tail + st::round_up((int64_t)batch * n_clusters * 8, 256));
     ip.user_probes = dev_out_probes;
+    uint32_t* q_done = (uint32_t*)((char*)ip.probes + st::round_up((int64_t)batch * n_probe * 4, 256));
+    ip.done = q_done;
 
     // Few enough probes for one workgroup to lay out: phases 2-4 run per query over the probed
     // ranges alone.  (A forced scoring path selects the scan-based route below instead, which also
@@ -1217,9 +1219,20 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
             qp.out_scores = dev_out_scores;
             qp.out_count = dev_out_count;
             qp.ovf = (uint32_t*)(ws + L.ovf);
+            qp.done = q_done;
+            qp.part_cnt = q_done + batch;
+            // Workgroups per query: enough to occupy the chip, as long as every part's share of the
+            // key buffer holds a round beside the K keys it keeps, the parts' survivors fit the final
+            // selection in LDS together, and the result is sorted in LDS.
+            int parts = 1;
+            if (!qp.srt)
+                while (parts * 2 <= st::kQueryParts && batch * parts * 2 <= st::kComputeUnits &&
+                       (int64_t)parts * 2 * K <= (int64_t)st::kTopkRegs * st::kQueryThreads &&
+                       L.gath_cap / (parts * 2) >= 2 * (int64_t)K + 64 * st::kQueryThreads)
+                    parts *= 2;
             {
                 TimedLaunch t(0, stream);
-                hipLaunchKernelGGL(st::ivf_query_kernel, dim3(batch), dim3(st::kQueryThreads), 0, stream, qp);
+                hipLaunchKernelGGL(st::ivf_query_kernel, dim3(batch, parts), dim3(st::kQueryThreads), 0, stream, qp);
             }
             ST_HIP(hipGetLastError());
             ST_HIP(hipEventRecord(stage->ev, stream));

@@ -27,6 +27,7 @@ struct IvfParams {
     const int64_t* cluster_off;   // [n_clusters + 1]
     int32_t d, n_clusters, n_probe, k_pad, batch;
     int64_t n_items;
+    uint32_t* done;               // [batch] zeroed here for the per-query kernel's parts, or null
     uint64_t* keys;               // [batch][n_clusters]  scratch: centroid keys
     int32_t* probes;              // [batch][n_probe]     probed clusters in rank order, -1 = none
     int32_t* user_probes;         // the same for the caller, or null
@@ -44,6 +45,7 @@ __global__ __launch_bounds__(kProbeThreads) void ivf_probe_kernel(IvfParams p)
     uint32_t* s_misc = s_hist + 256;                                      // [8]
     const int tid = threadIdx.x, b = blockIdx.x;
     const float sq = p.qscale[b];
+    if (tid == 0 && p.done) p.done[b] = 0u;
     uint64_t* keys = p.keys + (int64_t)b * p.n_clusters;
     int64_t qoff[kRowBlock];
 #pragma unroll
@@ -124,6 +126,7 @@ __global__ __launch_bounds__(256) void ivf_mask_kernel(const uint64_t* __restric
 // candidate can be lost (no regions, no thresholds from elsewhere).
 constexpr int kQueryThreads = 512;
 constexpr int kQueryProbes = 512;   // one probe per thread when the ranges are laid out
+constexpr int kQueryParts = 8;      // workgroups per query, at most
 
 struct IvfQueryParams {
     IvfParams ivf;
@@ -140,6 +143,10 @@ struct IvfQueryParams {
     float* out_scores;
     int32_t* out_count;
     uint32_t* ovf;             // [batch] "took the slow exact path" flags of the workspace: reset (this path has none)
+    // several workgroups per query (grid.y = parts <= kQueryParts): each takes every parts-th round
+    // with its own share of the key buffer; the one that finishes last merges the survivors
+    uint32_t* done;            // [batch] parts finished (zeroed by the probe kernel)
+    uint32_t* part_cnt;        // [batch][kQueryParts] keys each part kept
 };
 
 __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams p)
@@ -197,7 +204,9 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
     if (tid == 0) s_first[kQueryProbes] = total;
     __syncthreads();
 
-    uint64_t* buf = p.gath + (int64_t)b * p.gath_cap;
+    const int part = blockIdx.y, parts = gridDim.y;
+    const int64_t cap = p.gath_cap / parts;  // this workgroup's share of the query's key buffer
+    uint64_t* buf = p.gath + (int64_t)b * p.gath_cap + part * cap;
     uint64_t* sorted = p.srt ? p.srt + (int64_t)b * p.k_pad : s_sorted;
     uint32_t* s_n = &s_misc[4];
     int64_t qoff[kRowBlock];
@@ -206,10 +215,14 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
     const float sq = v.qscale[b];
     uint64_t tau = 0;
     // words per round: as many as the buffer is sure to hold beside the K keys kept
-    int64_t wpr = (p.gath_cap - p.K) / 64;
+    int64_t wpr = (cap - p.K) / 64;
     wpr = wpr > kQueryThreads ? kQueryThreads : (wpr < 1 ? 1 : wpr);
-    for (uint32_t w0 = 0; w0 < total; w0 += (uint32_t)wpr) {
-        if ((int64_t)*s_n + wpr * 64 > p.gath_cap) {  // uniform: *s_n is stable between barriers
+    {   // no longer than an even share of the query's words (whole wavefronts), so that every part has work
+        const int64_t share = (((int64_t)total + parts - 1) / parts + 63) & ~63LL;
+        if (share < wpr) wpr = share < 64 ? 64 : share;
+    }
+    for (uint32_t w0 = (uint32_t)(part * wpr); w0 < total; w0 += (uint32_t)(parts * wpr)) {
+        if ((int64_t)*s_n + wpr * 64 > cap) {  // uniform: *s_n is stable between barriers
             const int n_out = wg_topk(buf, (int64_t)*s_n, p.K, sorted, p.k_pad, s_hist, s_misc, s_red, false, &tau);
             for (int i = tid; i < n_out; i += kQueryThreads) buf[i] = sorted[i];
             __syncthreads();
@@ -271,8 +284,52 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
         }
         __syncthreads();
     }
+    uint32_t n_keys = *s_n;
+    if (parts > 1) {
+        // keep this part's best K (unordered) at the head of its share, then let the part that
+        // finishes last merge the survivors of all parts (at most kTopkRegs * kQueryThreads keys:
+        // the host chooses the number of parts accordingly)
+        if (n_keys > (uint32_t)p.K) {
+            uint64_t kth;
+            int kept;
+            if (n_keys <= (uint32_t)(kTopkRegs * kQueryThreads)) {  // register-resident select on a copy in LDS
+                uint64_t* s_keys = &s_stack[0][0];
+                __syncthreads();
+                for (uint32_t i = tid; i < n_keys; i += kQueryThreads) s_keys[i] = buf[i];
+                __syncthreads();
+                kept = lds_topk(s_keys, (int)n_keys, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, false, kth);
+                __syncthreads();
+            } else {
+                kept = wg_topk(buf, (int64_t)n_keys, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, false, &kth);
+            }
+            for (int i = tid; i < kept; i += kQueryThreads) buf[i] = s_sorted[i];
+            n_keys = (uint32_t)kept;
+        }
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            p.part_cnt[b * kQueryParts + part] = n_keys;
+            __threadfence();
+            s_misc[5] = atomicAdd(&p.done[b], 1u) == (uint32_t)(parts - 1) ? 1u : 0u;
+        }
+        __syncthreads();
+        if (!s_misc[5]) return;  // uniform
+        __threadfence();
+        uint64_t* s_keys = &s_stack[0][0];
+        uint32_t at = 0;
+        for (int pp = 0; pp < parts; ++pp) {
+            const uint32_t c = p.part_cnt[b * kQueryParts + pp];
+            const uint64_t* src = p.gath + (int64_t)b * p.gath_cap + pp * cap;
+            for (uint32_t i = tid; i < c; i += kQueryThreads) s_keys[at + i] = src[i];
+            at += c;
+        }
+        __syncthreads();
+        uint64_t kth;
+        const int n_fin = lds_topk(s_keys, (int)at, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, true, kth);
+        write_result(s_sorted, n_fin, p.K, p.out_ids + (int64_t)b * p.K, p.out_scores + (int64_t)b * p.K, p.out_count + b);
+        return;
+    }
     // final selection: in LDS (the stack is free now) when the keys and the result fit there
-    const uint32_t n_keys = *s_n;
     int n_out;
     if (!p.srt && n_keys <= (uint32_t)(kTopkRegs * kQueryThreads)) {
         uint64_t* s_keys = &s_stack[0][0];
