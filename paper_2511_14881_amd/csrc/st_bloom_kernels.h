@@ -139,9 +139,16 @@ __device__ inline uint64_t expr_eval_word(const int32_t* s_code, const int32_t* 
     for (int i = 0; i < n_ops; ++i) {
         const int op = s_code[i];
         if (op == 0) {
+            // four rows at a time, so that their latencies overlap (a short leaf repeats its last row)
             uint64_t w = ~0ULL;
             const int32_t* rows = s_rows + i * k_hashes;
-            for (int j = 0; j < k_hashes; ++j) w &= base[(int64_t)rows[j] * kTileWords];
+            for (int j = 0; j < k_hashes; j += 4) {
+                const int j1 = j + 1 < k_hashes ? j + 1 : k_hashes - 1, j2 = j + 2 < k_hashes ? j + 2 : k_hashes - 1,
+                          j3 = j + 3 < k_hashes ? j + 3 : k_hashes - 1;
+                const uint64_t a = base[(int64_t)rows[j] * kTileWords], b = base[(int64_t)rows[j1] * kTileWords];
+                const uint64_t c = base[(int64_t)rows[j2] * kTileWords], e = base[(int64_t)rows[j3] * kTileWords];
+                w &= (a & b) & (c & e);
+            }
             s_stack[top++][tid] = w;
         } else if (op == 3) {
             s_stack[top - 1][tid] = ~s_stack[top - 1][tid];
