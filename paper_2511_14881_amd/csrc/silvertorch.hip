@@ -1144,8 +1144,7 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
     ip.keys = (uint64_t*)tail;
     ip.probes = (int32_t*)(tail + st::round_up((int64_t)batch * n_clusters * 8, 256));
     ip.user_probes = dev_out_probes;
-    uint32_t* q_done = (uint32_t*)((char*)ip.probes + st::round_up((int64_t)batch * n_probe * 4, 256));
-    ip.done = q_done;
+    uint32_t* q_parts = (uint32_t*)((char*)ip.probes + st::round_up((int64_t)batch * n_probe * 4, 256));  // [batch][kQueryParts]
 
     // Few enough probes for one workgroup to lay out: phases 2-4 run per query over the probed
     // ranges alone.  (A forced scoring path selects the scan-based route below instead, which also
@@ -1219,8 +1218,13 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
             qp.out_scores = dev_out_scores;
             qp.out_count = dev_out_count;
             qp.ovf = (uint32_t*)(ws + L.ovf);
-            qp.done = q_done;
-            qp.part_cnt = q_done + batch;
+#ifdef ST_STAMPS
+            {
+                const char* e = getenv("ST_STAMPS_PTR");
+                qp.stamps = e ? (uint64_t*)strtoull(e, nullptr, 0) : nullptr;
+            }
+#endif
+            qp.part_cnt = q_parts;
             // Workgroups per query: enough to occupy the chip, as long as every part's share of the
             // key buffer holds a round beside the K keys it keeps, the parts' survivors fit the final
             // selection in LDS together, and the result is sorted in LDS.
@@ -1233,6 +1237,8 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
             {
                 TimedLaunch t(0, stream);
                 hipLaunchKernelGGL(st::ivf_query_kernel, dim3(batch, parts), dim3(st::kQueryThreads), 0, stream, qp);
+                if (parts > 1)
+                    hipLaunchKernelGGL(st::ivf_merge_kernel, dim3(batch), dim3(st::kQueryThreads), 0, stream, qp, parts);
             }
             ST_HIP(hipGetLastError());
             ST_HIP(hipEventRecord(stage->ev, stream));

@@ -27,7 +27,6 @@ struct IvfParams {
     const int64_t* cluster_off;   // [n_clusters + 1]
     int32_t d, n_clusters, n_probe, k_pad, batch;
     int64_t n_items;
-    uint32_t* done;               // [batch] zeroed here for the per-query kernel's parts, or null
     uint64_t* keys;               // [batch][n_clusters]  scratch: centroid keys
     int32_t* probes;              // [batch][n_probe]     probed clusters in rank order, -1 = none
     int32_t* user_probes;         // the same for the caller, or null
@@ -45,7 +44,6 @@ __global__ __launch_bounds__(kProbeThreads) void ivf_probe_kernel(IvfParams p)
     uint32_t* s_misc = s_hist + 256;                                      // [8]
     const int tid = threadIdx.x, b = blockIdx.x;
     const float sq = p.qscale[b];
-    if (tid == 0 && p.done) p.done[b] = 0u;
     uint64_t* keys = p.keys + (int64_t)b * p.n_clusters;
     int64_t qoff[kRowBlock];
 #pragma unroll
@@ -144,9 +142,9 @@ struct IvfQueryParams {
     int32_t* out_count;
     uint32_t* ovf;             // [batch] "took the slow exact path" flags of the workspace: reset (this path has none)
     // several workgroups per query (grid.y = parts <= kQueryParts): each takes every parts-th round
-    // with its own share of the key buffer; the one that finishes last merges the survivors
-    uint32_t* done;            // [batch] parts finished (zeroed by the probe kernel)
+    // with its own share of the key buffer and keeps its best K; ivf_merge_kernel merges them
     uint32_t* part_cnt;        // [batch][kQueryParts] keys each part kept
+    uint64_t* stamps;          // null unless the library is built with ST_STAMPS (timeline probe)
 };
 
 __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams p)
@@ -162,6 +160,9 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
     __shared__ int64_t s_word[kQueryThreads];  // first item of the word each thread evaluated this round
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, b = blockIdx.x;
     const IvfParams& v = p.ivf;
+    const int st_slot = (int)(blockIdx.x * gridDim.y + blockIdx.y);
+    (void)st_slot;
+    ST_STAMP(p.stamps, 0, st_slot, 0);
     static_assert(sizeof(s_stack) >= (size_t)kTopkRegs * kQueryThreads * 8, "the stack doubles as the final key buffer");
 
     // the program, and the item ranges of the probed clusters (clipped to the corpus)
@@ -203,6 +204,7 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
     if (tid < kQueryProbes) s_first[tid] = base + incl - words;
     if (tid == 0) s_first[kQueryProbes] = total;
     __syncthreads();
+    ST_STAMP(p.stamps, 0, st_slot, 1);
 
     const int part = blockIdx.y, parts = gridDim.y;
     const int64_t cap = p.gath_cap / parts;  // this workgroup's share of the query's key buffer
@@ -284,11 +286,10 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
         }
         __syncthreads();
     }
+    ST_STAMP(p.stamps, 0, st_slot, 2);
     uint32_t n_keys = *s_n;
     if (parts > 1) {
-        // keep this part's best K (unordered) at the head of its share, then let the part that
-        // finishes last merge the survivors of all parts (at most kTopkRegs * kQueryThreads keys:
-        // the host chooses the number of parts accordingly)
+        // keep this part's best K (unordered) at the head of its share
         if (n_keys > (uint32_t)p.K) {
             uint64_t kth;
             int kept;
@@ -305,28 +306,10 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
             for (int i = tid; i < kept; i += kQueryThreads) buf[i] = s_sorted[i];
             n_keys = (uint32_t)kept;
         }
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            p.part_cnt[b * kQueryParts + part] = n_keys;
-            __threadfence();
-            s_misc[5] = atomicAdd(&p.done[b], 1u) == (uint32_t)(parts - 1) ? 1u : 0u;
-        }
-        __syncthreads();
-        if (!s_misc[5]) return;  // uniform
-        __threadfence();
-        uint64_t* s_keys = &s_stack[0][0];
-        uint32_t at = 0;
-        for (int pp = 0; pp < parts; ++pp) {
-            const uint32_t c = p.part_cnt[b * kQueryParts + pp];
-            const uint64_t* src = p.gath + (int64_t)b * p.gath_cap + pp * cap;
-            for (uint32_t i = tid; i < c; i += kQueryThreads) s_keys[at + i] = src[i];
-            at += c;
-        }
-        __syncthreads();
-        uint64_t kth;
-        const int n_fin = lds_topk(s_keys, (int)at, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, true, kth);
-        write_result(s_sorted, n_fin, p.K, p.out_ids + (int64_t)b * p.K, p.out_scores + (int64_t)b * p.K, p.out_count + b);
+        ST_STAMP(p.stamps, 0, st_slot, 3);
+        // the merge is a kernel of its own (ivf_merge_kernel): a device-wide fence here, for a
+        // last-finisher merge in this kernel, measured 30 us per workgroup
+        if (tid == 0) p.part_cnt[b * kQueryParts + part] = n_keys;
         return;
     }
     // final selection: in LDS (the stack is free now) when the keys and the result fit there
@@ -342,6 +325,30 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
         n_out = wg_topk(buf, (int64_t)n_keys, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
     }
     write_result(sorted, n_out, p.K, p.out_ids + (int64_t)b * p.K, p.out_scores + (int64_t)b * p.K, p.out_count + b);
+}
+
+// Merge of the parts' survivors (at most kTopkRegs * kQueryThreads keys per query: the host chooses
+// the number of parts accordingly): one workgroup per query, selection and sort in LDS.
+__global__ __launch_bounds__(kQueryThreads) void ivf_merge_kernel(IvfQueryParams p, int parts)
+{
+    __shared__ uint64_t s_keys[kTopkRegs * kQueryThreads];
+    __shared__ uint64_t s_sorted[kLdsSortMax];
+    __shared__ uint32_t s_hist[3 * 256], s_misc[8];
+    __shared__ uint64_t s_red[32];
+    const int tid = threadIdx.x, b = blockIdx.x;
+    const int64_t cap = p.gath_cap / parts;
+    uint32_t at = 0;
+    for (int pp = 0; pp < parts; ++pp) {
+        uint32_t c = p.part_cnt[b * kQueryParts + pp];
+        c = c < (uint32_t)p.K ? c : (uint32_t)p.K;  // (a part keeps at most K, whatever the memory says)
+        const uint64_t* src = p.gath + (int64_t)b * p.gath_cap + pp * cap;
+        for (uint32_t i = tid; i < c; i += kQueryThreads) s_keys[at + i] = src[i];
+        at += c;
+    }
+    __syncthreads();
+    uint64_t kth;
+    const int n_fin = lds_topk(s_keys, (int)at, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, true, kth);
+    write_result(s_sorted, n_fin, p.K, p.out_ids + (int64_t)b * p.K, p.out_scores + (int64_t)b * p.K, p.out_count + b);
 }
 
 __global__ __launch_bounds__(256) void fill_zero_kernel(uint64_t* __restrict__ dst, int64_t n)
