@@ -1092,7 +1092,8 @@ int64_t st_search_ivf_workspace_bytes(int64_t n_items, int32_t d, int32_t batch,
     if (n_probe < 1 || n_probe > ST_MAX_PROBES) return fail(ST_EINVAL, "n_probe=%d out of range", n_probe);
     // centroid keys and probed cluster ids behind the expression search's workspace
     return st::round_up(base, 256) + st::round_up((int64_t)batch * n_clusters * 8, 256) +
-           st::round_up((int64_t)batch * n_probe * 4, 256) + st::round_up((int64_t)batch * (1 + st::kQueryParts) * 4, 256);
+           st::round_up((int64_t)batch * n_probe * 4, 256) +
+           st::round_up((int64_t)batch * (st::kQueryParts + st::kProbeParts) * 4, 256);
 }
 
 int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale, int64_t n_items,
@@ -1171,9 +1172,31 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
     }
 
     {   // phase 1: centroid scores and the n_probe best clusters of every query
+        // Many centroids: several workgroups per query, each on a slice, then a merge.  The number of
+        // parts is the largest that keeps a slice within the register-resident select and all parts'
+        // survivors within the merge's.
+        int parts = 1, chunk = n_clusters;
+        if (n_clusters >= 4096)
+            for (int pp = st::kProbeParts; pp >= 2; pp >>= 1) {
+                const int ch = (n_clusters + pp - 1) / pp;
+                if (ch <= st::kTopkRegs * st::kProbeThreads &&
+                    (int64_t)pp * std::min(n_probe, ch) <= (int64_t)st::kTopkRegs * st::kProbeMergeThreads) {
+                    parts = pp;
+                    chunk = ch;
+                    break;
+                }
+            }
         TimedLaunch t(3, stream);
-        hipLaunchKernelGGL(st::ivf_probe_kernel, dim3(batch), dim3(st::kProbeThreads), st::probe_lds_bytes(ip.k_pad),
-                           stream, ip);
+        if (parts > 1) {
+            uint32_t* probe_cnt = q_parts + (size_t)batch * st::kQueryParts;  // [batch][kProbeParts]
+            hipLaunchKernelGGL(st::ivf_probe_part_kernel, dim3(batch, parts), dim3(st::kProbeThreads), 0, stream, ip, chunk,
+                               probe_cnt);
+            hipLaunchKernelGGL(st::ivf_probe_merge_kernel, dim3(batch), dim3(st::kProbeMergeThreads), 0, stream, ip, chunk,
+                               parts, probe_cnt);
+        } else {
+            hipLaunchKernelGGL(st::ivf_probe_kernel, dim3(batch), dim3(st::kProbeThreads), st::probe_lds_bytes(ip.k_pad),
+                               stream, ip);
+        }
     }
     ST_HIP(hipGetLastError());
     if (n_tiles > 0) {

@@ -67,6 +67,77 @@ __global__ __launch_bounds__(kProbeThreads) void ivf_probe_kernel(IvfParams p)
     }
 }
 
+// Phase 1 for many centroids, in two kernels.  Part kernel, grid (batch, parts): a workgroup
+// scores its slice of the centroids (at most kTopkRegs * kProbeThreads of them) into LDS, keeps the
+// best min(n_probe, slice) keys with the register-resident select and leaves them, unordered, at
+// the head of its slice of the key scratch.  Merge kernel, one workgroup per query: the parts'
+// survivors (at most kTopkRegs * kProbeMergeThreads in all: the host chooses the number of parts
+// accordingly) are selected and sorted in LDS and the probed ids written.
+constexpr int kProbeParts = 16;
+constexpr int kProbeMergeThreads = 512;
+
+__global__ __launch_bounds__(kProbeThreads) void ivf_probe_part_kernel(IvfParams p, int chunk, uint32_t* part_cnt)
+{
+    __shared__ uint64_t s_keys[kTopkRegs * kProbeThreads];
+    __shared__ uint64_t s_sorted[kLdsSortMax];
+    __shared__ uint32_t s_hist[3 * 256], s_misc[8];
+    __shared__ uint64_t s_red[32];
+    const int tid = threadIdx.x, b = blockIdx.x, part = blockIdx.y;
+    const int c0 = part * chunk;
+    int n = p.n_clusters - c0;
+    n = n < 0 ? 0 : (n > chunk ? chunk : n);
+    const float sq = p.qscale[b];
+    int64_t qoff[kRowBlock];
+#pragma unroll
+    for (int r = 0; r < kRowBlock; ++r) qoff[r] = (int64_t)b * p.d;
+    for (int i = tid; i < n; i += kProbeThreads) {
+        const int c = c0 + i;
+        int acc[kRowBlock] = {0, 0, 0, 0, 0, 0, 0, 0};
+        dot_block<1>(reinterpret_cast<const int4*>(p.centroids + (int64_t)c * p.d), p.queries, qoff, p.d >> 4, acc);
+        s_keys[i] = make_key(rescale(acc[0], sq, p.cscale[c]), (uint32_t)c);
+    }
+    __syncthreads();
+    const int want = p.n_probe < n ? p.n_probe : n;
+    int kept = 0;
+    if (n > 0) {
+        uint64_t kth;
+        kept = lds_topk(s_keys, n, want, s_sorted, p.k_pad, s_hist, s_misc, s_red, false, kth);
+        __syncthreads();
+    }
+    uint64_t* dst = p.keys + (int64_t)b * p.n_clusters + c0;  // kept <= n: inside this part's slice
+    for (int i = tid; i < kept; i += kProbeThreads) dst[i] = s_sorted[i];
+    if (tid == 0) part_cnt[b * kProbeParts + part] = (uint32_t)kept;
+}
+
+__global__ __launch_bounds__(kProbeMergeThreads) void ivf_probe_merge_kernel(IvfParams p, int chunk, int parts,
+                                                                           const uint32_t* part_cnt)
+{
+    __shared__ uint64_t s_keys[kTopkRegs * kProbeMergeThreads];
+    __shared__ uint64_t s_sorted[kLdsSortMax];
+    __shared__ uint32_t s_hist[3 * 256], s_misc[8];
+    __shared__ uint64_t s_red[32];
+    const int tid = threadIdx.x, b = blockIdx.x;
+    uint32_t at = 0;
+    for (int pp = 0; pp < parts; ++pp) {
+        uint32_t c = part_cnt[b * kProbeParts + pp];
+        c = c < (uint32_t)p.n_probe ? c : (uint32_t)p.n_probe;  // (a part keeps at most n_probe, whatever the memory says)
+        const uint64_t* src = p.keys + (int64_t)b * p.n_clusters + (int64_t)pp * chunk;
+        if (at + c > (uint32_t)(kTopkRegs * kProbeMergeThreads)) c = (uint32_t)(kTopkRegs * kProbeMergeThreads) - at;
+        for (uint32_t i = tid; i < c; i += kProbeMergeThreads) s_keys[at + i] = src[i];
+        at += c;
+    }
+    __syncthreads();
+    const int want = p.n_probe < p.n_clusters ? p.n_probe : p.n_clusters;
+    uint64_t kth;
+    const int n_out = lds_topk(s_keys, (int)at, want, s_sorted, p.k_pad, s_hist, s_misc, s_red, true, kth);
+    __syncthreads();
+    for (int j = tid; j < p.n_probe; j += kProbeMergeThreads) {
+        const int32_t c = j < n_out ? (int32_t)key_item(s_sorted[j]) : -1;
+        p.probes[(int64_t)b * p.n_probe + j] = c;
+        if (p.user_probes) p.user_probes[(int64_t)b * p.n_probe + j] = c;
+    }
+}
+
 // grid (ceil(n_probe / kMaskProbes), batch): a workgroup takes kMaskProbes probed clusters of one
 // query, 32 threads per cluster (a cluster of a thousand items is 16 words).  prog_off / code /
 // leaf_rows as for bloom_expr_kernel, one program per query.  mask_rows: bit-sliced index with

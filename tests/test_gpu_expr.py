@@ -208,10 +208,13 @@ def check_ivf(w, programs_per_query, n_clusters, n_probe, K, queries=None, path=
 @pytest.mark.parametrize("n,d,B,n_c,n_p,K", [(3000, 64, 9, 7, 3, 20), (70_001, 128, 33, 300, 40, 100),
                                              (20_000, 64, 12, 50, 50, 30), (50_000, 128, 20, 2000, 1, 64),
                                              (40_000, 32, 5, 3, 8, 50), (30_000, 64, 6, 1500, 600, 40),
-                                             (20_000, 64, 4, 50, 20, 3000), (90_000, 48, 7, 512, 512, 10)])
+                                             (20_000, 64, 4, 50, 20, 3000), (90_000, 48, 7, 512, 512, 10),
+                                             (200_000, 64, 5, 5000, 40, 50), (100_000, 32, 3, 4096, 700, 30),
+                                             (70_000, 16, 2, 65536, 100, 20)])
 def test_probing_search_matches_oracle(n, d, B, n_c, n_p, K, path):
     # path 0: up to 512 probes run per query over the probed ranges; more probes, and the forced
-    # scorers (1, 2), take the route through per-query mask rows and the fused scan
+    # scorers (1, 2), take the route through per-query mask rows and the fused scan.  From 4096
+    # clusters on the centroid scoring is split over several workgroups per query.
     w = ragged_workload(500 + n, n, d, B, 24, 6, 128, 3)
     programs = random_programs(n + B + 1, B, 24, depth=3)
     check_ivf(w, programs, n_c, n_p, K, path=path, label=f"ragged n={n}")
