@@ -228,3 +228,32 @@ def test_probing_search_mid_recipe_scaled_and_full():
         programs = [(ops[off[b]:off[b + 1]].tolist(), ids[off[b]:off[b + 1]].tolist()) for b in range(cfg.batch)]
         check_ivf(w, programs, 1024, 64, cfg.top_k, queries=range(0, cfg.batch, step), label=f"mid@{n}",
                   fast_path_only=True)
+
+
+def test_probing_search_on_an_empty_corpus_and_with_empty_clusters_only():
+    B, d, K, n_c = 3, 32, 5, 4
+    q = torch.zeros((B, d), dtype=torch.int8, device="cuda")
+    qs = torch.ones(B, dtype=torch.float32, device="cuda")
+    cent = torch.ones((n_c, d), dtype=torch.int8, device="cuda")
+    cs = torch.ones(n_c, dtype=torch.float32, device="cuda")
+    ops, ids, off = pack([([], [])] * B)
+    # no items at all
+    bloom = st.st_bloom_build(np.zeros(1, np.int64), np.zeros(0, np.uint64), 0, 64, 2)
+    items = torch.zeros((0, d), dtype=torch.int8, device="cuda")
+    iscale = torch.zeros(0, dtype=torch.float32, device="cuda")
+    coff = torch.zeros(n_c + 1, dtype=torch.int64, device="cuda")
+    g_ids, g_scores, g_count, g_probes = st.st_search_ivf(bloom, items, iscale, cent, cs, coff, 2, q, qs, ops, ids, off, K)
+    torch.cuda.synchronize()
+    assert (_np(g_count) == 0).all() and (_np(g_ids) == -1).all() and np.isneginf(_np(g_scores)).all()
+    assert _np(g_probes).tolist() == [[0, 1]] * B  # equal scores: lower cluster ids first
+    bloom.free()
+    # items exist, but the probed clusters (ids 0 and 1) are empty
+    n = 100
+    bloom = st.st_bloom_build(np.arange(n + 1, dtype=np.int64), np.zeros(n, np.uint64), n, 64, 2)
+    items = torch.ones((n, d), dtype=torch.int8, device="cuda")
+    iscale = torch.ones(n, dtype=torch.float32, device="cuda")
+    coff = torch.tensor([0, 0, 0, 50, 100], dtype=torch.int64, device="cuda")
+    g_ids, g_scores, g_count, g_probes = st.st_search_ivf(bloom, items, iscale, cent, cs, coff, 2, q, qs, ops, ids, off, K)
+    torch.cuda.synchronize()
+    assert (_np(g_count) == 0).all() and (_np(g_ids) == -1).all()
+    bloom.free()
