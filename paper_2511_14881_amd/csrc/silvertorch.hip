@@ -1252,11 +1252,17 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
             // key buffer holds a round beside the K keys it keeps, the parts' survivors fit the final
             // selection in LDS together, and the result is sorted in LDS.
             int parts = 1;
-            if (!qp.srt)
-                while (parts * 2 <= st::kQueryParts && batch * parts * 2 <= st::kComputeUnits &&
-                       (int64_t)parts * 2 * K <= (int64_t)st::kTopkRegs * st::kQueryThreads &&
-                       L.gath_cap / (parts * 2) >= 2 * (int64_t)K + 64 * st::kQueryThreads)
-                    parts *= 2;
+            if (!qp.srt) {
+                auto fits = [&](int pp) {
+                    return pp <= st::kQueryParts && (int64_t)pp * K <= (int64_t)st::kTopkRegs * st::kQueryThreads &&
+                           L.gath_cap / pp >= 2 * (int64_t)K + 64 * st::kQueryThreads;
+                };
+                while (fits(parts * 2) && batch * parts * 2 <= st::kComputeUnits) parts *= 2;
+                // a large batch fills the chip by itself, but queries with many probed words still gain
+                // from parts (the longest query sets the kernel's duration): two rounds per part at least
+                const int64_t words = (int64_t)n_probe * (n_items / std::max(n_clusters, 1) / 64 + 1);
+                while (fits(parts * 2) && words / parts > 2 * st::kQueryThreads) parts *= 2;
+            }
             {
                 TimedLaunch t(0, stream);
                 hipLaunchKernelGGL(st::ivf_query_kernel, dim3(batch, parts), dim3(st::kQueryThreads), 0, stream, qp);
