@@ -6,7 +6,11 @@ One "step" is one pass of the whole path -- Bloom test, compaction, int8 scoring
 of synthetic queries against the resident corpus.  Inputs are generated on the GPU and are
 resident in HBM before the timed region starts.  Prints ONE JSON line.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config mid|tiny|large|multi|mfma]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config large|mid|tiny|multi|mfma]
+
+The headline record is the Large workload (10 M items x d = 256, batch 256: the largest
+memory-bound configuration).  Unless --no-others is given the same line also carries the Large
+selectivity sweep, the all-distinct-filters variant and a compact record for each other workload.
 """
 from __future__ import annotations
 
@@ -253,12 +257,185 @@ def value_model_bench(args, cfg, torch, st):
         "cpu_baseline": cpu}))
 
 
+def measured_read_peak(torch, st, gib: float = 2.0, reps: int = 10):
+    """Practical HBM read ceiling: the library's streaming-read kernel over a buffer far larger
+    than the caches, best of `reps` launches (HIP events on the launch stream)."""
+    n = int(gib * (1 << 30))
+    src = torch.empty(n, dtype=torch.uint8, device="cuda")
+    src.fill_(1)
+    wgs = 256 * 16
+    sink = torch.empty(wgs, dtype=torch.int32, device="cuda")
+    for _ in range(3):
+        st.st_stream_read(src, sink, wgs)
+    torch.cuda.synchronize()
+    best = None
+    for _ in range(reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        st.st_stream_read(src, sink, wgs)
+        e1.record()
+        e1.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None or ms < best else best
+    del src, sink
+    return n / (best * 1e-3) / 1e9
+
+
+def measure_search(args, torch, st, w, bloom, buf=None, prog=None, ivf=None, ivf_tensors=None, mfma_bound=False,
+                   traffic=None, read_peak=None):
+    """Times one workload: W warm-up steps, K steps bracketed by synchronisations (the contract's
+    ms_per_step), the same K steps again with a pair of HIP events around each (median / min) and
+    once more with events around every kernel (per-kernel durations); then the algorithmic bytes
+    and operations of a step.  Returns the record's pieces."""
+    cfg = w.cfg
+    T = max(cfg.n_tasks, 1)
+    if buf is None:
+        if ivf:
+            buf = st.IvfBuffers(cfg.n_items, cfg.d, cfg.batch, cfg.top_k, ivf[0], ivf[1], int(prog[2][-1]))
+        else:
+            buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, T, cfg.top_k,
+                                   n_expr_entries=None if prog is None else int(prog[2][-1]))
+
+    def step():
+        if ivf:
+            cent, cscale, coff = ivf_tensors
+            st.st_search_ivf(bloom, w.items, w.item_scale, cent, cscale, coff, ivf[1], w.queries, w.query_scale,
+                             prog[0], prog[1], prog[2], cfg.top_k, buffers=buf)
+        elif prog is not None:
+            st.st_search_expr(bloom, w.items, w.item_scale, w.queries, w.query_scale, prog[0], prog[1], prog[2],
+                              cfg.top_k, task_weight=w.task_weight, buffers=buf)
+        elif cfg.n_tasks > 0:
+            st.st_search_multitask(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.task_weight,
+                                   w.filt_ids, w.filt_offsets, cfg.top_k, buffers=buf)
+        else:
+            st.st_search(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.filt_ids,
+                         w.filt_offsets, cfg.top_k, buffers=buf)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    ms_per_step = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    # per-step durations on the GPU's clock (events on the launch stream around each call)
+    evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for e0, e1 in evs:
+        e0.record()
+        step()
+        e1.record()
+    torch.cuda.synchronize()
+    per = np.array([e0.elapsed_time(e1) for e0, e1 in evs])
+
+    # host time of one call with the GPU idle: what the calling thread spends before the call returns
+    host = []
+    for _ in range(min(args.steps, 20)):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        step()
+        host.append((time.perf_counter() - t0) * 1e6)
+    torch.cuda.synchronize()
+
+    # per-kernel durations, HIP events on the launch stream around every kernel of K more steps
+    plan_levels, _, _ = st.st_search_plan(cfg.n_items, cfg.batch * T, cfg.top_k)
+    st.st_timing_begin(args.steps * 3 * (len(plan_levels) + 6) + 8)
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    timing = st.st_timing_end()
+    scan_ms, scan_n = timing["scan"]
+    scan_ms_per_step = scan_ms / args.steps
+    n_levels = timing["select"][1] // args.steps  # one selection (or seed) launch per level
+
+    if ivf:
+        stats = stats_ivf(st, bloom, w, prog, ivf_tensors[2], buf.probes, ivf[0])
+    else:
+        stats = union_and_rows(st, bloom, w) if prog is None else union_and_rows_programs(st, bloom, w, prog)
+    n_words = (cfg.n_items + 63) // 64
+    a_bytes = (stats["rows_touched"] * n_words * 8 + stats["union_items"] * (cfg.d + 4)
+               + cfg.batch * T * cfg.d + cfg.batch * cfg.top_k * 12 + stats.get("extra_bytes", 0))
+    a_ops = 2.0 * cfg.d * T * stats["passing_pairs"]
+    stream_all = cfg.n_items * (cfg.d + 4) + cfg.n_items * cfg.m_bits // 8
+    kern_s = scan_ms_per_step * 1e-3
+    step_s = ms_per_step * 1e-3
+    if mfma_bound:
+        ach, ach_step, peak, unit, bound = a_ops / kern_s / 1e12, a_ops / step_s / 1e12, INT8_MFMA_PEAK_TOPS, "TOP/s", "mfma"
+    else:
+        ach, ach_step, peak, unit, bound = a_bytes / kern_s / 1e9, a_bytes / step_s / 1e9, HBM_PEAK_GBS, "GB/s", "hbm"
+    roofline = {
+        "bound": bound, "achieved": ach, "peak": peak, "unit": unit, "frac": ach / peak,
+        # the whole step (every launch and the gaps between them) against the same peak
+        "achieved_step": ach_step, "frac_step": ach_step / peak,
+        "traffic": traffic,
+        "traffic_source": None if traffic is None else "profiles/traffic.json (rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of an "
+                                                       "earlier run of this command; not measured in this run)",
+        "kernel": "scan (all of its launches of one step)", "kernel_ms_per_step": scan_ms_per_step,
+        "kernel_launches_per_step": scan_n / args.steps,
+        "algorithmic_bytes_per_step": a_bytes, "stream_all_bytes_per_step": stream_all,
+        "stream_all_GBs": stream_all / kern_s / 1e9 if kern_s > 0 else 0.0,
+        "algorithmic_ops_per_step": a_ops,
+        "select_ms_per_step": timing["select"][0] / args.steps,
+        "rescue_ms_per_step": timing["rescue"][0] / args.steps,
+        "filter_expr_ms_per_step": timing["expr"][0] / args.steps,
+    }
+    if read_peak and not mfma_bound:
+        roofline.update({"measured_peak": read_peak, "frac_of_measured": ach / read_peak,
+                         "frac_step_of_measured": ach_step / read_peak})
+    elif read_peak:
+        roofline.update({"measured_peak": read_peak,
+                         "hbm_frac_of_measured": a_bytes / kern_s / 1e9 / read_peak})
+    rec = {
+        "value": cfg.batch / step_s, "ms_per_step": ms_per_step,
+        "step_ms": {"mean": float(per.mean()), "median": float(np.median(per)), "min": float(per.min())},
+        "host_us_per_call": float(np.median(host)),
+        "levels": n_levels, "stats": stats, "roofline": roofline,
+    }
+    return rec, buf
+
+
+def config_block(cfg, rec, args, extra=None):
+    stats = rec["stats"]
+    out = {"workload": cfg.name, "n_items": cfg.n_items, "d": cfg.d, "batch": cfg.batch,
+           "n_tasks": cfg.n_tasks, "m_bits": cfg.m_bits, "k_hashes": cfg.k_hashes,
+           "filter_terms": cfg.n_terms, "top_k": cfg.top_k, "levels": rec["levels"],
+           "scoring_path": args.path, "distinct_filters": stats["distinct_filters"],
+           "union_selectivity": stats["union_items"] / max(cfg.n_items, 1),
+           "mean_filter_selectivity": float(np.mean(stats["per_filter_sel"]))}
+    if extra:
+        out.update(extra)
+    return out
+
+
+def brief(cfg, rec, args):
+    """Compact sub-record of a workload that is not the headline."""
+    r = rec["roofline"]
+    out = {"config": config_block(cfg, rec, args), "value": rec["value"], "unit": "queries/s",
+           "ms_per_step": rec["ms_per_step"], "step_ms": rec["step_ms"], "host_us_per_call": rec["host_us_per_call"],
+           "roofline": {k: r[k] for k in ("bound", "achieved", "peak", "unit", "frac", "achieved_step", "frac_step",
+                                          "kernel_ms_per_step", "kernel_launches_per_step", "select_ms_per_step",
+                                          "algorithmic_bytes_per_step", "algorithmic_ops_per_step", "traffic")}}
+    for k in ("measured_peak", "frac_of_measured", "frac_step_of_measured", "hbm_frac_of_measured"):
+        if k in r:
+            out["roofline"][k] = r[k]
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=50)
-    ap.add_argument("--config", default="mid")
+    ap.add_argument("--config", default="large",
+                    help="workload of the headline record: large (default: the largest memory-bound "
+                         "configuration), mid, tiny, multi, mfma")
+    ap.add_argument("--selectivity", type=float, default=0.0,
+                    help="variant of the workload: filters chosen for this exact-set selectivity instead of the "
+                         "recipe's (Large sweeps 0.001 .. the broadest available, 1.0); own workload name")
+    ap.add_argument("--no-others", action="store_true",
+                    help="only the headline workload: no sub-records for the other configurations, the Large "
+                         "selectivity sweep and the all-distinct-filters variant")
     ap.add_argument("--path", type=int, default=0, help="0 auto, 1 wavefront dot, 2 MFMA")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
@@ -309,8 +486,12 @@ def main():
     if args.value_model:
         value_model_bench(args, cfg, torch, st)
         return
+    variant = bool(args.distinct_filters or args.filter_programs or args.top_k > 0 or args.batch > 0 or args.ivf
+                   or args.selectivity > 0)
     if args.distinct_filters:
         cfg = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
+    if args.selectivity > 0:
+        cfg = synth.scaled(cfg, cfg.n_items, target_sel=args.selectivity, name=cfg.name + "+sel%g" % args.selectivity)
     if args.top_k > 0:
         cfg = synth.scaled(cfg, cfg.n_items, top_k=args.top_k, name=cfg.name + "+K%d" % args.top_k)
     if args.batch > 0:
@@ -325,6 +506,10 @@ def main():
         cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+ivf%d:%d" % ivf)
     elif args.filter_programs:
         cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+filter-programs")
+    others = not (args.no_others or variant)
+
+    read_peak = measured_read_peak(torch, st)
+
     t0 = time.time()
     w = synth.make_workload(cfg, device="cuda")
     torch.cuda.synchronize()
@@ -338,27 +523,8 @@ def main():
     prog = None
     if args.filter_programs:
         prog = synth.gen_filter_programs(cfg)[:3]
-    if ivf:
-        cent, cscale, coff = synth.gen_clusters(cfg, ivf[0], device="cuda")
-        buf = st.IvfBuffers(cfg.n_items, cfg.d, cfg.batch, cfg.top_k, ivf[0], ivf[1], int(prog[2][-1]))
-    else:
-        buf = st.SearchBuffers(cfg.n_items, cfg.d, cfg.batch, T, cfg.top_k,
-                               n_expr_entries=None if prog is None else int(prog[2][-1]))
+    ivf_tensors = synth.gen_clusters(cfg, ivf[0], device="cuda") if ivf else None
     st.st_set_scoring_path(args.path)
-
-    def step():
-        if ivf:
-            st.st_search_ivf(bloom, w.items, w.item_scale, cent, cscale, coff, ivf[1], w.queries, w.query_scale,
-                             prog[0], prog[1], prog[2], cfg.top_k, buffers=buf)
-        elif prog is not None:
-            st.st_search_expr(bloom, w.items, w.item_scale, w.queries, w.query_scale, prog[0], prog[1], prog[2],
-                              cfg.top_k, task_weight=w.task_weight, buffers=buf)
-        elif cfg.n_tasks > 0:
-            st.st_search_multitask(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.task_weight,
-                                   w.filt_ids, w.filt_offsets, cfg.top_k, buffers=buf)
-        else:
-            st.st_search(bloom, w.items, w.item_scale, w.queries, w.query_scale, w.filt_ids,
-                         w.filt_offsets, cfg.top_k, buffers=buf)
 
     if args.copy_probe:
         src = torch.ones(256 << 20, dtype=torch.uint8, device="cuda")
@@ -368,65 +534,18 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
-    ms_per_step = elapsed * 1e3 / args.steps
-
-    # per-kernel durations, HIP events on the launch stream around every kernel of K more steps
-    # room for three kernels per level; the library may add levels when it splits the query rows
-    plan_levels, _, _ = st.st_search_plan(cfg.n_items, cfg.batch * T, cfg.top_k)
-    st.st_timing_begin(args.steps * 3 * (len(plan_levels) + 6) + 8)
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    timing = st.st_timing_end()
-    scan_ms, scan_n = timing["scan"]
-    scan_ms_per_step = scan_ms / args.steps
-    n_levels = timing["select"][1] // args.steps  # one selection (or seed) launch per level
-
-    if ivf:
-        stats = stats_ivf(st, bloom, w, prog, coff, buf.probes, ivf[0])
-    else:
-        stats = union_and_rows(st, bloom, w) if prog is None else union_and_rows_programs(st, bloom, w, prog)
-    n_words = (cfg.n_items + 63) // 64
-    a_bytes = (stats["rows_touched"] * n_words * 8 + stats["union_items"] * (cfg.d + 4)
-               + cfg.batch * T * cfg.d + cfg.batch * cfg.top_k * 12 + stats.get("extra_bytes", 0))
-    a_ops = 2.0 * cfg.d * T * stats["passing_pairs"]
-    stream_all = cfg.n_items * (cfg.d + 4) + cfg.n_items * cfg.m_bits // 8
-    achieved_gbs = a_bytes / (scan_ms_per_step * 1e-3) / 1e9 if scan_ms_per_step > 0 else 0.0
-    achieved_tops = a_ops / (scan_ms_per_step * 1e-3) / 1e12 if scan_ms_per_step > 0 else 0.0
-    mfma_bound = args.config == "mfma"
-
-    traffic = None
-    tpath = os.path.join(ROOT, "profiles", "traffic.json")
-    if os.path.exists(tpath):
+    def traffic_of(name, is_variant):
+        tpath = os.path.join(ROOT, "profiles", "traffic.json")
+        if is_variant or not os.path.exists(tpath):
+            return None
         try:
-            variant = args.distinct_filters or args.filter_programs or args.top_k > 0 or args.batch > 0
-            traffic = None if variant else json.load(open(tpath)).get(args.config)
+            return json.load(open(tpath)).get(name)
         except Exception:
-            traffic = None
+            return None
 
-    if mfma_bound:
-        roofline = {"bound": "mfma", "achieved": achieved_tops, "peak": INT8_MFMA_PEAK_TOPS, "unit": "TOP/s",
-                    "frac": achieved_tops / INT8_MFMA_PEAK_TOPS, "traffic": traffic}
-    else:
-        roofline = {"bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                    "frac": achieved_gbs / HBM_PEAK_GBS, "traffic": traffic}
-    roofline.update({
-        "kernel": "scan", "kernel_ms_per_step": scan_ms_per_step, "kernel_launches_per_step": scan_n / args.steps,
-        "algorithmic_bytes_per_step": a_bytes, "stream_all_bytes_per_step": stream_all,
-        "stream_all_GBs": stream_all / (scan_ms_per_step * 1e-3) / 1e9 if scan_ms_per_step > 0 else 0.0,
-        "algorithmic_ops_per_step": a_ops,
-        "select_ms_per_step": timing["select"][0] / args.steps,
-        "rescue_ms_per_step": timing["rescue"][0] / args.steps,
-        "filter_expr_ms_per_step": timing["expr"][0] / args.steps,
-    })
+    rec, buf = measure_search(args, torch, st, w, bloom, prog=prog, ivf=ivf, ivf_tensors=ivf_tensors,
+                              mfma_bound=args.config == "mfma", traffic=traffic_of(args.config, variant),
+                              read_peak=read_peak)
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -447,6 +566,7 @@ def main():
         while spent < args.cpu_seconds and reps < 1000:
             t0 = time.perf_counter()
             if ivf:
+                cent, cscale, coff = ivf_tensors
                 po = prog[2][: b_s + 1]
                 O.search_ivf(sigs, cfg.m_bits, cfg.k_hashes, items, isc, cent.cpu().numpy(), cscale.cpu().numpy(),
                              np.minimum(coff.cpu().numpy(), n_s), ivf[1], q, qs, prog[0][: int(po[-1])],
@@ -466,27 +586,58 @@ def main():
         cpu = {"value": qps, "unit": "queries/s", "cores": O.num_threads(), "kind": "oracle",
                "sample": f"{b_s} queries x first {n_s} items, {reps} repetitions, {spent:.1f} s; "
                          f"scaled by {n_s}/{cfg.n_items} to the full corpus"}
+        del items, isc, off, ids, sigs
 
-    qps = cfg.batch / (ms_per_step * 1e-3)
     out = {
-        "metric": "filtered int8 top-K queries/sec", "value": qps, "unit": "queries/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "filtered int8 top-K queries/sec", "value": rec["value"], "unit": "queries/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rec["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "n_items": cfg.n_items, "d": cfg.d, "batch": cfg.batch,
-                   "n_tasks": cfg.n_tasks, "m_bits": cfg.m_bits, "k_hashes": cfg.k_hashes,
-                   "filter_terms": cfg.n_terms, "top_k": cfg.top_k, "levels": n_levels,
-                   "scoring_path": args.path, "distinct_filters": stats["distinct_filters"],
-                   "union_selectivity": stats["union_items"] / max(cfg.n_items, 1),
-                   "mean_filter_selectivity": float(np.mean(stats["per_filter_sel"])),
-                   **({"probed_item_fraction": stats["probed_item_fraction"]} if ivf else {})},
-        "items_scanned_per_s": cfg.n_items / (ms_per_step * 1e-3),
-        "item_query_pairs_per_s": cfg.n_items * cfg.batch / (ms_per_step * 1e-3),
+        "config": config_block(cfg, rec, args, {"probed_item_fraction": rec["stats"]["probed_item_fraction"]} if ivf else None),
+        "step_ms": rec["step_ms"], "host_us_per_call": rec["host_us_per_call"],
+        "items_scanned_per_s": cfg.n_items / (rec["ms_per_step"] * 1e-3),
+        "item_query_pairs_per_s": cfg.n_items * cfg.batch / (rec["ms_per_step"] * 1e-3),
         "bloom_build_items_per_s": cfg.n_items / build_s if build_s > 0 else None,
         "gen_seconds": gen_s,
-        "roofline": roofline,
+        "roofline": rec["roofline"],
         "cpu_baseline": cpu,
     }
+
+    if others:
+        # the same corpus with every query carrying its own filter (no work shared between queries)
+        cfg_d = synth.scaled(cfg, cfg.n_items, pool=cfg.batch, name=cfg.name + "+distinct-filters")
+        sample = w.feat_ids[: min(cfg.n_items, 200_000) * cfg.feats_per_item].cpu().numpy()
+        pool_d = synth.choose_filter_pool(cfg_d, sample)
+        fid_d, foff_d = synth.gen_filters(cfg_d, pool_d)
+        wd = synth.Workload(cfg_d, w.items, w.item_scale, w.feat_offsets, w.feat_ids, w.queries, w.query_scale,
+                            w.task_weight, fid_d, foff_d, pool_d)
+        rec_d, _ = measure_search(args, torch, st, wd, bloom, buf=buf, read_peak=read_peak)
+        out["distinct_filters_variant"] = brief(cfg_d, rec_d, args)
+        if args.config == "large":
+            sweep = []
+            for target in synth.LARGE_SWEEP:
+                ws = synth.refilter(w, target)
+                rec_s, _ = measure_search(args, torch, st, ws, bloom, buf=buf, read_peak=read_peak)
+                b = brief(ws.cfg, rec_s, args)
+                b["target_selectivity"] = target
+                sweep.append(b)
+            out["selectivity_sweep"] = sweep
+        del w, bloom, buf, wd
+        torch.cuda.empty_cache()
+        subs = {}
+        for name in ("tiny", "mid", "multi", "mfma", "large"):
+            if name == args.config:
+                continue
+            c2 = synth.CONFIGS[name]
+            w2 = synth.make_workload(c2, device="cuda")
+            bl2 = st.st_bloom_build(w2.feat_offsets, w2.feat_ids, c2.n_items, c2.m_bits, c2.k_hashes)
+            rec2, _ = measure_search(args, torch, st, w2, bl2, mfma_bound=name == "mfma",
+                                     traffic=traffic_of(name, False), read_peak=read_peak)
+            subs[name] = brief(c2, rec2, args)
+            bl2.free()
+            del w2, bl2
+            torch.cuda.empty_cache()
+        out["other_configs"] = subs
     print(json.dumps(out))
 
 

@@ -293,13 +293,34 @@ int st_value_model(const float* dev_task_scores, int64_t n, int32_t n_tasks,
                    const int32_t* host_ops, const float* host_consts, int32_t n_ops,
                    float* dev_out, void* hip_stream);
 
-/* Search scheduling knobs, mainly for tests: path = 0 auto, 1 force the wavefront
- * dot-product scorer, 2 force the int8 MFMA scorer where it applies.  Returns the old value. */
+/* Bandwidth probe for benchmarks: one kernel that reads bytes / 16 16-byte pieces of dev_src
+ * (16-byte aligned) with `workgroups` workgroups of 256 threads and writes one uint32 per workgroup
+ * to dev_sink ([workgroups]).  Its measured rate is the practical HBM read ceiling that the
+ * roofline fractions of the search kernels are quoted against beside the published peak.
+ * Asynchronous on hip_stream, no allocation; timed by st_timing_begin / _end as kind 0. */
+int st_stream_read(const void* dev_src, int64_t bytes, void* dev_sink, int32_t workgroups, void* hip_stream);
+
+/* Host part of st_search / st_search_multitask alone, for tests of the host logic and for timing
+ * it without a GPU: the argument checks on the sizes, the hashing of every filter id into
+ * signature rows (Eq. 4), the grouping of queries with equal filters, the split of the groups
+ * between the two scorers, the schedule, and the table blob a real call would upload.  Touches no
+ * device memory and enqueues nothing.  m_bits / k_hashes are those of the index a real call would
+ * pass.  host_out_summary[8] receives {distinct filters, groups scored with int8 MFMA, groups
+ * scored with the wavefront dot product, rows of workgroups the resident queries are split
+ * over, wavefronts per MFMA workgroup (0: none), levels, bytes of tables uploaded, 1 if the
+ * search starts with the per-query seed pass}.  Errors as for st_search. */
+int st_search_host_plan(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K,
+                        int32_t m_bits, int32_t k_hashes, const uint64_t* host_filt_ids,
+                        const int64_t* host_filt_offsets, int32_t* host_out_summary);
+
+/* Search scheduling knob for tests: path = 0 auto, 1 force the wavefront dot-product scorer,
+ * 2 force the int8 MFMA scorer where it applies.  The setting belongs to the calling thread
+ * (searches of other threads are not affected).  Returns the thread's old value. */
 int32_t st_set_scoring_path(int32_t path);
 
 /* Per-kernel timing for benchmarks.  Between st_timing_begin and st_timing_end every kernel the
- * search entry points launch is bracketed by two HIP events recorded on the caller's stream
- * (up to max_launches launches; not thread safe, one measuring thread at a time).
+ * search entry points launch from the calling thread is bracketed by two HIP events recorded on
+ * the caller's stream (up to max_launches launches; the state belongs to the calling thread).
  * st_timing_end waits for the recorded events and returns, per kernel kind (0 = scan,
  * 1 = select, 2 = slow exact path, 3 = filter expressions), the summed elapsed milliseconds in
  * host_out_ms[4] and the number of launches in host_out_launches[4]. */

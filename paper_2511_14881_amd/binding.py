@@ -23,6 +23,7 @@ EXPORTS = [
     "st_search_plan", "st_set_scoring_path", "st_timing_begin", "st_timing_end",
     "st_search_overflow_flags_offset", "st_bloom_mask_expr", "st_search_expr_workspace_bytes",
     "st_search_expr", "st_search_ivf_workspace_bytes", "st_search_ivf", "st_quantize_global", "st_value_model",
+    "st_search_host_plan", "st_stream_read",
 ]
 
 ST_OP_LEAF, ST_OP_AND, ST_OP_OR, ST_OP_NOT = 0, 1, 2, 3  # operations of a filter program
@@ -91,6 +92,10 @@ def lib() -> C.CDLL:
                                     i64, p]
         L.st_value_model.restype = C.c_int
         L.st_value_model.argtypes = [p, i64, i32, p, p, i32, p, p]
+        L.st_search_host_plan.restype = C.c_int
+        L.st_search_host_plan.argtypes = [i64, i32, i32, i32, i32, i32, i32, p, p, p]
+        L.st_stream_read.restype = C.c_int
+        L.st_stream_read.argtypes = [p, i64, p, i32, p]
         L.st_quantize_global.restype = C.c_int
         L.st_quantize_global.argtypes = [p, i64, i32, p, p, p, p, p]
         _lib = L
@@ -215,6 +220,17 @@ def st_search_plan(n_items: int, batch: int, K: int, q_split: int = 1):
     caps = np.zeros(2, dtype=np.int64)
     n = _check(lib().st_search_plan(n_items, batch, K, q_split, _hptr(levels), 32, _hptr(caps)))
     return levels[:n].copy(), int(caps[0]), int(caps[1])
+
+
+def st_search_host_plan(n_items: int, d: int, batch: int, n_tasks: int, K: int, m_bits: int, k_hashes: int,
+                        filt_ids, filt_offsets) -> dict:
+    """The host part of a search alone (no GPU): a summary of the groups and the schedule."""
+    ids, off = _filters(filt_ids, filt_offsets, batch)
+    out = np.zeros(8, dtype=np.int32)
+    _check(lib().st_search_host_plan(n_items, d, batch, n_tasks, K, m_bits, k_hashes, _hptr(ids), _hptr(off),
+                                     _hptr(out)))
+    keys = ("distinct_filters", "mfma_groups", "dot_groups", "q_split", "waves", "levels", "table_bytes", "seed_pass")
+    return {k: int(v) for k, v in zip(keys, out)}
 
 
 def st_set_scoring_path(path: int) -> int:
@@ -394,6 +410,13 @@ def st_search_ivf(bloom: BloomIndex, items, item_scale, centroids, centroid_scal
                                _dptr(buf.scores), _dptr(buf.count), _dptr(buf.probes), _dptr(buf.workspace),
                                buf.nbytes, _stream(stream)))
     return buf.ids, buf.scores, buf.count, buf.probes
+
+
+def st_stream_read(src: torch.Tensor, sink: torch.Tensor, workgroups: int, stream=None) -> None:
+    """Bandwidth probe: reads all of src (any dtype, contiguous) once; sink int32/uint32 [workgroups]."""
+    if not (src.is_cuda and src.is_contiguous() and sink.is_cuda and sink.numel() >= workgroups):
+        raise TypeError("src must be a contiguous CUDA tensor and sink hold one word per workgroup")
+    _check(lib().st_stream_read(_dptr(src), src.numel() * src.element_size(), _dptr(sink), workgroups, _stream(stream)))
 
 
 def st_quantize_global(x, stream=None):

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cmath>
 #include <cstdarg>
 #include <cstdio>
@@ -15,6 +16,7 @@
 #include <new>
 #include <vector>
 
+#include "st_stage_pool.h"
 #include "st_bloom_kernels.h"
 #include "st_mfma_kernels.h"
 #include "st_ivf_kernels.h"
@@ -36,6 +38,19 @@ int fail(int code, const char* fmt, ...)
     return code;
 }
 
+// The C ABI never lets an exception out: host allocations that fail become ST_ENOMEM.
+template <class F>
+int guarded(F&& body)
+{
+    try {
+        return body();
+    } catch (const std::bad_alloc&) {
+        return fail(ST_ENOMEM, "out of host memory");
+    } catch (...) {
+        return fail(ST_EINVAL, "unexpected failure in host code");
+    }
+}
+
 #define ST_HIP(call)                                                                       \
     do {                                                                                   \
         hipError_t e_ = (call);                                                            \
@@ -45,9 +60,13 @@ int fail(int code, const char* fmt, ...)
                         __LINE__);                                                         \
     } while (0)
 
-int g_scoring_path = 0;  // 0 auto, 1 wavefront dot product, 2 MFMA where it applies
+// Test aid: the scorer a search of the calling thread is forced onto (0 auto, 1 wavefront dot
+// product, 2 MFMA where it applies).  Per thread, so that one thread's setting never changes
+// another thread's search.
+thread_local int g_scoring_path = 0;
 
-// Optional per-kernel timing with HIP events recorded on the caller's stream around each launch.
+// Optional per-kernel timing with HIP events recorded on the caller's stream around each launch
+// (state of the calling thread: the thread that begins a measurement makes the calls and ends it).
 struct Timing {
     bool on = false;
     std::vector<hipEvent_t> ev;  // pairs: [2i] before, [2i+1] after launch i
@@ -55,7 +74,7 @@ struct Timing {
     size_t used = 0;             // launches recorded
     size_t dropped = 0;
 };
-Timing g_timing;
+thread_local Timing g_timing;
 
 struct TimedLaunch {
     hipStream_t stream;
@@ -75,40 +94,64 @@ struct TimedLaunch {
     }
 };
 
-// Pinned staging slots for the per-call group tables: the copy to the device is asynchronous,
-// so a slot is reused only after the event recorded behind its copy has completed.
-struct Stage {
-    void* host = nullptr;
-    void* dev_view = nullptr;  // the same memory as the device addresses it
-    size_t bytes = 0;
-    hipEvent_t ev = nullptr;
-    bool in_flight = false;
-};
-constexpr int kStages = 16;
-Stage g_stage[kStages];
-int g_stage_next = 0;
-std::mutex g_stage_mu;
+// Pinned staging slots for the per-call tables (st_stage_pool.h): a call owns its slot from
+// stage_get() until the StageHold goes out of scope, by which time the event behind the work that
+// reads the slot has been recorded (or, on an error path after something was enqueued, the stream
+// has been waited for).
+st::StagePool g_pool;
 
-int stage_acquire(size_t bytes, Stage** out)
+bool stage_event_done(void* e)
 {
-    std::lock_guard<std::mutex> lock(g_stage_mu);
-    Stage& s = g_stage[g_stage_next];
-    g_stage_next = (g_stage_next + 1) % kStages;
-    if (!s.ev) ST_HIP(hipEventCreateWithFlags(&s.ev, hipEventDisableTiming));
-    if (s.in_flight) {
-        ST_HIP(hipEventSynchronize(s.ev));
-        s.in_flight = false;
+    if (hipEventQuery((hipEvent_t)e) == hipSuccess) return true;
+    (void)hipGetLastError();  // "not ready" must not show up as the next launch's error
+    return false;
+}
+
+int stage_event_wait(void* e) { return hipEventSynchronize((hipEvent_t)e) == hipSuccess ? 0 : (int)ST_EHIP; }
+
+struct StageHold {
+    st::StageSlot* s = nullptr;
+    hipStream_t stream = nullptr;
+    bool enqueued = false;  // work that reads the slot is on the stream
+    bool recorded = false;  // ... and the slot's event behind it
+    void* host() const { return s->host; }
+    void* dev_view() const { return s->dev_view; }
+    ~StageHold()
+    {
+        if (!s) return;
+        if (enqueued && !recorded) (void)hipStreamSynchronize(stream);
+        g_pool.release(s, recorded);
     }
-    if (s.bytes < bytes) {
-        if (s.host) ST_HIP(hipHostFree(s.host));
-        s.host = nullptr;
-        s.bytes = 0;
+};
+
+int stage_get(size_t bytes, hipStream_t stream, StageHold* h)
+{
+    st::StageSlot* s = nullptr;
+    if (g_pool.acquire(stage_event_done, stage_event_wait, &s) != 0)
+        return fail(ST_EHIP, "waiting for a staging slot failed");
+    h->s = s;
+    h->stream = stream;
+    if (!s->event) {
+        hipEvent_t ev;
+        ST_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        s->event = ev;
+    }
+    if (s->bytes < bytes) {  // owned and not pending: nothing reads the old memory any more
+        if (s->host) ST_HIP(hipHostFree(s->host));
+        s->host = nullptr;
+        s->bytes = 0;
         const size_t want = std::max<size_t>(bytes, 64 * 1024);
-        ST_HIP(hipHostMalloc(&s.host, want, hipHostMallocDefault));
-        s.bytes = want;
-        ST_HIP(hipHostGetDevicePointer(&s.dev_view, s.host, 0));
+        ST_HIP(hipHostMalloc(&s->host, want, hipHostMallocDefault));
+        s->bytes = want;
+        ST_HIP(hipHostGetDevicePointer(&s->dev_view, s->host, 0));
     }
-    *out = &s;
+    return ST_OK;
+}
+
+int stage_record(StageHold* h)
+{
+    ST_HIP(hipEventRecord((hipEvent_t)h->s->event, h->stream));
+    h->recorded = true;
     return ST_OK;
 }
 
@@ -124,53 +167,86 @@ bool is_device_pointer(const void* p)
 }
 
 // Distinct filters of a batch, as sorted lists of signature rows (Eq. 4: the bits QB sets).
+// Groups are numbered in the order in which their first query appears; the queries of a group
+// are listed in ascending order.
 struct Groups {
     std::vector<int32_t> row_off, rows, q_off, q_list, q2grp;
     int32_t n_groups = 0;
 };
 
-int build_groups(const uint64_t* filt_ids, const int64_t* filt_off, int32_t n, int32_t m_bits,
-                 int32_t k_hashes, Groups* out)
+// Per-thread buffers the host part of a search reuses from call to call, so that a call
+// allocates nothing once the thread has seen the batch size.
+struct GroupSet;
+struct HostScratch;
+HostScratch& host_scratch();
+
+inline uint64_t hash_rows(const int32_t* r, int n)
 {
-    std::map<std::vector<int32_t>, int32_t> index;
-    std::vector<std::vector<int32_t>> keys;
-    std::vector<std::vector<int32_t>> members;
-    out->q2grp.assign(n, 0);
+    uint64_t h = 0xCBF29CE484222325ULL ^ (uint64_t)n;
+    for (int i = 0; i < n; ++i) h = (h ^ (uint64_t)(uint32_t)r[i]) * 0x100000001B3ULL;
+    return h ^ (h >> 29);
+}
+
+// Hashes every query's filter ids into signature rows, sorts and de-duplicates them, and groups
+// the queries whose row lists are equal (open-addressing table over the lists' hashes).
+int build_groups(const uint64_t* filt_ids, const int64_t* filt_off, int32_t n, int32_t m_bits,
+                 int32_t k_hashes, Groups* out, std::vector<int32_t>& table, std::vector<int32_t>& tmp)
+{
+    constexpr int kMemoBits = 7;
+    uint64_t memo_id[1 << kMemoBits];
+    bool memo_ok[1 << kMemoBits] = {};
+    int32_t memo_rows[1 << kMemoBits][ST_MAX_K_HASHES];
+    int32_t cap = 16;
+    while (cap < 2 * n) cap <<= 1;
+    table.assign((size_t)cap, -1);
+    out->q2grp.assign((size_t)n, 0);
+    out->row_off.assign(1, 0);
+    out->rows.clear();
+    out->n_groups = 0;
     for (int32_t b = 0; b < n; ++b) {
         if (filt_off[b + 1] < filt_off[b]) return fail(ST_EINVAL, "filter offsets decrease at query %d", b);
-        std::vector<int32_t> rows;
-        for (int64_t a = filt_off[b]; a < filt_off[b + 1]; ++a)
-            for (int j = 0; j < k_hashes; ++j)
-                rows.push_back((int32_t)st::bloom_bit(filt_ids[a], j, (uint32_t)m_bits));
-        std::sort(rows.begin(), rows.end());
-        rows.erase(std::unique(rows.begin(), rows.end()), rows.end());
-        if (rows.size() > ST_MAX_FILTER_BITS)
-            return fail(ST_EINVAL, "filter of query %d sets %zu signature bits (limit %d)", b, rows.size(),
-                        ST_MAX_FILTER_BITS);
-        auto it = index.find(rows);
-        int32_t g;
-        if (it == index.end()) {
-            g = (int32_t)keys.size();
-            index.emplace(rows, g);
-            keys.push_back(rows);
-            members.emplace_back();
-        } else {
-            g = it->second;
+        tmp.clear();
+        for (int64_t a = filt_off[b]; a < filt_off[b + 1]; ++a) {
+            // ids recur within a batch (few, broad filters): a small direct-mapped memo of this
+            // call's hashes saves the 64-bit remainders
+            const uint64_t id = filt_ids[a];
+            const int slot = (int)((id * 0x9E3779B97F4A7C15ULL) >> (64 - kMemoBits));
+            if (!memo_ok[slot] || memo_id[slot] != id) {
+                for (int j = 0; j < k_hashes; ++j) memo_rows[slot][j] = (int32_t)st::bloom_bit(id, j, (uint32_t)m_bits);
+                memo_id[slot] = id;
+                memo_ok[slot] = true;
+            }
+            tmp.insert(tmp.end(), memo_rows[slot], memo_rows[slot] + k_hashes);
         }
-        members[g].push_back(b);
+        std::sort(tmp.begin(), tmp.end());
+        const int32_t nr = (int32_t)(std::unique(tmp.begin(), tmp.end()) - tmp.begin());
+        if (nr > ST_MAX_FILTER_BITS)
+            return fail(ST_EINVAL, "filter of query %d sets %d signature bits (limit %d)", b, nr, ST_MAX_FILTER_BITS);
+        int32_t g = -1;
+        for (uint32_t at = (uint32_t)hash_rows(tmp.data(), nr) & (uint32_t)(cap - 1);; at = (at + 1) & (uint32_t)(cap - 1)) {
+            const int32_t e = table[at];
+            if (e < 0) {
+                g = out->n_groups++;
+                table[at] = g;
+                out->rows.insert(out->rows.end(), tmp.begin(), tmp.begin() + nr);
+                out->row_off.push_back((int32_t)out->rows.size());
+                break;
+            }
+            const int32_t r0 = out->row_off[e], len = out->row_off[e + 1] - r0;
+            if (len == nr && std::equal(tmp.begin(), tmp.begin() + nr, out->rows.begin() + r0)) {
+                g = e;
+                break;
+            }
+        }
         out->q2grp[b] = g;
     }
-    out->n_groups = (int32_t)keys.size();
-    out->row_off.assign(1, 0);
-    out->q_off.assign(1, 0);
-    out->rows.clear();
-    out->q_list.clear();
-    for (int32_t g = 0; g < out->n_groups; ++g) {
-        out->rows.insert(out->rows.end(), keys[g].begin(), keys[g].end());
-        out->row_off.push_back((int32_t)out->rows.size());
-        out->q_list.insert(out->q_list.end(), members[g].begin(), members[g].end());
-        out->q_off.push_back((int32_t)out->q_list.size());
-    }
+    // queries of each group, ascending (counting sort over the group numbers)
+    out->q_off.assign((size_t)out->n_groups + 1, 0);
+    for (int32_t b = 0; b < n; ++b) ++out->q_off[out->q2grp[b] + 1];
+    for (int32_t g = 0; g < out->n_groups; ++g) out->q_off[g + 1] += out->q_off[g];
+    out->q_list.assign((size_t)n, 0);
+    tmp.assign(out->q_off.begin(), out->q_off.end() - 1);
+    for (int32_t b = 0; b < n; ++b) out->q_list[tmp[out->q2grp[b]]++] = b;
     return ST_OK;
 }
 
@@ -189,8 +265,16 @@ struct Blob {
 
 // A subset of the groups with its own tables (one per scorer).
 struct GroupSet {
-    std::vector<int32_t> row_off{0}, rows, q_off{0}, q_list;
+    std::vector<int32_t> row_off, rows, q_off, q_list;
     int32_t n = 0;
+    void reset()
+    {
+        row_off.assign(1, 0);
+        q_off.assign(1, 0);
+        rows.clear();
+        q_list.clear();
+        n = 0;
+    }
     void add(const Groups& all, int32_t g)
     {
         rows.insert(rows.end(), all.rows.begin() + all.row_off[g], all.rows.begin() + all.row_off[g + 1]);
@@ -211,6 +295,99 @@ SetAt add_set(Blob& blob, const GroupSet& s)
     at.q_off = blob.add(s.q_off);
     at.q_list = blob.add(s.q_list);
     return at;
+}
+
+struct HostScratch {
+    Groups groups;
+    GroupSet set_mfma, set_dot;
+    std::vector<int32_t> table, tmp, blk_off, blk_row, prow, q_taupos, q_prow;
+    Blob blob;
+};
+
+HostScratch& host_scratch()
+{
+    thread_local HostScratch s;
+    return s;
+}
+
+// Schedules depend on the sizes of a call only, and the planner tries several region capacities
+// and segment sizes for each: results are kept (a few dozen shapes, oldest replaced first).
+struct PlanKey {
+    int64_t n_items;
+    int32_t K, q_split, seg_cap, seed_ok, waves, min_cap;
+    bool operator==(const PlanKey& o) const
+    {
+        return n_items == o.n_items && K == o.K && q_split == o.q_split && seg_cap == o.seg_cap && seed_ok == o.seed_ok &&
+               waves == o.waves && min_cap == o.min_cap;
+    }
+};
+struct PlanEntry {
+    PlanKey key;
+    st::Plan plan;
+    int rc;
+    bool used = false;
+};
+constexpr int kPlanCache = 32;
+PlanEntry g_plans[kPlanCache];
+int g_plan_next = 0;
+std::mutex g_plan_mu;
+
+int cached_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, st::Plan* out,
+                int32_t waves = 2048, int32_t min_cap = 64)
+{
+    // the batch enters the schedule only through "small enough for the seed pass"
+    const PlanKey key{n_items, K, q_split, seg_cap, batch_rows <= st::kSeedMaxRows ? 1 : 0, waves, min_cap};
+    {
+        std::lock_guard<std::mutex> lock(g_plan_mu);
+        for (const PlanEntry& e : g_plans)
+            if (e.used && e.key == key) {
+                if (e.rc == 0) *out = e.plan;
+                return e.rc;
+            }
+    }
+    st::Plan p;
+    memset(&p, 0, sizeof(p));
+    const int rc = st::make_plan(n_items, K, q_split, seg_cap, batch_rows, &p, waves, min_cap);
+    {
+        std::lock_guard<std::mutex> lock(g_plan_mu);
+        PlanEntry& e = g_plans[g_plan_next];
+        g_plan_next = (g_plan_next + 1) % kPlanCache;
+        e.key = key;
+        e.plan = p;
+        e.rc = rc;
+        e.used = true;
+    }
+    if (rc == 0) *out = p;
+    return rc;
+}
+
+// Likewise the configuration of the MFMA scan (split of the resident queries, wavefronts per
+// workgroup, workgroups per compute unit), a function of four sizes.
+struct MfmaCfgEntry {
+    int32_t n_blocks, d, n_tasks, n_groups;
+    int S, waves, wgs;
+    bool used = false;
+};
+MfmaCfgEntry g_mfma_cfg[kPlanCache];
+int g_mfma_cfg_next = 0;
+
+void cached_mfma_config(int n_blocks, int d, int n_tasks, int n_groups, int* S, int* waves, int* wgs)
+{
+    {
+        std::lock_guard<std::mutex> lock(g_plan_mu);
+        for (const MfmaCfgEntry& e : g_mfma_cfg)
+            if (e.used && e.n_blocks == n_blocks && e.d == d && e.n_tasks == n_tasks && e.n_groups == n_groups) {
+                *S = e.S;
+                *waves = e.waves;
+                *wgs = e.wgs;
+                return;
+            }
+    }
+    st::mfma_choose_config(n_blocks, d, n_tasks, n_groups, 32, S, waves, wgs);
+    std::lock_guard<std::mutex> lock(g_plan_mu);
+    MfmaCfgEntry& e = g_mfma_cfg[g_mfma_cfg_next];
+    g_mfma_cfg_next = (g_mfma_cfg_next + 1) % kPlanCache;
+    e = MfmaCfgEntry{n_blocks, d, n_tasks, n_groups, *S, *waves, *wgs, true};
 }
 
 // Filter programs of a batch (Sec. 4.3: operation array run on a stack) as device tables for
@@ -339,6 +516,7 @@ int32_t st_set_scoring_path(int32_t path)
 
 int st_timing_begin(int32_t max_launches)
 {
+    return guarded([&]() -> int {
     if (max_launches < 1 || max_launches > (1 << 20)) return fail(ST_EINVAL, "max_launches out of range");
     while (g_timing.ev.size() < 2 * (size_t)max_launches) {
         hipEvent_t e;
@@ -350,6 +528,7 @@ int st_timing_begin(int32_t max_launches)
     g_timing.dropped = 0;
     g_timing.on = true;
     return ST_OK;
+    });
 }
 
 int st_timing_end(double* out_ms, int64_t* out_launches)
@@ -379,6 +558,7 @@ int64_t st_bloom_layout_bytes(int64_t n_items, int32_t m_bits)
 int st_bloom_build(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_t n_items,
                    int32_t m_bits, int32_t k_hashes, void* hip_stream, st_bloom** out)
 {
+    return guarded([&]() -> int {
     if (!out) return fail(ST_EINVAL, "out is null");
     *out = nullptr;
     if (!feat_offsets) return fail(ST_EINVAL, "feat_offsets is null");
@@ -441,6 +621,7 @@ int st_bloom_build(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_
     }
     *out = b;
     return ST_OK;
+    });
 }
 
 int st_bloom_free(st_bloom* bloom)
@@ -477,6 +658,7 @@ int st_bloom_export_signatures(const st_bloom* bloom, uint64_t* dev_out, void* h
 int st_bloom_mask(const st_bloom* bloom, const uint64_t* host_filt_ids, const int64_t* host_filt_offsets,
                   int32_t n_filters, uint64_t* dev_mask, void* hip_stream)
 {
+    return guarded([&]() -> int {
     if (!bloom || !host_filt_offsets || !dev_mask) return fail(ST_EINVAL, "null argument");
     if (n_filters < 0 || n_filters > 65535) return fail(ST_EINVAL, "n_filters=%d out of range", n_filters);
     if (host_filt_offsets[n_filters] > 0 && !host_filt_ids) return fail(ST_EINVAL, "host_filt_ids is null");
@@ -514,6 +696,7 @@ int st_bloom_mask(const st_bloom* bloom, const uint64_t* host_filt_ids, const in
     rc = body();
     (void)hipFree(d_tab);
     return rc;
+    });
 }
 
 int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_split, int64_t* out_levels,
@@ -546,7 +729,7 @@ static int64_t search_ws_bytes(int64_t n_items, int32_t d, int32_t batch, int32_
     if (n_tasks < 1 || n_tasks > ST_MAX_TASKS) return fail(ST_EINVAL, "n_tasks=%d out of range", n_tasks);
     if (K < 1 || K > ST_MAX_TOP_K) return fail(ST_EINVAL, "K=%d out of range", K);
     st::Plan p;
-    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p, 2048, min_cap) != 0)
+    if (cached_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p, 2048, min_cap) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     return (int64_t)st::make_layout(p, batch, K, d, n_tasks).total;
 }
@@ -561,7 +744,7 @@ int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batc
     const int64_t total = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
     if (total < 0) return total;
     st::Plan p;
-    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p) != 0)
+    if (cached_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &p) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     return (int64_t)st::make_layout(p, batch, K, d, n_tasks).ovf;
 }
@@ -575,22 +758,25 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                        int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
                        void* dev_workspace, int64_t workspace_bytes, void* hip_stream,
                        const Groups* expr_groups = nullptr, const uint64_t* expr_rows = nullptr,
-                       int32_t expr_row_count = 0, bool allow_seed = true, int32_t min_cap = 64)
+                       int32_t expr_row_count = 0, bool allow_seed = true, int32_t min_cap = 64,
+                       int32_t* dry_out = nullptr)
 {
+    // dry_out: host part only (st_search_host_plan): no device pointer is looked at, nothing is
+    // enqueued, and the summary of the schedule goes to dry_out[8]
     // allow_seed = false: no seed pass (its threshold comes from a prefix of the corpus, which says
     // nothing when the passing items sit in a few item ranges, as after cluster probing)
     // expr_groups: the filters were evaluated beforehand into expr_row_count mask rows at
     // expr_rows, laid out like a Bloom index; each group then tests the one row it names
     if (!bloom) return fail(ST_EINVAL, "bloom is null");
-    if (!dev_queries || !dev_query_scale || (!host_filt_offsets && !expr_groups) || !dev_out_ids || !dev_out_scores ||
-        !dev_out_count || !dev_workspace)
+    if (!host_filt_offsets && !expr_groups) return fail(ST_EINVAL, "null argument");
+    if (!dry_out && (!dev_queries || !dev_query_scale || !dev_out_ids || !dev_out_scores || !dev_out_count || !dev_workspace))
         return fail(ST_EINVAL, "null argument");
     if (n_items != bloom->n_items)
         return fail(ST_EINVAL, "n_items=%lld but the index holds %lld", (long long)n_items, (long long)bloom->n_items);
-    if (n_items > 0 && (!dev_items || !dev_item_scale)) return fail(ST_EINVAL, "null corpus");
+    if (!dry_out && n_items > 0 && (!dev_items || !dev_item_scale)) return fail(ST_EINVAL, "null corpus");
     const int64_t need = search_ws_bytes(n_items, d, batch, n_tasks, K, min_cap);
     if (need < 0) return (int)need;
-    if (workspace_bytes < need)
+    if (!dry_out && workspace_bytes < need)
         return fail(ST_EWORKSPACE, "workspace has %lld bytes, %lld needed", (long long)workspace_bytes, (long long)need);
     if (((uintptr_t)dev_workspace & 255) || ((uintptr_t)dev_items & 15) || ((uintptr_t)dev_queries & 15) ||
         ((uintptr_t)dev_item_scale & 15))
@@ -605,12 +791,13 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             if (!std::isfinite(host_task_weight[t])) return fail(ST_EINVAL, "task weight %d is not finite", t);
     hipStream_t stream = (hipStream_t)hip_stream;
 
-    Groups groups;
+    HostScratch& hs = host_scratch();
+    Groups& groups = hs.groups;
     int rc = ST_OK;
     if (expr_groups)
         groups = *expr_groups;
     else
-        rc = build_groups(host_filt_ids, host_filt_offsets, batch, bloom->m_bits, bloom->k_hashes, &groups);
+        rc = build_groups(host_filt_ids, host_filt_offsets, batch, bloom->m_bits, bloom->k_hashes, &groups, hs.table, hs.tmp);
     if (rc != ST_OK) return rc;
 
     // split the groups between the two scorers: MFMA where scoring is a real dense contraction
@@ -635,8 +822,12 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         if (blocks_big > 0 && groups.n_groups <= st::kMfmaMaxGroups && blocks_all * 16 * d <= 4 * (int64_t)st::kMfmaQueryLds)
             min_rows = 1;
     }
-    GroupSet set_mfma, set_dot;
-    std::vector<int32_t> blk_off{0}, blk_row;
+    GroupSet &set_mfma = hs.set_mfma, &set_dot = hs.set_dot;
+    set_mfma.reset();
+    set_dot.reset();
+    std::vector<int32_t>&blk_off = hs.blk_off, &blk_row = hs.blk_row;
+    blk_off.assign(1, 0);
+    blk_row.clear();
     for (int32_t g = 0; g < groups.n_groups; ++g) {
         const int32_t n_q = groups.q_off[g + 1] - groups.q_off[g];
         if (shape_ok && n_q * n_tasks >= min_rows && set_mfma.n < st::kMfmaMaxGroups) {
@@ -657,7 +848,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     mp.region_slots = 1;
     int mfma_wgs = 1;  // workgroups of the MFMA scan a compute unit holds at once
     if (set_mfma.n) {
-        st::mfma_choose_config(mp.n_blocks, d, n_tasks, set_mfma.n, 32, &mp.q_split, &mp.waves, &mfma_wgs);
+        cached_mfma_config(mp.n_blocks, d, n_tasks, set_mfma.n, &mp.q_split, &mp.waves, &mfma_wgs);
         if (mp.q_split < 1) return fail(ST_EINVAL, "query batch too large for the resident-query scorer");
     }
 
@@ -672,15 +863,16 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     // wavefronts that scan a level side by side: the resident workgroups of one row of the grid
     const int32_t scan_waves = set_mfma.n ? std::max(1, std::min(plan_groups_per_row(mp.q_split), st::kComputeUnits * mfma_wgs / mp.q_split)) * mp.waves
                                           : st::scan_groups();  // (a whole workgroup shares a segment there)
-    if (st::make_plan(n_items, K, mp.q_split, seg_cap, allow_seed ? batch * n_tasks : st::kSeedMaxRows + 1, &plan, scan_waves,
-                      min_cap) != 0)
+    if (cached_plan(n_items, K, mp.q_split, seg_cap, allow_seed ? batch * n_tasks : st::kSeedMaxRows + 1, &plan, scan_waves,
+                    min_cap) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
-    if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1, 2048, min_cap) != 0)
+    if (cached_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1, 2048, min_cap) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     const st::Layout L = st::make_layout(plan1, batch, K, d, n_tasks);  // layout depends on sizes only
 
-    Blob blob;
+    Blob& blob = hs.blob;
+    blob.data.clear();
     Groups& ga = groups;
     const size_t at_all_row_off = blob.add(ga.row_off), at_all_rows = blob.add(ga.rows);
     const size_t at_all_q_off = blob.add(ga.q_off), at_all_q = blob.add(ga.q_list);
@@ -691,7 +883,9 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     // selection kernel stores each query's threshold in the resident-query image
     mp.q_split = std::max(mp.q_split, 1);
     const int32_t rows_local = ((mp.n_blocks + mp.q_split - 1) / mp.q_split) * 16;
-    std::vector<int32_t> prow((size_t)set_mfma.n * st::kPrefetchStride + 1, -1), q_taupos(batch, -1);
+    std::vector<int32_t>&prow = hs.prow, &q_taupos = hs.q_taupos;
+    prow.assign((size_t)set_mfma.n * st::kPrefetchStride + 1, -1);
+    q_taupos.assign((size_t)batch, -1);
     for (int32_t g = 0; g < set_mfma.n; ++g) {
         const int32_t nr = set_mfma.row_off[g + 1] - set_mfma.row_off[g];
         for (int32_t r = 0; r < nr && r < st::kPrefetchStride; ++r)
@@ -712,7 +906,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         if ((blk_off[g + 1] - blk_off[g] + mp.q_split - 1) / mp.q_split > 1) mp.multi_block = 1;
     const size_t at_prow = blob.add(prow), at_taupos = blob.add(q_taupos);
     // seed kernel: the first signature rows of every query's filter and their number
-    std::vector<int32_t> q_prow((size_t)batch * (st::kSeedRows + 1), -1);
+    std::vector<int32_t>& q_prow = hs.q_prow;
+    q_prow.assign((size_t)batch * (st::kSeedRows + 1), -1);
     for (int32_t b = 0; b < batch; ++b) {
         const int32_t g = groups.q2grp[b], nr = groups.row_off[g + 1] - groups.row_off[g];
         for (int32_t r = 0; r < nr && r < st::kSeedRows; ++r)
@@ -721,20 +916,32 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     }
     const size_t at_qprow = blob.add(q_prow);
     if (blob.bytes() > L.meta_bytes) return fail(ST_EINVAL, "group tables exceed their workspace slot");
+    if (dry_out) {
+        dry_out[0] = groups.n_groups;
+        dry_out[1] = set_mfma.n;
+        dry_out[2] = set_dot.n;
+        dry_out[3] = mp.q_split;
+        dry_out[4] = set_mfma.n ? mp.waves : 0;
+        dry_out[5] = plan.n_levels;
+        dry_out[6] = (int32_t)blob.bytes();
+        dry_out[7] = plan.n_levels > 0 && plan.level[0].seed ? 1 : 0;
+        return ST_OK;
+    }
 
     char* ws = (char*)dev_workspace;
-    Stage* stage = nullptr;
-    rc = stage_acquire(blob.bytes(), &stage);
+    StageHold stage;
+    rc = stage_get(blob.bytes(), stream, &stage);
     if (rc != ST_OK) return rc;
-    memcpy(stage->host, blob.data.data(), blob.bytes());
+    memcpy(stage.host(), blob.data.data(), blob.bytes());
     // A search that starts with the seed pass lets that kernel bring the tables over (it reads its
     // own from the pinned copy); otherwise they are copied ahead of the first kernel.
     const bool seed_uploads = plan.n_levels > 0 && plan.level[0].seed;
     if (!seed_uploads) {
-        ST_HIP(hipMemcpyAsync(ws + L.meta, stage->host, blob.bytes(), hipMemcpyHostToDevice, stream));
-        ST_HIP(hipEventRecord(stage->ev, stream));
+        stage.enqueued = true;
+        ST_HIP(hipMemcpyAsync(ws + L.meta, stage.host(), blob.bytes(), hipMemcpyHostToDevice, stream));
+        rc = stage_record(&stage);
+        if (rc != ST_OK) return rc;
     }
-    stage->in_flight = true;
     auto tab = [&](size_t at) { return (const int32_t*)(ws + L.meta + at); };
 
     st::ScanParams sp;
@@ -825,7 +1032,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
             st::SeedUpload up;
-            up.src = (const int32_t*)stage->dev_view;
+            up.src = (const int32_t*)stage.dev_view();
             up.dst = (int32_t*)(ws + L.meta);
             up.words = (int32_t)(blob.bytes() / 4);
             up.img_q = nullptr;
@@ -833,22 +1040,24 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                 up.img_q = mp.img_q;
                 up.img_sq = mp.img_sq;
                 up.img_qrow = mp.img_qrow;
-                up.blk_row = (const int32_t*)((const char*)stage->dev_view + at_blk_row);
+                up.blk_row = (const int32_t*)((const char*)stage.dev_view() + at_blk_row);
                 up.n_blocks = mp.n_blocks;
                 up.q_split = mp.q_split;
                 up.rows_local = rows_local;
                 mfma_started = true;
             }
             st::SelectParams se_seed = se;  // the seed pass reads its tables from the pinned copy
-            auto host_tab = [&](size_t at) { return (const int32_t*)((const char*)stage->dev_view + at); };
+            auto host_tab = [&](size_t at) { return (const int32_t*)((const char*)stage.dev_view() + at); };
             se_seed.q_prow = host_tab(at_qprow);
             se_seed.q2grp = host_tab(at_q2grp);
             se_seed.q_taupos = host_tab(at_taupos);
             se_seed.scan.grp_row_off = host_tab(at_all_row_off);
             se_seed.scan.grp_rows = host_tab(at_all_rows);
             seed_parts = st::seed_parts(batch, L.k_pad);
+            stage.enqueued = true;
             ST_HIP(st::launch_seed(se_seed, L_.end, batch, seed_parts, up, stream));
-            ST_HIP(hipEventRecord(stage->ev, stream));
+            rc = stage_record(&stage);
+            if (rc != ST_OK) return rc;
             continue;
         }
         for (st::ScanParams* q : {&sp_m, &sp_d}) {
@@ -919,12 +1128,12 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             const size_t big_bytes = (size_t)L.k_pad * 8;
             constexpr size_t kBigSortMax = 128 * 1024;
             se.big_sort = (se.srt && big_bytes <= kBigSortMax) ? 1 : 0;
-            static bool lds_set = false;
-            if (!lds_set) {
+            static std::atomic<bool> lds_set{false};  // (setting the attribute twice is harmless)
+            if (!lds_set.load(std::memory_order_acquire)) {
                 ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&st::select_kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)std::max<size_t>(st::kSelectLdsBytes, kBigSortMax)));
-                lds_set = true;
+                lds_set.store(true, std::memory_order_release);
             }
             const size_t lds = std::max<size_t>((size_t)st::select_lds_bytes(se.lds_keys), se.big_sort ? big_bytes : 0);
             hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), lds, stream, se);
@@ -940,9 +1149,11 @@ int st_search(const st_bloom* bloom, const int8_t* dev_items, const float* dev_i
               int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count, void* dev_workspace,
               int64_t workspace_bytes, void* hip_stream)
 {
+    return guarded([&]() -> int {
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, 1,
                        nullptr, host_filt_ids, host_filt_offsets, K, dev_out_ids, dev_out_scores,
                        dev_out_count, dev_workspace, workspace_bytes, hip_stream);
+    });
 }
 
 int st_search_multitask(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
@@ -952,15 +1163,37 @@ int st_search_multitask(const st_bloom* bloom, const int8_t* dev_items, const fl
                         int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
                         void* dev_workspace, int64_t workspace_bytes, void* hip_stream)
 {
+    return guarded([&]() -> int {
     if (!host_task_weight) return fail(ST_EINVAL, "host_task_weight is null");
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch,
                        n_tasks, host_task_weight, host_filt_ids, host_filt_offsets, K, dev_out_ids,
                        dev_out_scores, dev_out_count, dev_workspace, workspace_bytes, hip_stream);
+    });
+}
+
+int st_search_host_plan(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K, int32_t m_bits,
+                        int32_t k_hashes, const uint64_t* host_filt_ids, const int64_t* host_filt_offsets,
+                        int32_t* host_out_summary)
+{
+    return guarded([&]() -> int {
+        if (!host_out_summary) return fail(ST_EINVAL, "host_out_summary is null");
+        if (m_bits < 1 || m_bits > ST_MAX_M_BITS) return fail(ST_EINVAL, "m_bits=%d out of range", m_bits);
+        if (k_hashes < 1 || k_hashes > ST_MAX_K_HASHES) return fail(ST_EINVAL, "k_hashes=%d out of range", k_hashes);
+        st_bloom desc;  // sizes only: the dry run reads no device memory
+        desc.n_items = n_items;
+        desc.m_bits = m_bits;
+        desc.k_hashes = k_hashes;
+        const float unit_weights[ST_MAX_TASKS] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};
+        return search_impl(&desc, nullptr, nullptr, n_items, d, nullptr, nullptr, batch, n_tasks,
+                           n_tasks > 1 ? unit_weights : nullptr, host_filt_ids, host_filt_offsets, K, nullptr, nullptr,
+                           nullptr, nullptr, 0, nullptr, nullptr, nullptr, 0, true, 64, host_out_summary);
+    });
 }
 
 int st_bloom_mask_expr(const st_bloom* bloom, const int32_t* host_expr_ops, const uint64_t* host_expr_ids,
                        const int64_t* host_expr_offsets, int32_t n_exprs, uint64_t* dev_mask, void* hip_stream)
 {
+    return guarded([&]() -> int {
     if (!bloom || !host_expr_offsets || !dev_mask) return fail(ST_EINVAL, "null argument");
     if (n_exprs < 0 || n_exprs > 65535) return fail(ST_EINVAL, "n_exprs=%d out of range", n_exprs);
     ExprTables tab;
@@ -990,6 +1223,7 @@ int st_bloom_mask_expr(const st_bloom* bloom, const int32_t* host_expr_ops, cons
     rc = body();
     (void)hipFree(d_tab);
     return rc;
+    });
 }
 
 static int64_t expr_ws_bytes(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks, int32_t K,
@@ -1018,6 +1252,7 @@ int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* 
                    int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count, void* dev_workspace,
                    int64_t workspace_bytes, void* hip_stream)
 {
+    return guarded([&]() -> int {
     if (!bloom || !host_expr_offsets || !dev_workspace) return fail(ST_EINVAL, "null argument");
     if (!host_task_weight && n_tasks != 1) return fail(ST_EINVAL, "n_tasks=%d needs host_task_weight", n_tasks);
     const int64_t base = st_search_workspace_bytes(n_items, d, batch, n_tasks, K);
@@ -1047,18 +1282,19 @@ int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* 
         const size_t bytes = (n_off + n_code + n_rows) * 4;
         if (bytes > expr_table_bytes(batch, host_expr_offsets[batch], ST_MAX_K_HASHES))
             return fail(ST_EINVAL, "program tables exceed their workspace slot");
-        Stage* stage = nullptr;
-        rc = stage_acquire(bytes, &stage);
+        StageHold stage;
+        rc = stage_get(bytes, stream, &stage);
         if (rc != ST_OK) return rc;
-        int32_t* h = (int32_t*)stage->host;
+        int32_t* h = (int32_t*)stage.host();
         memcpy(h, tab.prog_off.data(), n_off * 4);
         if (n_code) memcpy(h + n_off, tab.code.data(), n_code * 4);
         if (n_rows) memcpy(h + n_off + n_code, tab.leaf_rows.data(), n_rows * 4);
         // small tables are read by the kernel straight from the pinned slot (each workgroup fetches
         // its program once); larger ones are copied to the workspace first
-        const int32_t* t_dev = (const int32_t*)stage->dev_view;
+        const int32_t* t_dev = (const int32_t*)stage.dev_view();
+        stage.enqueued = true;
         if (bytes > 64 * 1024) {
-            ST_HIP(hipMemcpyAsync(d_tab, stage->host, bytes, hipMemcpyHostToDevice, stream));
+            ST_HIP(hipMemcpyAsync(d_tab, stage.host(), bytes, hipMemcpyHostToDevice, stream));
             t_dev = d_tab;
         }
         const int64_t n_words = n_tiles * st::kTileWords;  // whole tiles: the pad words become 0
@@ -1070,12 +1306,13 @@ int st_search_expr(const st_bloom* bloom, const int8_t* dev_items, const float* 
                                tab.n_exprs, mask_rows);
         }
         ST_HIP(hipGetLastError());
-        ST_HIP(hipEventRecord(stage->ev, stream));
-        stage->in_flight = true;
+        rc = stage_record(&stage);
+        if (rc != ST_OK) return rc;
     }
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, n_tasks,
                        host_task_weight, nullptr, nullptr, K, dev_out_ids, dev_out_scores, dev_out_count,
                        dev_workspace, base, hip_stream, &groups, mask_rows, tab.n_exprs);
+    });
 }
 
 // Region capacity of the probing search: the largest, so that the first level (every pair
@@ -1104,6 +1341,7 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
                   int32_t K, int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
                   int32_t* dev_out_probes, void* dev_workspace, int64_t workspace_bytes, void* hip_stream)
 {
+    return guarded([&]() -> int {
     if (!bloom || !host_expr_offsets || !dev_workspace || !dev_centroids || !dev_centroid_scale ||
         !dev_cluster_offsets || !dev_queries || !dev_query_scale)
         return fail(ST_EINVAL, "null argument");
@@ -1204,21 +1442,22 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
         const size_t bytes = (n_off + n_code + n_rows) * 4;
         if (bytes > expr_table_bytes(batch, host_expr_offsets[batch], ST_MAX_K_HASHES))
             return fail(ST_EINVAL, "program tables exceed their workspace slot");
-        Stage* stage = nullptr;
-        rc = stage_acquire(bytes, &stage);
+        StageHold stage;
+        rc = stage_get(bytes, stream, &stage);
         if (rc != ST_OK) return rc;
-        int32_t* h = (int32_t*)stage->host;
+        int32_t* h = (int32_t*)stage.host();
         memcpy(h, tab.prog_off.data(), n_off * 4);
         if (n_code) memcpy(h + n_off, tab.code.data(), n_code * 4);
         if (n_rows) memcpy(h + n_off + n_code, tab.leaf_rows.data(), n_rows * 4);
-        const int32_t* t_dev = (const int32_t*)stage->dev_view;
+        const int32_t* t_dev = (const int32_t*)stage.dev_view();
+        stage.enqueued = true;
         if (bytes > 64 * 1024) {
-            ST_HIP(hipMemcpyAsync(d_tab, stage->host, bytes, hipMemcpyHostToDevice, stream));
+            ST_HIP(hipMemcpyAsync(d_tab, stage.host(), bytes, hipMemcpyHostToDevice, stream));
             t_dev = d_tab;
         }
         if (per_query) {
             st::Plan plan1;
-            if (st::make_plan(n_items, K, 1, st::kMaxSegItems, batch, &plan1, 2048, kIvfCap) != 0)
+            if (cached_plan(n_items, K, 1, st::kMaxSegItems, batch, &plan1, 2048, kIvfCap) != 0)
                 return fail(ST_EINVAL, "no schedule for these sizes");
             const st::Layout L = st::make_layout(plan1, batch, K, d, 1);
             st::IvfQueryParams qp;
@@ -1270,9 +1509,7 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
                     hipLaunchKernelGGL(st::ivf_merge_kernel, dim3(batch), dim3(st::kQueryThreads), 0, stream, qp, parts);
             }
             ST_HIP(hipGetLastError());
-            ST_HIP(hipEventRecord(stage->ev, stream));
-            stage->in_flight = true;
-            return ST_OK;
+            return stage_record(&stage);
         }
         {   // phase 2: the filter over the probed ranges only, into zeroed mask rows
             TimedLaunch t(3, stream);
@@ -1284,13 +1521,14 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
                                t_dev + n_off + n_code, mask_rows);
         }
         ST_HIP(hipGetLastError());
-        ST_HIP(hipEventRecord(stage->ev, stream));
-        stage->in_flight = true;
+        rc = stage_record(&stage);
+        if (rc != ST_OK) return rc;
     }
     // phases 3 and 4
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, 1, nullptr,
                        nullptr, nullptr, K, dev_out_ids, dev_out_scores, dev_out_count, dev_workspace, base,
                        hip_stream, &groups, mask_rows, batch, false, kIvfCap);
+    });
 }
 
 int st_quantize_global(const float* dev_x, int64_t n_rows, int32_t d, int8_t* dev_q, float* dev_row_scale,
@@ -1317,6 +1555,20 @@ int st_quantize_global(const float* dev_x, int64_t n_rows, int32_t d, int8_t* de
         TimedLaunch t(0, stream);
         hipLaunchKernelGGL(st::quant_apply_kernel, dim3(grid), dim3(st::kQuantThreads), 0, stream, dev_x, n, n_rows, mm,
                            dev_q, dev_row_scale, dev_minmax);
+    }
+    ST_HIP(hipGetLastError());
+    return ST_OK;
+}
+
+int st_stream_read(const void* dev_src, int64_t bytes, void* dev_sink, int32_t workgroups, void* hip_stream)
+{
+    if (!dev_src || !dev_sink || bytes < 0) return fail(ST_EINVAL, "null argument or negative size");
+    if (((uintptr_t)dev_src & 15) || ((uintptr_t)dev_sink & 3)) return fail(ST_EINVAL, "misaligned buffer (source 16 B, sink 4 B)");
+    if (workgroups < 1 || workgroups > 65536) return fail(ST_EINVAL, "workgroups=%d out of range", workgroups);
+    {
+        TimedLaunch t(0, (hipStream_t)hip_stream);
+        hipLaunchKernelGGL(st::stream_read_kernel, dim3((unsigned)workgroups), dim3(st::kStreamThreads), 0,
+                           (hipStream_t)hip_stream, (const int4*)dev_src, bytes / 16, (uint32_t*)dev_sink);
     }
     ST_HIP(hipGetLastError());
     return ST_OK;

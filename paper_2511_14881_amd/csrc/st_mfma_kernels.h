@@ -20,9 +20,12 @@
 // so with T in {1, 2, 4} tasks the rows one lane holds are whole queries and the Value-Model
 // sum needs no cross-lane traffic.
 #pragma once
+#include <atomic>
 #include <type_traits>
 
-#include "st_search_kernels.h"
+#include "st_device.h"
+#include "st_plan.h"
+#include "st_scan_params.h"
 
 namespace st {
 
@@ -124,7 +127,10 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
     // the per-row constants are read from LDS once for both: LDS bandwidth, not the matrix cores,
     // bounds the loop when a filter group holds many query blocks); their ring holds two pairs.
     constexpr bool PAIRS = NW == 8 && KS <= 2;
-    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? ST_NB2 : 2));
+    #ifndef ST_NB4
+#define ST_NB4 2
+#endif
+    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? ST_NB2 : (KS == 4 ? ST_NB4 : 2)));
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
@@ -429,7 +435,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
 
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 1);
     int thr_E = -1000;  // exponent the wavefront's integer bounds were built for (none yet)
+#ifdef ST_STAMPS
+    uint64_t acc_t[4] = {0, 0, 0, 0}, acc_last = wall_clock64();
+#define ST_ACC(k) do { const uint64_t now_ = wall_clock64(); acc_t[k] += now_ - acc_last; acc_last = now_; } while (0)
+#else
+#define ST_ACC(k) do { } while (0)
+#endif
     for (bool first = true; stage_ok(cur); first = false) {
+        ST_ACC(3);
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(cur) * seg_items;
         const int g0 = cur.batch * FB;
         const int nf = min(FB, p.n_groups - g0);
@@ -523,6 +536,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             }
         }
 
+        ST_ACC(0);
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
         // contracted: uniform bases + 32-bit lane offsets (the segment spans at most 512 * D bytes)
@@ -552,7 +566,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
             const uint32_t off = (uint32_t)(idx * D);
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
+#ifdef ST_EXP_NOROWS
+                const int4 v = make_int4((int)off, k, lane, idx);
+#else
                 const int4 v = *reinterpret_cast<const int4*>(seg_rows + (off + 64u * k));
+#endif
                 w.b[k] = v4i{v.x, v.y, v.z, v.w};
             }
             w.si = s_scl[idx];
@@ -637,6 +655,14 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                               uint64_t (&hits)[4]) -> bool {
             const int thv[4] = {thr.x, thr.y, thr.z, thr.w};
             uint64_t any = 0;
+#ifdef ST_EXP_NOTEST
+            {
+                const int mx = max(max(acc[0], acc[1]), max(acc[2], acc[3]));
+                hits[0] = hits[1] = hits[2] = hits[3] = ballot(mx == 0x7fffffff + thv[0] * 0);
+                val[0] = val[1] = val[2] = val[3] = 0;
+                return (hits[0] & valid) != 0;
+            }
+#endif
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 hits[r] = ballot(__mulhi(acc[r], w.si_fix) >= thv[r]);
@@ -672,6 +698,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         };
         auto block_mfma = [&](const v4i (&a)[KS], const UnitRegs<KS>& w) -> v4i {
             v4i acc = {0, 0, 0, 0};
+#ifdef ST_EXP_NOMFMA
+#pragma unroll
+            for (int k = 0; k < KS; ++k) acc += a[k] ^ w.b[k];
+            return acc;
+#endif
 #pragma unroll
             for (int k = 0; k < KS; ++k) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[k], w.b[k], acc, 0, 0, 0);
             return acc;
@@ -897,12 +928,19 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
                 }
             }
             if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 5);
+            ST_ACC(1);
             while (qn > 0) drain();
+            ST_ACC(2);
         }
         if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 6);
         cur = nxt;
     }
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 7);
+#ifdef ST_STAMPS
+    if (p.stamps && threadIdx.x == 0 && wg_lin < 4096) {
+        for (int k = 0; k < 4; ++k) p.stamps[((p.stamp_level * 4096) + wg_lin) * 16 + 12 + k] = acc_t[k];
+    }
+#endif
     __syncthreads();
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 8);
     // region fill counts: real ones for the queries this workgroup row owns, zero for the others
@@ -1014,46 +1052,62 @@ inline int mfma_lds_bytes(int n_blocks, int S, int d, int n_tasks, int n_groups,
 template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW, bool ADMIT = false>
 inline hipError_t launch_scan_mfma_t(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
-    static int max_set = 0;  // largest dynamic LDS size this instantiation has been allowed
-    if (mp.lds_total > max_set) {
+    static std::atomic<int> max_set{0};  // largest dynamic LDS size this instantiation has been allowed
+    if (mp.lds_total > max_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW, ADMIT>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, mp.lds_total);
         if (e != hipSuccess) return e;
-        max_set = mp.lds_total;
+        max_set.store(mp.lds_total, std::memory_order_release);
     }
     const dim3 grid((unsigned)gx, (unsigned)mp.q_split);
     hipLaunchKernelGGL((scan_mfma_kernel<KS, TT, WEIGHTED, MULTI, NW, ADMIT>), grid, dim3(NW * 64), (size_t)mp.lds_total, stream, sp, mp);
     return hipGetLastError();
 }
 
+// The instantiations are compiled in one translation unit per embedding width (st_mfma_ks*.hip),
+// so that the library builds in parallel; each defines its launcher through this template.
 // gx = workgroups per row of the grid (at most groups / q_split); region index = x + y * gx
-inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
+template <int KS>
+inline hipError_t launch_scan_mfma_ks(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
-    if (sp.seg_items > mp.seg_stride || mp.seg_stride > kMfmaSegItems || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
-    const int ks = sp.d / 64, tt = sp.n_tasks;
+    const int tt = sp.n_tasks;
     // first level, one segment per region: every pair is a candidate and is stored directly
     const bool admit = !sp.use_tau && sp.seg_per_visit == 1 && sp.seg_items <= sp.cap;
 // plain search has one task per query (several tasks always come with weights)
-#define ST_ARM(K_, T_, W_, M_, N_, A_)                                                                           \
-    ((W_ || T_ == 1) ? launch_scan_mfma_t<K_, (W_ || T_ == 1) ? T_ : 1, W_, M_, N_, A_>(sp, mp, gx, stream)       \
+#define ST_ARM(T_, W_, M_, N_, A_)                                                                               \
+    ((W_ || T_ == 1) ? launch_scan_mfma_t<KS, (W_ || T_ == 1) ? T_ : 1, W_, M_, N_, A_>(sp, mp, gx, stream)       \
                      : hipErrorInvalidValue)
-#define ST_CASE(K_, T_)                                                                                          \
-    if (ks == K_ && tt == T_) {                                                                                  \
+#define ST_CASE(T_)                                                                                              \
+    if (tt == T_) {                                                                                              \
         if (mp.waves == 8 && admit)                                                                              \
-            return sp.weighted ? ST_ARM(K_, T_, true, true, 8, true) : ST_ARM(K_, T_, false, true, 8, true);     \
+            return sp.weighted ? ST_ARM(T_, true, true, 8, true) : ST_ARM(T_, false, true, 8, true);             \
         if (mp.waves == 8)                                                                                       \
-            return sp.weighted ? ST_ARM(K_, T_, true, true, 8, false) : ST_ARM(K_, T_, false, true, 8, false);   \
+            return sp.weighted ? ST_ARM(T_, true, true, 8, false) : ST_ARM(T_, false, true, 8, false);           \
         if (mp.multi_block || mp.region_slots != 1 || mp.seg_stride != 256)                                      \
-            return sp.weighted ? ST_ARM(K_, T_, true, true, 4, false) : ST_ARM(K_, T_, false, true, 4, false);   \
-        return sp.weighted ? ST_ARM(K_, T_, true, false, 4, false) : ST_ARM(K_, T_, false, false, 4, false);     \
+            return sp.weighted ? ST_ARM(T_, true, true, 4, false) : ST_ARM(T_, false, true, 4, false);           \
+        return sp.weighted ? ST_ARM(T_, true, false, 4, false) : ST_ARM(T_, false, false, 4, false);             \
     }
-    ST_CASE(1, 1) ST_CASE(1, 2) ST_CASE(1, 4)
-    ST_CASE(2, 1) ST_CASE(2, 2) ST_CASE(2, 4)
-    ST_CASE(4, 1) ST_CASE(4, 2) ST_CASE(4, 4)
-    ST_CASE(8, 1) ST_CASE(8, 2) ST_CASE(8, 4)
+    ST_CASE(1) ST_CASE(2) ST_CASE(4)
 #undef ST_ARM
 #undef ST_CASE
     return hipErrorInvalidValue;
+}
+
+hipError_t launch_scan_mfma_ks1(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream);
+hipError_t launch_scan_mfma_ks2(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream);
+hipError_t launch_scan_mfma_ks4(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream);
+hipError_t launch_scan_mfma_ks8(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream);
+
+inline hipError_t launch_scan_mfma(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
+{
+    if (sp.seg_items > mp.seg_stride || mp.seg_stride > kMfmaSegItems || sp.n_groups > kMfmaMaxGroups) return hipErrorInvalidValue;
+    switch (sp.d) {
+        case 64: return launch_scan_mfma_ks1(sp, mp, gx, stream);
+        case 128: return launch_scan_mfma_ks2(sp, mp, gx, stream);
+        case 256: return launch_scan_mfma_ks4(sp, mp, gx, stream);
+        case 512: return launch_scan_mfma_ks8(sp, mp, gx, stream);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace st

@@ -1,0 +1,11 @@
+// Instantiations of the int8 MFMA scan for d = 512 (8 contraction steps of 64 bytes per row).
+#include "st_mfma_kernels.h"
+
+namespace st {
+
+hipError_t launch_scan_mfma_ks8(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
+{
+    return launch_scan_mfma_ks<8>(sp, mp, gx, stream);
+}
+
+}  // namespace st

@@ -119,4 +119,34 @@ __global__ __launch_bounds__(kQuantThreads) void quant_apply_kernel(const float*
     }
 }
 
+// Plain streaming read for bandwidth measurements: every thread reads 16-byte pieces a whole
+// grid apart (four in flight per step) and folds them into one word, so that nothing but the
+// loads remains; one word per workgroup is written.  The measured rate of this kernel is the
+// practical ceiling the HBM-bound kernels of the library are compared with.
+constexpr int kStreamThreads = 256;
+__global__ __launch_bounds__(kStreamThreads) void stream_read_kernel(const int4* __restrict__ src, int64_t n16,
+                                                                     uint32_t* __restrict__ sink)
+{
+    const int64_t stride = (int64_t)gridDim.x * kStreamThreads;
+    int64_t i = (int64_t)blockIdx.x * kStreamThreads + threadIdx.x;
+    int acc = 0;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const int4 a = src[i], b = src[i + stride], c = src[i + 2 * stride], d = src[i + 3 * stride];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w ^ b.x ^ b.y ^ b.z ^ b.w ^ c.x ^ c.y ^ c.z ^ c.w ^ d.x ^ d.y ^ d.z ^ d.w;
+    }
+    for (; i < n16; i += stride) {
+        const int4 a = src[i];
+        acc ^= a.x ^ a.y ^ a.z ^ a.w;
+    }
+    for (int o = 32; o > 0; o >>= 1) acc ^= __shfl_xor(acc, o);
+    __shared__ int s_part[kStreamThreads / 64];
+    if ((threadIdx.x & 63) == 0) s_part[threadIdx.x >> 6] = acc;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int v = 0;
+        for (int w = 0; w < kStreamThreads / 64; ++w) v ^= s_part[w];
+        sink[blockIdx.x] = (uint32_t)v;
+    }
+}
+
 }  // namespace st

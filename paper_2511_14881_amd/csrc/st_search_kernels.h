@@ -3,68 +3,17 @@
 // candidate regions overflowed (rescue).  Paper: Sec. 4.1 (Eq. 4), Sec. 4.2, Sec. 4.3
 // (Algorithm 1 phases 3-4), Sec. 5.2.
 #pragma once
+#include <atomic>
+
 #include "st_bloom_kernels.h"
 #include "st_device.h"
 #include "st_plan.h"
+#include "st_scan_params.h"
 
 namespace st {
 
 constexpr int kScanThreads = 256;
 constexpr int kFilterBatch = 16;  // distinct filters handled per pass over a segment
-
-constexpr int kTauParts = 8;  // thresholds per query (the seed pass leaves one per slice; readers take the minimum)
-
-struct ScanParams {
-    // Bloom index
-    const uint64_t* bloom;
-    int32_t m_bits;
-    // corpus
-    const int8_t* items;
-    const float* iscale;
-    int64_t n_items;
-    int32_t d;
-    // queries
-    const int8_t* queries;  // [B, T, d]
-    const float* qscale;    // [B, T]
-    int32_t batch;
-    int32_t n_tasks;
-    int32_t weighted;       // 0: single task, score = rescale; 1: fmaf chain over tasks
-    float w[8];
-    // filter groups: queries that share one set of signature rows
-    int32_t n_groups;
-    const int32_t* grp_row_off;  // [F+1]
-    const int32_t* grp_rows;
-    const int32_t* grp_q_off;    // [F+1]
-    const int32_t* grp_q;        // query indices, grouped
-    // level
-    int64_t item_begin, item_end;
-    int32_t seg_items;
-    int32_t seg_per_visit;       // consecutive segments a workgroup takes before striding on
-    int32_t use_tau;
-    const uint64_t* tau;         // [B][kTauParts]
-    int32_t tau_parts;           // entries of tau in use per query
-    // output regions
-    uint64_t* cand;              // [B][G][cap]
-    uint32_t* cnt;               // [B][G]
-    uint32_t* ovf;               // [B]
-    int32_t cap;
-    int32_t groups;              // G (== gridDim.x)
-    uint64_t* stamps;            // null unless the library is built with ST_STAMPS (timeline probe)
-    int32_t stamp_level;         // level index the probe files this launch under
-};
-
-// Timeline probe for tuning builds (-DST_STAMPS): thread 0 of a workgroup records the 10-ns wall
-// clock at point k into stamps[((kind * 4096) + slot) * 16 + k].  Compiles to nothing otherwise.
-#ifdef ST_STAMPS
-#define ST_STAMP(buf, kind, slot, k)                                                                   \
-    do {                                                                                               \
-        if ((buf) && threadIdx.x == 0 && (slot) < 4096) (buf)[(((kind) * 4096) + (slot)) * 16 + (k)] = wall_clock64(); \
-    } while (0)
-#else
-#define ST_STAMP(buf, kind, slot, k) \
-    do {                             \
-    } while (0)
-#endif
 
 // Score of one (query, item) pair from the item row held by this lane.
 __device__ inline float pair_score(const ScanParams& p, int q, const int8_t* item_row, float s_i)
@@ -1177,12 +1126,12 @@ template <int D16>
 inline hipError_t launch_seed_t(const SelectParams& se, int64_t seed_items, int batch, int parts, const SeedUpload& up,
                                 hipStream_t stream)
 {
-    static bool lds_set = false;
-    if (!lds_set) {
+    static std::atomic<bool> lds_set{false};
+    if (!lds_set.load(std::memory_order_acquire)) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&seed_kernel<D16>),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, kSelectLdsBytes);
         if (e != hipSuccess) return e;
-        lds_set = true;
+        lds_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL(seed_kernel<D16>, dim3(batch, parts), dim3(kSeedThreads), kSelectLdsBytes, stream, se, seed_items,
                        up);

@@ -281,6 +281,24 @@ def make_workload(cfg: Config, device="cpu") -> Workload:
     return Workload(cfg, items, item_scale, off, ids, q, qs, w, fid, foff, pool)
 
 
+def refilter(w: Workload, target_sel: float, name: str | None = None) -> Workload:
+    """The same corpus and queries with another filter pool: conjunctions whose exact-set
+    selectivity is closest to target_sel (1.0 = the broadest the 32 most frequent ids allow).
+    Shares every tensor with w; only the config and the host filter arrays are new."""
+    cfg = scaled(w.cfg, w.cfg.n_items, target_sel=target_sel,
+                 name=name or f"{w.cfg.name}+sel{target_sel:g}")
+    sample_items = min(cfg.n_items, 200_000)
+    sample = w.feat_ids[: sample_items * cfg.feats_per_item].cpu().numpy()
+    pool = choose_filter_pool(cfg, sample)
+    fid, foff = gen_filters(cfg, pool)
+    return Workload(cfg, w.items, w.item_scale, w.feat_offsets, w.feat_ids, w.queries, w.query_scale,
+                    w.task_weight, fid, foff, pool)
+
+
+# selectivity targets of the Large workload's sweep (the last one: the broadest available)
+LARGE_SWEEP = (0.001, 0.01, 0.05, 1.0)
+
+
 # operation codes of a filter program (postfix order), as the library's header defines them
 OP_LEAF, OP_AND, OP_OR, OP_NOT = 0, 1, 2, 3
 
