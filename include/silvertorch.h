@@ -150,6 +150,24 @@ int st_search(const st_bloom* bloom, const int8_t* dev_items, const float* dev_i
               int32_t K, int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
               void* dev_workspace, int64_t workspace_bytes, void* hip_stream);
 
+/* st_search for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid allocation.  The workspace is a
+ * fixed device array of ST_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until
+ * the process ends); the call allocates nothing, on the device or pinned (the staging slots and
+ * the array's address are set up by st_bloom_build on that device).  Sizes whose
+ * st_search_workspace_bytes() exceeds ST_STATIC_SCRATCH_BYTES give ST_EWORKSPACE (the Mid shape,
+ * 1 M items x batch 64 x K 100, fits); a batch whose filter tables exceed a 64 KB staging slot gives
+ * ST_EINVAL.  Every call on a GPU uses that GPU's one array: calls that overlap in time on one
+ * GPU (two streams, two threads) race, callers serialise them.  Nothing in the array has to
+ * survive from call to call and nothing has to be cleared: every kernel of a search writes what
+ * it later reads.  Arguments, outputs, ordering, asynchrony and errors otherwise as for st_search. */
+#define ST_STATIC_SCRATCH_BYTES (80ll << 20)
+int st_search_static(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale,
+                     int64_t n_items, int32_t d, const int8_t* dev_queries, const float* dev_query_scale,
+                     int32_t batch, const uint64_t* host_filt_ids, const int64_t* host_filt_offsets,
+                     int32_t K, int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count,
+                     void* hip_stream);
+
 /* Multi-task variant (Sec. 5.2): one embedding per task and query, item embeddings shared,
  * one result list per query on the Value Model's weighted sum of the per-task scores.
  *   dev_queries [batch, n_tasks, d], dev_query_scale [batch, n_tasks],

@@ -23,7 +23,7 @@ EXPORTS = [
     "st_search_plan", "st_set_scoring_path", "st_timing_begin", "st_timing_end",
     "st_search_overflow_flags_offset", "st_bloom_mask_expr", "st_search_expr_workspace_bytes",
     "st_search_expr", "st_search_ivf_workspace_bytes", "st_search_ivf", "st_quantize_global", "st_value_model",
-    "st_search_host_plan", "st_stream_read",
+    "st_search_host_plan", "st_stream_read", "st_search_static",
 ]
 
 ST_OP_LEAF, ST_OP_AND, ST_OP_OR, ST_OP_NOT = 0, 1, 2, 3  # operations of a filter program
@@ -66,6 +66,8 @@ def lib() -> C.CDLL:
         L.st_search_overflow_flags_offset.argtypes = [i64, i32, i32, i32, i32]
         L.st_search.restype = C.c_int
         L.st_search.argtypes = [p, p, p, i64, i32, p, p, i32, p, p, i32, p, p, p, p, i64, p]
+        L.st_search_static.restype = C.c_int
+        L.st_search_static.argtypes = [p, p, p, i64, i32, p, p, i32, p, p, i32, p, p, p, p]
         L.st_search_multitask.restype = C.c_int
         L.st_search_multitask.argtypes = [p, p, p, i64, i32, p, p, i32, i32, p, p, p, i32, p, p, p, p,
                                           i64, p]
@@ -288,6 +290,32 @@ def st_search(bloom: BloomIndex, items, item_scale, queries, query_scale, filt_i
                            _dptr(buf.scores), _dptr(buf.count), _dptr(buf.workspace), buf.nbytes,
                            _stream(stream)))
     return buf.ids, buf.scores, buf.count
+
+
+ST_STATIC_SCRATCH_BYTES = 80 << 20
+
+
+def st_search_static(bloom: BloomIndex, items, item_scale, queries, query_scale, filt_ids, filt_offsets,
+                     K: int, out=None, stream=None):
+    """st_search on the library's own fixed workspace (no allocation inside the call).  out: the
+    (ids, scores, count) tensors to fill; allocated here, outside the library, if not given."""
+    _need(items, torch.int8, "items")
+    _need(item_scale, torch.float32, "item_scale")
+    _need(queries, torch.int8, "queries")
+    _need(query_scale, torch.float32, "query_scale")
+    n, d = items.shape
+    B = queries.shape[0]
+    if queries.dim() != 2 or queries.shape[1] != d or query_scale.numel() != B or item_scale.numel() != n:
+        raise ValueError("shape mismatch")
+    ids, off = _filters(filt_ids, filt_offsets, B)
+    if out is None:
+        out = (torch.empty((B, K), dtype=torch.int64, device="cuda"),
+               torch.empty((B, K), dtype=torch.float32, device="cuda"),
+               torch.empty(B, dtype=torch.int32, device="cuda"))
+    _check(lib().st_search_static(C.c_void_p(bloom.handle), _dptr(items), _dptr(item_scale), n, d, _dptr(queries),
+                                  _dptr(query_scale), B, _hptr(ids), _hptr(off), K, _dptr(out[0]), _dptr(out[1]),
+                                  _dptr(out[2]), _stream(stream)))
+    return out
 
 
 def st_search_multitask(bloom: BloomIndex, items, item_scale, queries, query_scale, task_weight,

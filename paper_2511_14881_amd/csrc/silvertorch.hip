@@ -25,6 +25,10 @@
 #include "st_plan.h"
 #include "st_search_kernels.h"
 
+// Workspace of st_search_static, the entry point for callers that may not allocate: device
+// memory that exists from the moment the code object is loaded, one copy per GPU.
+static __device__ __align__(256) unsigned char scratch[ST_STATIC_SCRATCH_BYTES];
+
 namespace {
 
 thread_local char g_err[512] = "";
@@ -124,6 +128,9 @@ struct StageHold {
     }
 };
 
+// Set while st_search_static runs in the calling thread: nothing may be allocated then.
+thread_local bool t_no_alloc = false;
+
 int stage_get(size_t bytes, hipStream_t stream, StageHold* h)
 {
     st::StageSlot* s = nullptr;
@@ -131,6 +138,9 @@ int stage_get(size_t bytes, hipStream_t stream, StageHold* h)
         return fail(ST_EHIP, "waiting for a staging slot failed");
     h->s = s;
     h->stream = stream;
+    if (t_no_alloc && (!s->event || s->bytes < bytes))
+        return fail(ST_EINVAL, "the tables of this batch (%zu bytes) exceed the pre-allocated staging slots (%zu bytes)",
+                    bytes, s->bytes);
     if (!s->event) {
         hipEvent_t ev;
         ST_HIP(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
@@ -152,6 +162,34 @@ int stage_record(StageHold* h)
 {
     ST_HIP(hipEventRecord((hipEvent_t)h->s->event, h->stream));
     h->recorded = true;
+    return ST_OK;
+}
+
+// Per-device set-up, run by st_bloom_build (which allocates anyway and precedes every search on
+// its device): the address of this device's copy of the static workspace, and, once per process,
+// pinned memory and an event for every staging slot, so that st_search_static finds all of it in
+// place.  In host code the array's name is only a handle for hipGetSymbolAddress; the address
+// kept here is what kernels and copies are given.
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_setup_mu;
+
+int device_setup(int device)
+{
+    if (device < 0 || device >= kMaxDevices) return fail(ST_EINVAL, "device %d out of range", device);
+    std::lock_guard<std::mutex> lock(g_setup_mu);
+    if (!g_scratch_ptr[device]) {
+        void* ptr = nullptr;
+        ST_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255)) return fail(ST_EHIP, "static workspace has no usable device address");
+        g_scratch_ptr[device] = ptr;
+    }
+    for (int i = 0; i < st::kStageSlots; ++i) {
+        // slots nobody has used yet (a slot in use has its memory and event already)
+        StageHold h;
+        const int rc = stage_get(64 * 1024, nullptr, &h);
+        if (rc != ST_OK) return rc;
+    }
     return ST_OK;
 }
 
@@ -579,6 +617,8 @@ int st_bloom_build(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_
     uint64_t* d_ids = nullptr;
     auto body = [&]() -> int {
         ST_HIP(hipGetDevice(&b->device));
+        const int rc_setup = device_setup(b->device);
+        if (rc_setup != ST_OK) return rc_setup;
         if (b->bytes > 0) ST_HIP(hipMalloc((void**)&b->dev, (size_t)b->bytes));
         if (n_items == 0) return ST_OK;
         const int64_t* off = feat_offsets;
@@ -1153,6 +1193,33 @@ int st_search(const st_bloom* bloom, const int8_t* dev_items, const float* dev_i
     return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, 1,
                        nullptr, host_filt_ids, host_filt_offsets, K, dev_out_ids, dev_out_scores,
                        dev_out_count, dev_workspace, workspace_bytes, hip_stream);
+    });
+}
+
+int st_search_static(const st_bloom* bloom, const int8_t* dev_items, const float* dev_item_scale, int64_t n_items,
+                     int32_t d, const int8_t* dev_queries, const float* dev_query_scale, int32_t batch,
+                     const uint64_t* host_filt_ids, const int64_t* host_filt_offsets, int32_t K,
+                     int64_t* dev_out_ids, float* dev_out_scores, int32_t* dev_out_count, void* hip_stream)
+{
+    return guarded([&]() -> int {
+        if (!bloom) return fail(ST_EINVAL, "bloom is null");
+        const int64_t need = st_search_workspace_bytes(n_items, d, batch, 1, K);
+        if (need < 0) return (int)need;
+        if (need > (int64_t)ST_STATIC_SCRATCH_BYTES)
+            return fail(ST_EWORKSPACE, "these sizes need %lld bytes of workspace, the static one holds %lld: use st_search",
+                        (long long)need, (long long)ST_STATIC_SCRATCH_BYTES);
+        int device = -1;
+        ST_HIP(hipGetDevice(&device));
+        if (device != bloom->device) return fail(ST_EINVAL, "the index lives on device %d, the current device is %d", bloom->device, device);
+        void* ws = device >= 0 && device < kMaxDevices ? g_scratch_ptr[device] : nullptr;
+        if (!ws) return fail(ST_EINVAL, "no static workspace on device %d (st_bloom_build sets it up)", device);
+        struct NoAlloc {
+            NoAlloc() { t_no_alloc = true; }
+            ~NoAlloc() { t_no_alloc = false; }
+        } guard;
+        return search_impl(bloom, dev_items, dev_item_scale, n_items, d, dev_queries, dev_query_scale, batch, 1,
+                           nullptr, host_filt_ids, host_filt_offsets, K, dev_out_ids, dev_out_scores, dev_out_count,
+                           ws, (int64_t)ST_STATIC_SCRATCH_BYTES, hip_stream);
     });
 }
 
