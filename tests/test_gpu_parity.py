@@ -251,6 +251,36 @@ def test_big_configs_full_size_sampled_queries(name):
     check_search(w, cfg.top_k, queries=range(0, cfg.batch, step), fast_path_only=True)
 
 
+# ------------------------------------------------------------------ Large: the selectivity sweep
+# The Large workload is specified with its filters' selectivity swept from 0.1 % to the broadest
+# conjunction the frequent ids allow (about 15 %): almost every 16-item unit is padding at the low
+# end, the candidate queues and regions are under the most pressure at the high end.
+@pytest.mark.parametrize("path", PATHS)
+@pytest.mark.parametrize("target", S.LARGE_SWEEP)
+def test_large_selectivity_sweep_small(target, path):
+    cfg = S.scaled(S.CONFIGS["large"], 150_000, batch=64, target_sel=target)
+    w = S.make_workload(cfg)
+    check_search(w, cfg.top_k, path=path, label=f"large recipe, selectivity target {target:g}")
+
+
+_LARGE_FULL = {}
+
+
+@pytest.mark.parametrize("target", S.LARGE_SWEEP)
+def test_large_selectivity_sweep_full_size(target):
+    # full-size corpus and batch in the launch configuration bench.py times; the oracle recomputes
+    # 32 queries spread over the batch (every distinct filter of the batch is among them)
+    if "w" not in _LARGE_FULL:
+        _LARGE_FULL["w"] = S.make_workload(S.CONFIGS["large"], device="cuda")
+    w = S.refilter(_LARGE_FULL["w"], target)
+    sels = set(tuple(f) for f in w.pool)
+    assert len(sels) == w.cfg.pool
+    check_search(w, w.cfg.top_k, queries=range(0, w.cfg.batch, 8), fast_path_only=True,
+                 label=f"large at full size, selectivity target {target:g}")
+    if target == S.LARGE_SWEEP[-1]:
+        _LARGE_FULL.clear()
+
+
 @pytest.mark.parametrize("d,T,all_pass", [(128, 0, False), (128, 0, True), (64, 2, False), (48, 0, False), (256, 4, False)])
 def test_seed_pass_small_batch_large_corpus(d, T, all_pass):
     # few query rows over a corpus of at least 8 x 32768 items: the prefix is scanned by one
