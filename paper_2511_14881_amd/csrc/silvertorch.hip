@@ -1062,6 +1062,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     se.q_taupos = tab(at_taupos);
     se.q_prow = tab(at_qprow);
     bool mfma_started = false;  // the first MFMA launch builds the resident-query image
+    bool density_on = false;    // the first level counts the pairs it admits (chooses the later levels' form of the scan)
     int seed_parts = 1;         // slices per query of the seed pass (one threshold each)
     for (int lv = 0; lv < plan.n_levels; ++lv) {
         const st::Level& L_ = plan.level[lv];
@@ -1151,6 +1152,21 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             regions = set_dot.n ? plan.groups : gx * mp.region_slots * mp.q_split;
             st::mfma_lds_layout(&mp, d, n_tasks, set_mfma.n, mp.waves);
             mp.first_level = mfma_started ? 0 : 1;
+            // A first level that admits every pair also counts them: the later levels choose the
+            // form of the scan by how many items a filter passes per segment.
+            {
+                st::ScanParams probe = sp_m;
+                probe.use_tau = lv > 0;
+                const bool admit_all = lv == 0 && mp.waves == 8 && !set_dot.n && probe.seg_per_visit == 1 && probe.seg_items <= probe.cap;
+                if (lv == 0) {
+                    density_on = admit_all;
+                    mp.density_acc = admit_all ? (unsigned long long*)(ws + L.density) : nullptr;
+                    // pairs of the level if every filter passed kDenseItems items per 512-item segment
+                    mp.density_limit = (unsigned long long)((L_.end - L_.begin) * (int64_t)batch / 512 * st::kDenseItems);
+                } else if (!density_on) {
+                    mp.density_acc = nullptr;
+                }
+            }
             mfma_started = true;
             TimedLaunch t(0, stream);
             ST_HIP(st::launch_scan_mfma(sp_m, mp, gx, stream));
@@ -1162,6 +1178,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             ST_HIP(hipGetLastError());
         }
         se.regions = regions;
+        se.density_acc = (lv == 0 && density_on) ? (unsigned long long*)(ws + L.density) : nullptr;
         {
             TimedLaunch t(1, stream);
             // K above the LDS sort size: the final ordering of k_pad keys runs in LDS where they fit

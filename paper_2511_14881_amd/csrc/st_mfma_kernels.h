@@ -40,6 +40,7 @@ constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the 
 constexpr int kMfmaSegItems = 512;         // items per wavefront segment, at most (8 mask words x 8 filters = 64 lanes)
 constexpr int kQueueSlots = 128;           // queued admissions per wavefront (drained whenever 64 are waiting)
 constexpr int kMaxRegionSlots = 8;         // candidate regions one workgroup may fill in a launch
+constexpr int kDenseItems = 12;            // passing items per filter and 512-item segment from which full units are the rule
 
 
 struct MfmaParams {
@@ -68,6 +69,11 @@ struct MfmaParams {
     // visit by visit, so that the regions fill as evenly as with one workgroup per region.
     int32_t region_slots;
     int32_t seg_stride;          // items the per-wavefront LDS lists are laid out for (256 or 512, >= seg_items)
+    // Passing (query, item) pairs of the first level, summed over the batch by its selection: the
+    // first-level scan clears it, the selection adds each query's count, the later levels compare
+    // it with density_limit to choose between the two forms of the scan (null: none of this).
+    unsigned long long* density_acc;
+    unsigned long long density_limit;
     // dynamic LDS layout (byte offsets)
     int32_t lds_sq, lds_tauf, lds_tau64, lds_qrow, lds_cnt, lds_list, lds_queue, lds_prow, lds_blkoff, lds_rowoff, lds_tq, lds_thr, lds_scl, lds_total;
 };
@@ -93,6 +99,7 @@ struct UnitRegs {
     v4i b[KS];
     float si;    // scale of the lane's item
     int si_fix;  // the same as a fixed-point factor for the integer cull (plain search)
+    int si_fix2;  // second form of the scan: the lane's item as the 10-bit code a queued pair carries
     int item;    // lane's item (l % 16), relative to the segment start; -1 = padding lane
     int gi;      // filter within the batch (uniform)
 };
@@ -109,7 +116,7 @@ struct UnitRegs {
 // ADMIT = first level with one segment per region (8-wavefront workgroups only): no threshold
 // exists yet, every passing pair is a candidate and goes straight to its region.
 template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW, bool ADMIT = false>
-__global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
+__device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaParams& mp)
 {
     static_assert(!ADMIT || NW == 8, "the first-level variant exists for 8-wavefront workgroups");
     constexpr int kThreads = NW * 64;
@@ -958,6 +965,13 @@ __global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) v
         }
     }
     ST_STAMP(p.stamps, p.stamp_level, wg_lin, 9);
+}
+
+template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW, bool ADMIT = false>
+__global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
+{
+    if (ADMIT && mp.density_acc && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *mp.density_acc = 0ULL;
+    scan_mfma_body<KS, TT, WEIGHTED, MULTI, NW, ADMIT>(p, mp);
 }
 
 inline bool mfma_shape_ok(int d, int n_tasks)

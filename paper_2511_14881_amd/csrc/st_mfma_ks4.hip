@@ -1,10 +1,13 @@
 // Instantiations of the int8 MFMA scan for d = 256 (4 contraction steps of 64 bytes per row).
-#include "st_mfma_kernels.h"
+#include "st_mfma2_kernels.h"
 
 namespace st {
 
 hipError_t launch_scan_mfma_ks4(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
+#ifndef ST_NO_SCAN2
+    if (scan_mfma2_applies(sp, mp)) return launch_scan_mfma2_ks<4>(sp, mp, gx, stream);
+#endif
     return launch_scan_mfma_ks<4>(sp, mp, gx, stream);
 }
 

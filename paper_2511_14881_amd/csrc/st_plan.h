@@ -200,6 +200,7 @@ inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_ca
 // Byte offsets of the pieces of the device workspace.
 struct Layout {
     size_t meta, meta_bytes;  // uploaded group tables
+    size_t density;           // uint64           passing pairs of the first level, summed over the batch
     size_t tau;               // uint64 [B][8]    admission threshold per query (seed pass: one per slice, the minimum counts)
     size_t ovf;               // uint32 [B]       1 = a candidate region overflowed
     size_t topk_keys;         // uint64 [B][K]    running top-K, sorted
@@ -229,6 +230,7 @@ inline Layout make_layout(const Plan& p, int32_t batch, int32_t K, int32_t d = 1
     auto take = [&](size_t bytes) { size_t o = off; off = (size_t)round_up((int64_t)(off + bytes), 256); return o; };
     L.meta_bytes = meta_bound_bytes(batch);
     L.meta = take(L.meta_bytes);
+    L.density = take(8);
     L.tau = take((size_t)batch * 8 * 8);
     L.ovf = take((size_t)batch * 4);
     L.topk_keys = take((size_t)batch * K * 8);

@@ -568,6 +568,7 @@ struct SelectParams {
     // slow exact path (last level only): corpus, queries, all filter groups
     ScanParams scan;
     const int32_t* q2grp;   // [B] group of each query
+    unsigned long long* density_acc;  // first level only: receives the query's candidate count (null: none)
 };
 
 constexpr int kSelectThreads = 512;
@@ -682,6 +683,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         all += v;
     }
     const uint32_t total = n_prev + all;
+    if (p.density_acc && tid == 0) atomicAdd(p.density_acc, (unsigned long long)all);
     ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 1);
     const bool in_lds = total <= (uint32_t)lds_keys;
     // More candidates than LDS holds, result sorted in LDS: the candidates are narrowed down where
