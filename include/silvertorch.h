@@ -50,7 +50,7 @@ typedef enum st_status {
 #define ST_MAX_FILTER_BITS 64   /* distinct signature bits one query's filter may set (<= k * terms) */
 #define ST_MAX_BATCH 4096
 #define ST_MAX_TASKS 8
-#define ST_MAX_TOP_K 16384
+#define ST_MAX_TOP_K 131072    /* the paper's pre-filter sizes reach O(10^5) items, Sec. 5.1 */
 #define ST_MAX_DIM 4096         /* d, a multiple of 16 */
 #define ST_MAX_CLUSTERS 65536   /* clusters of st_search_ivf */
 #define ST_MAX_PROBES 2048      /* clusters probed per query */

@@ -643,10 +643,18 @@ int st_bloom_build(const int64_t* feat_offsets, const uint64_t* feat_ids, int64_
             ST_HIP(hipMemcpyAsync(d_ids, feat_ids, (size_t)nnz * 8, hipMemcpyHostToDevice, stream));
             ids = d_ids;
         }
-        const int64_t n_words = b->n_tiles * st::kTileWords;
-        const unsigned grid = (unsigned)((n_words + 3) / 4);
-        hipLaunchKernelGGL(st::bloom_build_kernel, dim3(grid), dim3(256), 0, stream, off, ids, n_items,
-                           m_bits, k_hashes, n_words, b->dev);
+        const size_t lds = (size_t)std::min<int32_t>(m_bits, st::kBuildSlabRows) * st::kTileWords * 8;
+        static std::atomic<bool> lds_set{false};
+        if (!lds_set.load(std::memory_order_acquire)) {
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&st::bloom_build_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, st::kBuildSlabRows * st::kTileWords * 8));
+            lds_set.store(true, std::memory_order_release);
+        }
+        {
+            TimedLaunch t(0, stream);
+            hipLaunchKernelGGL(st::bloom_build_kernel, dim3((unsigned)b->n_tiles), dim3(st::kBuildThreads), lds, stream, off,
+                               ids, n_items, m_bits, k_hashes, b->dev);
+        }
         ST_HIP(hipGetLastError());
         ST_HIP(hipStreamSynchronize(stream));
         return ST_OK;
@@ -1184,7 +1192,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             // K above the LDS sort size: the final ordering of k_pad keys runs in LDS where they fit
             const size_t big_bytes = (size_t)L.k_pad * 8;
             constexpr size_t kBigSortMax = 128 * 1024;
-            se.big_sort = (se.srt && big_bytes <= kBigSortMax) ? 1 : 0;
+            se.big_sort = se.srt ? (big_bytes <= kBigSortMax ? 1 : 2) : 0;
             static std::atomic<bool> lds_set{false};  // (setting the attribute twice is harmless)
             if (!lds_set.load(std::memory_order_acquire)) {
                 ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&st::select_kernel),
@@ -1192,7 +1200,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                                            (int)std::max<size_t>(st::kSelectLdsBytes, kBigSortMax)));
                 lds_set.store(true, std::memory_order_release);
             }
-            const size_t lds = std::max<size_t>((size_t)st::select_lds_bytes(se.lds_keys), se.big_sort ? big_bytes : 0);
+            const size_t lds = std::max<size_t>((size_t)st::select_lds_bytes(se.lds_keys), se.big_sort == 1 ? big_bytes : 0);
             hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), lds, stream, se);
         }
         ST_HIP(hipGetLastError());

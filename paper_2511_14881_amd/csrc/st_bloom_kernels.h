@@ -10,44 +10,47 @@
 
 namespace st {
 
-// One wavefront per 64-item word; lane = item.  For each 64-row slab of the signature the lane
-// recomputes its item's hashes, keeps the bits that fall into the slab, and the wavefront
-// transposes the 64x64 bit block with ballots: lane b ends up holding row (slab*64 + b).
-__global__ __launch_bounds__(256) void bloom_build_kernel(const int64_t* __restrict__ feat_offsets,
-                                                          const uint64_t* __restrict__ feat_ids,
-                                                          int64_t n_items, int32_t m_bits,
-                                                          int32_t k_hashes, int64_t n_words_padded,
-                                                          uint64_t* __restrict__ bloom)
+// One workgroup per 1024-item tile.  The tile's block of the index -- m rows of 128 bytes -- is
+// assembled in LDS (in slabs of kBuildSlabRows rows where m is larger): every thread hashes the
+// ids of its items once per slab (k positions each, Sec. 4.1), sets the item's bit in the rows the
+// positions name with LDS atomic ORs, and the finished rows go out as one contiguous, coalesced
+// copy.  Hash work is therefore independent of m up to the slab size, and HBM sees the feature
+// lists once and the index once.
+constexpr int kBuildThreads = 256;
+constexpr int kBuildSlabRows = 1024;  // 128 KB of LDS
+
+__global__ __launch_bounds__(kBuildThreads) void bloom_build_kernel(const int64_t* __restrict__ feat_offsets,
+                                                                    const uint64_t* __restrict__ feat_ids,
+                                                                    int64_t n_items, int32_t m_bits,
+                                                                    int32_t k_hashes, uint64_t* __restrict__ bloom)
 {
-    const int lane = lane_id();
-    const int64_t gw = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);  // global word index
-    if (gw >= n_words_padded) return;                                 // whole wavefront leaves together
-    const int64_t item = gw * 64 + lane;
-    int64_t f_begin = 0, f_end = 0;
-    if (item < n_items) {
-        f_begin = feat_offsets[item];
-        f_end = feat_offsets[item + 1];
-    }
-    const int64_t tile = gw >> 4;
-    const int w = (int)(gw & 15);
-    uint64_t* base = bloom + (tile * (int64_t)m_bits) * kTileWords + w;
-    const int n_slabs = (m_bits + 63) >> 6;
-    for (int slab = 0; slab < n_slabs; ++slab) {
-        uint64_t sig = 0;
-        for (int64_t p = f_begin; p < f_end; ++p) {
-            const uint64_t f = feat_ids[p];
-            for (int j = 0; j < k_hashes; ++j) {
-                const uint32_t b = bloom_bit(f, j, (uint32_t)m_bits);
-                if ((int)(b >> 6) == slab) sig |= 1ULL << (b & 63);
+    extern __shared__ __attribute__((aligned(16))) uint32_t s_bits[];  // [rows][32]: the 16 words of a row as 32-bit halves
+    const int tid = threadIdx.x;
+    const int64_t tile = blockIdx.x;
+    const int64_t item0 = tile * kTileItems;
+    const bool pow2 = (m_bits & (m_bits - 1)) == 0;
+    for (int slab0 = 0; slab0 < m_bits; slab0 += kBuildSlabRows) {
+        const int rows = min(kBuildSlabRows, m_bits - slab0);
+        for (int i = tid; i < rows * 8; i += kBuildThreads) reinterpret_cast<int4*>(s_bits)[i] = make_int4(0, 0, 0, 0);
+        __syncthreads();
+        for (int it = tid; it < kTileItems; it += kBuildThreads) {
+            const int64_t item = item0 + it;
+            if (item >= n_items) break;
+            const int64_t f_end = feat_offsets[item + 1];
+            const uint32_t bit = 1u << (it & 31);
+            for (int64_t e = feat_offsets[item]; e < f_end; ++e) {
+                const uint64_t f = feat_ids[e];
+                for (int j = 0; j < k_hashes; ++j) {
+                    const uint64_t h = splitmix64(f ^ (uint64_t)j);
+                    const int r = (int)(pow2 ? (h & (uint64_t)(m_bits - 1)) : (h % (uint64_t)m_bits)) - slab0;
+                    if (r >= 0 && r < rows) atomicOr(&s_bits[r * 32 + (it >> 5)], bit);
+                }
             }
         }
-        uint64_t mine = 0;
-        for (int b = 0; b < 64; ++b) {
-            const uint64_t bal = ballot((sig >> b) & 1ULL);
-            if (lane == b) mine = bal;
-        }
-        const int row = slab * 64 + lane;
-        if (row < m_bits) base[(int64_t)row * kTileWords] = mine;
+        __syncthreads();
+        int4* dst = reinterpret_cast<int4*>(bloom + (tile * (int64_t)m_bits + slab0) * kTileWords);
+        for (int i = tid; i < rows * 8; i += kBuildThreads) dst[i] = reinterpret_cast<const int4*>(s_bits)[i];
+        __syncthreads();
     }
 }
 

@@ -560,7 +560,7 @@ struct SelectParams {
     uint32_t* ovf;          // [B]
     int32_t lds_keys;       // candidates per query the selection gathers in LDS (<= kLdsKeys; sizes its LDS)
     int32_t first, last;
-    int32_t big_sort;       // 1: K above the LDS sort size and the launch's LDS holds k_pad keys (see the kernel)
+    int32_t big_sort;       // K above the LDS sort size: the set is carried unordered; 1: the launch's LDS holds k_pad keys for the final order, 2: ordered in global memory
     int32_t may_overflow;   // 0: the level's regions cannot overflow (every pair admitted, one visit per region): the flag is reset
     int64_t* out_ids;       // [B][K]
     float* out_scores;
@@ -825,8 +825,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         // Large K: the set is carried from level to level unordered (only its K-th key is needed);
         // the last level orders it in LDS, which holds all k_pad keys once the selection's own
         // buffers are no longer in use.
-        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red, false, &kth);
-        if (p.last) {
+        // (big_sort 2: more keys than LDS holds; the last level then orders them where they lie)
+        const bool lds_final = p.big_sort == 1;
+        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red,
+                        p.last && !lds_final, &kth);
+        if (p.last && lds_final) {
             uint64_t* big = reinterpret_cast<uint64_t*>(sel_lds);  // [k_pad]: the launch sized the LDS for it
             int P = 1;
             while (P < n_out) P <<= 1;

@@ -307,10 +307,12 @@ def test_ragged_sizes_and_filters(n, d, B, K, T, path):
         assert (ids[b, count[b]:] == -1).all() and np.isneginf(scores[b, count[b]:]).all()
 
 
-@pytest.mark.parametrize("K,B", [(5000, 6), (16384, 2)])
+@pytest.mark.parametrize("K,B", [(5000, 6), (16384, 2), (50_000, 3), (100_000, 2)])
 def test_top_k_above_the_lds_sort_size(K, B):
-    # K above 2048: the running top-K is sorted in global memory and several levels feed it
-    n = 300_000
+    # K above 2048: the running top-K lives in global memory, is carried unordered from level to
+    # level and ordered once at the end (in LDS up to 16384 keys, in global memory above: the
+    # paper's pre-filter sizes of 10^4 - 10^5 items, Sec. 5.1)
+    n = 300_000 if K <= 16384 else 700_000
     w = ragged_workload(31 + K, n, 64, B, 12, 4, 100, 3)
     w.filt_ids = np.array([3], dtype=np.uint64)           # query 0 filtered, the others take every item
     w.filt_offsets = np.array([0] + [1] * B, dtype=np.int64)

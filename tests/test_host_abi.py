@@ -49,7 +49,8 @@ def test_index_size_is_items_times_bits_over_eight():
 
 @pytest.mark.parametrize("n,B,K", [(0, 1, 1), (1, 1, 10), (10_000, 1, 10), (1_000_000, 64, 100),
                                    (10_000_000, 256, 500), (5_000_000, 128, 200),
-                                   (20_000_000, 1024, 1000), (123_457, 7, 16384), (2**31 - 1, 4, 5)])
+                                   (20_000_000, 1024, 1000), (123_457, 7, 16384), (3_000_000, 16, 100_000),
+                                   (2**31 - 1, 4, 5)])
 @pytest.mark.parametrize("q_split", [1, 2, 8])
 def test_schedule_covers_the_corpus_once(n, B, K, q_split):
     levels, groups, cap = st.st_search_plan(n, B, K, q_split)
@@ -82,7 +83,7 @@ def test_workspace_size_and_argument_checks():
     assert st.st_search_workspace_bytes(1_000_000, 128, 128, 1, 100) > a
     for bad in [(-1, 128, 1, 1, 1), (10, 100, 1, 1, 1), (10, 0, 1, 1, 1), (10, 128, 0, 1, 1),
                 (10, 128, 5000, 1, 1), (10, 128, 1, 0, 1), (10, 128, 1, 9, 1), (10, 128, 1, 1, 0),
-                (10, 128, 1, 1, 20000), (10, 8192, 1, 1, 1)]:
+                (10, 128, 1, 1, 200000), (10, 8192, 1, 1, 1)]:
         with pytest.raises(st.StError) as e:
             st.st_search_workspace_bytes(*bad)
         assert e.value.code == st.ST_EINVAL
