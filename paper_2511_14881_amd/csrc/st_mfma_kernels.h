@@ -573,11 +573,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
             const uint32_t off = (uint32_t)(idx * D);
 #pragma unroll
             for (int k = 0; k < KS; ++k) {
-#ifdef ST_EXP_NOROWS
-                const int4 v = make_int4((int)off, k, lane, idx);
-#else
                 const int4 v = *reinterpret_cast<const int4*>(seg_rows + (off + 64u * k));
-#endif
                 w.b[k] = v4i{v.x, v.y, v.z, v.w};
             }
             w.si = s_scl[idx];
@@ -662,14 +658,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
                               uint64_t (&hits)[4]) -> bool {
             const int thv[4] = {thr.x, thr.y, thr.z, thr.w};
             uint64_t any = 0;
-#ifdef ST_EXP_NOTEST
-            {
-                const int mx = max(max(acc[0], acc[1]), max(acc[2], acc[3]));
-                hits[0] = hits[1] = hits[2] = hits[3] = ballot(mx == 0x7fffffff + thv[0] * 0);
-                val[0] = val[1] = val[2] = val[3] = 0;
-                return (hits[0] & valid) != 0;
-            }
-#endif
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 hits[r] = ballot(__mulhi(acc[r], w.si_fix) >= thv[r]);
@@ -705,11 +693,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
         };
         auto block_mfma = [&](const v4i (&a)[KS], const UnitRegs<KS>& w) -> v4i {
             v4i acc = {0, 0, 0, 0};
-#ifdef ST_EXP_NOMFMA
-#pragma unroll
-            for (int k = 0; k < KS; ++k) acc += a[k] ^ w.b[k];
-            return acc;
-#endif
 #pragma unroll
             for (int k = 0; k < KS; ++k) acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(a[k], w.b[k], acc, 0, 0, 0);
             return acc;

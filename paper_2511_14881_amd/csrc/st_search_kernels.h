@@ -362,6 +362,8 @@ __device__ inline void write_result(const uint64_t* sorted, int n_out, int K, in
 // blockDim.x a multiple of 256 and at most 1024, k_pad <= room in sorted (LDS).  The key buffer
 // is overwritten (it serves as scratch once the keys sit in registers).
 //
+// The key buffer must hold max(n, 1024) entries (the final ordering of 512 keys uses it as scratch).
+//
 // kth receives the K-th best key (0 if n < K).  With want_sorted the best min(n, K) keys end up
 // in sorted[] in descending order; without, they are there in no particular order (callers that
 // only carry the set forward and need the threshold skip the sort).
@@ -487,6 +489,40 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
         }
     }
     ST_STAMP(stamps, st_kind, st_slot, st_k + 2);
+    if (P <= nt && P > 256) {
+        // One key per thread, bitonic network (descending; the padding zeros sink to the end).  The
+        // exchange partner sits in the same wavefront for distances below 64 (two 32-bit shuffles),
+        // beyond that the keys go through LDS with one barrier per stage (two buffers alternate).
+        // 45 stages for 512 keys, 6 of them through LDS: a rank sort reads every key in every
+        // thread instead, 2 MB of LDS traffic for 512 keys.
+        uint64_t* bufs[2] = {keys, keys + P};  // the key buffer is free once the keys sit in `sorted`
+        uint64_t key = tid < P ? sorted[tid] : 0ULL;
+        int flip = 0;
+        for (int k2 = 2; k2 <= P; k2 <<= 1) {
+            const bool desc = (tid & k2) == 0;
+            for (int j = k2 >> 1; j > 0; j >>= 1) {
+                uint64_t other;
+                if (j >= 64) {
+                    if (tid < P) bufs[flip][tid] = key;
+                    __syncthreads();
+                    other = tid < P ? bufs[flip][tid ^ j] : 0ULL;
+                    flip ^= 1;
+                } else {
+                    const uint32_t ol = __shfl_xor((uint32_t)key, j), oh = __shfl_xor((uint32_t)(key >> 32), j);
+                    other = ((uint64_t)oh << 32) | ol;
+                }
+                const bool lower = (tid & j) == 0;          // the lower index of the pair
+                const bool want_max = lower == desc;        // descending run: the lower index keeps the larger key
+                const bool take = want_max ? other > key : other < key;
+                key = take ? other : key;
+            }
+        }
+        __syncthreads();
+        if (tid < P) sorted[tid] = key;
+        __syncthreads();
+        if (n_out == K) kth = sorted[K - 1];
+        return n_out;
+    }
     if (P <= nt) {
         // rank sort with every thread at work: thread (c, i) counts, among one share of the list,
         // the keys that precede key i; shares are summed in LDS (padding zeros tie among
@@ -665,9 +701,34 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     const int per = (R + NT - 1) / NT;
     const uint32_t* cq = p.cnt + (int64_t)q * p.groups;
     uint32_t mine = 0;
-    for (int j = 0; j < per; ++j) {
-        const int w = tid * per + j;
-        if (w < R) mine += min(cq[w], (uint32_t)p.cap);
+    // With at most two regions per thread (the usual layout) the first eight keys of each region
+    // are requested together with its count, before the count is known: a region holds a handful
+    // of keys as a rule, so this is one memory round trip instead of two (what lies beyond the
+    // count is stale workspace and is dropped).
+    constexpr int kHead = 8;
+    const bool spec = per <= 2 && gridDim.x <= 512;  // (larger batches fill the chip several times over: latency is hidden, bytes are not)
+    uint32_t hc[2] = {0u, 0u};
+    int4 hv[2][kHead / 2];
+    if (spec) {
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int w = tid * per + jj;
+            const bool live = jj < per && w < R;
+            const int4* src = reinterpret_cast<const int4*>(p.cand + ((int64_t)q * p.groups + (live ? w : 0)) * p.cap);
+            if (live) {
+                hc[jj] = cq[w];
+#pragma unroll
+                for (int u = 0; u < kHead / 2; ++u) hv[jj][u] = src[u];  // (a region holds at least 64 entries)
+            }
+        }
+        hc[0] = min(hc[0], (uint32_t)p.cap);
+        hc[1] = min(hc[1], (uint32_t)p.cap);
+        mine = hc[0] + hc[1];
+    } else {
+        for (int j = 0; j < per; ++j) {
+            const int w = tid * per + j;
+            if (w < R) mine += min(cq[w], (uint32_t)p.cap);
+        }
     }
     uint32_t incl = mine;
     for (int o = 1; o < 64; o <<= 1) {
@@ -712,26 +773,57 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         for (int i = tid; i < (int)n_prev; i += NT) f(p.topk_keys[(int64_t)q * p.K + i]);
     };
     if (!narrow) {
-        // contiguous copy: regions in order after the running top-K
+        // contiguous copy: regions in order after the running top-K.  A thread's regions are taken
+        // two at a time, the first eight keys of both requested before any is stored (a region
+        // holds a handful of keys as a rule: one memory round trip instead of one per four keys).
         uint32_t off = n_prev + wbase + incl - mine;
-        for (int j = 0; j < per; ++j) {
-            const int w = tid * per + j;
-            if (w < R) {
-                const uint32_t c = min(cq[w], (uint32_t)p.cap);
-                const uint64_t* src = p.cand + ((int64_t)q * p.groups + w) * p.cap;
-                for (uint32_t i0 = 0; i0 < c; i0 += 4) {
-                    uint64_t v[4];
+        for (int j0 = 0; j0 < per; j0 += 2) {
+            uint32_t c[2];
+            const uint64_t* src[2];
+            uint64_t v[2][kHead];
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+                const int w = tid * per + j0 + jj;
+                const bool live = j0 + jj < per && w < R;
+                c[jj] = spec ? hc[jj] : (live ? min(cq[w], (uint32_t)p.cap) : 0u);
+                src[jj] = p.cand + ((int64_t)q * p.groups + (live ? w : 0)) * p.cap;
+            }
+            if (spec) {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int u = 0; u < kHead / 2; ++u) {
+                        v[jj][2 * u] = ((uint64_t)(uint32_t)hv[jj][u].y << 32) | (uint32_t)hv[jj][u].x;
+                        v[jj][2 * u + 1] = ((uint64_t)(uint32_t)hv[jj][u].w << 32) | (uint32_t)hv[jj][u].z;
+                    }
+            } else {
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj)
+#pragma unroll
+                    for (int u = 0; u < kHead; ++u)
+                        if ((uint32_t)u < c[jj]) v[jj][u] = src[jj][u];
+            }
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj) {
+#pragma unroll
+                for (int u = 0; u < kHead; ++u)
+                    if ((uint32_t)u < c[jj]) {
+                        if (in_lds) s_keys[off + u] = v[jj][u];
+                        else gkeys[off + u] = v[jj][u];
+                    }
+                for (uint32_t i0 = kHead; i0 < c[jj]; i0 += 4) {
+                    uint64_t t[4];
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        if (i0 + u < c) v[u] = src[i0 + u];
+                        if (i0 + u < c[jj]) t[u] = src[jj][i0 + u];
 #pragma unroll
                     for (int u = 0; u < 4; ++u)
-                        if (i0 + u < c) {
-                            if (in_lds) s_keys[off + i0 + u] = v[u];
-                            else gkeys[off + i0 + u] = v[u];
+                        if (i0 + u < c[jj]) {
+                            if (in_lds) s_keys[off + i0 + u] = t[u];
+                            else gkeys[off + i0 + u] = t[u];
                         }
                 }
-                off += c;
+                off += c[jj];
             }
         }
         for (int i = tid; i < (int)n_prev; i += NT) {
@@ -817,10 +909,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         __syncthreads();
         keep = keep < (uint32_t)lds_keys ? keep : (uint32_t)lds_keys;  // keys are distinct: never cut
         n_out = lds_topk(s_keys, (int)keep, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
-                         1, q, 9);
+                         8 + p.scan.stamp_level, q, 9);
     } else if (in_lds && !p.srt) {
         n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
-                         1, q, 9);
+                         8 + p.scan.stamp_level, q, 9);
     } else if (p.big_sort) {
         // Large K: the set is carried from level to level unordered (only its K-th key is needed);
         // the last level orders it in LDS, which holds all k_pad keys once the selection's own
