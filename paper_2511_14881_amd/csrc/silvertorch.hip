@@ -1012,12 +1012,6 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     sp.ovf = (uint32_t*)(ws + L.ovf);
     sp.cap = plan.cap;
     sp.groups = plan.groups;
-#ifdef ST_STAMPS
-    {  // tuning builds: ST_STAMPS_PTR = device address of a zeroed uint64 [17][4096][16] buffer (scan levels 0-7, select levels 8-15, seed 16)
-        const char* e = getenv("ST_STAMPS_PTR");
-        sp.stamps = e ? (uint64_t*)strtoull(e, nullptr, 0) : nullptr;
-    }
-#endif
 
     st::ScanParams sp_m = sp, sp_d = sp, sp_all = sp;
     sp_m.n_groups = set_mfma.n;
@@ -1077,7 +1071,6 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         se.first = lv == 0 || (lv == 1 && plan.level[0].seed);  // no candidate list from before
         se.last = lv == plan.n_levels - 1;
         se.may_overflow = lv > 0;
-        se.scan.stamp_level = sp_m.stamp_level = sp_d.stamp_level = lv < 8 ? lv : 7;
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
             st::SeedUpload up;
@@ -1572,12 +1565,6 @@ int st_search_ivf(const st_bloom* bloom, const int8_t* dev_items, const float* d
             qp.out_scores = dev_out_scores;
             qp.out_count = dev_out_count;
             qp.ovf = (uint32_t*)(ws + L.ovf);
-#ifdef ST_STAMPS
-            {
-                const char* e = getenv("ST_STAMPS_PTR");
-                qp.stamps = e ? (uint64_t*)strtoull(e, nullptr, 0) : nullptr;
-            }
-#endif
             qp.part_cnt = q_parts;
             // Workgroups per query: enough to occupy the chip, as long as every part's share of the
             // key buffer holds a round beside the K keys it keeps, the parts' survivors fit the final

@@ -215,7 +215,6 @@ struct IvfQueryParams {
     // several workgroups per query (grid.y = parts <= kQueryParts): each takes every parts-th round
     // with its own share of the key buffer and keeps its best K; ivf_merge_kernel merges them
     uint32_t* part_cnt;        // [batch][kQueryParts] keys each part kept
-    uint64_t* stamps;          // null unless the library is built with ST_STAMPS (timeline probe)
 };
 
 __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams p)
@@ -231,9 +230,6 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
     __shared__ int64_t s_word[kQueryThreads];  // first item of the word each thread evaluated this round
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, b = blockIdx.x;
     const IvfParams& v = p.ivf;
-    const int st_slot = (int)(blockIdx.x * gridDim.y + blockIdx.y);
-    (void)st_slot;
-    ST_STAMP(p.stamps, 0, st_slot, 0);
     static_assert(sizeof(s_stack) >= (size_t)kTopkRegs * kQueryThreads * 8, "the stack doubles as the final key buffer");
 
     // the program, and the item ranges of the probed clusters (clipped to the corpus)
@@ -275,7 +271,6 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
     if (tid < kQueryProbes) s_first[tid] = base + incl - words;
     if (tid == 0) s_first[kQueryProbes] = total;
     __syncthreads();
-    ST_STAMP(p.stamps, 0, st_slot, 1);
 
     const int part = blockIdx.y, parts = gridDim.y;
     const int64_t cap = p.gath_cap / parts;  // this workgroup's share of the query's key buffer
@@ -357,7 +352,6 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
         }
         __syncthreads();
     }
-    ST_STAMP(p.stamps, 0, st_slot, 2);
     uint32_t n_keys = *s_n;
     if (parts > 1) {
         // keep this part's best K (unordered) at the head of its share
@@ -377,7 +371,6 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
             for (int i = tid; i < kept; i += kQueryThreads) buf[i] = s_sorted[i];
             n_keys = (uint32_t)kept;
         }
-        ST_STAMP(p.stamps, 0, st_slot, 3);
         // the merge is a kernel of its own (ivf_merge_kernel): a device-wide fence here, for a
         // last-finisher merge in this kernel, measured 30 us per workgroup
         if (tid == 0) p.part_cnt[b * kQueryParts + part] = n_keys;

@@ -284,11 +284,7 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
         for (int r = 0; r < PR; ++r) pre[r] = ~0ULL;
         prefetch_issue(nxt);
         // the wavefront's last stage (or several filter batches per segment): partial units too
-#ifdef ST_X_NOCARRY
-        const bool flush = true;
-#else
         const bool flush = !can_carry || !stage_ok(nxt);
-#endif
         const int c = __popcll(mask);
         int incl = c;
         for (int o = 1; o < SW; o <<= 1) {
@@ -470,9 +466,6 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
             }
             const int t0 = __mul24(acc[0], w.si_fix) + k.neg.x, t1 = __mul24(acc[1], w.si_fix) + k.neg.y;
             const int t2 = __mul24(acc[2], w.si_fix) + k.neg.z, t3 = __mul24(acc[3], w.si_fix) + k.neg.w;
-#ifdef ST_X_NOPUSH
-            return ballot(max(max(t0, t1), max(t2, t3)) == 0x7ffffff0) & valid & force;
-#endif
             return (ballot(max(max(t0, t1), max(t2, t3)) >= 0) & valid) | force;
         };
         // A block with possible admissions: the rows they are in; their pairs are queued.
@@ -510,10 +503,6 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
             valid = ballot(w.item >= 0);
             force = 0;
             if (WEIGHTED) return;
-#ifdef ST_X_NOBEGIN
-            w.si_fix = 200 + (w.item & 1);
-            return;
-#endif
             force = ballot((w.item >= 0) & !((w.si > 0.0f) & (w.si < two_E)));
             // (at least 1: the product of a tiny scale may round to zero, its ceiling does not)
             w.si_fix = max(__float2int_ru(fminf(w.si * fix_scale, (float)(1 << P))), 1);

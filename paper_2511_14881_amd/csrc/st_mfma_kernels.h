@@ -104,12 +104,6 @@ struct UnitRegs {
     int gi;      // filter within the batch (uniform)
 };
 
-#ifndef ST_MINW
-#define ST_MINW 4
-#endif
-#ifndef ST_NB2
-#define ST_NB2 3
-#endif
 // MULTI = some filter group holds more than one 16-row query block in a row of workgroups.
 // NW = wavefronts per workgroup: 4, or 8 when the resident queries leave room for one workgroup
 // per compute unit only (twice the wavefronts then share one query image).
@@ -134,10 +128,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     // the per-row constants are read from LDS once for both: LDS bandwidth, not the matrix cores,
     // bounds the loop when a filter group holds many query blocks); their ring holds two pairs.
     constexpr bool PAIRS = NW == 8 && KS <= 2;
-    #ifndef ST_NB4
-#define ST_NB4 2
-#endif
-    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? ST_NB2 : (KS == 4 ? ST_NB4 : 2)));
+    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? 3 : 2));
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
@@ -151,9 +142,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int S = mp.q_split, y = blockIdx.y;
-    const int wg_lin = blockIdx.x + y * gridDim.x;  // workgroup index (timeline probe only)
-    (void)wg_lin;
-    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 0);
     const int l16 = lane & 15, kg = lane >> 4;
     // Plain search: tau / s_q per row, so that a pair can only be admitted if dot * s_i reaches it.
     // +inf marks padding rows (never admitted), -inf rows that cannot be culled (no threshold yet,
@@ -296,7 +284,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     // global load behind the LDS stores that precede it, so a copy loop per table would pay one
     // memory round trip each.  The first share of every table (all of it for ordinary sizes) is
     // therefore requested up front, into registers, and stored afterwards; loops take what is left.
-    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 10);
     const int n_prow = p.n_groups * kPrefetchStride;
     const int n_piece = mp.first_level ? 0 : mp.rows_local * CH;   // 16-byte pieces of the query image
     const int n_imgrow = mp.first_level ? 0 : mp.rows_local;
@@ -345,7 +332,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
             if ((tid % TT) == 0) s_tau64[tid / TT] = v_tau;
         }
     }
-    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 11);
     for (int i = tid; i < R * nq_pad; i += kThreads) s_cnt[i] = 0;
     if (tid == 0) *s_work = (uint32_t)NW;  // numbers 0 .. NW-1 are the wavefronts' first segments
     for (int i = tid + kThreads; i < n_prow; i += kThreads) s_prow[i] = mp.prow[i];
@@ -440,16 +426,8 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
 #pragma unroll
     for (int k = 0; k < KS; ++k) a_off[k] = l16 * D + (((kg + 4 * k) ^ swz<KS>(l16)) << 4);
 
-    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 1);
     int thr_E = -1000;  // exponent the wavefront's integer bounds were built for (none yet)
-#ifdef ST_STAMPS
-    uint64_t acc_t[4] = {0, 0, 0, 0}, acc_last = wall_clock64();
-#define ST_ACC(k) do { const uint64_t now_ = wall_clock64(); acc_t[k] += now_ - acc_last; acc_last = now_; } while (0)
-#else
-#define ST_ACC(k) do { } while (0)
-#endif
     for (bool first = true; stage_ok(cur); first = false) {
-        ST_ACC(3);
         const int64_t item0 = p.item_begin + (int64_t)stage_seg(cur) * seg_items;
         const int g0 = cur.batch * FB;
         const int nf = min(FB, p.n_groups - g0);
@@ -468,7 +446,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
 #pragma unroll
         for (int r = 0; r < PR; ++r) pre[r] = ~0ULL;
         prefetch_issue(nxt);
-        if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 2);
         const int c = __popcll(mask);
         int incl = c;  // running count over the words of my filter
         for (int o = 1; o < SW; o <<= 1) {
@@ -500,7 +477,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
         // first local query row and local block count of filter gi -> lane gi
         const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
         const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;
-        if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 3);
 
         // Item scales of the segment into LDS.  Plain search: their maximum fixes a power of two
         // 2^E above every scale of the segment; the lane's scale becomes the fixed-point factor
@@ -543,7 +519,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
             }
         }
 
-        ST_ACC(0);
         // (3) units = (filter gi, 16 passing items from b0), in filter order.  A ring of NB
         // register slots keeps the item rows of the next NB units in flight while one is
         // contracted: uniform bases + 32-bit lane offsets (the segment spans at most 512 * D bytes)
@@ -905,7 +880,6 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
             unit_load(r1);
             if (NB > 2) unit_load(r2);
             if (NB > 3) unit_load(r3);
-            if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 4);
             for (int base = 0; base < n_units; base += NB) {
                 if (PAIRS && !ADMIT) {
                     step2(r0, r1, base);
@@ -917,22 +891,11 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
                     if (NB > 3) step(r3, base + 3);
                 }
             }
-            if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 5);
-            ST_ACC(1);
             while (qn > 0) drain();
-            ST_ACC(2);
         }
-        if (first) ST_STAMP(p.stamps, p.stamp_level, wg_lin, 6);
         cur = nxt;
     }
-    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 7);
-#ifdef ST_STAMPS
-    if (p.stamps && threadIdx.x == 0 && wg_lin < 4096) {
-        for (int k = 0; k < 4; ++k) p.stamps[((p.stamp_level * 4096) + wg_lin) * 16 + 12 + k] = acc_t[k];
-    }
-#endif
     __syncthreads();
-    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 8);
     // region fill counts: real ones for the queries this workgroup row owns, zero for the others
     for (int i = tid * TT; i < mp.n_blocks * 16; i += kThreads * TT) {
         const int grow = mp.blk_row[i];
@@ -947,11 +910,10 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
             if (c > (uint32_t)p.cap) p.ovf[q] = 1u;
         }
     }
-    ST_STAMP(p.stamps, p.stamp_level, wg_lin, 9);
 }
 
 template <int KS, int TT, bool WEIGHTED, bool MULTI, int NW, bool ADMIT = false>
-__global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? ST_MINW : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
+__global__ __launch_bounds__(NW * 64, (NW == 8 ? 2 : (KS <= 2 ? 4 : 2))) void scan_mfma_kernel(ScanParams p, MfmaParams mp)
 {
     if (ADMIT && mp.density_acc && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) *mp.density_acc = 0ULL;
     scan_mfma_body<KS, TT, WEIGHTED, MULTI, NW, ADMIT>(p, mp);

@@ -5,9 +5,7 @@ namespace st {
 
 hipError_t launch_scan_mfma_ks4(const ScanParams& sp, const MfmaParams& mp, int gx, hipStream_t stream)
 {
-#ifndef ST_NO_SCAN2
     if (scan_mfma2_applies(sp, mp)) return launch_scan_mfma2_ks<4>(sp, mp, gx, stream);
-#endif
     return launch_scan_mfma_ks<4>(sp, mp, gx, stream);
 }
 

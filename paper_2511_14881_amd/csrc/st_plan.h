@@ -45,22 +45,8 @@ inline int32_t pow2_ceil(int32_t v)
     return p;
 }
 
-// Workgroups the scan kernels are launched with (fixes the candidate-region layout).  The
-// environment variable ST_SCAN_GROUPS overrides the default for tuning runs: a power of two
-// between 64 and 2048, read once per process.
-inline int scan_groups()
-{
-    static int g = 0;
-    if (g == 0) {
-        g = kScanGroups;
-        const char* e = getenv("ST_SCAN_GROUPS");
-        if (e) {
-            const int v = atoi(e);
-            if (v >= 64 && v <= kMaxScanGroups && (v & (v - 1)) == 0) g = v;
-        }
-    }
-    return g;
-}
+// Workgroups the scan kernels are launched with (fixes the candidate-region layout).
+inline int scan_groups() { return kScanGroups; }
 
 // Levels for a given region capacity.  g_eff = workgroups that share one query's candidates
 // (all of them, unless the query rows are split over several workgroup rows).
@@ -168,21 +154,6 @@ inline int choose_cap(int64_t n_items, int32_t K, int32_t min_cap = 64)
     return best;
 }
 
-// Largest segment the planner may use; ST_SEG_ITEMS overrides it for tuning runs.
-inline int seg_limit(int32_t seg_cap)
-{
-    static int e = -1;
-    if (e < 0) {
-        e = 0;
-        const char* s = getenv("ST_SEG_ITEMS");
-        if (s) {
-            const int v = atoi(s);
-            if (v >= 64 && v <= kMaxSegItems && (v & (v - 1)) == 0) e = v;
-        }
-    }
-    return e > 0 && e < seg_cap ? e : seg_cap;
-}
-
 // min_cap: smallest region capacity to consider.  Searches whose passing items sit in a few dense
 // item ranges (cluster probing) ask for the largest: a long first level that admits everything
 // then gives every query a threshold, and a dense range cannot overflow a region.
@@ -194,7 +165,7 @@ inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_ca
     // the seed pass borrows the candidate regions and the gather buffer of a query as scratch
     const bool seed_fits = K <= kLdsSortMax && (int64_t)scan_groups() * cap >= 2 * (int64_t)kSeedItems;
     const int64_t seed = seed_fits ? seed_items_for(n_items, batch_rows) : 0;
-    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_limit(seg_cap), seed, waves < 1 ? 1 : waves, out);
+    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_cap, seed, waves < 1 ? 1 : waves, out);
 }
 
 // Byte offsets of the pieces of the device workspace.

@@ -42,21 +42,6 @@ struct ScanParams {
     uint32_t* ovf;               // [B]
     int32_t cap;
     int32_t groups;              // G (== gridDim.x)
-    uint64_t* stamps;            // null unless the library is built with ST_STAMPS (timeline probe)
-    int32_t stamp_level;         // level index the probe files this launch under
 };
-
-// Timeline probe for tuning builds (-DST_STAMPS): thread 0 of a workgroup records the 10-ns wall
-// clock at point k into stamps[((kind * 4096) + slot) * 16 + k].  Compiles to nothing otherwise.
-#ifdef ST_STAMPS
-#define ST_STAMP(buf, kind, slot, k)                                                                   \
-    do {                                                                                               \
-        if ((buf) && threadIdx.x == 0 && (slot) < 4096) (buf)[(((kind) * 4096) + (slot)) * 16 + (k)] = wall_clock64(); \
-    } while (0)
-#else
-#define ST_STAMP(buf, kind, slot, k) \
-    do {                             \
-    } while (0)
-#endif
 
 }  // namespace st

@@ -371,10 +371,8 @@ constexpr int kTopkRegs = 16;
 
 __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, int k_pad,
                                uint32_t* s_hist3 /*[3][256]*/, uint32_t* s_misc /*[8]*/, uint64_t* s_red /*[2*16]*/,
-                               bool want_sorted, uint64_t& kth, uint64_t* stamps = nullptr, int st_kind = 0,
-                               int st_slot = 0, int st_k = 0)
+                               bool want_sorted, uint64_t& kth)
 {
-    (void)stamps; (void)st_kind; (void)st_slot; (void)st_k;
     const int tid = threadIdx.x, nt = blockDim.x, lane = tid & 63, wv = tid >> 6, nw = nt >> 6;
     const int n_out = n < K ? n : K;
     int P = 1;
@@ -413,7 +411,6 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
         uint64_t prefix = k0 & prefix_mask;
         uint32_t want = (uint32_t)K;
         int pass = 0;
-        ST_STAMP(stamps, st_kind, st_slot, st_k);
         for (int shift = top_shift; shift >= 0; shift -= 8, ++pass) {
             uint32_t* hist = s_hist3 + (pass % 3) * 256;
 #pragma unroll
@@ -459,7 +456,6 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
         // keys are distinct: exactly K of them are >= prefix; when the search stopped on a whole
         // bucket the K-th key is the smallest of them
         const uint64_t bound = prefix;
-        ST_STAMP(stamps, st_kind, st_slot, st_k + 1);
         uint64_t low = ~0ULL;
 #pragma unroll
         for (int j = 0; j < kTopkRegs; ++j)
@@ -488,7 +484,6 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
             return n_out;
         }
     }
-    ST_STAMP(stamps, st_kind, st_slot, st_k + 2);
     if (P <= nt && P > 256) {
         // One key per thread, bitonic network (descending; the padding zeros sink to the end).  The
         // exchange partner sits in the same wavefront for distances below 64 (two 32-bit shuffles),
@@ -682,7 +677,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     uint32_t* s_wsum = s_misc + 8;                                                 // [16]
     const int q = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     constexpr int NT = kSelectThreads;
-    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 0);
     // counts are clamped to what the buffers can hold, whatever the memory says
     uint32_t n_prev = p.first ? 0u : p.topk_cnt[q];
     n_prev = n_prev < (uint32_t)p.K ? n_prev : (uint32_t)p.K;
@@ -745,7 +739,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     }
     const uint32_t total = n_prev + all;
     if (p.density_acc && tid == 0) atomicAdd(p.density_acc, (unsigned long long)all);
-    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 1);
     const bool in_lds = total <= (uint32_t)lds_keys;
     // More candidates than LDS holds, result sorted in LDS: the candidates are narrowed down where
     // they lie (below), not copied.
@@ -833,7 +826,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         }
     }
     __syncthreads();
-    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 2);
 
     uint64_t* sorted = p.srt ? p.srt + (int64_t)q * p.k_pad : s_sorted;
     int n_out;
@@ -908,11 +900,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         });
         __syncthreads();
         keep = keep < (uint32_t)lds_keys ? keep : (uint32_t)lds_keys;  // keys are distinct: never cut
-        n_out = lds_topk(s_keys, (int)keep, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
-                         8 + p.scan.stamp_level, q, 9);
+        n_out = lds_topk(s_keys, (int)keep, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
     } else if (in_lds && !p.srt) {
-        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth, p.scan.stamps,
-                         8 + p.scan.stamp_level, q, 9);
+        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
     } else if (p.big_sort) {
         // Large K: the set is carried from level to level unordered (only its K-th key is needed);
         // the last level orders it in LDS, which holds all k_pad keys once the selection's own
@@ -947,7 +937,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
         kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
     }
-    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 3);
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
         if (tid == 0) {
@@ -963,11 +952,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         write_result(sorted, n_out, p.K, p.out_ids + (int64_t)q * p.K, p.out_scores + (int64_t)q * p.K,
                      p.out_count + q);
     }
-    ST_STAMP(p.scan.stamps, 8 + p.scan.stamp_level, q, 4);
-#ifdef ST_STAMPS
-    if (p.scan.stamps && q < 4096)  // end of the slowest thread
-        atomicMax((unsigned long long*)&p.scan.stamps[(((8 + p.scan.stamp_level) * 4096) + q) * 16 + 5], (unsigned long long)wall_clock64());
-#endif
 }
 
 // Seed pass for small batches: the prefix [0, seed_items) of the corpus is scanned per query by
@@ -1026,7 +1010,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     constexpr int NT = kSeedThreads;
     const ScanParams& sp = p.scan;
     const int slot = q * parts + part;
-    ST_STAMP(sp.stamps, 16, slot, 0);
     {  // this workgroup's share of the table blob
         const int n_wg = (int)(gridDim.x * gridDim.y);
         const int share = (up.words + n_wg - 1) / n_wg;
@@ -1113,7 +1096,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     }
     if (lane == 63) s_wsum[wv] = incl;
     __syncthreads();
-    ST_STAMP(sp.stamps, 16, slot, 1);
     uint32_t wbase = 0, total = 0;
     for (int w = 0; w < NT / 64; ++w) {
         const uint32_t v = s_wsum[w];
@@ -1136,7 +1118,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
-    ST_STAMP(sp.stamps, 16, slot, 2);
     // scores: one lane per passing item
     if (D16 == 0) {
         for (uint32_t e = tid; e < total; e += NT) {
@@ -1186,7 +1167,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     __syncthreads();
-    ST_STAMP(sp.stamps, 16, slot, 3);
 
     // This slice's share of the threshold: its ceil(K / parts)-th best key.  With every slice
     // holding that many keys at or above its own value, the prefix holds at least K keys at or
@@ -1198,13 +1178,12 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     while (rank_pad < rank) rank_pad <<= 1;
     uint64_t kth = 0;
     if (in_lds) {
-        (void)lds_topk(s_keys, (int)total, rank, s_sorted, rank_pad, s_hist, s_misc, s_red, false, kth, sp.stamps, 16, slot, 9);
+        (void)lds_topk(s_keys, (int)total, rank, s_sorted, rank_pad, s_hist, s_misc, s_red, false, kth);
     } else {
         uint64_t* sorted = gpart + (int64_t)part * pstride;  // K <= pstride entries of scratch
         const int n_out = wg_topk(gkeys, (int64_t)total, rank, sorted, rank_pad, s_hist, s_misc, s_red);
         kth = n_out == rank ? sorted[rank - 1] : 0ULL;
     }
-    ST_STAMP(sp.stamps, 16, slot, 4);
     if (tid == 0) {
         p.tau[(int64_t)q * kTauParts + part] = kth;
         if (p.tau_img) {
@@ -1216,7 +1195,6 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
             p.topk_cnt[q] = 0u;
         }
     }
-    ST_STAMP(sp.stamps, 16, slot, 8);
 }
 
 template <int D16>
