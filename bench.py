@@ -136,9 +136,20 @@ def stats_ivf(st, bloom, w, prog, coff, probes, n_clusters):
         leaf_row_words += words_b * cfg.k_hashes * sum(1 for o in progs[q2p[b]][0] if o == 0)
     n_words = (cfg.n_items + 63) // 64
     extra = n_clusters * (cfg.d + 4) + 2 * cfg.batch * n_clusters * 8 + leaf_row_words * 8 + 2 * cfg.batch * n_words * 8
+    # Scratch memory of the filter stage per batch (the comparison of Sec. 6.2.3, Fig. 9): a full
+    # filter pass first materialises one bit per item and query (filter-then-probe); filtering only
+    # inside the probed clusters needs the probed words alone (probe-then-filter), and the
+    # per-query kernel of this library keeps even those in LDS: what it touches in HBM beside the
+    # index is the centroid keys, the probed ids and the keys of the passing items.
+    scratch = {
+        "filter_then_probe_mask_bytes": cfg.batch * n_words * 8,
+        "probe_then_filter_mask_bytes": probed_words * 8,
+        "per_query_kernel_hbm_scratch_bytes": cfg.batch * n_clusters * 8 + cfg.batch * len(probes[0]) * 4 + passing_pairs * 8,
+        "mask_row_route_hbm_scratch_bytes": 2 * cfg.batch * ((cfg.n_items + 1023) // 1024) * 128 + cfg.batch * n_clusters * 8,
+    }
     return {"distinct_filters": cfg.batch, "rows_touched": 0, "extra_bytes": extra, "union_items": int(union.sum()),
             "passing_pairs": passing_pairs, "per_filter_sel": base["per_filter_sel"],
-            "probed_item_fraction": float(probed_words * 64) / max(cfg.n_items * cfg.batch, 1)}
+            "probed_item_fraction": float(probed_words * 64) / max(cfg.n_items * cfg.batch, 1), "filter_scratch": scratch}
 
 
 def quantize_bench(args, cfg, torch, st):
@@ -499,11 +510,13 @@ def main():
     ivf = None
     if args.ivf:
         ivf = tuple(int(x) for x in args.ivf.split(":"))
-        if cfg.n_tasks > 0 or len(ivf) != 2:
-            print("bench.py: --ivf takes N_CLUSTERS:N_PROBE and a single-task workload", file=sys.stderr)
+        if len(ivf) != 2:
+            print("bench.py: --ivf takes N_CLUSTERS:N_PROBE", file=sys.stderr)
             sys.exit(2)
         args.filter_programs = True
-        cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+ivf%d:%d" % ivf)
+        # a multi-task workload probes with every task embedding as a query of its own (Sec. 5.2:
+        # the tasks of a request are batched against the one index and return task-specific lists)
+        cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+ivf%d:%d" % ivf + ("+task-lists" if cfg.n_tasks > 0 else ""))
     elif args.filter_programs:
         cfg = synth.scaled(cfg, cfg.n_items, name=cfg.name + "+filter-programs")
     others = not (args.no_others or variant)
@@ -523,6 +536,10 @@ def main():
     prog = None
     if args.filter_programs:
         prog = synth.gen_filter_programs(cfg)[:3]
+    if ivf and cfg.n_tasks > 0:
+        w, prog = synth.flatten_tasks(w, prog)
+        cfg = w.cfg
+        T = 1
     ivf_tensors = synth.gen_clusters(cfg, ivf[0], device="cuda") if ivf else None
     st.st_set_scoring_path(args.path)
 
@@ -593,7 +610,8 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": rec["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int8",
         "data": "synthetic",
-        "config": config_block(cfg, rec, args, {"probed_item_fraction": rec["stats"]["probed_item_fraction"]} if ivf else None),
+        "config": config_block(cfg, rec, args, {"probed_item_fraction": rec["stats"]["probed_item_fraction"],
+                                                "filter_scratch": rec["stats"]["filter_scratch"]} if ivf else None),
         "step_ms": rec["step_ms"], "host_us_per_call": rec["host_us_per_call"],
         "items_scanned_per_s": cfg.n_items / (rec["ms_per_step"] * 1e-3),
         "item_query_pairs_per_s": cfg.n_items * cfg.batch / (rec["ms_per_step"] * 1e-3),

@@ -333,6 +333,29 @@ def gen_filter_programs(cfg: Config, pool: int = 8, with_not: bool = True):
             np.asarray(off, dtype=np.int64), programs)
 
 
+def flatten_tasks(w: Workload, prog):
+    """A multi-task workload as single-task queries: every task embedding of a query becomes a
+    query of its own with the original query's filter program (the paper batches the tasks of a
+    request against one index and gets task-specific lists, Sec. 5.2).  prog = (ops, ids, offsets)
+    per original query; returns the flattened workload and programs."""
+    cfg = w.cfg
+    T = max(cfg.n_tasks, 1)
+    ops, ids, off = prog
+    f_ops, f_ids, f_off = [], [], [0]
+    for b in range(cfg.batch):
+        for _ in range(T):
+            f_ops.extend(ops[off[b]:off[b + 1]].tolist())
+            f_ids.extend(ids[off[b]:off[b + 1]].tolist())
+            f_off.append(len(f_ops))
+    fo = w.filt_offsets
+    fid = np.concatenate([np.tile(w.filt_ids[fo[b]:fo[b + 1]], T) for b in range(cfg.batch)]) if cfg.batch else w.filt_ids
+    foff = np.concatenate([[0], np.cumsum(np.repeat(fo[1:] - fo[:-1], T))]).astype(np.int64)
+    c2 = scaled(cfg, cfg.n_items, batch=cfg.batch * T, n_tasks=0, name=cfg.name)
+    w2 = Workload(c2, w.items, w.item_scale, w.feat_offsets, w.feat_ids, w.queries.reshape(cfg.batch * T, cfg.d),
+                  w.query_scale.reshape(cfg.batch * T), None, fid.astype(np.uint64), foff, w.pool)
+    return w2, (np.asarray(f_ops, dtype=np.int32), np.asarray(f_ids, dtype=np.uint64), np.asarray(f_off, dtype=np.int64))
+
+
 S_CLUSTERS = 11  # random stream of the cluster layout and the centroids
 
 

@@ -230,6 +230,20 @@ def test_probing_search_mid_recipe_scaled_and_full():
                   fast_path_only=True)
 
 
+def test_probing_search_with_multitask_queries_returns_task_specific_lists():
+    # Sec. 5.2: the task embeddings of a request are batched against the one index and every task
+    # gets its own list; here each of the T = 4 embeddings of a query probes its own clusters with
+    # the query's filter program (the multi-task recipe flattened to B * T single-task queries)
+    cfg = S.scaled(S.CONFIGS["multi"], 150_000, batch=12)
+    w = S.make_workload(cfg)
+    ops, ids, off, _ = S.gen_filter_programs(cfg)
+    w2, (f_ops, f_ids, f_off) = S.flatten_tasks(w, (ops, ids, off))
+    assert w2.cfg.batch == 48 and w2.queries.shape == (48, cfg.d)
+    programs = [(f_ops[f_off[b]:f_off[b + 1]].tolist(), f_ids[f_off[b]:f_off[b + 1]].tolist()) for b in range(48)]
+    assert programs[0] == programs[3] and programs[4] == programs[7]  # the tasks of a query share its filter
+    check_ivf(w2, programs, 256, 16, cfg.top_k, label="multi recipe, task-specific lists", fast_path_only=True)
+
+
 def test_probing_search_on_an_empty_corpus_and_with_empty_clusters_only():
     B, d, K, n_c = 3, 32, 5, 4
     q = torch.zeros((B, d), dtype=torch.int8, device="cuda")
