@@ -268,26 +268,27 @@ def value_model_bench(args, cfg, torch, st):
         "cpu_baseline": cpu}))
 
 
-def measured_read_peak(torch, st, gib: float = 2.0, reps: int = 10):
+def measured_read_peak(torch, st, gib: float = 4.0, reps: int = 10):
     """Practical HBM read ceiling: the library's streaming-read kernel over a buffer far larger
-    than the caches, best of `reps` launches (HIP events on the launch stream)."""
+    than the caches, best of `reps` launches at the best of three launch shapes (two workgroups
+    per compute unit measured fastest: 6.3 TB/s; HIP events on the launch stream)."""
     n = int(gib * (1 << 30))
     src = torch.empty(n, dtype=torch.uint8, device="cuda")
     src.fill_(1)
-    wgs = 256 * 16
-    sink = torch.empty(wgs, dtype=torch.int32, device="cuda")
-    for _ in range(3):
-        st.st_stream_read(src, sink, wgs)
-    torch.cuda.synchronize()
     best = None
-    for _ in range(reps):
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        st.st_stream_read(src, sink, wgs)
-        e1.record()
-        e1.synchronize()
-        ms = e0.elapsed_time(e1)
-        best = ms if best is None or ms < best else best
+    for wgs in (256, 512, 65536):
+        sink = torch.empty(wgs, dtype=torch.int32, device="cuda")
+        for _ in range(2):
+            st.st_stream_read(src, sink, wgs)
+        torch.cuda.synchronize()
+        for _ in range(reps):
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            st.st_stream_read(src, sink, wgs)
+            e1.record()
+            e1.synchronize()
+            ms = e0.elapsed_time(e1)
+            best = ms if best is None or ms < best else best
     del src, sink
     return n / (best * 1e-3) / 1e9
 
