@@ -533,7 +533,16 @@ def main():
     t0 = time.time()
     bloom = st.st_bloom_build(w.feat_offsets, w.feat_ids, cfg.n_items, cfg.m_bits, cfg.k_hashes)
     torch.cuda.synchronize()
-    build_s = time.time() - t0
+    build_first_s = time.time() - t0
+    # steady state: the same build again (the first call also sets the library up on the device)
+    build_s = build_first_s
+    for _ in range(3):
+        t0 = time.time()
+        b2 = st.st_bloom_build(w.feat_offsets, w.feat_ids, cfg.n_items, cfg.m_bits, cfg.k_hashes)
+        torch.cuda.synchronize()
+        build_s = min(build_s, time.time() - t0)
+        b2.free()
+        del b2
     prog = None
     if args.filter_programs:
         prog = synth.gen_filter_programs(cfg)[:3]
@@ -617,6 +626,7 @@ def main():
         "items_scanned_per_s": cfg.n_items / (rec["ms_per_step"] * 1e-3),
         "item_query_pairs_per_s": cfg.n_items * cfg.batch / (rec["ms_per_step"] * 1e-3),
         "bloom_build_items_per_s": cfg.n_items / build_s if build_s > 0 else None,
+        "bloom_build_first_call_items_per_s": cfg.n_items / build_first_s if build_first_s > 0 else None,
         "gen_seconds": gen_s,
         "roofline": rec["roofline"],
         "cpu_baseline": cpu,

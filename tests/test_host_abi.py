@@ -115,3 +115,63 @@ def test_null_arguments_are_rejected_without_touching_a_gpu():
                               None, None, 0, None) == st.ST_EINVAL
     assert lib.st_score_pairs(None, None, 16, None, None, None, None, 0, None, None, None) == st.ST_EINVAL
     assert lib.st_set_scoring_path(0) in (0, 1, 2)
+
+
+def _plan(n, d, batch, tasks, K, m, k, filters):
+    ids, off = [], [0]
+    for f in filters:
+        ids += list(f)
+        off.append(len(ids))
+    return st.st_search_host_plan(n, d, batch, tasks, K, m, k, np.array(ids, dtype=np.uint64),
+                                  np.array(off, dtype=np.int64))
+
+
+def test_host_plan_groups_queries_by_their_filter_as_a_set():
+    # Sec. 4.2: a filter is the conjunction of its terms, so the order of the terms, and a term
+    # given twice, make no new filter; queries of one filter share one group
+    rng = np.random.default_rng(3)
+    pool = [tuple(int(x) for x in rng.integers(1, 1 << 40, 2)) for _ in range(8)]
+    same_order = [pool[q % 8] for q in range(64)]
+    mixed_order = [pool[q % 8][::-1] if q % 2 else pool[q % 8] for q in range(64)]
+    a = _plan(1_000_000, 128, 64, 1, 100, 256, 3, same_order)
+    b = _plan(1_000_000, 128, 64, 1, 100, 256, 3, mixed_order)
+    assert a == b
+    assert a["distinct_filters"] == 8 and a["mfma_groups"] == 8 and a["dot_groups"] == 0
+    assert a["levels"] == 2 and a["seed_pass"] == 1 and a["q_split"] == 1 and a["waves"] == 4
+    c = _plan(1_000_000, 128, 4, 1, 100, 256, 3, [(7, 7), (), (9,), ()])
+    assert c["distinct_filters"] == 3  # {7}, the empty filter (twice), {9}
+    d = _plan(1_000_000, 128, 3, 1, 100, 256, 3, [(7, 7), (7,), (7, 7, 7)])
+    assert d["distinct_filters"] == 1
+
+
+def test_host_plan_routes_groups_by_size_and_shape():
+    # one query per filter: nothing to share, every group goes to the wavefront-dot form
+    solo = _plan(1_000_000, 128, 64, 1, 100, 256, 3, [(i + 1,) for i in range(64)])
+    assert solo["distinct_filters"] == 64 and solo["mfma_groups"] == 0 and solo["dot_groups"] == 64
+    # the four benchmark shapes: level counts as st_search_plan gives them, the large batches in
+    # 8-wavefront workgroups without a seed pass, batch 1024 split over two passes of query rows
+    pool = [(11 * i + 1, 13 * i + 2) for i in range(8)]
+    large = _plan(10_000_000, 256, 256, 1, 500, 512, 4, [pool[q % 8] for q in range(256)])
+    assert (large["mfma_groups"], large["waves"], large["levels"], large["seed_pass"]) == (8, 8, 3, 0)
+    multi = _plan(5_000_000, 128, 128, 4, 200, 256, 3, [pool[q % 8] for q in range(128)])
+    assert (multi["mfma_groups"], multi["waves"], multi["levels"], multi["seed_pass"]) == (8, 8, 3, 0)
+    dense = _plan(20_000_000, 128, 1024, 1, 1000, 128, 2, [pool[q % 2][:1] for q in range(1024)])
+    assert dense["distinct_filters"] == 2 and dense["q_split"] == 2 and dense["levels"] == 5
+    for p, shape in ((large, (10_000_000, 256, 500)), (multi, (5_000_000, 128 * 4, 200)),
+                     (dense, (20_000_000, 1024, 1000))):
+        levels, _, _ = st.st_search_plan(*shape, p["q_split"])
+        assert p["levels"] == len(levels)
+    # the per-call tables stay small: they are what one call uploads before its first launch
+    assert 0 < large["table_bytes"] < 64 * 1024 and 0 < dense["table_bytes"] < 64 * 1024
+
+
+def test_host_plan_rejects_bad_arguments():
+    with pytest.raises(ValueError):
+        _plan(1_000_000, 128, 2, 1, 100, 256, 3, [(1,)])  # offsets shorter than the batch: the binding refuses
+    with pytest.raises(st.StError) as e:
+        st.st_search_host_plan(1_000_000, 100, 1, 1, 100, 256, 3, np.array([1], dtype=np.uint64),
+                               np.array([0, 1], dtype=np.int64))
+    assert e.value.code == st.ST_EINVAL
+    with pytest.raises(st.StError):
+        st.st_search_host_plan(1_000_000, 128, 1, 1, 200_000, 256, 3, np.array([1], dtype=np.uint64),
+                               np.array([0, 1], dtype=np.int64))
