@@ -352,11 +352,11 @@ HostScratch& host_scratch()
 // and segment sizes for each: results are kept (a few dozen shapes, oldest replaced first).
 struct PlanKey {
     int64_t n_items;
-    int32_t K, q_split, seg_cap, seed_ok, waves, min_cap;
+    int32_t K, q_split, seg_cap, seed_ok, waves, min_cap, optimistic;
     bool operator==(const PlanKey& o) const
     {
         return n_items == o.n_items && K == o.K && q_split == o.q_split && seg_cap == o.seg_cap && seed_ok == o.seed_ok &&
-               waves == o.waves && min_cap == o.min_cap;
+               waves == o.waves && min_cap == o.min_cap && optimistic == o.optimistic;
     }
 };
 struct PlanEntry {
@@ -371,10 +371,10 @@ int g_plan_next = 0;
 std::mutex g_plan_mu;
 
 int cached_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, st::Plan* out,
-                int32_t waves = 2048, int32_t min_cap = 64)
+                int32_t waves = 2048, int32_t min_cap = 64, bool optimistic = true)
 {
     // the batch enters the schedule only through "small enough for the seed pass"
-    const PlanKey key{n_items, K, q_split, seg_cap, batch_rows <= st::kSeedMaxRows ? 1 : 0, waves, min_cap};
+    const PlanKey key{n_items, K, q_split, seg_cap, batch_rows <= st::kSeedMaxRows ? 1 : 0, waves, min_cap, optimistic ? 1 : 0};
     {
         std::lock_guard<std::mutex> lock(g_plan_mu);
         for (const PlanEntry& e : g_plans)
@@ -385,7 +385,7 @@ int cached_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, in
     }
     st::Plan p;
     memset(&p, 0, sizeof(p));
-    const int rc = st::make_plan(n_items, K, q_split, seg_cap, batch_rows, &p, waves, min_cap);
+    const int rc = st::make_plan(n_items, K, q_split, seg_cap, batch_rows, &p, waves, min_cap, optimistic);
     {
         std::lock_guard<std::mutex> lock(g_plan_mu);
         PlanEntry& e = g_plans[g_plan_next];
@@ -811,8 +811,9 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
 {
     // dry_out: host part only (st_search_host_plan): no device pointer is looked at, nothing is
     // enqueued, and the summary of the schedule goes to dry_out[8]
-    // allow_seed = false: no seed pass (its threshold comes from a prefix of the corpus, which says
-    // nothing when the passing items sit in a few item ranges, as after cluster probing)
+    // allow_seed = false: no seed pass and no thresholds tighter than the K-th best so far (both
+    // rest on a prefix of the corpus, which says nothing when the passing items sit in a few item
+    // ranges, as after cluster probing)
     // expr_groups: the filters were evaluated beforehand into expr_row_count mask rows at
     // expr_rows, laid out like a Bloom index; each group then tests the one row it names
     if (!bloom) return fail(ST_EINVAL, "bloom is null");
@@ -912,7 +913,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     const int32_t scan_waves = set_mfma.n ? std::max(1, std::min(plan_groups_per_row(mp.q_split), st::kComputeUnits * mfma_wgs / mp.q_split)) * mp.waves
                                           : st::scan_groups();  // (a whole workgroup shares a segment there)
     if (cached_plan(n_items, K, mp.q_split, seg_cap, allow_seed ? batch * n_tasks : st::kSeedMaxRows + 1, &plan, scan_waves,
-                    min_cap) != 0)
+                    min_cap, allow_seed) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
     if (cached_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1, 2048, min_cap) != 0)
@@ -1071,6 +1072,8 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         se.first = lv == 0 || (lv == 1 && plan.level[0].seed);  // no candidate list from before
         se.last = lv == plan.n_levels - 1;
         se.may_overflow = lv > 0;
+        se.keep = se.last ? K : L_.keep;
+        se.keep_prev = lv > 0 ? plan.level[lv - 1].keep : K;
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
             st::SeedUpload up;

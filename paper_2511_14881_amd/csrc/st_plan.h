@@ -3,14 +3,19 @@
 //
 // The corpus is scanned exactly once, in consecutive chunks ("levels").  Level 0 admits every
 // passing (query, item) pair; after each level a selection kernel reduces the candidates to the
-// running top-K and publishes its K-th key as the admission threshold of the next level (any
-// item of the final top-K is at least as good as the K-th best of a prefix of the corpus, so
-// nothing is lost).  Levels grow geometrically so that the expected number of admitted
-// candidates per (workgroup, query) region stays at a quarter of the region's capacity.
+// best `keep` keys seen so far and publishes the keep-th as the admission threshold of the next
+// level.  With keep = K that threshold is safe by construction (any item of the final top-K is at
+// least as good as the K-th best of a prefix of the corpus).  A smaller keep gives a tighter
+// threshold that is right unless the prefix holds at least `keep` of the final top-K items; the
+// last selection notices that case (fewer than K keys at or above the threshold in the whole
+// corpus) and recomputes the query exactly, so the result is exact either way (optimistic_keep).
+// Levels grow geometrically so that the expected number of admitted candidates per
+// (workgroup, query) region stays at a quarter of the region's capacity.
 #pragma once
 #include <stdint.h>
 #include <stddef.h>
 #include <stdlib.h>
+#include <math.h>
 
 namespace st {
 
@@ -27,6 +32,7 @@ struct Level {
     int32_t seg_items;       // items one workgroup stages per step (multiple of 64, divides 1024)
     int32_t seg_per_visit;   // consecutive segments a workgroup takes before striding on
     int32_t seed;            // 1: this prefix is handled by the per-query seed kernel
+    int32_t keep;            // keys per query the selection after this level keeps (K on the last level)
 };
 
 struct Plan {
@@ -60,10 +66,37 @@ inline int64_t seed_items_for(int64_t n_items, int32_t batch_rows)
     return (batch_rows <= kSeedMaxRows && n_items >= 8 * (int64_t)kSeedItems) ? kSeedItems : 0;
 }
 
+// Keys of a prefix of `prefix` items out of n_items worth keeping when the K best of the whole
+// corpus are wanted.  The K best items sit at K of the n_items positions; if positions carry no
+// information about scores (the order of the corpus is arbitrary with respect to a query), the
+// number X of them inside the prefix is hypergeometric with mean m = K * prefix / n_items, and
+// P(X >= r) <= exp(-m * ((r/m) * ln(r/m) - (r/m - 1))) (Chernoff bound, valid for sampling without
+// replacement).  The smallest r that brings the bound under 1e-12 is returned: the r-th best key
+// of the prefix is then below the K-th best of the corpus except with that probability, and the
+// exact fallback of the last selection covers the exception (and corpora whose order does carry
+// information).  Never more than K, which is always safe.
+inline int32_t optimistic_keep(int32_t K, int64_t prefix, int64_t n_items)
+{
+    if (prefix >= n_items || K < 1) return K;
+    const double m = (double)K * (double)prefix / (double)n_items;
+    const double need = 27.631;  // ln(1e12)
+    double lo = m > 1.0 ? m : 1.0, hi = (double)K;
+    auto bound = [&](double r) { const double x = r / m; return m * (x * log(x) - (x - 1.0)); };
+    if (bound(hi) < need) return K;
+    for (int it = 0; it < 64 && hi - lo > 0.5; ++it) {
+        const double mid = 0.5 * (lo + hi);
+        if (bound(mid) >= need) hi = mid; else lo = mid;
+    }
+    const int64_t r = (int64_t)ceil(hi) + 1;
+    return r < (int64_t)K ? (int32_t)r : K;
+}
+
 // `waves` = wavefronts that scan one level side by side (per row of workgroups): it sizes the
 // segments of a level.
+// optimistic = false: every selection keeps K keys (thresholds safe by construction); for searches
+// whose passing items sit in a few item ranges, where a prefix says nothing about the rest.
 inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, int32_t seg_cap, int64_t seed_items,
-                       int32_t waves, Plan* out)
+                       int32_t waves, Plan* out, bool optimistic = true)
 {
     Plan p;
     p.groups = scan_groups();
@@ -78,27 +111,35 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
     const int32_t seg0 = cap < seg_cap ? cap : seg_cap;
     if (seed_items > 0) {
         n0 = seed_items < n_items ? seed_items : n_items;
-        p.level[p.n_levels++] = Level{0, n0, 0, 0, 1};
+        p.level[p.n_levels++] = Level{0, n0, 0, 0, 1, K};  // (the seed pass leaves a safe threshold)
     } else {
-        p.level[p.n_levels++] = Level{0, n0, seg0, cap / seg0, 0};
+        p.level[p.n_levels++] = Level{0, n0, seg0, cap / seg0, 0, K};
     }
+    // keys kept after the level just planned = what the next level's threshold admits per growth
+    auto keep_after = [&](int64_t prefix, bool seed_level) -> int32_t {
+        if (prefix >= n_items || !optimistic || seed_level) return K;
+        return optimistic_keep(K, prefix, n_items);
+    };
+    int32_t keep = keep_after(n0, seed_items > 0);
+    p.level[0].keep = keep;
     int64_t cur = n0;
     // The seed pass only leaves a threshold behind (no candidate list): the level after it starts
     // over at item 0, with the growth still counted from the prefix the threshold comes from.
     int64_t next_begin = seed_items > 0 ? 0 : n0;
-    // expected admissions per region in a level that grows the scanned prefix by `grow` are
-    // K*(grow-1)/g_eff; aim at cap/4.  Never grow by less than 2x (extreme K with few sharing
-    // workgroups): regions may then overflow and the slow exact path takes those queries.
-    double grow = 1.0 + (double)cap * (double)g_eff / (4.0 * (double)K);
-    // a level should not admit more candidates per query (about K * (grow - 1)) than the selection
-    // kernel handles in LDS together with the running top-K
-    if (K <= kLdsSortMax) {
-        const double fit = 1.0 + 0.8 * (double)(kSelectLdsKeys - K) / (double)K;
-        if (grow > fit) grow = fit;
-    }
-    if (grow < 2.0) grow = 2.0;
     while (cur < n_items) {
         if (p.n_levels >= kMaxLevels) return -1;
+        // expected admissions per region in a level that grows the scanned prefix by `grow` are
+        // keep*(grow-1)/g_eff; aim at cap/4.  Never grow by less than 2x (extreme K with few sharing
+        // workgroups): regions may then overflow and the slow exact path takes those queries.
+        double grow = 1.0 + (double)cap * (double)g_eff / (4.0 * (double)keep);
+        // a level should not admit more candidates per query (about keep * (grow - 1)) than the
+        // selection kernel handles in LDS together with the running list; the estimate from `keep`
+        // keys has a relative spread of keep^-1/2, hence the wider margin below K
+        if (K <= kLdsSortMax) {
+            const double fit = 1.0 + (keep < K ? 0.6 : 0.8) * (double)(kSelectLdsKeys - K) / (double)keep;
+            if (grow > fit) grow = fit;
+        }
+        if (grow < 2.0) grow = 2.0;
         double want = (double)cur * grow;
         int64_t nxt = want >= (double)n_items ? n_items : (int64_t)want;
         if (nxt < n_items) nxt = nxt / 1024 * 1024;
@@ -113,7 +154,7 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
         int32_t seg = seg_cap;
         {
             const int64_t span = nxt - next_begin;
-            const double admitted = (double)K * ((double)nxt / (double)(cur > 0 ? cur : 1) - 1.0);
+            const double admitted = (double)keep * ((double)nxt / (double)(cur > 0 ? cur : 1) - 1.0);
             const int64_t min_seg_count = (int64_t)(4.0 * admitted / (double)cap) + 1;
             int64_t best = -1;
             for (int32_t c = seg_cap; c >= 64; c >>= 1) {
@@ -126,7 +167,8 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
                 }
             }
         }
-        p.level[p.n_levels++] = Level{next_begin, nxt, seg, 4, 0};  // one segment per wavefront of the workgroup
+        keep = keep_after(nxt, false);
+        p.level[p.n_levels++] = Level{next_begin, nxt, seg, 4, 0, keep};  // one segment per wavefront of the workgroup
         cur = nxt;
         next_begin = nxt;
     }
@@ -158,14 +200,14 @@ inline int choose_cap(int64_t n_items, int32_t K, int32_t min_cap = 64)
 // item ranges (cluster probing) ask for the largest: a long first level that admits everything
 // then gives every query a threshold, and a dense range cannot overflow a region.
 inline int make_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, Plan* out,
-                     int32_t waves = 2048, int32_t min_cap = 64)
+                     int32_t waves = 2048, int32_t min_cap = 64, bool optimistic = true)
 {
     const int cap = choose_cap(n_items, K, min_cap);
     if (cap < 0 || q_split < 1 || scan_groups() % q_split) return -1;
     // the seed pass borrows the candidate regions and the gather buffer of a query as scratch
     const bool seed_fits = K <= kLdsSortMax && (int64_t)scan_groups() * cap >= 2 * (int64_t)kSeedItems;
     const int64_t seed = seed_fits ? seed_items_for(n_items, batch_rows) : 0;
-    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_cap, seed, waves < 1 ? 1 : waves, out);
+    return make_levels(n_items, K, cap, scan_groups() / q_split, seg_cap, seed, waves < 1 ? 1 : waves, out, optimistic);
 }
 
 // Byte offsets of the pieces of the device workspace.

@@ -584,7 +584,9 @@ struct SelectParams {
     int64_t gath_cap;
     uint64_t* srt;          // [B][k_pad] or null (sort in LDS)
     int32_t K, k_pad;
-    uint64_t* tau;          // [B][kTauParts] out (entry 0; the seed pass writes one per slice)
+    int32_t keep;           // keys this selection keeps (K on the last level; fewer: a tighter threshold for the next level)
+    int32_t keep_prev;      // what the selection before this one kept (K: its threshold was safe by construction)
+    uint64_t* tau;          // [B][kTauParts] in/out (entry 0; the seed pass writes one per slice)
     uint64_t* tau_img;      // thresholds in the order of the scorer's resident query image, or null
     const int32_t* q_taupos;  // [B] position of each query in tau_img (-1: none)
     const int32_t* q_prow;    // [B][kSeedRows + 1] first signature rows of each query's filter (-1 padded), then their count
@@ -739,6 +741,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     }
     const uint32_t total = n_prev + all;
     if (p.density_acc && tid == 0) atomicAdd(p.density_acc, (unsigned long long)all);
+    // A threshold tighter than the K-th best so far has let through every key at or above it and
+    // nothing else.  If those are fewer than K in the whole corpus the threshold was too tight for
+    // this query (its best items crowd the head of the corpus): recompute the query exactly.
+    const uint64_t tau_prev = (!p.first && p.keep_prev < p.K) ? p.tau[(int64_t)q * kTauParts] : 0ULL;
+    if (p.last && tau_prev != 0ULL && total < (uint32_t)p.K) {  // uniform over the workgroup
+        if (tid == 0) p.ovf[q] = 1u;  // reported like an overflow: the query took the slow exact path
+        __syncthreads();
+        rescue_query(p, q, s_sorted, s_hist, s_misc, s_red, s_mask, &s_misc[4]);
+        return;
+    }
     const bool in_lds = total <= (uint32_t)lds_keys;
     // More candidates than LDS holds, result sorted in LDS: the candidates are narrowed down where
     // they lie (below), not copied.
@@ -839,7 +851,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         static_assert(kBins * 4 <= kLdsSortMax * 8, "histogram borrows the sort buffer");
         uint32_t* hist = reinterpret_cast<uint32_t*>(s_sorted);
         uint64_t prefix = 0, pmask = 0;
-        uint32_t want = (uint32_t)p.K, above = 0;  // above: keys over the prefix bucket (all kept)
+        uint32_t want = (uint32_t)p.keep, above = 0;  // above: keys over the prefix bucket (all kept)
         uint64_t bound = 0;
         uint32_t keep = 0;
         for (int shift = 52;;) {
@@ -900,16 +912,16 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         });
         __syncthreads();
         keep = keep < (uint32_t)lds_keys ? keep : (uint32_t)lds_keys;  // keys are distinct: never cut
-        n_out = lds_topk(s_keys, (int)keep, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
+        n_out = lds_topk(s_keys, (int)keep, p.keep, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
     } else if (in_lds && !p.srt) {
-        n_out = lds_topk(s_keys, (int)total, p.K, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
+        n_out = lds_topk(s_keys, (int)total, p.keep, s_sorted, p.k_pad, s_hist, s_misc, s_red, p.last != 0, kth);
     } else if (p.big_sort) {
         // Large K: the set is carried from level to level unordered (only its K-th key is needed);
         // the last level orders it in LDS, which holds all k_pad keys once the selection's own
         // buffers are no longer in use.
         // (big_sort 2: more keys than LDS holds; the last level then orders them where they lie)
         const bool lds_final = p.big_sort == 1;
-        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red,
+        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.keep, sorted, p.k_pad, s_hist, s_misc, s_red,
                         p.last && !lds_final, &kth);
         if (p.last && lds_final) {
             uint64_t* big = reinterpret_cast<uint64_t*>(sel_lds);  // [k_pad]: the launch sized the LDS for it
@@ -934,13 +946,15 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
             sorted = big;
         }
     } else {
-        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.K, sorted, p.k_pad, s_hist, s_misc, s_red);
-        kth = n_out == p.K ? sorted[p.K - 1] : 0ULL;
+        n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.keep, sorted, p.k_pad, s_hist, s_misc, s_red);
+        kth = n_out == p.keep ? sorted[p.keep - 1] : 0ULL;
     }
     if (!p.last) {
         for (int i = tid; i < n_out; i += NT) p.topk_keys[(int64_t)q * p.K + i] = sorted[i];
         if (tid == 0) {
-            const uint64_t t64 = kth;
+            // fewer keys than this level keeps: what is there is every key at or above the
+            // threshold in force, which therefore stays (0: none yet, everything passing is kept)
+            const uint64_t t64 = kth ? kth : tau_prev;
             p.topk_cnt[q] = (uint32_t)n_out;
             p.tau[(int64_t)q * kTauParts] = t64;
             if (p.tau_img) {

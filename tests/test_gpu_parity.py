@@ -370,6 +370,28 @@ def test_rising_scores_overflow_the_regions_and_take_the_exact_slow_path():
         assert ids[0, 0] == n - 1 and ids[1, 0] == 0
 
 
+def test_best_items_at_the_head_of_the_corpus_defeat_the_tight_threshold_and_take_the_exact_slow_path():
+    # Batches too large for the seed pass keep fewer than K keys after the first level (the planner's
+    # optimistic_keep), i.e. they admit by a threshold tighter than the K-th best so far.  That
+    # threshold is too tight exactly when the best items crowd the first level: here scores fall with
+    # the id, the K best are items 0..K-1, and nothing of the second level reaches the threshold.  The
+    # last selection sees fewer than K keys at or above it and recomputes the query exactly.
+    # Query 1 has its scores rise with the id (the regions overflow instead); both must be exact.
+    n, d, B, K = 300_000, 64, 130, 500
+    levels, _, _ = st.st_search_plan(n, B, K)
+    assert len(levels) == 2 and levels[0, 2] != 0  # two cooperative levels, no seed pass
+    w = ragged_workload(9, n, d, B, 10, 3, 64, 2)
+    w.items = torch.ones((n, d), dtype=torch.int8)
+    w.queries = torch.ones((B, d), dtype=torch.int8)
+    w.queries[1::2] = -1
+    w.item_scale = (1.5 - torch.arange(n, dtype=torch.float32) / n).contiguous()
+    w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
+    for path in (0, 1):
+        ids, _, count = check_search(w, K, queries=[0, 1, 2, 3, 128, 129], path=path, label="falling scores",
+                                     slow_path=(list(range(B)), []))
+        assert ids[0, 0] == 0 and ids[1, 0] == n - 1 and (count == K).all()
+
+
 @pytest.mark.parametrize("B", [16, 48])
 def test_loose_threshold_admits_most_pairs_of_a_later_level(B):
     # K is close to the number of items of the first level that pass the filter, so the threshold
