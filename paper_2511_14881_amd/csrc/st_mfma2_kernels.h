@@ -63,9 +63,12 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
     // wave-private state
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * seg_stride;     // [FB][seg] this segment's passing items
     uint32_t* s_carry = reinterpret_cast<uint32_t*>(lds + mp.lds_scl) + wave * FB * kCarry;       // [FB][kCarry] absolute items carried over
-    // queued pairs that passed the bound: fp32 score << 32 | local query row << 10 | item code
-    // (bit 9 clear: place in the current segment; set: index into the carry area)
-    uint64_t* s_queue = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;
+    // queued lanes (one item x four query rows each) with a possible admission: the four
+    // accumulators, and item scale << 32 | first local query row << 10 | item code (bit 9 clear:
+    // place in the current segment; set: index into the carry area).  64 entries per wavefront.
+    static_assert(kQueueSlots * 8 >= 64 * 16, "the accumulators of 64 queued lanes take the queue area");
+    int4* q_acc = reinterpret_cast<int4*>(lds + mp.lds_queue + wave * mfma_queue_bytes(KS * 64, NW));
+    uint64_t* q_meta = reinterpret_cast<uint64_t*>(lds + mp.lds_scl + NW * FB * kCarry * 4) + wave * 64;
     float* s_tq = reinterpret_cast<float*>(lds + mp.lds_tq);                                      // [rows_local] tau / s_q per row
     int* s_neg = reinterpret_cast<int*>(lds + mp.lds_thr) + wave * mp.rows_local;                 // [rows_local] NEG per row for the current E
 
@@ -378,39 +381,60 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                 }
             }
         };
-        // Pairs that passed the bound are queued with their exact fp32 score (wave-private LDS,
-        // positions from a ballot) and drained 64 at a time, one per lane, so that key, comparison
-        // with the query's threshold key and counter update run with every lane at work.  The
-        // store is issued in assembly so that the compiler keeps counting loads only when it waits
-        // for a unit's rows (see scan_mfma_kernel).
+        // A lane whose block test leaves an admission possible is queued as it is -- its four
+        // accumulators, its scale, where its rows and its item are -- and the queue is emptied 64
+        // lanes at a time: exact fp32 scores, keys, comparison with each query's threshold key and
+        // counter updates then run with every lane at work, for the four rows of a queued lane.
+        // The store is issued in assembly so that the compiler keeps counting loads only when it
+        // waits for a unit's rows (see scan_mfma_kernel).
         auto drain = [&]() {
-            const int base = qn > 64 ? qn - 64 : 0;
-            if (base + lane < qn) {
-                const uint64_t e = s_queue[base + lane];
-                const int srow = (int)(((uint32_t)e >> 10) & 0x3FFFFFu);
+            if (lane < qn) {
+                const int4 a4 = q_acc[lane];
+                const uint64_t e = q_meta[lane];
+                const float si = __uint_as_float((uint32_t)(e >> 32));
+                const int lrow4 = (int)((uint32_t)e >> 10);
                 const uint32_t code = (uint32_t)e & 1023u;
                 const uint32_t carried = s_carry[code & (FB * kCarry - 1)];
                 const uint32_t item = (code & 512u) ? carried : (uint32_t)item0 + code;
-                const uint64_t key = make_key(__uint_as_float((uint32_t)(e >> 32)), item);
-                const int grow = s_qrow[srow];
-                if (grow >= 0 && key >= s_tau64[srow / TT]) {
-                    const uint32_t at = atomicAdd(&cnt_s[srow / TT], 1u);
-                    if (at < (uint32_t)p.cap) {
-                        uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + region) * p.cap + at;
-                        asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(dst), "v"(key) : "memory");
+                const float4 sq4 = *reinterpret_cast<const float4*>(s_sq + lrow4);
+                const int4 qr4 = *reinterpret_cast<const int4*>(s_qrow + lrow4);
+                const int accv[4] = {a4.x, a4.y, a4.z, a4.w};
+                const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
+                const int qrv[4] = {qr4.x, qr4.y, qr4.z, qr4.w};
+                float sc[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) sc[r] = rescale(accv[r], sqv[r], si);
+#pragma unroll
+                for (int q0 = 0; q0 < 4; q0 += TT) {
+                    float v = sc[q0];
+                    if (WEIGHTED) {
+                        v = 0.0f;
+#pragma unroll
+                        for (int tt = 0; tt < TT; ++tt) v = __fmaf_rn(p.w[tt], sc[q0 + tt], v);
+                    }
+                    const uint64_t key = make_key(v, item);
+                    const int srow = lrow4 + q0, grow = qrv[q0];
+                    if (grow >= 0 && key >= s_tau64[srow / TT]) {
+                        const uint32_t at = atomicAdd(&cnt_s[srow / TT], 1u);
+                        if (at < (uint32_t)p.cap) {
+                            uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + region) * p.cap + at;
+                            asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(dst), "v"(key) : "memory");
+                        }
                     }
                 }
             }
-            qn = base;
+            qn = 0;
         };
-        // Queues the lanes m (uniform, non-zero) of one row (r of a lane's four) with their scores.
-        auto push_row = [&](int lrow, int r, const UnitRegs<KS>& w, uint64_t m, float score) {
+        // Queues the lanes m (uniform, non-zero) of the block that starts at local row lrow.
+        auto block_push = [&](int lrow, const v4i& acc, const UnitRegs<KS>& w, uint64_t m) {
+            const int n = __popcll(m);
+            if (qn + n > 64) drain();
             if ((m >> lane) & 1ULL) {
                 const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
-                s_queue[pos] = ((uint64_t)__float_as_uint(score) << 32) | (uint32_t)(((lrow + 4 * kg + r) << 10) | w.si_fix2);
+                q_acc[pos] = make_int4(acc[0], acc[1], acc[2], acc[3]);
+                q_meta[pos] = ((uint64_t)__float_as_uint(w.si) << 32) | (uint32_t)(((lrow + 4 * kg) << 10) | w.si_fix2);
             }
-            qn += __popcll(m);
-            if (qn >= 64) drain();
+            qn += n;
         };
         auto block_a = [&](int lrow, v4i (&a)[KS]) {
             const int8_t* qp = s_q + lrow * D;
@@ -468,33 +492,6 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
             const int t2 = __mul24(acc[2], w.si_fix) + k.neg.z, t3 = __mul24(acc[3], w.si_fix) + k.neg.w;
             return (ballot(max(max(t0, t1), max(t2, t3)) >= 0) & valid) | force;
         };
-        // A block with possible admissions: the rows they are in; their pairs are queued.
-        auto block_push = [&](int lrow, const RowK& k, const v4i& acc, const UnitRegs<KS>& w, uint64_t valid, uint64_t force) {
-            if (WEIGHTED) {
-                const float sqv[4] = {k.sq.x, k.sq.y, k.sq.z, k.sq.w};
-                const float tfv[4] = {k.tf.x, k.tf.y, k.tf.z, k.tf.w};
-                float sc[4];
-#pragma unroll
-                for (int r = 0; r < 4; ++r) sc[r] = rescale(acc[r], sqv[r], w.si);
-#pragma unroll
-                for (int q0 = 0; q0 < 4; q0 += TT) {
-                    float agg = 0.0f;
-#pragma unroll
-                    for (int tt = 0; tt < TT; ++tt) agg = __fmaf_rn(p.w[tt], sc[q0 + tt], agg);
-                    const uint64_t m = ballot(agg >= tfv[q0]) & valid;
-                    if (m) push_row(lrow, q0, w, m, agg);
-                }
-                return;
-            }
-            const int negv[4] = {k.neg.x, k.neg.y, k.neg.z, k.neg.w};
-            const float4 sq4 = row_sq(lrow);
-            const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const uint64_t m = (ballot(__mul24(acc[r], w.si_fix) + negv[r] >= 0) & valid) | force;
-                if (m) push_row(lrow, r, w, m, rescale(acc[r], sqv[r], w.si));
-            }
-        };
         // Start of a unit's contraction: lanes that hold an item, the fixed-point factor of the
         // lane's scale, and the lanes the bound cannot be trusted for (a scale at or above 2^E, not
         // finite or not positive; every lane of the wavefront's first unit): `force`.  No branch
@@ -542,7 +539,7 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                 k.sq = cur_sq;
                 k.tf = cur_tf;
                 k.neg = cur_neg;
-                if (block_test(k, acc, w, valid, force)) block_push(lrow0, k, acc, w, valid, force);
+                { const uint64_t y = block_test(k, acc, w, valid, force); if (y) block_push(lrow0, acc, w, y); }
                 unit_end(w, force);
                 return;
             }
@@ -559,10 +556,10 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                     const v4i c0 = block_mfma(a0, w), c1 = block_mfma(a1, w), c2 = block_mfma(a2, w), c3 = block_mfma(a3, w);
                     const uint64_t y0 = block_test(k0, c0, w, valid, force), y1 = block_test(k1, c1, w, valid, force);
                     const uint64_t y2 = block_test(k2, c2, w, valid, force), y3 = block_test(k3, c3, w, valid, force);
-                    if (y0) block_push(l0, k0, c0, w, valid, force);
-                    if (y1) block_push(l0 + 16, k1, c1, w, valid, force);
-                    if (y2) block_push(l0 + 32, k2, c2, w, valid, force);
-                    if (y3) block_push(l0 + 48, k3, c3, w, valid, force);
+                    if (y0) block_push(l0, c0, w, y0);
+                    if (y1) block_push(l0 + 16, c1, w, y1);
+                    if (y2) block_push(l0 + 32, c2, w, y2);
+                    if (y3) block_push(l0 + 48, c3, w, y3);
                 }
             }
             for (; j + 2 <= nblk; j += 2) {
@@ -573,15 +570,15 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                 const RowK k0 = row_k(l0), k1 = row_k(l0 + 16);
                 const v4i c0 = block_mfma(a0, w), c1 = block_mfma(a1, w);
                 const uint64_t y0 = block_test(k0, c0, w, valid, force), y1 = block_test(k1, c1, w, valid, force);
-                if (y0) block_push(l0, k0, c0, w, valid, force);
-                if (y1) block_push(l0 + 16, k1, c1, w, valid, force);
+                if (y0) block_push(l0, c0, w, y0);
+                if (y1) block_push(l0 + 16, c1, w, y1);
             }
             for (; j < nblk; ++j) {
                 v4i a[KS];
                 block_a(lrow0 + 16 * j, a);
                 const RowK k = row_k(lrow0 + 16 * j);
                 const v4i acc = block_mfma(a, w);
-                if (block_test(k, acc, w, valid, force)) block_push(lrow0 + 16 * j, k, acc, w, valid, force);
+                { const uint64_t y = block_test(k, acc, w, valid, force); if (y) block_push(lrow0 + 16 * j, acc, w, y); }
             }
             unit_end(w, force);
         };
@@ -602,10 +599,10 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                 const v4i c00 = block_mfma(a0, w0), c01 = block_mfma(a0, w1), c10 = block_mfma(a1, w0), c11 = block_mfma(a1, w1);
                 const uint64_t y00 = block_test(k0, c00, w0, valid0, force0), y01 = block_test(k0, c01, w1, valid1, force1);
                 const uint64_t y10 = block_test(k1, c10, w0, valid0, force0), y11 = block_test(k1, c11, w1, valid1, force1);
-                if (y00) block_push(l0, k0, c00, w0, valid0, force0);
-                if (y01) block_push(l0, k0, c01, w1, valid1, force1);
-                if (y10) block_push(l0 + 16, k1, c10, w0, valid0, force0);
-                if (y11) block_push(l0 + 16, k1, c11, w1, valid1, force1);
+                if (y00) block_push(l0, c00, w0, y00);
+                if (y01) block_push(l0, c01, w1, y01);
+                if (y10) block_push(l0 + 16, c10, w0, y10);
+                if (y11) block_push(l0 + 16, c11, w1, y11);
             }
             for (; j < nblk; ++j) {
                 const int l0 = lrow0 + 16 * j;
@@ -614,8 +611,8 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                 const RowK k = row_k(l0);
                 const v4i c0 = block_mfma(a, w0), c1 = block_mfma(a, w1);
                 const uint64_t y0 = block_test(k, c0, w0, valid0, force0), y1 = block_test(k, c1, w1, valid1, force1);
-                if (y0) block_push(l0, k, c0, w0, valid0, force0);
-                if (y1) block_push(l0, k, c1, w1, valid1, force1);
+                if (y0) block_push(l0, c0, w0, y0);
+                if (y1) block_push(l0, c1, w1, y1);
             }
             unit_end(w0, force0);
             unit_end(w1, force1);
@@ -652,7 +649,7 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                     if (NB > 3) step(r3, base + 3);
                 }
             }
-            while (qn > 0) drain();
+            if (qn > 0) drain();
         }
         // (4) what the full units left over goes to the carry area: entry j of filter f, for the
         // (f, j) pairs of two passes over the wavefront.  All sources are read before anything is

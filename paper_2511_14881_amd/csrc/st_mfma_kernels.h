@@ -38,7 +38,12 @@ constexpr int kMfmaQueryLds = 64 * 1024;   // LDS bytes for resident query rows 
 constexpr int kMfmaMinRows = 4;            // a group needs this many query rows to go to MFMA
 constexpr int kMfmaMaxGroups = 128;        // groups one MFMA launch takes (the rest go to the dot scorer)
 constexpr int kMfmaSegItems = 512;         // items per wavefront segment, at most (8 mask words x 8 filters = 64 lanes)
-constexpr int kQueueSlots = 128;           // queued admissions per wavefront (drained whenever 64 are waiting)
+constexpr int kQueueSlots = 128;           // (size of the accumulator part of the queue, in 8-byte words)
+constexpr int kQueueLanes = 64;            // queued lanes per wavefront: four accumulator values and a code each
+constexpr int kQueueBytes = kQueueSlots * 8 + kQueueLanes * 4;
+// queue bytes per wavefront: kernels that contract two units at once (8 wavefronts, d <= 128) queue
+// pair by pair and need no code array
+constexpr int mfma_queue_bytes(int d, int waves) { return (waves == 8 && d <= 128) ? kQueueSlots * 8 : kQueueBytes; }
 constexpr int kMaxRegionSlots = 8;         // candidate regions one workgroup may fill in a launch
 constexpr int kDenseItems = 12;            // passing items per filter and 512-item segment from which full units are the rule
 
@@ -157,7 +162,10 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     // entries of the upper half of a 512-item segment follow those of the lower half, so the
     // number of lower-half entries per filter restores the ninth bit.
     uint8_t* s_list = reinterpret_cast<uint8_t*>(lds + mp.lds_list) + wave * FB * seg_stride;  // wave-private [FB][seg]
-    uint64_t* s_queue = reinterpret_cast<uint64_t*>(lds + mp.lds_queue) + wave * kQueueSlots;  // wave-private
+    constexpr int QB = mfma_queue_bytes(KS * 64, NW);
+    int4* q_acc = reinterpret_cast<int4*>(lds + mp.lds_queue + wave * QB);                        // wave-private
+    uint64_t* s_queue = reinterpret_cast<uint64_t*>(q_acc);                                       // (the pair form of the queue)
+    uint32_t* q_code = reinterpret_cast<uint32_t*>(lds + mp.lds_queue + wave * QB + kQueueSlots * 8);  // (lane form only)
     float* s_tq = reinterpret_cast<float*>(lds + mp.lds_tq);                                    // [rows_local] tau / s_q per row
     int* s_thr = reinterpret_cast<int*>(lds + mp.lds_thr) + wave * mp.rows_local;               // wave-private [rows_local]
     float* s_scl = reinterpret_cast<float*>(lds + mp.lds_scl) + wave * seg_stride;              // wave-private [seg] item scales
@@ -565,11 +573,12 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
                 }
             }
         };
-        // Admissions are queued (wave-private LDS, positions from a ballot: no waiting) and
-        // drained 64 at a time, one candidate per lane, so that the LDS round trips of the
-        // counter update are paid once per 64 candidates instead of once per unit.  An entry holds
-        // the local row, the item's place in the segment and the aggregated score (weighted
-        // search) or the int32 dot product (plain search, rescaled here).
+        // A lane whose block test leaves an admission possible is queued as it is (wave-private LDS,
+        // positions from a ballot: no waiting): its four values -- the int32 dot products (plain
+        // search, rescaled when drained) or the aggregated scores (weighted search) -- and a code
+        // with the first of its four local rows and the item's place in the segment.  The queue is
+        // drained 64 lanes at a time, so that keys, the comparisons with the queries' threshold
+        // keys and the LDS round trips of the counter updates are paid with every lane at work.
         //
         // The store of a drained candidate is written in assembly.  On this target loads and stores
         // share one outstanding-operation counter; a store the compiler knows of, possibly pending,
@@ -579,7 +588,38 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
         // for "at most n operations outstanding" is met once enough operations have completed, the
         // loads complete in the order they were issued, so the load waited for is among them with
         // or without the store.  (Nothing in the kernel reads the stored keys back.)
-        auto drain = [&]() {  // takes the last (up to) 64 queued entries; the order inside a region is free
+        auto drain_lanes = [&]() {  // empties the queue: one queued lane (an item and four query rows) per lane
+            if (lane < qn) {
+                const int4 a4 = q_acc[lane];
+                const uint32_t code = q_code[lane];
+                const int lrow4 = (int)(code >> 9);  // first of the lane's four local rows
+                const int it = (int)(code & 511u);
+                const float si = s_scl[it];
+                const float4 sq4 = *reinterpret_cast<const float4*>(s_sq + lrow4);
+                const int4 qr4 = *reinterpret_cast<const int4*>(s_qrow + lrow4);
+                const int accv[4] = {a4.x, a4.y, a4.z, a4.w};
+                const float sqv[4] = {sq4.x, sq4.y, sq4.z, sq4.w};
+                const int qrv[4] = {qr4.x, qr4.y, qr4.z, qr4.w};
+#pragma unroll
+                for (int q0 = 0; q0 < 4; q0 += TT) {
+                    // weighted search: the aggregate of query q0 was queued; plain: its int32 dot product
+                    const float score = WEIGHTED ? __uint_as_float((uint32_t)accv[q0]) : rescale(accv[q0], sqv[q0], si);
+                    const uint64_t key = make_key(score, (uint32_t)(item0 + it));
+                    const int srow = lrow4 + q0, grow = qrv[q0];
+                    if (grow >= 0 && key >= s_tau64[srow / TT]) {
+                        const uint32_t at = atomicAdd(&cnt_s[srow / TT], 1u);
+                        if (at < (uint32_t)p.cap) {
+                            uint64_t* dst = p.cand + ((int64_t)(grow / TT) * p.groups + region) * p.cap + at;
+                            asm volatile("global_store_dwordx2 %0, %1, off" : : "v"(dst), "v"(key) : "memory");
+                        }
+                    }
+                }
+            }
+            qn = 0;
+        };
+        // The queue pair by pair: an entry holds the local row, the item's place in the segment and
+        // the aggregated score (weighted search) or the int32 dot product (plain search).
+        auto drain_pairs = [&]() {  // takes the last (up to) 64 queued entries; the order inside a region is free
             const int base = qn > 64 ? qn - 64 : 0;
             if (base + lane < qn) {
                 const uint64_t e = s_queue[base + lane];
@@ -641,8 +681,26 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
             }
             return (any & valid) != 0;
         };
+        // Queues the lanes of a block that hold a possible admission, as they are: the four values
+        // of the lane and where its rows and its item are.  The exact test of each of the four
+        // pairs runs when the queue is drained, with every lane at work.
+        auto push_lanes = [&](int lrow, const UnitRegs<KS>& w, uint64_t valid, const uint32_t (&val)[4],
+                              const uint64_t (&hits)[4]) {
+            uint64_t m = 0;
+#pragma unroll
+            for (int r = 0; r < 4; r += TT) m |= hits[r];
+            m &= valid;  // (non-zero: the caller has tested it)
+            const int n = __popcll(m);
+            if (qn + n > kQueueLanes) drain_lanes();
+            if ((m >> lane) & 1ULL) {
+                const int pos = qn + __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0u));
+                q_acc[pos] = make_int4((int)val[0], TT == 1 ? (int)val[1] : 0, TT <= 2 ? (int)val[2] : 0, TT == 1 ? (int)val[3] : 0);
+                q_code[pos] = (uint32_t)(((lrow + 4 * kg) << 9) | w.item);
+            }
+            qn += n;
+        };
         // Queues the candidates of a block (rare path).
-        auto block_push = [&](int lrow, const UnitRegs<KS>& w, uint64_t valid, const uint32_t (&val)[4],
+        auto push_pairs = [&](int lrow, const UnitRegs<KS>& w, uint64_t valid, const uint32_t (&val)[4],
                               const uint64_t (&hits)[4]) {
 #pragma unroll
             for (int r = 0; r < 4; r += TT) {
@@ -654,8 +712,27 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
                         s_queue[pos] = ((uint64_t)val[r] << 32) | (uint32_t)(((lrow + 4 * kg + r) << 9) | w.item);
                     }
                     qn += __popcll(m);
-                    if (qn >= 64) drain();
+                    if (qn >= 64) drain_pairs();
                 }
+            }
+        };
+        // Which form of the queue: whole lanes where a unit meets few query blocks (the exact test
+        // of four pairs per queued lane is then cheaper than queueing pair by pair); pairs where two
+        // units share every block's operands (dense batches: few lanes hold an admission, and the
+        // pair form keeps fewer values alive across the blocks of a round).
+        constexpr bool LANEQ = !PAIRS;
+        auto block_push = [&](int lrow, const UnitRegs<KS>& w, uint64_t valid, const uint32_t (&val)[4],
+                              const uint64_t (&hits)[4]) {
+            if (LANEQ)
+                push_lanes(lrow, w, valid, val, hits);
+            else
+                push_pairs(lrow, w, valid, val, hits);
+        };
+        auto drain_all = [&]() {
+            if (LANEQ) {
+                if (qn > 0) drain_lanes();
+            } else {
+                while (qn > 0) drain_pairs();
             }
         };
         auto block_a = [&](int lrow, v4i (&a)[KS]) {
@@ -891,7 +968,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
                     if (NB > 3) step(r3, base + 3);
                 }
             }
-            while (qn > 0) drain();
+            drain_all();
         }
         cur = nxt;
     }
@@ -987,7 +1064,7 @@ inline void mfma_lds_layout(MfmaParams* mp, int d, int n_tasks, int n_groups, in
     mp->lds_qrow = take(mp->rows_local * 4);
     mp->lds_cnt = take((mp->region_slots * (mp->rows_local / n_tasks + 1) + 1) * 4);  // + the segment counter
     mp->lds_list = take(waves * kMfmaFilterBatch * mp->seg_stride);
-    mp->lds_queue = take(waves * kQueueSlots * 8);
+    mp->lds_queue = take(waves * mfma_queue_bytes(d, waves));
     mp->lds_prow = take(n_groups * kPrefetchStride * 4);
     mp->lds_blkoff = take((2 * n_groups + 2) * 4);
     mp->lds_rowoff = take((n_groups + 1) * 4);
