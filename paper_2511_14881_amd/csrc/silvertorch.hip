@@ -1074,6 +1074,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         se.may_overflow = lv > 0;
         se.keep = se.last ? K : L_.keep;
         se.keep_prev = lv > 0 ? plan.level[lv - 1].keep : K;
+        se.tau_parts = lv == 0 ? 0 : ((lv == 1 && plan.level[0].seed) ? seed_parts : 1);
         if (L_.seed) {  // per-query scan + selection of the prefix in one launch
             TimedLaunch t(1, stream);
             st::SeedUpload up;

@@ -111,17 +111,20 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
     const int32_t seg0 = cap < seg_cap ? cap : seg_cap;
     if (seed_items > 0) {
         n0 = seed_items < n_items ? seed_items : n_items;
-        p.level[p.n_levels++] = Level{0, n0, 0, 0, 1, K};  // (the seed pass leaves a safe threshold)
+        p.level[p.n_levels++] = Level{0, n0, 0, 0, 1, K};
     } else {
         p.level[p.n_levels++] = Level{0, n0, seg0, cap / seg0, 0, K};
     }
     // keys kept after the level just planned = what the next level's threshold admits per growth
-    auto keep_after = [&](int64_t prefix, bool seed_level) -> int32_t {
-        if (prefix >= n_items || !optimistic || seed_level) return K;
+    auto keep_after = [&](int64_t prefix) -> int32_t {
+        if (prefix >= n_items || !optimistic) return K;
         return optimistic_keep(K, prefix, n_items);
     };
-    int32_t keep = keep_after(n0, seed_items > 0);
+    int32_t keep = keep_after(n0);
     p.level[0].keep = keep;
+    // (the seed pass takes the smallest of its slices' ceil(keep / slices)-th best keys, which lies
+    // at or below the keep-th best of the prefix: count on twice as many admissions)
+    if (seed_items > 0 && keep < K) keep = 2 * keep < K ? 2 * keep : K;
     int64_t cur = n0;
     // The seed pass only leaves a threshold behind (no candidate list): the level after it starts
     // over at item 0, with the growth still counted from the prefix the threshold comes from.
@@ -167,7 +170,7 @@ inline int make_levels(int64_t n_items, int32_t K, int32_t cap, int32_t g_eff, i
                 }
             }
         }
-        keep = keep_after(nxt, false);
+        keep = keep_after(nxt);
         p.level[p.n_levels++] = Level{next_begin, nxt, seg, 4, 0, keep};  // one segment per wavefront of the workgroup
         cur = nxt;
         next_begin = nxt;

@@ -586,6 +586,7 @@ struct SelectParams {
     int32_t K, k_pad;
     int32_t keep;           // keys this selection keeps (K on the last level; fewer: a tighter threshold for the next level)
     int32_t keep_prev;      // what the selection before this one kept (K: its threshold was safe by construction)
+    int32_t tau_parts;      // entries of tau the scan of this level admitted by (the smallest counts; 0: no threshold)
     uint64_t* tau;          // [B][kTauParts] in/out (entry 0; the seed pass writes one per slice)
     uint64_t* tau_img;      // thresholds in the order of the scorer's resident query image, or null
     const int32_t* q_taupos;  // [B] position of each query in tau_img (-1: none)
@@ -744,7 +745,11 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
     // A threshold tighter than the K-th best so far has let through every key at or above it and
     // nothing else.  If those are fewer than K in the whole corpus the threshold was too tight for
     // this query (its best items crowd the head of the corpus): recompute the query exactly.
-    const uint64_t tau_prev = (!p.first && p.keep_prev < p.K) ? p.tau[(int64_t)q * kTauParts] : 0ULL;
+    uint64_t tau_prev = 0ULL;
+    if (p.keep_prev < p.K && p.tau_parts > 0) {
+        tau_prev = ~0ULL;
+        for (int pp = 0; pp < p.tau_parts; ++pp) tau_prev = min(tau_prev, p.tau[(int64_t)q * kTauParts + pp]);
+    }
     if (p.last && tau_prev != 0ULL && total < (uint32_t)p.K) {  // uniform over the workgroup
         if (tid == 0) p.ovf[q] = 1u;  // reported like an overflow: the query took the slow exact path
         __syncthreads();
@@ -1182,12 +1187,13 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     }
     __syncthreads();
 
-    // This slice's share of the threshold: its ceil(K / parts)-th best key.  With every slice
-    // holding that many keys at or above its own value, the prefix holds at least K keys at or
-    // above the smallest of them, so the minimum over the slices is a valid admission threshold
-    // (0 = this slice has too few passing items: no threshold).  Nothing else is carried over: the
-    // level after the seed pass scans the prefix again.
-    const int rank = (p.K + parts - 1) / parts;
+    // This slice's share of the threshold: its ceil(keep / parts)-th best key.  With every slice
+    // holding that many keys at or above its own value, the prefix holds at least `keep` keys at or
+    // above the smallest of them, so the minimum over the slices lies at or below the keep-th best
+    // key of the prefix: a valid admission threshold for keep = K, and for a smaller keep the
+    // tighter one the schedule counts on (0 = this slice has too few passing items: no threshold).
+    // Nothing else is carried over: the level after the seed pass scans the prefix again.
+    const int rank = (p.keep + parts - 1) / parts;
     int rank_pad = 1;
     while (rank_pad < rank) rank_pad <<= 1;
     uint64_t kth = 0;

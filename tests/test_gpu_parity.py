@@ -392,6 +392,26 @@ def test_best_items_at_the_head_of_the_corpus_defeat_the_tight_threshold_and_tak
         assert ids[0, 0] == 0 and ids[1, 0] == n - 1 and (count == K).all()
 
 
+def test_best_items_inside_the_seed_prefix_defeat_its_tight_threshold_and_take_the_exact_slow_path():
+    # Small batches take their first threshold from the seed pass over the first 32768 items, and
+    # that threshold too is tighter than the K-th best of the prefix.  Here every item of the prefix
+    # carries a scale sixteen times that of the rest, so the K best of the corpus all lie in the
+    # prefix, spread evenly over its slices: the threshold lands among them, fewer than K keys of
+    # the corpus reach it, and the last selection recomputes every query exactly.
+    n, d, B, K = 300_000, 64, 6, 500
+    levels, _, _ = st.st_search_plan(n, B, K)
+    assert levels[0, 2] == 0 and len(levels) == 2  # seed pass, then one level over the corpus
+    w = ragged_workload(10, n, d, B, 10, 3, 64, 2)
+    scale = torch.full((n,), 0.25, dtype=torch.float32)
+    scale[:32768] = 4.0
+    w.item_scale = scale.contiguous()
+    w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
+    for path in (0, 1):
+        ids, _, count = check_search(w, K, path=path, label="top items inside the seed prefix",
+                                     slow_path=(list(range(B)), []))
+        assert (count == K).all() and (ids < 32768).all()
+
+
 @pytest.mark.parametrize("B", [16, 48])
 def test_loose_threshold_admits_most_pairs_of_a_later_level(B):
     # K is close to the number of items of the first level that pass the filter, so the threshold
