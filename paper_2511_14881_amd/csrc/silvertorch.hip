@@ -1197,7 +1197,7 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
                                            (int)std::max<size_t>(st::kSelectLdsBytes, kBigSortMax)));
                 lds_set.store(true, std::memory_order_release);
             }
-            const size_t lds = std::max<size_t>((size_t)st::select_lds_bytes(se.lds_keys), se.big_sort == 1 ? big_bytes : 0);
+            const size_t lds = std::max<size_t>((size_t)st::select_lds_bytes(se.lds_keys), se.big_sort == 1 ? big_bytes : (se.big_sort == 2 ? kBigSortMax : 0));
             hipLaunchKernelGGL(st::select_kernel, dim3(batch), dim3(st::kSelectThreads), lds, stream, se);
         }
         ST_HIP(hipGetLastError());

@@ -206,6 +206,20 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
     const int tid = threadIdx.x, nt = blockDim.x;
     const int n_out = n < (int64_t)K ? (int)n : K;
     uint64_t low = ~0ULL;  // smallest key this thread put into sorted[]
+    // f(key) for every key of buf, this thread's share: eight loads are requested before the first
+    // is used (one memory round trip per eight keys instead of one per key)
+    auto for_each = [&](auto&& f) {
+        constexpr int U = 8;
+        int64_t i = tid;
+        for (; i + (int64_t)(U - 1) * nt < n; i += (int64_t)U * nt) {
+            uint64_t v[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[u] = buf[i + (int64_t)u * nt];
+#pragma unroll
+            for (int u = 0; u < U; ++u) f(v[u]);
+        }
+        for (; i < n; i += nt) f(buf[i]);
+    };
     // power-of-two size the sorting network runs on
     int P = 1;
     while (P < n_out) P <<= 1;
@@ -219,11 +233,10 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
     } else {
         // bits shared by every key need no pass: find the highest byte in which two keys differ
         uint64_t lo = ~0ULL, hi = 0ULL;
-        for (int64_t i = tid; i < n; i += nt) {
-            const uint64_t key = buf[i];
+        for_each([&](uint64_t key) {
             lo = key < lo ? key : lo;
             hi = key > hi ? key : hi;
-        }
+        });
         for (int o = 32; o > 0; o >>= 1) {
             const uint64_t l2 = __shfl_xor((unsigned long long)lo, o), h2 = __shfl_xor((unsigned long long)hi, o);
             lo = l2 < lo ? l2 : lo;
@@ -243,10 +256,9 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
         for (int shift = top_shift; shift >= 0; shift -= 8) {
             for (int i = tid; i < 256; i += nt) s_hist[i] = 0;
             __syncthreads();
-            for (int64_t i = tid; i < n; i += nt) {
-                const uint64_t key = buf[i];
+            for_each([&](uint64_t key) {
                 if ((key & prefix_mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255], 1u);
-            }
+            });
             __syncthreads();
             if (tid < 64) {
                 // lane l owns digits 255-4l .. 252-4l (descending); find the digit where the
@@ -283,14 +295,13 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
         const uint64_t kth = prefix;  // keys are distinct: exactly K of them are >= kth
         if (tid == 0) s_misc[2] = 0;
         __syncthreads();
-        for (int64_t i = tid; i < n; i += nt) {
-            const uint64_t key = buf[i];
+        for_each([&](uint64_t key) {
             if (key >= kth) {
                 const uint32_t slot = atomicAdd(&s_misc[2], 1u);
                 if (slot < (uint32_t)P) sorted[slot] = key;
                 if (key < low) low = key;
             }
-        }
+        });
         for (int i = K + tid; i < P; i += nt) sorted[i] = 0ULL;
     }
     __syncthreads();
@@ -338,6 +349,55 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
         }
     }
     return n_out;
+}
+
+// Descending bitonic sort of P keys in global memory (P a power of two above C) by one workgroup,
+// blocked through an LDS buffer of C keys (C a power of two): every stage whose partner distance
+// is below C runs on chunks held in LDS, only the log2(P / C) * (log2(P / C) + 1) / 2 stages at
+// distance C and above touch global memory.  All threads of the workgroup must call it.
+__device__ inline void blocked_bitonic_desc(uint64_t* g, int P, uint64_t* chunk, int C)
+{
+    const int tid = threadIdx.x, nt = blockDim.x;
+    auto lds_stages = [&](int c0, int k2, int j_first) {  // stages j_first .. 1 of merge size k2 on the chunk at c0
+        for (int j = j_first; j > 0; j >>= 1) {
+            for (int i = tid; i < C; i += nt) {
+                const int x = i ^ j;
+                if (x > i) {
+                    const uint64_t a = chunk[i], b = chunk[x];
+                    const bool desc = ((c0 + i) & k2) == 0;
+                    if (desc ? (a < b) : (a > b)) { chunk[i] = b; chunk[x] = a; }
+                }
+            }
+            __syncthreads();
+        }
+    };
+    for (int c0 = 0; c0 < P; c0 += C) {
+        for (int i = tid; i < C; i += nt) chunk[i] = g[c0 + i];
+        __syncthreads();
+        for (int k2 = 2; k2 <= C; k2 <<= 1) lds_stages(c0, k2, k2 >> 1);
+        for (int i = tid; i < C; i += nt) g[c0 + i] = chunk[i];
+        __syncthreads();
+    }
+    for (int k2 = 2 * C; k2 <= P; k2 <<= 1) {
+        for (int j = k2 >> 1; j >= C; j >>= 1) {
+            for (int i = tid; i < P; i += nt) {
+                const int x = i ^ j;
+                if (x > i) {
+                    const uint64_t a = g[i], b = g[x];
+                    const bool desc = (i & k2) == 0;
+                    if (desc ? (a < b) : (a > b)) { g[i] = b; g[x] = a; }
+                }
+            }
+            __syncthreads();
+        }
+        for (int c0 = 0; c0 < P; c0 += C) {
+            for (int i = tid; i < C; i += nt) chunk[i] = g[c0 + i];
+            __syncthreads();
+            lds_stages(c0, k2, C >> 1);
+            for (int i = tid; i < C; i += nt) g[c0 + i] = chunk[i];
+            __syncthreads();
+        }
+    }
 }
 
 // Writes one query's result row from sorted keys, padding with id -1 / score -inf.
@@ -927,7 +987,20 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
         // (big_sort 2: more keys than LDS holds; the last level then orders them where they lie)
         const bool lds_final = p.big_sort == 1;
         n_out = wg_topk(in_lds ? s_keys : gkeys, (int64_t)total, p.keep, sorted, p.k_pad, s_hist, s_misc, s_red,
-                        p.last && !lds_final, &kth);
+                        false, &kth);
+        if (p.last && !lds_final) {
+            // more keys than LDS holds: ordered in global memory, chunk by chunk through LDS
+            constexpr int kChunk = 16384;  // (the launch sized the LDS for it)
+            int P = 1;
+            while (P < n_out) P <<= 1;
+            __syncthreads();
+            for (int i = n_out + tid; i < P; i += NT) sorted[i] = 0ULL;
+            __syncthreads();
+            if (P > kChunk)
+                blocked_bitonic_desc(sorted, P, reinterpret_cast<uint64_t*>(sel_lds), kChunk);
+            else
+                (void)wg_topk(sorted, (int64_t)n_out, n_out, sorted, P, s_hist, s_misc, s_red);
+        }
         if (p.last && lds_final) {
             uint64_t* big = reinterpret_cast<uint64_t*>(sel_lds);  // [k_pad]: the launch sized the LDS for it
             int P = 1;
