@@ -307,6 +307,25 @@ def test_ragged_sizes_and_filters(n, d, B, K, T, path):
         assert (ids[b, count[b]:] == -1).all() and np.isneginf(scores[b, count[b]:]).all()
 
 
+@pytest.mark.parametrize("seed,n,d,B,K,T,vocab", [
+    (101, 90_000, 64, 130, 1, 0, 12), (102, 150_000, 64, 200, 10, 0, 30), (103, 260_000, 128, 256, 100, 0, 8),
+    (104, 400_000, 64, 140, 1000, 0, 12), (105, 400_000, 64, 136, 3000, 0, 6), (106, 180_000, 128, 66, 40, 2, 12),
+    (107, 300_000, 128, 40, 200, 4, 10), (108, 300_000, 64, 100, 7, 0, 40), (109, 500_000, 64, 24, 500, 0, 12),
+    (110, 270_000, 256, 160, 64, 0, 20), (111, 131_073, 64, 129, 2048, 0, 5), (112, 350_000, 64, 512, 30, 0, 16)])
+def test_levels_with_tight_thresholds_on_mixed_selectivities(seed, n, d, B, K, T, vocab):
+    # Plans of two and more levels (with and without a seed pass) on batches whose filters range
+    # from "every item" over a few percent down to a handful of items and none at all: selections
+    # that keep fewer than K keys meet queries with more, with fewer and with no passing items in
+    # the first level (the last two admit without a threshold), K above and below what passes, one
+    # to four tasks.  Every query is compared with the oracle, and none may need the slow path.
+    w = ragged_workload(seed, n, d, B, vocab, 3, 128, 2, T=T)
+    levels, _, _ = st.st_search_plan(n, B * max(T, 1), K)
+    assert len(levels) >= 2
+    ids, scores, count = check_search(w, K, label=f"mixed selectivities seed={seed}", fast_path_only=True)
+    for b in range(B):
+        assert (ids[b, count[b]:] == -1).all()
+
+
 @pytest.mark.parametrize("K,B", [(5000, 6), (16384, 2), (50_000, 3), (100_000, 2)])
 def test_top_k_above_the_lds_sort_size(K, B):
     # K above 2048: the running top-K lives in global memory, is carried unordered from level to
