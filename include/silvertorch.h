@@ -194,7 +194,8 @@ int st_score_pairs(const int8_t* dev_items, const float* dev_item_scale, int32_t
 /* Diagnostic: byte offset, inside a workspace laid out for these sizes (the arguments of
  * st_search_workspace_bytes), of the per-query overflow flags: uint32 [batch], valid once a
  * search on that workspace has completed.  1 = one of the query's candidate regions overflowed
- * in some level and the query was recomputed by the slow exact path (Algorithm 1 phases 3-4 are
+ * in some level, or fewer than K keys reached a threshold tighter than the K-th best so far,
+ * and the query was recomputed by the slow exact path (Algorithm 1 phases 3-4 are
  * then evaluated for that query alone, over the whole corpus); results are exact either way, the
  * flag only tells that the fast path did not hold.  Negative st_status on bad sizes. */
 int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batch, int32_t n_tasks,
@@ -203,8 +204,12 @@ int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batc
 /* Host-side description of how a search of these sizes is scheduled (pure arithmetic, no
  * GPU): writes up to max_levels rows of 3 int64 {item_begin, item_end, segment_items} and
  * returns the number of levels, or a negative st_status.  The corpus is scanned once, in
- * consecutive chunks ("levels"); after each chunk the running top-K and its K-th key become
- * the admission threshold of the next.  q_split (a power of two, 1 unless the query rows of a large batch are
+ * consecutive chunks ("levels"); after each chunk a selection keeps the best keys seen so far
+ * and the last of them becomes the admission threshold of the next (fewer than K keys are kept
+ * before the last level: a tighter threshold, checked and backed by the exact slow path at the
+ * end).  The rows give the sizes; a search served by the 8-wavefront MFMA scan alone takes the
+ * items of its first level as segments spread evenly over the corpus rather than as the prefix
+ * [item_begin, item_end) and scans the rest from item 0.  q_split (a power of two, 1 unless the query rows of a large batch are
  * spread over several rows of workgroups) divides the workgroups that share one query's
  * candidates.  out_caps receives {workgroups, region_capacity}. */
 int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_split,

@@ -1064,6 +1064,21 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     se.tau_img = set_mfma.n ? mp.img_tau : nullptr;
     se.q_taupos = tab(at_taupos);
     se.q_prow = tab(at_qprow);
+    // Sample mode: the first level of a search that the 8-wavefront MFMA scan serves alone scans
+    // its G * cap items as segments spread evenly over the corpus instead of a prefix, and the
+    // second level scans the whole corpus without them.  The threshold the first selection
+    // publishes rests on the assumption that the order of the corpus says nothing about a query's
+    // scores; a strided sample keeps that true for corpora ordered along some trend (by age, by
+    // popularity, by category), where a prefix would not.
+    int64_t samp_stride = 0;
+    if (plan.n_levels >= 2 && !plan.level[0].seed && allow_seed && set_mfma.n && !set_dot.n && mp.waves == 8) {
+        const st::Level& L0 = plan.level[0];
+        const int64_t segs = (L0.end - L0.begin) / L0.seg_items;
+        if (L0.begin == 0 && segs > 0 && (L0.end - L0.begin) % L0.seg_items == 0 && L0.seg_items % 64 == 0) {
+            const int64_t stride = n_items / segs / 64 * 64;
+            if (stride >= 2 * (int64_t)L0.seg_items) samp_stride = stride;
+        }
+    }
     bool mfma_started = false;  // the first MFMA launch builds the resident-query image
     bool density_on = false;    // the first level counts the pairs it admits (chooses the later levels' form of the scan)
     int seed_parts = 1;         // slices per query of the seed pass (one threshold each)
@@ -1107,14 +1122,18 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             continue;
         }
         for (st::ScanParams* q : {&sp_m, &sp_d}) {
-            q->item_begin = L_.begin;
+            q->item_begin = (samp_stride && lv == 1) ? 0 : L_.begin;
             q->item_end = L_.end;
+            q->samp_role = samp_stride ? (lv == 0 ? 1 : 2) : 0;
+            q->samp_stride_items = samp_stride;
+            q->samp_segs = samp_stride ? (int32_t)((plan.level[0].end - plan.level[0].begin) / plan.level[0].seg_items) : 0;
+            q->samp_seg_items = samp_stride ? plan.level[0].seg_items : 0;
             q->seg_items = L_.seg_items;
             q->seg_per_visit = L_.seg_per_visit;
             q->use_tau = lv > 0;
             q->tau_parts = (lv == 1 && plan.level[0].seed) ? seed_parts : 1;
         }
-        const int64_t n_seg = (L_.end - L_.begin + L_.seg_items - 1) / L_.seg_items;
+        const int64_t n_seg = (L_.end - sp_m.item_begin + L_.seg_items - 1) / L_.seg_items;
         // workgroups of the MFMA scan that are resident at once, per row of the grid
         const int32_t resident = std::max(1, st::pow2_ceil(st::kComputeUnits * mfma_wgs / mp.q_split + 1) / 2);
         // Past the first level a visit is one segment per wavefront of the workgroup; a level with

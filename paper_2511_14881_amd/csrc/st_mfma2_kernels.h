@@ -95,6 +95,13 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
         const int i = st.num / spv;
         return ((int)blockIdx.x + i * (int)gridDim.x) * spv + (st.num - i * spv);
     };
+    auto seg_first = [&](const Stage& st) -> int64_t { return p.item_begin + (int64_t)stage_seg(st) * seg_items; };
+    auto in_sample = [&](int64_t first) -> bool {  // the 64-item word at `first` belongs to the first level's sample
+        if (p.samp_role != 2) return false;
+        const uint32_t fw = (uint32_t)(first >> 6), sw = (uint32_t)(p.samp_stride_items >> 6);  // in words: 32 bits do
+        const uint32_t j = fw / sw;
+        return j < (uint32_t)p.samp_segs && fw - j * sw < (uint32_t)(p.samp_seg_items >> 6);
+    };
     auto stage_next = [&](const Stage& st) -> Stage {
         if (!stage_ok(st)) return st;
         if (st.batch + 1 < n_batches) return Stage{st.num, st.batch + 1};
@@ -115,7 +122,7 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
         if (!pair_lane || !stage_ok(st)) return;
         const int g = st.batch * FB + pr_gi;
         if (g >= p.n_groups) return;
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(st) * seg_items) >> 6) + pr_w;
+        const int64_t gw = (seg_first(st) >> 6) + pr_w;
         if (gw * 64 >= item_lim) return;
         const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
@@ -128,9 +135,9 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
         if (!pair_lane) return 0ULL;
         const int g = st.batch * FB + pr_gi;
         if (g >= p.n_groups) return 0ULL;
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(st) * seg_items) >> 6) + pr_w;
+        const int64_t gw = (seg_first(st) >> 6) + pr_w;
         const int64_t first = gw * 64;
-        if (first >= item_lim) return 0ULL;
+        if (first >= item_lim || in_sample(first)) return 0ULL;
         const int64_t left = item_lim - first;
         uint64_t mask = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
 #pragma unroll
@@ -153,7 +160,7 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
                 hi = mp.prow_pack[g][1];
                 nr = (int)((mp.prow_n >> (8 * g)) & 255);
             }
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(cur) * seg_items) >> 6) + pr_w;
+        const int64_t gw = (seg_first(cur) >> 6) + pr_w;
         if (pr_gi < p.n_groups && gw * 64 < item_lim) {
             const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
@@ -272,7 +279,7 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
     int n_carry = 0;  // lane f < FB: entries of filter f in the carry area
     const bool can_carry = n_batches == 1;
     for (bool first = true; stage_ok(cur); first = false) {
-        const int64_t item0 = p.item_begin + (int64_t)stage_seg(cur) * seg_items;
+        const int64_t item0 = seg_first(cur);
         const int g0 = cur.batch * FB;
         const int nf = min(FB, p.n_groups - g0);
         const int slot = R == 1 ? 0 : cur.num % R;

@@ -178,7 +178,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     const int seg_items = p.seg_items;
     const int SW = seg_items >> 6;  // mask words per segment (1, 2, 4 or 8)
     const int spv = p.seg_per_visit;
-    const int64_t item_lim = p.item_end < p.n_items ? p.item_end : p.n_items;
+    const int64_t item_lim = p.samp_role == 1 ? p.n_items : (p.item_end < p.n_items ? p.item_end : p.n_items);
     const int n_seg = (int)((p.item_end - p.item_begin + seg_items - 1) / seg_items);
     const int n_visit = (n_seg + spv - 1) / spv;
     const int n_batches = (p.n_groups + FB - 1) / FB;
@@ -196,6 +196,16 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     auto stage_seg = [&](const Stage& st) {  // segment index in the level (may lie past its end: no items there)
         const int i = st.num / spv;
         return ((int)blockIdx.x + i * (int)gridDim.x) * spv + (st.num - i * spv);
+    };
+    auto seg_first = [&](const Stage& st) -> int64_t {  // first item of the stage's segment
+        const int64_t sg = stage_seg(st);
+        return p.samp_role == 1 ? sg * p.samp_stride_items : p.item_begin + sg * seg_items;
+    };
+    auto in_sample = [&](int64_t first) -> bool {  // role 2: the 64-item word at `first` belongs to the sample
+        if (p.samp_role != 2) return false;
+        const uint32_t fw = (uint32_t)(first >> 6), sw = (uint32_t)(p.samp_stride_items >> 6);  // in words: 32 bits do
+        const uint32_t j = fw / sw;
+        return j < (uint32_t)p.samp_segs && fw - j * sw < (uint32_t)(p.samp_seg_items >> 6);
     };
     auto stage_next = [&](const Stage& st) -> Stage {
         if (!stage_ok(st)) return st;
@@ -217,7 +227,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
         if (!pair_lane || !stage_ok(st)) return;
         const int g = st.batch * FB + pr_gi;
         if (g >= p.n_groups) return;
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(st) * seg_items) >> 6) + pr_w;
+        const int64_t gw = (seg_first(st) >> 6) + pr_w;
         if (gw * 64 >= item_lim) return;
         const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
@@ -243,7 +253,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     auto scale_issue = [&](const Stage& st) {
         pre_sc = pre_sc2 = make_float4(0.f, 0.f, 0.f, 0.f);
         if (!stage_ok(st) || 4 * lane >= seg_items) return;
-        const int64_t i0 = p.item_begin + (int64_t)stage_seg(st) * seg_items + 4 * lane;
+        const int64_t i0 = seg_first(st) + 4 * lane;
         pre_sc = scale_fetch(i0);
         if (!LEAN && seg_items > 256) pre_sc2 = scale_fetch(i0 + 256);
     };
@@ -251,9 +261,9 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
         if (!pair_lane) return 0ULL;
         const int g = st.batch * FB + pr_gi;
         if (g >= p.n_groups) return 0ULL;
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(st) * seg_items) >> 6) + pr_w;
+        const int64_t gw = (seg_first(st) >> 6) + pr_w;
         const int64_t first = gw * 64;
-        if (first >= item_lim) return 0ULL;
+        if (first >= item_lim || in_sample(first)) return 0ULL;
         const int64_t left = item_lim - first;
         uint64_t mask = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
 #pragma unroll
@@ -276,7 +286,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
                 hi = mp.prow_pack[g][1];
                 nr = (int)((mp.prow_n >> (8 * g)) & 255);
             }
-        const int64_t gw = ((p.item_begin + (int64_t)stage_seg(cur) * seg_items) >> 6) + pr_w;
+        const int64_t gw = (seg_first(cur) >> 6) + pr_w;
         if (pr_gi < p.n_groups && gw * 64 < item_lim) {
             const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
@@ -436,7 +446,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
 
     int thr_E = -1000;  // exponent the wavefront's integer bounds were built for (none yet)
     for (bool first = true; stage_ok(cur); first = false) {
-        const int64_t item0 = p.item_begin + (int64_t)stage_seg(cur) * seg_items;
+        const int64_t item0 = seg_first(cur);
         const int g0 = cur.batch * FB;
         const int nf = min(FB, p.n_groups - g0);
         // candidate region: one per visit on the first level (a region then holds the candidates of

@@ -10,7 +10,9 @@
 // last selection notices that case (fewer than K keys at or above the threshold in the whole
 // corpus) and recomputes the query exactly, so the result is exact either way (optimistic_keep).
 // Levels grow geometrically so that the expected number of admitted candidates per
-// (workgroup, query) region stays at a quarter of the region's capacity.
+// (workgroup, query) region stays at a quarter of the region's capacity.  (The plan gives sizes;
+// whether the first level's items are a prefix or segments spread over the corpus is the
+// launcher's choice.)
 #pragma once
 #include <stdint.h>
 #include <stddef.h>

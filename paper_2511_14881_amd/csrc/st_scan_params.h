@@ -36,6 +36,13 @@ struct ScanParams {
     int32_t use_tau;
     const uint64_t* tau;         // [B][kTauParts]
     int32_t tau_parts;           // entries of tau in use per query
+    // Sample mode (samp_role != 0): the first level does not scan a prefix of the corpus but
+    // samp_segs segments of samp_seg_items items spread evenly over it, segment s starting at item
+    // s * samp_stride_items -- what its selection learns about a query's scores then does not
+    // depend on trends along the item order.  Role 1: this launch scans the sample; role 2: it
+    // scans [item_begin, item_end) and leaves the sample's words out.
+    int64_t samp_stride_items;
+    int32_t samp_segs, samp_seg_items, samp_role;
     // output regions
     uint64_t* cand;              // [B][G][cap]
     uint32_t* cnt;               // [B][G]

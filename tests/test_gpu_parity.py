@@ -411,6 +411,27 @@ def test_best_items_at_the_head_of_the_corpus_defeat_the_tight_threshold_and_tak
         assert ids[0, 0] == 0 and ids[1, 0] == n - 1 and (count == K).all()
 
 
+def test_scores_along_a_trend_keep_the_fast_path_where_the_first_level_is_a_sample():
+    # Large batches served by the 8-wavefront MFMA scan alone take their first level as segments
+    # spread evenly over the corpus, not as a prefix.  Here the item scales fall twentyfold along
+    # the item order (a corpus ordered by age or popularity), so the best items of every query
+    # crowd the head of the corpus: a prefix holds far more of the final top-K than its share, and
+    # a threshold drawn from it would be too tight.  The sample sees the trend like the rest of
+    # the corpus does, and no query needs the slow exact path.
+    n, d, B, K = 300_000, 256, 256, 500
+    summary = st.st_search_host_plan(n, d, B, 1, K, 64, 2, np.zeros(0, np.uint64), np.zeros(B + 1, np.int64))
+    assert summary["waves"] == 8 and summary["levels"] == 2 and summary["seed_pass"] == 0
+    w = ragged_workload(11, n, d, B, 10, 3, 64, 2)
+    w.item_scale = (4.0 * torch.exp(-3.0 * torch.arange(n, dtype=torch.float32) / n)).contiguous()
+    w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
+    ids, _, count = check_search(w, K, queries=range(0, B, 16), label="scores along a trend, sampled first level",
+                                 slow_path=([], list(range(B))))
+    assert (count == K).all()
+    # the premise: the prefix a plain first level would scan holds well over its share of the results
+    share = 65536 / n
+    assert np.mean(ids[::16] < 65536) > 2.5 * share
+
+
 def test_best_items_inside_the_seed_prefix_defeat_its_tight_threshold_and_take_the_exact_slow_path():
     # Small batches take their first threshold from the seed pass over the first 32768 items, and
     # that threshold too is tighter than the K-th best of the prefix.  Here every item of the prefix
