@@ -1097,6 +1097,10 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
             up.dst = (int32_t*)(ws + L.meta);
             up.words = (int32_t)(blob.bytes() / 4);
             up.img_q = nullptr;
+            {  // the words of the pass, spread evenly over the corpus (whole words only)
+                const int64_t pass_words = L_.end / 64, all_words = n_items / 64;
+                up.word_stride = (L_.end % 64 == 0 && pass_words > 0 && all_words >= 2 * pass_words) ? (int32_t)(all_words / pass_words) : 1;
+            }
             if (set_mfma.n) {  // the seed pass stages the scorer's query image as well
                 up.img_q = mp.img_q;
                 up.img_sq = mp.img_sq;

@@ -1082,6 +1082,11 @@ struct SeedUpload {
     int32_t* img_qrow;         // [q_split][rows_local]  global query row or -1 (padding)
     const int32_t* blk_row;    // [n_blocks * 16] query row of every block row, pinned host memory
     int32_t n_blocks, q_split, rows_local;
+    // The 64-item words of the seed pass are spread evenly over the corpus: word i of the pass is
+    // word i * word_stride of the corpus (1: a prefix), and the slices take the pass's words in
+    // turn.  What the pass learns about a query's scores then does not depend on trends along the
+    // item order, and every slice sees what the others see.
+    int32_t word_stride;
 };
 
 // D16 = d / 16 for d in {64, 128, 256} (item rows staged in registers, two items per thread in
@@ -1145,6 +1150,12 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
             }
         }
     }
+    const int64_t ws = up.word_stride > 1 ? up.word_stride : 1;
+    // Place in the corpus of position l of this slice.  The pass's words are dealt out to the slices
+    // in turn (word j of slice `part` is word j * parts + part of the pass), so that every slice is
+    // itself spread over the whole corpus.
+    auto corpus_word = [&](int64_t slice_word) -> int64_t { return (slice_word * parts + part) * ws; };
+    auto corpus_item = [&](int64_t l) -> int64_t { return (corpus_word(l >> 6) << 6) | (l & 63); };
     const int64_t n_all = seed_items < sp.n_items ? seed_items : sp.n_items;
     const int64_t part_items = seed_items / parts;  // whole tiles
     const int64_t begin = part * part_items;
@@ -1165,7 +1176,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     if (tid < n_words) {
         const int64_t left = n - (int64_t)tid * 64;
         mword = left >= 64 ? ~0ULL : ((1ULL << left) - 1ULL);
-        const int64_t gw = (begin >> 6) + tid;
+        const int64_t gw = corpus_word(tid);
         const uint64_t* base = sp.bloom + ((gw >> 4) * (int64_t)sp.m_bits) * kTileWords + (gw & 15);
         const int* qr = p.q_prow + q * (kSeedRows + 1);
         const int nr = qr[kSeedRows];
@@ -1213,7 +1224,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     // scores: one lane per passing item
     if (D16 == 0) {
         for (uint32_t e = tid; e < total; e += NT) {
-            const int64_t item = begin + (in_lds ? (int64_t)slist[e] : (int64_t)glist[e]);
+            const int64_t item = corpus_item(in_lds ? (int64_t)slist[e] : (int64_t)glist[e]);
             const float sc = pair_score(sp, q, sp.items + item * sp.d, sp.iscale[item]);
             const uint64_t key = make_key(sc, (uint32_t)item);
             if (in_lds) s_keys[e] = key;
@@ -1230,7 +1241,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
             for (int u = 0; u < 2; ++u) {
                 const uint32_t e = e0 + u * NT;
                 const uint32_t ec = e < total ? e : e0;
-                item[u] = begin + (in_lds ? (int64_t)slist[ec] : (int64_t)glist[ec]);
+                item[u] = corpus_item(in_lds ? (int64_t)slist[ec] : (int64_t)glist[ec]);
                 const int4* rp = reinterpret_cast<const int4*>(sp.items + item[u] * (DD * 16));
 #pragma unroll
                 for (int c = 0; c < DD; ++c) ra[u][c] = rp[c];

@@ -411,16 +411,19 @@ def test_best_items_at_the_head_of_the_corpus_defeat_the_tight_threshold_and_tak
         assert ids[0, 0] == 0 and ids[1, 0] == n - 1 and (count == K).all()
 
 
-def test_scores_along_a_trend_keep_the_fast_path_where_the_first_level_is_a_sample():
+@pytest.mark.parametrize("d,B,seeded", [(256, 256, False), (64, 16, True)])
+def test_scores_along_a_trend_keep_the_fast_path_where_the_first_level_is_a_sample(d, B, seeded):
     # Large batches served by the 8-wavefront MFMA scan alone take their first level as segments
-    # spread evenly over the corpus, not as a prefix.  Here the item scales fall twentyfold along
-    # the item order (a corpus ordered by age or popularity), so the best items of every query
-    # crowd the head of the corpus: a prefix holds far more of the final top-K than its share, and
-    # a threshold drawn from it would be too tight.  The sample sees the trend like the rest of
-    # the corpus does, and no query needs the slow exact path.
-    n, d, B, K = 300_000, 256, 256, 500
+    # spread evenly over the corpus, not as a prefix, and so does the seed pass of small batches
+    # with its tiles.  Here the item scales fall twentyfold along the item order (a corpus ordered
+    # by age or popularity), so the best items of every query crowd the head of the corpus: a
+    # prefix holds far more of the final top-K than its share, and a threshold drawn from it would
+    # be too tight.  The sample sees the trend like the rest of the corpus does, and no query
+    # needs the slow exact path.
+    n, K = 300_000, 500
     summary = st.st_search_host_plan(n, d, B, 1, K, 64, 2, np.zeros(0, np.uint64), np.zeros(B + 1, np.int64))
-    assert summary["waves"] == 8 and summary["levels"] == 2 and summary["seed_pass"] == 0
+    assert summary["levels"] == 2 and summary["seed_pass"] == (1 if seeded else 0)
+    assert seeded or summary["waves"] == 8
     w = ragged_workload(11, n, d, B, 10, 3, 64, 2)
     w.item_scale = (4.0 * torch.exp(-3.0 * torch.arange(n, dtype=torch.float32) / n)).contiguous()
     w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
@@ -428,28 +431,38 @@ def test_scores_along_a_trend_keep_the_fast_path_where_the_first_level_is_a_samp
                                  slow_path=([], list(range(B))))
     assert (count == K).all()
     # the premise: the prefix a plain first level would scan holds well over its share of the results
-    share = 65536 / n
-    assert np.mean(ids[::16] < 65536) > 2.5 * share
+    prefix = 32768 if seeded else 65536
+    assert np.mean(ids[::16] < prefix) > 2.5 * prefix / n
 
 
-def test_best_items_inside_the_seed_prefix_defeat_its_tight_threshold_and_take_the_exact_slow_path():
-    # Small batches take their first threshold from the seed pass over the first 32768 items, and
-    # that threshold too is tighter than the K-th best of the prefix.  Here every item of the prefix
-    # carries a scale sixteen times that of the rest, so the K best of the corpus all lie in the
-    # prefix, spread evenly over its slices: the threshold lands among them, fewer than K keys of
-    # the corpus reach it, and the last selection recomputes every query exactly.
+def test_hot_items_exactly_where_the_seed_pass_looks_defeat_it_and_take_the_exact_slow_path():
+    # Small batches take their first threshold from the seed pass over 512 words of 64 items spread
+    # evenly over the corpus, and that threshold too is tighter than the K-th best of what the pass
+    # has seen.  Here exactly the words the pass looks at carry a scale sixteen times that of the
+    # rest (a period in the corpus that matches the stride of the sample), so the K best of the
+    # corpus all lie inside the sample: the threshold lands among them, fewer than K keys of the
+    # corpus reach it, and the last selection recomputes every query exactly.  A block of hot
+    # items anywhere else (second call) is seen in proportion and stays on the fast path.
     n, d, B, K = 300_000, 64, 6, 500
     levels, _, _ = st.st_search_plan(n, B, K)
     assert levels[0, 2] == 0 and len(levels) == 2  # seed pass, then one level over the corpus
+    pass_words = int(levels[0, 1]) // 64
+    stride = (n // 64) // pass_words
+    assert stride >= 2
     w = ragged_workload(10, n, d, B, 10, 3, 64, 2)
+    w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
+    word = torch.arange(n) // 64
+    sampled = (word % stride == 0) & (word // stride < pass_words)
+    w.item_scale = torch.where(sampled, torch.tensor(4.0), torch.tensor(0.25)).contiguous()
+    for path in (0, 1):
+        ids, _, count = check_search(w, K, path=path, label="hot items at the sampled words",
+                                     slow_path=(list(range(B)), []))
+        assert (count == K).all() and sampled.numpy()[ids].all()
     scale = torch.full((n,), 0.25, dtype=torch.float32)
     scale[:32768] = 4.0
     w.item_scale = scale.contiguous()
-    w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
-    for path in (0, 1):
-        ids, _, count = check_search(w, K, path=path, label="top items inside the seed prefix",
-                                     slow_path=(list(range(B)), []))
-        assert (count == K).all() and (ids < 32768).all()
+    ids, _, count = check_search(w, K, label="a block of hot items", slow_path=([], list(range(B))))
+    assert (count == K).all() and (ids < 32768).all()
 
 
 @pytest.mark.parametrize("B", [16, 48])
@@ -568,15 +581,20 @@ def test_error_paths_return_codes():
 
 
 def test_overflow_in_the_level_after_the_seed_pass_is_caught():
-    # The seed pass looks at the first 32768 items only.  Here no item of that prefix passes the
-    # filter of the even queries, so their threshold stays open and the one level after the seed
-    # pass admits a whole dense block of passing items: far more than the candidate regions hold.
-    # Those queries must be flagged and recomputed by the slow exact path, not silently truncated.
+    # The seed pass looks at 512 words of 64 items spread over the corpus only.  Here no item of
+    # those words passes the filter of the even queries, so their threshold stays open and the one
+    # level after the seed pass admits a whole dense block of passing items: far more than the
+    # candidate regions hold.  Those queries must be flagged and recomputed by the slow exact path,
+    # not silently truncated.
     n, d, B, K = 300_000, 64, 6, 50
     w = ragged_workload(91, n, d, B, 30, 3, 128, 3)
     off = np.arange(n + 1, dtype=np.int64)
     ids = np.full(n, 2000, dtype=np.int64)
     ids[100_000:160_000] = 1000
+    levels, _, _ = st.st_search_plan(n, B, K)
+    assert levels[0, 2] == 0  # seed pass
+    stride = (n // 64) // (int(levels[0, 1]) // 64)
+    ids[(np.arange(n) // 64) % stride == 0] = 2000  # nothing the pass looks at passes filter 1000
     filters = [[1000] if b % 2 == 0 else [2000] for b in range(B)]
     w.feat_offsets, w.feat_ids = torch.from_numpy(off), torch.from_numpy(ids)
     w.filt_ids = np.array([x for f in filters for x in f], dtype=np.uint64)
