@@ -1721,13 +1721,19 @@ int st_value_model(const float* dev_task_scores, int64_t n, int32_t n_tasks, con
     }
     if (depth != 1) return fail(ST_EINVAL, "formula leaves %d results", depth);
     if (n == 0) return ST_OK;
-    const int64_t quads = (n + st::kVmItems - 1) / st::kVmItems;
-    const unsigned grid = (unsigned)std::min<int64_t>((quads + st::kVmThreads - 1) / st::kVmThreads, st::kComputeUnits * 16);
+    const int64_t sets = (n + st::kVmItems - 1) / st::kVmItems;  // items of one thread
+    const unsigned grid = (unsigned)std::min<int64_t>((sets + st::kVmThreads - 1) / st::kVmThreads, st::kComputeUnits * 16);
     {
+        static std::atomic<bool> lds_set{false};  // (setting the attribute twice is harmless)
+        if (!lds_set.load(std::memory_order_acquire)) {
+            ST_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&st::value_model_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)st::vm_lds_bytes(st::kVmDepth)));
+            lds_set.store(true, std::memory_order_release);
+        }
         TimedLaunch t(0, (hipStream_t)hip_stream);
         hipLaunchKernelGGL(st::value_model_kernel, dim3(grid), dim3(st::kVmThreads),
-                           (size_t)deepest * st::kVmThreads * sizeof(float4), (hipStream_t)hip_stream,
-                           dev_task_scores, n, n_tasks, prog, dev_out);
+                           st::vm_lds_bytes(deepest), (hipStream_t)hip_stream,
+                           dev_task_scores, n, n_tasks, prog, st::vm_lds_slots(deepest), dev_out);
     }
     ST_HIP(hipGetLastError());
     return ST_OK;
