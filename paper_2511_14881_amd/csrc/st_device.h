@@ -78,4 +78,76 @@ __device__ inline uint64_t ballot(bool pred) { return __builtin_amdgcn_ballot_w6
 
 __device__ inline int lane_id() { return (int)(threadIdx.x & 63); }
 
+// ---- cross-lane steps with data-parallel register moves.  A shuffle (__shfl*) goes through the
+// LDS pipe and a chain of six dependent ones costs well over a thousand cycles; a move that reads
+// another lane's register directly costs a few.  The hardware offers them inside rows of 16 lanes
+// (shift right by n: lane l reads lane l - n) and as broadcasts of a row's last lane into the rows
+// after it, which is all a scan or a reduction over the wavefront needs.
+
+// Value of lane l - N for the lanes whose source lies in their own row of 16; 0 for the others.
+template <int N>
+__device__ inline uint32_t row_shr(uint32_t v)
+{
+    static_assert(N >= 1 && N <= 15, "shift within a row of 16 lanes");
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x110 + N, 0xF, 0xF, false);
+}
+// Lane 15 of rows 0 and 2 into every lane of rows 1 and 3 (0 elsewhere); lane 31 into rows 2 and 3.
+__device__ inline uint32_t row_bcast15(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x142, 0xA, 0xF, false); }
+__device__ inline uint32_t row_bcast31(uint32_t v) { return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, 0x143, 0xC, 0xF, false); }
+
+// Inclusive prefix sum over the wavefront (lane l: sum of lanes 0 .. l).
+__device__ inline uint32_t wave_scan_add(uint32_t v)
+{
+    v += row_shr<1>(v);
+    v += row_shr<2>(v);
+    v += row_shr<4>(v);
+    v += row_shr<8>(v);
+    v += row_bcast15(v);
+    v += row_bcast31(v);
+    return v;
+}
+// Maximum over the wavefront, delivered in lane 63 (overlapping windows do no harm to a maximum;
+// lanes without a source take 0).
+__device__ inline uint32_t wave_max_u32(uint32_t v)
+{
+    uint32_t o;
+    o = row_shr<1>(v); v = o > v ? o : v;
+    o = row_shr<2>(v); v = o > v ? o : v;
+    o = row_shr<4>(v); v = o > v ? o : v;
+    o = row_shr<8>(v); v = o > v ? o : v;
+    o = row_bcast15(v); v = o > v ? o : v;
+    o = row_bcast31(v); v = o > v ? o : v;
+    return v;
+}
+// Maximum of a 64-bit value over the wavefront, delivered in lane 63.
+__device__ inline uint64_t wave_max_u64(uint64_t v)
+{
+#define ST_MAX64_STEP(MOVE)                                                      \
+    {                                                                            \
+        const uint64_t o = ((uint64_t)MOVE((uint32_t)(v >> 32)) << 32) | MOVE((uint32_t)v); \
+        v = o > v ? o : v;                                                       \
+    }
+    ST_MAX64_STEP(row_shr<1>)
+    ST_MAX64_STEP(row_shr<2>)
+    ST_MAX64_STEP(row_shr<4>)
+    ST_MAX64_STEP(row_shr<8>)
+    ST_MAX64_STEP(row_bcast15)
+    ST_MAX64_STEP(row_bcast31)
+#undef ST_MAX64_STEP
+    return v;
+}
+// Bitwise OR over the wavefront, delivered in lane 63.
+__device__ inline uint32_t wave_or_u32(uint32_t v)
+{
+    v |= row_shr<1>(v);
+    v |= row_shr<2>(v);
+    v |= row_shr<4>(v);
+    v |= row_shr<8>(v);
+    v |= row_bcast15(v);
+    v |= row_bcast31(v);
+    return v;
+}
+// A value of lane `src` (the same in every lane) for all lanes.
+__device__ inline uint32_t lane_value(uint32_t v, int src) { return (uint32_t)__builtin_amdgcn_readlane((int)v, src); }
+
 }  // namespace st

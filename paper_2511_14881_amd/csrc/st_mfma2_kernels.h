@@ -297,10 +297,10 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
         const bool flush = !can_carry || !stage_ok(nxt);
         const int c = __popcll(mask);
         int incl = c;
-        for (int o = 1; o < SW; o <<= 1) {
-            const int v = __shfl_up(incl, o);
-            if (pr_w >= o) incl += v;
-        }
+        // (the words of a filter sit in neighbouring lanes of one 16-lane row: register moves, no shuffles)
+        if (SW > 1) { const int v = (int)row_shr<1>((uint32_t)incl); if (pr_w >= 1) incl += v; }
+        if (SW > 2) { const int v = (int)row_shr<2>((uint32_t)incl); if (pr_w >= 2) incl += v; }
+        if (SW > 4) { const int v = (int)row_shr<4>((uint32_t)incl); if (pr_w >= 4) incl += v; }
         {
             int pos = incl - c;
             uint8_t* list = s_list + pr_gi * seg_stride;
@@ -318,10 +318,10 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
         const int gtot = gnc + gcur;
         const int gunits = flush ? (gtot + 15) >> 4 : gtot >> 4;
         int ucum = gunits;
-        for (int o = 1; o < FB; o <<= 1) {
-            const int v = __shfl_up(ucum, o);
-            if (lane >= o) ucum += v;
-        }
+        static_assert(FB == 8, "three steps cover the filters of a batch");
+        { const int v = (int)row_shr<1>((uint32_t)ucum); if (lane >= 1) ucum += v; }
+        { const int v = (int)row_shr<2>((uint32_t)ucum); if (lane >= 2) ucum += v; }
+        { const int v = (int)row_shr<4>((uint32_t)ucum); if (lane >= 4) ucum += v; }
         const int n_units = __builtin_amdgcn_readlane(ucum, FB - 1);
         const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
         const int gnblk = lane < nf ? s_gnblk[g0 + lane] : 0;

@@ -466,10 +466,10 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
         prefetch_issue(nxt);
         const int c = __popcll(mask);
         int incl = c;  // running count over the words of my filter
-        for (int o = 1; o < SW; o <<= 1) {
-            const int v = __shfl_up(incl, o);
-            if (pr_w >= o) incl += v;
-        }
+        // (the words of a filter sit in neighbouring lanes of one 16-lane row: register moves, no shuffles)
+        if (SW > 1) { const int v = (int)row_shr<1>((uint32_t)incl); if (pr_w >= 1) incl += v; }
+        if (SW > 2) { const int v = (int)row_shr<2>((uint32_t)incl); if (pr_w >= 2) incl += v; }
+        if (SW > 4) { const int v = (int)row_shr<4>((uint32_t)incl); if (pr_w >= 4) incl += v; }
         {
             int pos = incl - c;
             uint8_t* list = s_list + pr_gi * seg_stride;
@@ -487,10 +487,10 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
         const int glow = lane < nf ? low_words : 0;
         const int gunits = (gcount + 15) >> 4;
         int ucum = gunits;  // inclusive over filters
-        for (int o = 1; o < FB; o <<= 1) {
-            const int v = __shfl_up(ucum, o);
-            if (lane >= o) ucum += v;
-        }
+        static_assert(FB == 8, "three steps cover the filters of a batch");
+        { const int v = (int)row_shr<1>((uint32_t)ucum); if (lane >= 1) ucum += v; }
+        { const int v = (int)row_shr<2>((uint32_t)ucum); if (lane >= 2) ucum += v; }
+        { const int v = (int)row_shr<4>((uint32_t)ucum); if (lane >= 4) ucum += v; }
         const int n_units = __builtin_amdgcn_readlane(ucum, FB - 1);
         // first local query row and local block count of filter gi -> lane gi
         const int glrow = lane < nf ? s_glrow[g0 + lane] : 0;
@@ -513,7 +513,9 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
             if (!WEIGHTED && n_units > 0) {
                 float smax = fmaxf(fmaxf(sc4.x, sc4.y), fmaxf(sc4.z, sc4.w));
                 smax = fmaxf(smax, fmaxf(fmaxf(sc4b.x, sc4b.y), fmaxf(sc4b.z, sc4b.w)));
-                for (int o = 32; o > 0; o >>= 1) smax = fmaxf(smax, __shfl_xor(smax, o));
+                // the largest of the wavefront: scales are positive, so their bit patterns order as they
+                // do (a negative or non-finite scale comes out on top and switches the cull off below)
+                smax = __uint_as_float(lane_value(wave_max_u32(__float_as_uint(smax)), 63));
                 int E = 0;
                 bool cull = smax > 0.0f && smax < __builtin_inff();
                 if (cull) {

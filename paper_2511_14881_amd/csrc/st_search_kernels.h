@@ -266,11 +266,7 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
                 const int l = tid;
                 uint32_t h[4], sum = 0;
                 for (int j = 0; j < 4; ++j) { h[j] = s_hist[255 - 4 * l - j]; sum += h[j]; }
-                uint32_t incl = sum;
-                for (int o = 1; o < 64; o <<= 1) {
-                    const uint32_t v = __shfl_up(incl, o);
-                    if (l >= o) incl += v;
-                }
+                const uint32_t incl = wave_scan_add(sum);
                 uint32_t before = incl - sum;  // keys in digits above this lane's four
                 if (before < want && want <= incl) {
                     for (int j = 0; j < 4; ++j) {
@@ -455,12 +451,8 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
             kr[j] = i < n ? keys[i] : 0ULL;  // 0 is below every real key
             if (i < n) diff |= kr[j] ^ k0;
         }
-        uint32_t dl = (uint32_t)diff, dh = (uint32_t)(diff >> 32);
-        for (int o = 32; o > 0; o >>= 1) {
-            dl |= __shfl_xor(dl, o);
-            dh |= __shfl_xor(dh, o);
-        }
-        if (lane == 0) s_red[wv] = ((uint64_t)dh << 32) | dl;
+        const uint32_t dl = wave_or_u32((uint32_t)diff), dh = wave_or_u32((uint32_t)(diff >> 32));
+        if (lane == 63) s_red[wv] = ((uint64_t)dh << 32) | dl;
         for (int i = tid; i < 3 * 256; i += nt) s_hist3[i] = 0;
         if (tid == 0) s_misc[2] = 0;
         __syncthreads();
@@ -485,11 +477,7 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
             uint32_t h[4], sum = 0;
 #pragma unroll
             for (int j = 0; j < 4; ++j) { h[j] = hist[255 - 4 * lane - j]; sum += h[j]; }
-            uint32_t incl = sum;
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t v = __shfl_up(incl, o);
-                if (lane >= o) incl += v;
-            }
+            const uint32_t incl = wave_scan_add(sum);
             uint32_t before = incl - sum;
             const bool mine = before < want && want <= incl;
             uint32_t digit = 0, rest = 0, whole = 0;
@@ -505,9 +493,9 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
                 }
             }
             const int src = __ffsll((long long)ballot(mine)) - 1;  // exactly one lane
-            digit = __shfl(digit, src);
-            rest = __shfl(rest, src);
-            whole = __shfl(whole, src);
+            digit = lane_value(digit, src);
+            rest = lane_value(rest, src);
+            whole = lane_value(whole, src);
             prefix |= (uint64_t)digit << shift;
             prefix_mask |= 0xFFULL << shift;
             want = rest;
@@ -527,14 +515,8 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
         for (int i = K + tid; i < P; i += nt) sorted[i] = 0ULL;
         if (!want_sorted) {
             // threshold = smallest collected key: wavefront minimum, then across wavefronts
-            uint32_t ll = (uint32_t)low, lh = (uint32_t)(low >> 32);
-            for (int o = 32; o > 0; o >>= 1) {
-                const uint32_t ol = __shfl_xor(ll, o), oh = __shfl_xor(lh, o);
-                const bool less = oh < lh || (oh == lh && ol < ll);
-                ll = less ? ol : ll;
-                lh = less ? oh : lh;
-            }
-            if (lane == 0) s_red[16 + wv] = ((uint64_t)lh << 32) | ll;
+            const uint64_t wave_low = ~wave_max_u64(~low);  // (lanes without a key hold ~0)
+            if (lane == 63) s_red[16 + wv] = wave_low;
         }
         __syncthreads();
         if (!want_sorted) {
@@ -546,7 +528,8 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
     }
     if (P <= nt && P > 256) {
         // One key per thread, bitonic network (descending; the padding zeros sink to the end).  The
-        // exchange partner sits in the same wavefront for distances below 64 (two 32-bit shuffles),
+        // exchange partner sits in the same wavefront for distances below 64 (two 32-bit shuffles:
+        // exchanges by register moves measured slower here, the independent shuffles of a stage overlap),
         // beyond that the keys go through LDS with one barrier per stage (two buffers alternate).
         // 45 stages for 512 keys, 6 of them through LDS: a rank sort reads every key in every
         // thread instead, 2 MB of LDS traffic for 512 keys.
@@ -787,11 +770,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
             if (w < R) mine += min(cq[w], (uint32_t)p.cap);
         }
     }
-    uint32_t incl = mine;
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t v = __shfl_up(incl, o);
-        if (lane >= o) incl += v;
-    }
+    const uint32_t incl = wave_scan_add(mine);
     if (lane == 63) s_wsum[wv] = incl;
     __syncthreads();
     uint32_t wbase = 0, all = 0;
@@ -931,11 +910,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectParams p)
             uint32_t h[kPer], sum = 0;
 #pragma unroll
             for (int j = 0; j < kPer; ++j) { h[j] = hist[kBins - 1 - kPer * tid - j]; sum += h[j]; }
-            uint32_t inc = sum;
-            for (int o = 1; o < 64; o <<= 1) {
-                const uint32_t v = __shfl_up(inc, o);
-                if (lane >= o) inc += v;
-            }
+            const uint32_t inc = wave_scan_add(sum);
             if (lane == 63) s_wsum[wv] = inc;
             __syncthreads();
             uint32_t base = 0;
@@ -1055,6 +1030,71 @@ constexpr int kSeedThreads = 512;
 constexpr int kSeedRows = 8;       // signature rows per query in the seed kernel's row table
 constexpr int kSeedMaxParts = kTauParts;
 static_assert(kSeedItems / 64 <= kSeedThreads, "one Bloom word per thread");
+
+// A threshold from the rank-th best of n keys in LDS, for a small rank, computed in registers
+// (one barrier, no histogram passes: the radix selection costs about 5 us whatever the rank).
+// It works on the keys' score halves.  A round takes the largest score below that of the round
+// before, so after `rank` rounds at least `rank` keys lie at or above the score found.  Every
+// wavefront runs the rounds over its share of the keys and leaves its `rank` best distinct
+// scores in LDS; the first wavefront then runs them once more over those, and returns the
+// smallest key with the score it ends on -- at or below the rank-th best key, equal to it up to
+// the item id unless scores tie among the best.  Fewer distinct scores than `rank`: the smallest
+// score if there are `rank` keys at all, else 0 (no threshold).  For workgroups of at most 8
+// wavefronts and n <= 1024 keys per wavefront; the result is valid in the first wavefront.
+constexpr int kSmallRank = 8;
+constexpr int kSmallRankPerLane = 16;
+
+__device__ inline uint64_t wg_threshold_small(const uint64_t* keys, int n, int rank, uint32_t* s_best /*[8][kSmallRank]*/)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6, nw = blockDim.x >> 6;
+    // rounds over the values in kr[0 .. nj): the distinct maxima in falling order, `found` of them
+    auto rounds = [&](const uint32_t (&kr)[kSmallRankPerLane], int nj, uint32_t (&best)[kSmallRank]) -> int {
+        uint32_t bound = 0xFFFFFFFFu;  // exclusive; above every score half
+        int found = 0;
+#pragma unroll
+        for (int r = 0; r < kSmallRank; ++r) best[r] = 0u;
+#pragma unroll
+        for (int r = 0; r < kSmallRank; ++r) {
+            if (r >= rank) break;
+            uint32_t m = 0;
+#pragma unroll
+            for (int j = 0; j < kSmallRankPerLane; ++j) {
+                if (j >= nj) break;  // (the same in every lane)
+                const uint32_t c = kr[j] < bound ? kr[j] : 0u;
+                m = c > m ? c : m;
+            }
+            m = lane_value(wave_max_u32(m), 63);
+            if (m == 0) break;
+            best[r] = m;
+            bound = m;
+            ++found;
+        }
+        return found;
+    };
+    uint32_t kr[kSmallRankPerLane], best[kSmallRank];
+    const int nj = (n + 64 * nw - 1) / (64 * nw);  // keys per lane, at most kSmallRankPerLane
+#pragma unroll
+    for (int j = 0; j < kSmallRankPerLane; ++j) {
+        const int i = lane + 64 * (wv + nw * j);
+        kr[j] = (j < nj && i < n) ? (uint32_t)(keys[i] >> 32) : 0u;  // (score halves are never 0)
+    }
+    (void)rounds(kr, nj, best);
+#pragma unroll
+    for (int r = 0; r < kSmallRank; ++r)
+        if (lane == r) s_best[wv * kSmallRank + r] = best[r];
+    __syncthreads();
+    uint64_t kth = 0;
+    if (wv == 0) {
+        kr[0] = lane < nw * kSmallRank ? s_best[lane] : 0u;
+        const int found = rounds(kr, 1, best);
+        uint32_t last = 0;
+#pragma unroll
+        for (int r = 0; r < kSmallRank; ++r)
+            if (r < found) last = best[r];
+        if (found == rank || (found > 0 && n >= rank)) kth = (uint64_t)last << 32;
+    }
+    return kth;
+}
 
 // Slices per query: enough workgroups to occupy the chip, whole 1024-item tiles per slice.
 inline int seed_parts(int batch, int k_pad)
@@ -1192,11 +1232,7 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
         }
     }
     const uint32_t mine = (uint32_t)__popcll(mword);
-    uint32_t incl = mine;
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t v = __shfl_up(incl, o);
-        if (lane >= o) incl += v;
-    }
+    const uint32_t incl = wave_scan_add(mine);
     if (lane == 63) s_wsum[wv] = incl;
     __syncthreads();
     uint32_t wbase = 0, total = 0;
@@ -1277,11 +1313,16 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     // key of the prefix: a valid admission threshold for keep = K, and for a smaller keep the
     // tighter one the schedule counts on (0 = this slice has too few passing items: no threshold).
     // Nothing else is carried over: the level after the seed pass scans the prefix again.
+    // (Small ranks over few keys -- the usual case -- take the one-wavefront form, whose value may lie
+    // below the rank-th best key by the ties in its score: still a valid threshold.)
     const int rank = (p.keep + parts - 1) / parts;
     int rank_pad = 1;
     while (rank_pad < rank) rank_pad <<= 1;
     uint64_t kth = 0;
-    if (in_lds) {
+    static_assert(NT / 64 * kSmallRankPerLane * 64 >= kLdsKeys, "every count of keys that fits LDS fits the registers of the small form");
+    if (in_lds && rank <= kSmallRank) {
+        kth = wg_threshold_small(s_keys, (int)total, rank, reinterpret_cast<uint32_t*>(s_red));  // (thread 0 publishes it)
+    } else if (in_lds) {
         (void)lds_topk(s_keys, (int)total, rank, s_sorted, rank_pad, s_hist, s_misc, s_red, false, kth);
     } else {
         uint64_t* sorted = gpart + (int64_t)part * pstride;  // K <= pstride entries of scratch
