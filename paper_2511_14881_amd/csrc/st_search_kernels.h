@@ -104,18 +104,20 @@ __global__ __launch_bounds__(kScanThreads) void scan_wavedot_kernel(ScanParams p
             for (int gi = wave; gi < nf; gi += kScanThreads / 64) {
                 uint64_t mask = lane < seg_words ? s_mask[gi][lane] : 0ULL;
                 const int c = __popcll(mask);
+                // (the words of a tile sit in the first 16 lanes: one row, register moves)
+                static_assert(kTileWords == 16, "the prefix sum below covers one row of 16 lanes");
                 int incl = c;
-                for (int o = 1; o < kTileWords; o <<= 1) {
-                    const int v = __shfl_up(incl, o);
-                    if (lane >= o) incl += v;
-                }
+                incl += (int)row_shr<1>((uint32_t)incl);
+                incl += (int)row_shr<2>((uint32_t)incl);
+                incl += (int)row_shr<4>((uint32_t)incl);
+                incl += (int)row_shr<8>((uint32_t)incl);
                 int pos = incl - c;
                 while (mask) {
                     const int b = __ffsll((long long)mask) - 1;
                     mask &= mask - 1;
                     s_list[gi][pos++] = (uint16_t)(lane * 64 + b);
                 }
-                const int total = __shfl(incl, kTileWords - 1);
+                const int total = (int)lane_value((uint32_t)incl, kTileWords - 1);
                 if (lane == 0) s_listcnt[gi] = total;
             }
             __syncthreads();
@@ -237,12 +239,9 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
             lo = key < lo ? key : lo;
             hi = key > hi ? key : hi;
         });
-        for (int o = 32; o > 0; o >>= 1) {
-            const uint64_t l2 = __shfl_xor((unsigned long long)lo, o), h2 = __shfl_xor((unsigned long long)hi, o);
-            lo = l2 < lo ? l2 : lo;
-            hi = h2 > hi ? h2 : hi;
-        }
-        if ((tid & 63) == 0) { s_red[(tid >> 6) * 2] = lo; s_red[(tid >> 6) * 2 + 1] = hi; }
+        lo = ~wave_max_u64(~lo);  // (both in lane 63)
+        hi = wave_max_u64(hi);
+        if ((tid & 63) == 63) { s_red[(tid >> 6) * 2] = lo; s_red[(tid >> 6) * 2 + 1] = hi; }
         __syncthreads();
         for (int w = 0; w < (nt >> 6); ++w) {
             const uint64_t l2 = s_red[2 * w], h2 = s_red[2 * w + 1];
@@ -303,11 +302,8 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
     __syncthreads();
     if (kth_out) {
         // the K-th best key is the smallest one kept (keys are distinct), when there are K of them
-        for (int o = 32; o > 0; o >>= 1) {
-            const uint64_t l2 = __shfl_xor((unsigned long long)low, o);
-            low = l2 < low ? l2 : low;
-        }
-        if ((tid & 63) == 0) s_red[tid >> 6] = low;
+        low = ~wave_max_u64(~low);  // (in lane 63)
+        if ((tid & 63) == 63) s_red[tid >> 6] = low;
         __syncthreads();
         for (int w = 0; w < (nt >> 6); ++w) low = s_red[w] < low ? s_red[w] : low;
         *kth_out = n_out == K ? low : 0ULL;
