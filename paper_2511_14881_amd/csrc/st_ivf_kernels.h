@@ -252,10 +252,7 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
     }
     // exclusive prefix sum of the word counts over the workgroup
     uint32_t incl = words;
-    for (int o = 1; o < 64; o <<= 1) {
-        const uint32_t t = __shfl_up(incl, o);
-        if (lane >= o) incl += t;
-    }
+    incl = wave_scan_add(incl);
     if (lane == 63) s_wsum[wv] = incl;
     if (tid == 0) {
         s_misc[4] = 0;  // keys in the buffer
@@ -322,11 +319,8 @@ __global__ __launch_bounds__(kQueryThreads) void ivf_query_kernel(IvfQueryParams
         s_word[tid] = first;
         const int cnt = __popcll(m);
         int inc = cnt;
-        for (int o = 1; o < 64; o <<= 1) {
-            const int t = __shfl_up(inc, o);
-            if (lane >= o) inc += t;
-        }
-        const int wave_total = __shfl(inc, 63);
+        inc = (int)wave_scan_add((uint32_t)inc);
+        const int wave_total = (int)lane_value((uint32_t)inc, 63);
         auto pair_at = [&](int e) -> uint16_t* {
             return reinterpret_cast<uint16_t*>(&s_stack[e >> 8][wv * 64]) + (e & 255);
         };
