@@ -248,11 +248,15 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
             lo = l2 < lo ? l2 : lo;
             hi = h2 > hi ? h2 : hi;
         }
-        const int top_shift = 56 - (__clzll((long long)(lo ^ hi)) >> 3) * 8;  // n > K >= 1: lo != hi
+        // The first digit starts at the highest bit in which two keys differ (not at a byte boundary:
+        // a digit with a few distinct values sends all keys to a few counters, and updates of one
+        // LDS word are served one after the other); the last one may overlap bits already fixed.
+        const int top_bit = 63 - __clzll((long long)(lo ^ hi));  // n > K >= 1: lo != hi
+        const int top_shift = top_bit >= 7 ? top_bit - 7 : 0;
         uint64_t prefix_mask = top_shift == 56 ? 0ULL : ~((1ULL << (top_shift + 8)) - 1ULL);
         uint64_t prefix = hi & prefix_mask;
         uint32_t want = (uint32_t)K;  // rank (1-based, from the top) still to locate inside the prefix bucket
-        for (int shift = top_shift; shift >= 0; shift -= 8) {
+        for (int shift = top_shift;; shift = shift >= 8 ? shift - 8 : 0) {
             for (int i = tid; i < 256; i += nt) s_hist[i] = 0;
             __syncthreads();
             for_each([&](uint64_t key) {
@@ -285,7 +289,7 @@ __device__ inline int wg_topk(const uint64_t* buf, int64_t n, int K, uint64_t* s
             want = s_misc[1];
             const bool done = s_misc[3] != 0u;
             __syncthreads();
-            if (done) break;
+            if (done || shift == 0) break;
         }
         const uint64_t kth = prefix;  // keys are distinct: exactly K of them are >= kth
         if (tid == 0) s_misc[2] = 0;
@@ -454,12 +458,14 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
         __syncthreads();
         diff = 0;
         for (int w = 0; w < nw; ++w) diff |= s_red[w];
-        const int top_shift = 56 - (__clzll((long long)diff) >> 3) * 8;  // n > K >= 1 distinct keys: diff != 0
+        // (first digit from the highest differing bit, last one overlapping, as in wg_topk)
+        const int top_bit = 63 - __clzll((long long)diff);  // n > K >= 1 distinct keys: diff != 0
+        const int top_shift = top_bit >= 7 ? top_bit - 7 : 0;
         uint64_t prefix_mask = top_shift == 56 ? 0ULL : ~((1ULL << (top_shift + 8)) - 1ULL);
         uint64_t prefix = k0 & prefix_mask;
         uint32_t want = (uint32_t)K;
         int pass = 0;
-        for (int shift = top_shift; shift >= 0; shift -= 8, ++pass) {
+        for (int shift = top_shift;; shift = shift >= 8 ? shift - 8 : 0, ++pass) {
             uint32_t* hist = s_hist3 + (pass % 3) * 256;
 #pragma unroll
             for (int j = 0; j < kTopkRegs; ++j)
@@ -495,7 +501,7 @@ __device__ inline int lds_topk(uint64_t* keys, int n, int K, uint64_t* sorted, i
             prefix |= (uint64_t)digit << shift;
             prefix_mask |= 0xFFULL << shift;
             want = rest;
-            if (whole) break;  // uniform: every wavefront computed the same
+            if (whole || shift == 0) break;  // uniform: every wavefront computed the same
         }
         // keys are distinct: exactly K of them are >= prefix; when the search stopped on a whole
         // bucket the K-th key is the smallest of them
