@@ -1040,9 +1040,9 @@ static_assert(kSeedItems / 64 <= kSeedThreads, "one Bloom word per thread");
 // wavefront runs the rounds over its share of the keys and leaves its `rank` best distinct
 // scores in LDS; the first wavefront then runs them once more over those, and returns the
 // smallest key with the score it ends on -- at or below the rank-th best key, equal to it up to
-// the item id unless scores tie among the best.  Fewer distinct scores than `rank`: the smallest
-// score if there are `rank` keys at all, else 0 (no threshold).  For workgroups of at most 8
-// wavefronts and n <= 1024 keys per wavefront; the result is valid in the first wavefront.
+// the item id unless scores tie among the best.  Fewer distinct scores than `rank` (fewer keys, or
+// many ties): 0, and the caller takes the exact selection.  For workgroups of at most 8 wavefronts
+// and n <= 1024 keys per wavefront; the result is valid in the first wavefront.
 constexpr int kSmallRank = 8;
 constexpr int kSmallRankPerLane = 16;
 
@@ -1093,7 +1093,7 @@ __device__ inline uint64_t wg_threshold_small(const uint64_t* keys, int n, int r
 #pragma unroll
         for (int r = 0; r < kSmallRank; ++r)
             if (r < found) last = best[r];
-        if (found == rank || (found > 0 && n >= rank)) kth = (uint64_t)last << 32;
+        if (found == rank) kth = (uint64_t)last << 32;
     }
     return kth;
 }
@@ -1315,15 +1315,23 @@ __global__ __launch_bounds__(kSeedThreads) void seed_kernel(SelectParams p, int6
     // key of the prefix: a valid admission threshold for keep = K, and for a smaller keep the
     // tighter one the schedule counts on (0 = this slice has too few passing items: no threshold).
     // Nothing else is carried over: the level after the seed pass scans the prefix again.
-    // (Small ranks over few keys -- the usual case -- take the one-wavefront form, whose value may lie
-    // below the rank-th best key by the ties in its score: still a valid threshold.)
+    // (Small ranks -- the usual case -- are taken in registers; that value may lie below the rank-th
+    // best key by the ties in its score, which a threshold may.  A slice with fewer distinct scores
+    // than the rank goes to the exact selection.)
     const int rank = (p.keep + parts - 1) / parts;
     int rank_pad = 1;
     while (rank_pad < rank) rank_pad <<= 1;
     uint64_t kth = 0;
     static_assert(NT / 64 * kSmallRankPerLane * 64 >= kLdsKeys, "every count of keys that fits LDS fits the registers of the small form");
-    if (in_lds && rank <= kSmallRank) {
-        kth = wg_threshold_small(s_keys, (int)total, rank, reinterpret_cast<uint32_t*>(s_red));  // (thread 0 publishes it)
+    bool small_done = false;
+    if (in_lds && rank <= kSmallRank && total >= (uint32_t)rank) {
+        kth = wg_threshold_small(s_keys, (int)total, rank, reinterpret_cast<uint32_t*>(s_red));
+        if (tid == 0) s_misc[6] = kth != 0ULL ? 1u : 0u;  // (a tie-heavy slice: the exact selection below)
+        __syncthreads();
+        small_done = s_misc[6] != 0u;  // (word 6 serves nothing else in this kernel)
+    }
+    if (small_done) {
+        // (thread 0 holds the value and publishes it)
     } else if (in_lds) {
         (void)lds_topk(s_keys, (int)total, rank, s_sorted, rank_pad, s_hist, s_misc, s_red, false, kth);
     } else {

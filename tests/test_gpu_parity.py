@@ -374,6 +374,18 @@ def test_duplicate_rows_tie_in_id_order():
     check_search(w, 700, label="300 copies of 100 rows")
 
 
+def test_three_distinct_rows_on_the_seeded_path_stay_exact():
+    # small batch, large corpus: the seed pass takes its thresholds from the best few distinct scores
+    # of its slices; a corpus of three distinct rows has fewer than that, so the pass must fall back
+    # to the exact selection (and the flood of equal scores that follows to the slow exact path)
+    n, d, B = 300_000, 64, 4
+    w = ragged_workload(21, n, d, B, 10, 3, 64, 2)
+    w.items = w.items[:3].repeat(n // 3, 1).contiguous()
+    w.item_scale = w.item_scale[:3].repeat(n // 3).contiguous()
+    w.filt_ids, w.filt_offsets = np.zeros(0, np.uint64), np.zeros(B + 1, np.int64)
+    check_search(w, 50, label="three distinct rows, seeded path")
+
+
 def test_rising_scores_overflow_the_regions_and_take_the_exact_slow_path():
     # every later item beats every earlier one, so each level admits everything it scans:
     # the candidate regions overflow and the affected queries are recomputed by the slow path
