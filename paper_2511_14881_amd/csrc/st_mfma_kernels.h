@@ -133,7 +133,9 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     // the per-row constants are read from LDS once for both: LDS bandwidth, not the matrix cores,
     // bounds the loop when a filter group holds many query blocks); their ring holds two pairs.
     constexpr bool PAIRS = NW == 8 && KS <= 2;
-    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? 3 : 2));
+    // (the small-batch variant at d = 128 measures best with two slots: its wavefronts wait on other things than rows,
+    // and the registers of a third slot cost more than its loads in flight bring)
+    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? (LEAN ? 2 : 3) : 2));
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
