@@ -940,9 +940,9 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
         for (int32_t r = 0; r < nr && r < st::kPrefetchStride; ++r)
             prow[(size_t)g * st::kPrefetchStride + r] = set_mfma.rows[set_mfma.row_off[g] + r];
         if (g < st::kMfmaFilterBatch) {
-            for (int32_t r = 0; r < nr && r < st::kPrefetchRows; ++r)
+            for (int32_t r = 0; r < nr && r < st::kPrefetchStride; ++r)
                 mp.prow_pack[g][r / 4] |= (uint64_t)(uint16_t)set_mfma.rows[set_mfma.row_off[g] + r] << (16 * (r % 4));
-            mp.prow_n |= (uint64_t)std::min<int32_t>(nr, st::kPrefetchRows) << (8 * g);
+            mp.prow_n |= (uint64_t)std::min<int32_t>(nr, st::kPrefetchStride) << (8 * g);
         }
     }
     for (size_t i = 0; i < blk_row.size(); ++i)

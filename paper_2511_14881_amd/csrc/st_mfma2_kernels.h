@@ -151,21 +151,21 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
     };
     // first Bloom words: rows from the kernel arguments, requested before any table is read
     if (pair_lane && stage_ok(cur)) {
-        uint64_t lo = 0, hi = 0;
+        uint64_t pk[4] = {0, 0, 0, 0};
         int nr = 0;
 #pragma unroll
         for (int g = 0; g < FB; ++g)
             if (pr_gi == g) {
-                lo = mp.prow_pack[g][0];
-                hi = mp.prow_pack[g][1];
+#pragma unroll
+                for (int c = 0; c < PR / 4; ++c) pk[c] = mp.prow_pack[g][c];
                 nr = (int)((mp.prow_n >> (8 * g)) & 255);
             }
         const int64_t gw = (seg_first(cur) >> 6) + pr_w;
         if (pr_gi < p.n_groups && gw * 64 < item_lim) {
             const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
-            for (int r = 0; r < kPrefetchRows; ++r) {
-                const int row = (int)(((r < 4 ? lo : hi) >> (16 * (r & 3))) & 0xFFFF);
+            for (int r = 0; r < PR; ++r) {
+                const int row = (int)((pk[r >> 2] >> (16 * (r & 3))) & 0xFFFF);
                 if (r < nr) pre[r] = base[(int64_t)row * kTileWords];
             }
         }
@@ -287,7 +287,7 @@ __device__ __forceinline__ void scan_mfma2_body(const ScanParams& p, const MfmaP
         uint32_t* cnt_s = s_cnt + slot * nq_pad;
 
         // (1) + (2): mask word of my (filter, word) pair, set bits into the filter's list
-        pre_valid = first ? kPrefetchRows : PR;
+        pre_valid = PR;  // (the first stage's rows came from the kernel arguments, as many)
         uint64_t mask = prefetch_mask(cur);
         const Stage nxt = stage_next(cur);
 #pragma unroll

@@ -58,8 +58,9 @@ struct MfmaParams {
     // The same rows for the first batch of filters, resident in the kernel arguments so that the
     // very first Bloom words can be requested before anything has been read from memory:
     // row r of filter g is bits [16*(r%4), +16) of prow_pack[g][r/4]; prow_n holds the row counts.
-    uint64_t prow_pack[kMfmaFilterBatch][2];
-    uint64_t prow_n;             // byte g = min(rows of filter g, kPrefetchRows)
+    // (4-wavefront workgroups take the first kPrefetchRows of them, 8-wavefront ones all.)
+    uint64_t prow_pack[kMfmaFilterBatch][kPrefetchStride / 4];
+    uint64_t prow_n;             // byte g = min(rows of filter g, kPrefetchStride)
     // Resident-query image in the workspace: written by workgroup x = 0 of each row of the grid
     // on the first level, read by every workgroup afterwards (one round trip instead of two).
     int8_t* img_q;               // [S][rows_local][d]   swizzled as in LDS
@@ -135,7 +136,8 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     constexpr bool PAIRS = NW == 8 && KS <= 2;
     // (the small-batch variant at d = 128 measures best with two slots: its wavefronts wait on other things than rows,
     // and the registers of a third slot cost more than its loads in flight bring)
-    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? (LEAN ? 2 : 3) : 2));
+    // (the admit-everything first level at d = 256 has one short segment per wavefront: four slots halve its round trips)
+    constexpr int NB = PAIRS ? 4 : (KS == 1 ? 4 : (KS == 2 ? (LEAN ? 2 : 3) : ((ADMIT && KS == 4) ? 4 : 2)));
     int8_t* s_q = reinterpret_cast<int8_t*>(lds);
     float* s_sq = reinterpret_cast<float*>(lds + mp.lds_sq);
     float* s_tauf = reinterpret_cast<float*>(lds + mp.lds_tauf);
@@ -222,7 +224,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     const bool pair_lane = lane < FB * SW;
     const int pr_gi = lane / SW, pr_w = lane - pr_gi * SW;
     uint64_t pre[PR];
-    int pre_valid = 0;  // rows of the current stage that were prefetched (the first stage gets kPrefetchRows from the kernel arguments)
+    int pre_valid = 0;  // rows of the current stage that were prefetched
 #pragma unroll
     for (int r = 0; r < PR; ++r) pre[r] = ~0ULL;
     auto prefetch_issue = [&](const Stage& st) {
@@ -279,21 +281,21 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
     };
     // ---- first Bloom words: rows from the kernel arguments, requested before any table is read
     if (pair_lane && stage_ok(cur)) {
-        uint64_t lo = 0, hi = 0;
+        uint64_t pk[4] = {0, 0, 0, 0};
         int nr = 0;
 #pragma unroll
         for (int g = 0; g < FB; ++g)
             if (pr_gi == g) {
-                lo = mp.prow_pack[g][0];
-                hi = mp.prow_pack[g][1];
+#pragma unroll
+                for (int c = 0; c < PR / 4; ++c) pk[c] = mp.prow_pack[g][c];
                 nr = (int)((mp.prow_n >> (8 * g)) & 255);
             }
         const int64_t gw = (seg_first(cur) >> 6) + pr_w;
         if (pr_gi < p.n_groups && gw * 64 < item_lim) {
             const uint64_t* base = p.bloom + ((gw >> 4) * (int64_t)p.m_bits) * kTileWords + (gw & 15);
 #pragma unroll
-            for (int r = 0; r < kPrefetchRows; ++r) {
-                const int row = (int)(((r < 4 ? lo : hi) >> (16 * (r & 3))) & 0xFFFF);
+            for (int r = 0; r < PR; ++r) {
+                const int row = (int)((pk[r >> 2] >> (16 * (r & 3))) & 0xFFFF);
                 if (r < nr) pre[r] = base[(int64_t)row * kTileWords];
             }
         }
@@ -460,7 +462,7 @@ __device__ __forceinline__ void scan_mfma_body(const ScanParams& p, const MfmaPa
 
         // (1) + (2): mask word of my pair, then the set bits of each filter's words, in item
         // order, into the filter's list
-        pre_valid = first ? kPrefetchRows : PR;
+        pre_valid = PR;  // (the first stage's rows came from the kernel arguments, as many)
         uint64_t mask = prefetch_mask(cur);
         const Stage nxt = stage_next(cur);
 #pragma unroll
