@@ -209,7 +209,9 @@ int64_t st_search_overflow_flags_offset(int64_t n_items, int32_t d, int32_t batc
  * before the last level: a tighter threshold, checked and backed by the exact slow path at the
  * end).  The rows give the sizes; a search served by the 8-wavefront MFMA scan alone takes the
  * items of its first level as segments spread evenly over the corpus rather than as the prefix
- * [item_begin, item_end) and scans the rest from item 0.  q_split (a power of two, 1 unless the query rows of a large batch are
+ * [item_begin, item_end) and scans the rest from item 0, and then also halves that level where the
+ * schedule has two levels and the second would still hand the last selection few keys (small K).
+ * q_split (a power of two, 1 unless the query rows of a large batch are
  * spread over several rows of workgroups) divides the workgroups that share one query's
  * candidates.  out_caps receives {workgroups, region_capacity}. */
 int32_t st_search_plan(int64_t n_items, int32_t batch, int32_t K, int32_t q_split,

@@ -371,10 +371,11 @@ int g_plan_next = 0;
 std::mutex g_plan_mu;
 
 int cached_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, int32_t batch_rows, st::Plan* out,
-                int32_t waves = 2048, int32_t min_cap = 64, bool optimistic = true)
+                int32_t waves = 2048, int32_t min_cap = 64, bool optimistic = true, bool small_first = false)
 {
     // the batch enters the schedule only through "small enough for the seed pass"
-    const PlanKey key{n_items, K, q_split, seg_cap, batch_rows <= st::kSeedMaxRows ? 1 : 0, waves, min_cap, optimistic ? 1 : 0};
+    const PlanKey key{n_items, K, q_split, seg_cap, batch_rows <= st::kSeedMaxRows ? 1 : 0, waves, min_cap,
+                      (optimistic ? 1 : 0) | (small_first ? 2 : 0)};
     {
         std::lock_guard<std::mutex> lock(g_plan_mu);
         for (const PlanEntry& e : g_plans)
@@ -385,7 +386,7 @@ int cached_plan(int64_t n_items, int32_t K, int32_t q_split, int32_t seg_cap, in
     }
     st::Plan p;
     memset(&p, 0, sizeof(p));
-    const int rc = st::make_plan(n_items, K, q_split, seg_cap, batch_rows, &p, waves, min_cap, optimistic);
+    const int rc = st::make_plan(n_items, K, q_split, seg_cap, batch_rows, &p, waves, min_cap, optimistic, small_first);
     {
         std::lock_guard<std::mutex> lock(g_plan_mu);
         PlanEntry& e = g_plans[g_plan_next];
@@ -912,8 +913,11 @@ static int search_impl(const st_bloom* bloom, const int8_t* dev_items, const flo
     // wavefronts that scan a level side by side: the resident workgroups of one row of the grid
     const int32_t scan_waves = set_mfma.n ? std::max(1, std::min(plan_groups_per_row(mp.q_split), st::kComputeUnits * mfma_wgs / mp.q_split)) * mp.waves
                                           : st::scan_groups();  // (a whole workgroup shares a segment there)
+    // (searches that will take their first level as a sample spread over the corpus -- the condition of
+    // samp_stride below -- may plan a smaller one)
+    const bool spread_first = allow_seed && set_mfma.n && !set_dot.n && mp.waves == 8;
     if (cached_plan(n_items, K, mp.q_split, seg_cap, allow_seed ? batch * n_tasks : st::kSeedMaxRows + 1, &plan, scan_waves,
-                    min_cap, allow_seed) != 0)
+                    min_cap, allow_seed, spread_first) != 0)
         return fail(ST_EINVAL, "no schedule for these sizes");
     st::Plan plan1;
     if (cached_plan(n_items, K, 1, st::kMaxSegItems, batch * n_tasks, &plan1, 2048, min_cap) != 0)
