@@ -210,3 +210,31 @@ def test_optimistic_keep_bounds_the_chance_of_a_too_tight_threshold(tmp_path):
         assert r >= mean  # never below the expected count
     # the benchmark shapes get thresholds far tighter than the K-th best of the prefix
     assert keeps[0] <= 32 and keeps[1] <= 32 and keeps[2] <= 32
+
+
+def test_first_level_is_halved_only_where_the_last_selection_stays_small(tmp_path):
+    # A search that samples its first level may take it at half the size when two levels remain and
+    # the second would hand the final selection at most 3500 keys per query (K + what it admits).
+    import shutil
+    import subprocess
+    cxx = shutil.which("g++")
+    if cxx is None:
+        pytest.skip("no host C++ compiler")
+    exe = str(tmp_path / "plan_levels")
+    src = os.path.join(ROOT, "tests", "plan_keep_host_test.cpp")
+    inc = os.path.join(ROOT, "paper_2511_14881_amd", "csrc")
+    subprocess.run([cxx, "-std=c++17", "-O1", "-I", inc, src, "-o", exe], check=True)
+    cases = [(5_000_000, 200, 1), (5_000_000, 200, 0), (10_000_000, 500, 1), (20_000_000, 1000, 1), (1_000_000, 100, 1),
+             (40_000, 10, 1)]
+    out = subprocess.run([exe, "levels"] + [str(x) for c in cases for x in c], capture_output=True, text=True, check=True)
+    rows = [tuple(int(v) for v in line.split()) for line in out.stdout.splitlines()]
+    assert rows[0] == (2, 32768)        # Multi's sizes: halved
+    assert rows[1] == (2, 65536)        # ... not for a search that keeps the prefix
+    assert rows[2] == (2, 65536)        # Large: 18 * 304 + 500 keys would be too many
+    assert rows[3][0] == 3 and rows[3][1] == 65536   # three levels: left alone
+    assert rows[4] == (2, 32768)        # K = 100 on 1 M items: 27 * 29.5 + 100
+    assert rows[5][1] == 40_000         # a corpus smaller than the first level: one level
+    for (n, K, small), (levels, end0) in zip(cases, rows):
+        if small and levels == 2 and end0 == 32768:
+            keep = int(subprocess.run([exe, str(K), str(end0), str(n)], capture_output=True, text=True, check=True).stdout)
+            assert K + keep * (n / end0 - 1) <= 3500
